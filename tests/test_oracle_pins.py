@@ -1,0 +1,283 @@
+"""Pins for the CPU oracle: what the definition and the mathematics fix.
+
+Each pin is a function of an "oracle-like" namespace so that the same pins can
+be turned on deliberately broken copies of the oracle (test_pins_catch_planted
+_mistakes): a plausible mistake anywhere in it must fail at least one pin.
+"""
+import math
+import os
+import types
+
+import numpy as np
+import pytest
+
+import oracle.rmsnorm_family as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "hand_worked_2x2.txt")
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.Philox(seed))
+
+
+def _rand(seed, M, K, N):
+    r = _rng(seed)
+    X = r.standard_normal((M, K))
+    g = r.random(K) + 0.5
+    W1 = r.standard_normal((K, N)) / math.sqrt(K)
+    W2 = r.standard_normal((K, N)) / math.sqrt(K)
+    return X, g, W1, W2
+
+
+def _golden():
+    vals = {}
+    with open(GOLD) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, v = line.split()
+            vals[k] = float(v)
+    return vals
+
+
+# ---- pins --------------------------------------------------------------------------------
+
+def pin_hand_worked(o):
+    """tests/golden/hand_worked_2x2.txt: closed-form values of a 1x2 example."""
+    gv = _golden()
+    s2 = gv["sqrt2"]
+    X = np.array([[3.0, 4.0]])
+    W = np.array([[1.0, 2.0], [3.0, 4.0]])
+    W2 = np.array([[1.0, 0.0], [0.0, 2.0]])
+    one = np.array([1.0, 1.0])
+    g = np.array([2.0, 0.5])
+    np.testing.assert_allclose(o.rms_norm(X, one, 0.0), [[0.6 * s2, 0.8 * s2]], rtol=1e-15)
+    np.testing.assert_allclose(o.rmsnorm_matmul(X, one, W, 0.0), [[3 * s2, 4.4 * s2]], rtol=1e-15)
+    np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W, 0.0), [[2.4 * s2, 4 * s2]], rtol=1e-15)
+    np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W, 3.5), [[3.0, 5.0]], rtol=1e-15)
+    np.testing.assert_allclose(o.rmsnorm_gated_mlp(X, g, W, W2, 3.5),
+                               [[gv["silu3"] * 1.5, gv["silu5"] * 1.0]], rtol=1e-15)
+
+
+def pin_scale_invariance(o):
+    """RMSNorm(cX) = RMSNorm(X) for c > 0 at eps = 0; closed-form ratio at eps > 0."""
+    X, g, W, _ = _rand(1, 5, 48, 7)
+    base = o.rmsnorm_matmul(X, g, W, 0.0)
+    for c in (0.5, 3.0, 1e3):
+        np.testing.assert_allclose(o.rmsnorm_matmul(c * X, g, W, 0.0), base, rtol=1e-12, atol=1e-14)
+    eps = 1e-2
+    ms = np.mean(X * X, axis=1, keepdims=True)
+    for c in (0.5, 3.0):
+        ratio = np.sqrt((ms + eps) / (ms + eps / c**2))
+        np.testing.assert_allclose(o.rms_norm(c * X, g, eps), o.rms_norm(X, g, eps) * ratio, rtol=1e-12)
+
+
+def pin_unit_rms(o):
+    """g = 1: every normalised row has RMS 1 at eps = 0, sqrt(ms/(ms+eps)) otherwise."""
+    X, _, _, _ = _rand(2, 6, 64, 1)
+    one = np.ones(64)
+    Nrm = o.rms_norm(X, one, 0.0)
+    np.testing.assert_allclose(np.sqrt(np.mean(Nrm * Nrm, axis=1)), 1.0, rtol=1e-14)
+    eps = 0.25
+    ms = np.mean(X * X, axis=1)
+    Nrm = o.rms_norm(X, one, eps)
+    np.testing.assert_allclose(np.sqrt(np.mean(Nrm * Nrm, axis=1)), np.sqrt(ms / (ms + eps)), rtol=1e-13)
+
+
+def pin_identity_weight(o):
+    """W = I returns the normalised X."""
+    X, g, _, _ = _rand(3, 4, 32, 1)
+    np.testing.assert_allclose(o.rmsnorm_matmul(X, g, np.eye(32), 1e-6), o.rms_norm(X, g, 1e-6),
+                               rtol=0, atol=0)
+    # and the normalised X itself, element by element, from scalar arithmetic
+    Nrm = o.rms_norm(X, g, 1e-6)
+    for m in range(4):
+        ms = sum(float(x) * float(x) for x in X[m]) / 32
+        for k in range(32):
+            assert Nrm[m, k] == pytest.approx(X[m, k] / math.sqrt(ms + 1e-6) * g[k], rel=1e-14)
+
+
+def _brute_plain(X, g, W, eps):
+    M, K, N = len(X), len(g), len(W[0])
+    Y = [[0.0] * N for _ in range(M)]
+    for m in range(M):
+        for j in range(N):
+            acc = 0.0
+            for k in range(K):
+                ms = 0.0
+                for kk in range(K):
+                    ms += X[m][kk] * X[m][kk]
+                acc += X[m][k] / math.sqrt(ms / K + eps) * g[k] * W[k][j]
+            Y[m][j] = acc
+    return np.array(Y)
+
+
+def pin_brute_force(o):
+    """Deliberately naive scalar loops agree on tiny, non-square shapes."""
+    for seed, (M, K, N) in enumerate([(1, 1, 1), (3, 5, 2), (4, 16, 8), (2, 7, 3)]):
+        X, g, W1, W2 = _rand(10 + seed, M, K, N)
+        for eps in (0.0, 1e-6, 0.3):
+            ref = _brute_plain(X.tolist(), g.tolist(), W1.tolist(), eps)
+            np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W1, eps), ref, rtol=1e-12, atol=1e-14)
+            a = _brute_plain(X.tolist(), g.tolist(), W1.tolist(), eps)
+            b = _brute_plain(X.tolist(), g.tolist(), W2.tolist(), eps)
+            ref_g = np.array([[a[m, j] / (1.0 + math.exp(-a[m, j])) * b[m, j] for j in range(N)]
+                              for m in range(M)])
+            np.testing.assert_allclose(o.rmsnorm_gated_mlp(X, g, W1, W2, eps), ref_g, rtol=1e-12, atol=1e-14)
+
+
+def pin_fused_order(o):
+    """Table 1, "matmul commutes with div denominator": scale after the product."""
+    X, g, W, _ = _rand(4, 9, 40, 11)
+    eps = 1e-6
+    r = 1.0 / np.sqrt(np.mean(X * X, axis=1, keepdims=True) + eps)
+    fused = ((X * g) @ W) * r
+    np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W, eps), fused, rtol=1e-12, atol=1e-14)
+
+
+def pin_closed_form_rows(o):
+    """Constant row -> sign(c) * g^T W; one-hot row a*e_j -> sign(a) sqrt(K) g_j W[j,:] (eps = 0)."""
+    K, N = 24, 5
+    _, g, W, _ = _rand(5, 1, K, N)
+    for c in (2.5, -0.125):
+        X = np.full((1, K), c)
+        np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W, 0.0), [math.copysign(1, c) * (g @ W)], rtol=1e-13)
+    for a, j in ((3.0, 0), (-0.7, 17), (1e-3, K - 1)):
+        X = np.zeros((1, K))
+        X[0, j] = a
+        np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W, 0.0),
+                                   [math.copysign(1, a) * math.sqrt(K) * g[j] * W[j]], rtol=1e-13)
+    # eps > 0, zero row: output exactly zero, no NaN
+    assert np.all(o.rmsnorm_matmul(np.zeros((2, K)), g, W, 1e-6) == 0.0)
+
+
+def pin_partitions(o):
+    """Table 1, parallelized matmul: column partition exact, split-K sums to the whole."""
+    X, g, W, W2 = _rand(6, 7, 64, 24)
+    eps = 1e-6
+    full = o.rmsnorm_matmul(X, g, W, eps)
+    np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W[:, 8:16], eps), full[:, 8:16], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(o.rmsnorm_matmul(X[2:5], g, W, eps), full[2:5], rtol=1e-13, atol=1e-15)
+    Nrm = o.rms_norm(X, g, eps)
+    parts = sum(Nrm[:, s:s + 16] @ W[s:s + 16] for s in range(0, 64, 16))
+    np.testing.assert_allclose(parts, full, rtol=1e-12, atol=1e-14)
+    fullg = o.rmsnorm_gated_mlp(X, g, W, W2, eps)
+    np.testing.assert_allclose(o.rmsnorm_gated_mlp(X, g, W[:, 5:9], W2[:, 5:9], eps), fullg[:, 5:9],
+                               rtol=1e-13, atol=1e-15)
+
+
+def pin_gated_identities(o):
+    """W1 = 0 -> 0; silu(a) - silu(-a) = a; silu(0) = 0; gated = silu(plain(W1)) * plain(W2)."""
+    X, g, W1, W2 = _rand(7, 5, 32, 9)
+    eps = 1e-6
+    assert np.all(o.rmsnorm_gated_mlp(X, g, np.zeros_like(W1), W2, eps) == 0.0)
+    a = np.linspace(-40, 40, 161)
+    np.testing.assert_allclose(o.silu(a) - o.silu(-a), a, rtol=1e-13, atol=1e-15)
+    assert o.silu(np.array([0.0]))[0] == 0.0
+    assert o.silu(np.array([-800.0]))[0] == 0.0 and o.silu(np.array([800.0]))[0] == 800.0
+    assert o.silu(np.array([1.0]))[0] == pytest.approx(1.0 / (1.0 + math.exp(-1.0)), rel=1e-15)
+    ya = o.rmsnorm_matmul(X, g, W1, eps)
+    yb = o.rmsnorm_matmul(X, g, W2, eps)
+    np.testing.assert_allclose(o.rmsnorm_gated_mlp(X, g, W1, W2, eps), o.silu(ya) * yb, rtol=1e-13, atol=1e-300)
+    # the activation sits on W1 only: swapping the weights changes the result
+    assert not np.allclose(o.rmsnorm_gated_mlp(X, g, W1, W2, eps), o.rmsnorm_gated_mlp(X, g, W2, W1, eps))
+    # scale goes on before the activation: silu is not homogeneous
+    Xs = 4.0 * X
+    np.testing.assert_allclose(o.rmsnorm_gated_mlp(Xs, g, W1, W2, 0.0), o.rmsnorm_gated_mlp(X, g, W1, W2, 0.0),
+                               rtol=1e-12, atol=1e-14)
+
+
+def pin_torch_second_opinion(o):
+    """torch float64 CPU routines as an independent library (textbook special case)."""
+    torch = pytest.importorskip("torch")
+    X, g, W1, W2 = _rand(8, 6, 128, 20)
+    eps = 1e-6
+    tX, tg, tW1, tW2 = (torch.from_numpy(a) for a in (X, g, W1, W2))
+    nrm = tX * torch.rsqrt(tX.pow(2).mean(dim=1, keepdim=True) + eps) * tg
+    np.testing.assert_allclose(o.rmsnorm_matmul(X, g, W1, eps), (nrm @ tW1).numpy(), rtol=1e-12, atol=1e-14)
+    ref = torch.nn.functional.silu(nrm @ tW1) * (nrm @ tW2)
+    np.testing.assert_allclose(o.rmsnorm_gated_mlp(X, g, W1, W2, eps), ref.numpy(), rtol=1e-12, atol=1e-14)
+
+
+def pin_output_variance(o):
+    """i.i.d. inputs of the benchmark recipe: Var(Y) = E[g^2] ms/(ms+eps) = 13/12 (weak, statistical)."""
+    r = _rng(9)
+    M, K, N = 32, 512, 256
+    X = r.standard_normal((M, K))
+    g = r.random(K) + 0.5
+    W = r.standard_normal((K, N)) / math.sqrt(K)
+    Y = o.rmsnorm_matmul(X, g, W, 1e-6)
+    assert abs(Y.var() - 13.0 / 12.0) < 0.05
+    assert abs(Y.mean()) < 0.05
+
+
+PINS = [pin_hand_worked, pin_scale_invariance, pin_unit_rms, pin_identity_weight, pin_brute_force,
+        pin_fused_order, pin_closed_form_rows, pin_partitions, pin_gated_identities,
+        pin_torch_second_opinion, pin_output_variance]
+
+
+@pytest.mark.parametrize("pin", PINS, ids=lambda p: p.__name__)
+def test_pin(pin):
+    pin(O)
+
+
+# ---- planted mistakes: each broken oracle must be caught by some pin -----------------------
+
+def _mutant(**over):
+    ns = types.SimpleNamespace(rms_norm=O.rms_norm, rmsnorm_matmul=O.rmsnorm_matmul,
+                               rmsnorm_gated_mlp=O.rmsnorm_gated_mlp, silu=O.silu)
+    for k, v in over.items():
+        setattr(ns, k, v)
+    # rebuild the composite functions on top of the (possibly replaced) pieces
+    if "rmsnorm_matmul" not in over:
+        ns.rmsnorm_matmul = lambda X, g, W, eps: np.matmul(ns.rms_norm(X, g, eps), W)
+    if "rmsnorm_gated_mlp" not in over:
+        def gated(X, g, W1, W2, eps):
+            n = ns.rms_norm(X, g, eps)
+            return ns.silu(n @ W1) * (n @ W2)
+        ns.rmsnorm_gated_mlp = gated
+    return ns
+
+
+def _norm_variant(fn):
+    def rms_norm(X, g, eps):
+        X = np.asarray(X, dtype=np.float64)
+        return np.stack([fn(X[m], np.asarray(g), eps) for m in range(X.shape[0])]) if X.shape[0] else X.copy()
+    return rms_norm
+
+
+MUTANTS = {
+    "sum_not_mean": _mutant(rms_norm=_norm_variant(lambda x, g, e: x / np.sqrt(np.sum(x * x) + e) * g)),
+    "eps_outside_root": _mutant(rms_norm=_norm_variant(lambda x, g, e: x / (np.sqrt(np.mean(x * x)) + e) * g)),
+    "eps_dropped": _mutant(rms_norm=_norm_variant(lambda x, g, e: x / np.sqrt(np.mean(x * x)) * g)),
+    "bessel_K_minus_1": _mutant(rms_norm=_norm_variant(
+        lambda x, g, e: x / np.sqrt(np.sum(x * x) / max(len(x) - 1, 1) + e) * g)),
+    "gain_dropped": _mutant(rms_norm=_norm_variant(lambda x, g, e: x / np.sqrt(np.mean(x * x) + e))),
+    "gain_inside_sum": _mutant(rms_norm=_norm_variant(
+        lambda x, g, e: x * g / np.sqrt(np.mean((x * g) ** 2) + e))),
+    "mean_subtracted": _mutant(rms_norm=_norm_variant(
+        lambda x, g, e: (x - x.mean()) / np.sqrt(np.mean((x - x.mean()) ** 2) + e) * g)),
+    "abs_mean_not_rms": _mutant(rms_norm=_norm_variant(lambda x, g, e: x / (np.mean(np.abs(x)) + e) * g)),
+    "W_transposed": _mutant(rmsnorm_matmul=lambda X, g, W, eps: np.matmul(
+        O.rms_norm(X, g, eps), W.T if W.shape[0] == W.shape[1] else W)),
+    "silu_on_W2": _mutant(rmsnorm_gated_mlp=lambda X, g, W1, W2, eps: O.rmsnorm_gated_mlp(X, g, W2, W1, eps)),
+    "no_activation": _mutant(rmsnorm_gated_mlp=lambda X, g, W1, W2, eps: (
+        O.rmsnorm_matmul(X, g, W1, eps) * O.rmsnorm_matmul(X, g, W2, eps))),
+    "sigmoid_not_silu": _mutant(silu=lambda a: 1.0 / (1.0 + np.exp(-np.asarray(a, dtype=np.float64)))),
+    "silu_wrong_sign": _mutant(silu=lambda a: np.asarray(a) / (1.0 + np.exp(np.asarray(a, dtype=np.float64)))),
+    "scale_after_silu": _mutant(rmsnorm_gated_mlp=lambda X, g, W1, W2, eps: (
+        O.silu((X * g) @ W1) * ((X * g) @ W2) / (np.mean(X * X, axis=1, keepdims=True) + eps))),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_catch_planted_mistakes(name):
+    mutant = MUTANTS[name]
+    caught = []
+    for pin in PINS:
+        try:
+            with np.errstate(all="ignore"):
+                pin(mutant)
+        except (AssertionError, FloatingPointError, ZeroDivisionError):
+            caught.append(pin.__name__)
+    assert caught, f"no pin notices the planted mistake {name!r}"
