@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused RMSNorm -> MatMul library on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload IDX] [--no-extra] [--no-cpu]
+
+A step is one library call (one pass of the whole fused path: sums of squares in the K-loop, gain,
+GEMM, split-K reduction, 1/rms, and the SiLU gate for the gated workloads) over one batch of seeded
+synthetic input that is already resident in HBM.  The headline workload is benchmark configuration
+index 1 (decode RMSNorm -> MatMul, bf16, X[16,4096], W[4096,4096]); the other three bf16
+configurations are timed too and reported under "other_workloads".
+
+Decode workloads rotate over enough distinct weight buffers (>= 1 GiB in total) that W is streamed
+from HBM and not from the 256 MB last-level cache; the cache-hot single-buffer time is reported
+separately.  One JSON line goes to stdout; progress goes to stderr.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+import prism_inputs as pi  # noqa: E402
+
+METRIC = "fused RMSNorm+GEMM: HBM GB/s (decode) and TFLOP/s (prefill), % of roofline"
+HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def counted_bytes(wl):
+    """Algorithmic bytes of one call: X + g + W (+ W2) + Y, each once, in the storage type."""
+    e = 2 if wl.dtype == pi.BF16 else 4
+    nw = 2 if wl.gated else 1
+    return e * (wl.M * wl.K + wl.K + nw * wl.K * wl.N + wl.M * wl.N)
+
+
+def counted_flops(wl):
+    """Algorithmic flops of one call: 2 M K N per weight matrix (norm, gain and gate not counted)."""
+    return 2 * wl.M * wl.K * wl.N * (2 if wl.gated else 1)
+
+
+def is_decode(wl):
+    return wl.M <= 16
+
+
+class Runner:
+    """Pre-marshalled library calls over R rotating buffer sets of one workload."""
+
+    def __init__(self, wl, sets, stored=None):
+        import torch
+        import paper_2604_15272_amd as P
+        self.P, self.torch, self.wl = P, torch, wl
+        stored = stored if stored is not None else pi.draw_workload(wl)
+        self.stored = stored
+        tdt = torch.bfloat16 if wl.dtype == pi.BF16 else torch.float32
+
+        def dev(a):
+            t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+            return t.view(torch.bfloat16) if wl.dtype == pi.BF16 else t
+
+        self.X, self.g = dev(stored["X"]), dev(stored["g"])
+        names = ("W1", "W2") if wl.gated else ("W",)
+        base = [dev(stored[n]) for n in names]
+        # Further sets are row-rotated copies: same distribution, different addresses.
+        self.W = [base] + [[torch.roll(w, r, 0).contiguous() for w in base] for r in range(1, sets)]
+        self.Y = [torch.empty((wl.M, wl.N), dtype=tdt, device="cuda") for _ in range(sets)]
+        self.op = P.PRISM_OP_RMSNORM_GATED_MLP if wl.gated else P.PRISM_OP_RMSNORM_MATMUL
+        self.dt = P.PRISM_BF16 if wl.dtype == pi.BF16 else P.PRISM_F32
+        P.ensure_workspace(P.prism_workspace_bytes(self.op, wl.M, wl.K, wl.N, self.dt))
+        self.plan = P.prism_plan(self.op, wl.M, wl.K, wl.N, self.dt)
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        vp = ctypes.c_void_p
+        dims = (ctypes.c_int64(wl.M), ctypes.c_int64(wl.K), ctypes.c_int64(wl.N), ctypes.c_float(wl.eps),
+                ctypes.c_int32(self.dt), stream)
+        fn = P.lib.prism_rmsnorm_gated_mlp if wl.gated else P.lib.prism_rmsnorm_matmul
+        self.fn = fn
+        self.args = [(vp(self.X.data_ptr()), vp(self.g.data_ptr()), *[vp(w.data_ptr()) for w in self.W[s]],
+                      vp(self.Y[s].data_ptr())) + dims for s in range(sets)]
+        self.sets = sets
+
+    def run(self, steps, first=0):
+        fn, args, sets = self.fn, self.args, self.sets
+        for i in range(steps):
+            st = fn(*args[(first + i) % sets])
+            if st != 0:
+                raise RuntimeError(f"library call failed: {self.P.prism_status_string(st)}")
+
+    def timed(self, steps, warmup, sets_used=None):
+        """Returns (wall ms per step, HIP-event ms per step) over exactly `steps` calls."""
+        torch = self.torch
+        if sets_used == 1:
+            saved, self.args, self.sets = (self.args, self.sets), self.args[:1], 1
+        self.run(warmup)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        self.run(steps, first=warmup)
+        e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        if sets_used == 1:
+            self.args, self.sets = saved
+        return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+    def output(self, s=0):
+        import torch
+        y = self.Y[s]
+        if self.wl.dtype == pi.BF16:
+            return pi.to_f64(y.view(torch.uint16).cpu().numpy(), pi.BF16)
+        return y.cpu().numpy().astype(np.float64)
+
+
+def measure(idx, steps, warmup):
+    wl = pi.WORKLOADS[idx]
+    nbytes, flops = counted_bytes(wl), counted_flops(wl)
+    dec = is_decode(wl)
+    wbytes = 2 * wl.K * wl.N * (2 if wl.gated else 1)
+    sets = max(2, -(-(1 << 30) // wbytes)) if dec else 1
+    log(f"[bench] workload {idx} {wl.name}: M={wl.M} K={wl.K} N={wl.N} gated={wl.gated} sets={sets}")
+    r = Runner(wl, sets)
+    wall_ms, ev_ms = r.timed(steps, warmup)
+    res = {
+        "workload": wl.name, "config_index": idx, "M": wl.M, "K": wl.K, "N": wl.N, "gated": wl.gated,
+        "plan": r.plan, "steps": steps, "ms_per_step": wall_ms, "event_ms_per_step": ev_ms,
+        "buffer_sets": sets,
+    }
+    if dec:
+        res.update(value=nbytes / (wall_ms * 1e-3) / 1e9, unit="GB/s", bound="hbm",
+                   achieved=nbytes / (ev_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS)
+        _, hot_ms = r.timed(steps, warmup, sets_used=1)
+        res["cache_hot_event_ms_per_step"] = hot_ms
+        res["cache_hot_GBps"] = nbytes / (hot_ms * 1e-3) / 1e9
+    else:
+        res.update(value=flops / (wall_ms * 1e-3) / 1e12, unit="TFLOP/s", bound="mfma",
+                   achieved=flops / (ev_ms * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS)
+    res["frac"] = res["achieved"] / res["peak"]
+    log(f"[bench]   {res['value']:.1f} {res['unit']} wall, {res['achieved']:.1f} by HIP events "
+        f"({100 * res['frac']:.1f}% of {res['bound']} peak), {ev_ms * 1e3:.2f} us/call")
+    return res, r
+
+
+def cpu_baseline(runner):
+    """The oracle, as it stands, timed on this host on the headline workload (all of it: it is small)."""
+    import oracle  # the cpu_baseline leg is the only place the benchmark touches the oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    wl, st = runner.wl, runner.stored
+    X, g = pi.to_f64(st["X"], wl.dtype), pi.to_f64(st["g"], wl.dtype)
+    Ws = [pi.to_f64(st[n], wl.dtype) for n in (("W1", "W2") if wl.gated else ("W",))]
+    fn = (lambda: oracle.rmsnorm_gated_mlp(X, g, Ws[0], Ws[1], wl.eps)) if wl.gated else (
+        lambda: oracle.rmsnorm_matmul(X, g, Ws[0], wl.eps))
+    yhat = fn()  # untimed first call (page-in), also the parity reference
+    reps, t0 = 0, time.perf_counter()
+    while reps < 200 and time.perf_counter() - t0 < 10.0:
+        fn()
+        reps += 1
+    sec = (time.perf_counter() - t0) / reps
+    runner.run(1)
+    runner.torch.cuda.synchronize()
+    y = runner.output(0)
+    err = float(np.max(np.abs(y - yhat) / (np.abs(yhat) + 1.0)))
+    return {
+        "value": counted_bytes(wl) / sec / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"whole {wl.name} workload (M={wl.M}), fp64 numpy oracle, mean of {reps} calls, "
+                  f"inputs already widened to fp64; {sec * 1e3:.2f} ms per call",
+        "gpu_vs_oracle_worst_err": err,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", type=int, default=1, help="benchmark configuration index (1..4)")
+    ap.add_argument("--no-extra", action="store_true", help="time only the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        log("bench.py measures one GPU: this build has no multi-GPU path (no collectives, no sharding); "
+            "run with --gpus 1")
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU")
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    head, runner = measure(a.workload, a.steps, a.warmup)
+    out = {
+        "metric": METRIC, "value": head["value"], "unit": head["unit"], "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": head["workload"], "M": head["M"], "K": head["K"], "N": head["N"],
+                   "gated": head["gated"], "plan": head["plan"], "buffer_sets": head["buffer_sets"]},
+        "roofline": {"bound": head["bound"], "achieved": head["achieved"], "peak": head["peak"],
+                     "unit": head["unit"], "frac": head["frac"], "traffic": None,
+                     "event_ms_per_launch": head["event_ms_per_step"]},
+    }
+    if "cache_hot_GBps" in head:
+        out["cache_hot"] = {"GBps": head["cache_hot_GBps"], "event_ms_per_launch": head["cache_hot_event_ms_per_step"]}
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(runner)
+        log(f"[bench] oracle: {out['cpu_baseline']['value']:.2f} GB/s on {out['cpu_baseline']['cores']} threads; "
+            f"GPU vs oracle worst err {out['cpu_baseline']['gpu_vs_oracle_worst_err']:.2e}")
+    del runner
+    if not a.no_extra:
+        others = []
+        for idx, st, wu in ((3, 500, 30), (2, 200, 20), (4, 40, 5)):
+            if idx == a.workload:
+                continue
+            torch.cuda.empty_cache()
+            res, r = measure(idx, st, wu)
+            del r
+            others.append({k: res[k] for k in ("workload", "plan", "steps", "ms_per_step", "event_ms_per_step",
+                                               "value", "unit", "bound", "achieved", "peak", "frac")})
+        out["other_workloads"] = others
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,142 @@
+/*
+ * prism.h - C ABI of the fused RMSNorm -> MatMul operator family for AMD MI355X (gfx950).
+ *
+ * The library computes, in one kernel launch and without ever writing the
+ * normalised input to memory,
+ *
+ *     Y = rms_norm(X; g, eps) . W                            (prism_rmsnorm_matmul)
+ *     Y = silu(rms_norm(X) . W1) * (rms_norm(X) . W2)        (prism_rmsnorm_gated_mlp)
+ *
+ * with rms_norm(X)[m,k] = X[m,k] * g[k] / sqrt(mean_k X[m,:]^2 + eps).
+ *
+ * These are the "RMSNorm", "RMSNorm-MLP" and "SwiGLU" workloads of the paper
+ * (Section 7.1).  The kernels use the rewrite the paper's verifier licenses
+ * (Table 1, "matmul commutes with div denominator"): the per-row sum of squares
+ * is accumulated inside the GEMM K-loop and 1/rms is applied to the finished
+ * accumulator, exactly as the running example's fused program accumulates its
+ * row reduction in the loop and divides after it (Figure 1(b)).
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     allocates and frees nothing.  X, g, W* are only read; Y is overwritten and
+ *     must not overlap any input.
+ *   - Layout: row-major, contiguous.  X[M,K], g[K], W[K,N], Y[M,N].
+ *   - dtype names the storage type of X, g, W*, Y alike.  PRISM_BF16 multiplies
+ *     on the bf16 matrix cores and accumulates in fp32; PRISM_F32 uses fp32 FMAs.
+ *   - Pointers must be 16-byte aligned.
+ *   - Work is enqueued on `stream` and the call returns without waiting for it.
+ *   - Errors are reported by return code only; nothing is printed or thrown.
+ *     M == 0 or N == 0 returns PRISM_OK without a launch.
+ */
+#ifndef PRISM_H
+#define PRISM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Same opaque type as <hip/hip_runtime_api.h>; repeated so C callers need no HIP headers. */
+typedef struct ihipStream_t* hipStream_t;
+
+typedef enum {
+    PRISM_OK = 0,
+    PRISM_ERR_INVALID_ARG = 1, /* null or misaligned pointer, negative size, K == 0, eps < 0 or not finite */
+    PRISM_ERR_UNSUPPORTED = 2, /* unknown dtype/op/path, or a forced path that cannot run this shape */
+    PRISM_ERR_WORKSPACE = 3,   /* the chosen kernel needs a workspace and none (or too small a one) is set */
+    PRISM_ERR_HIP = 4          /* the HIP runtime reported an error at launch */
+} prism_status_t;
+
+typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1 } prism_dtype_t;
+
+typedef enum { PRISM_OP_RMSNORM_MATMUL = 0, PRISM_OP_RMSNORM_GATED_MLP = 1 } prism_op_t;
+
+/* Kernel families.  AUTO picks by shape; the others are for tests and tuning sweeps. */
+typedef enum {
+    PRISM_PATH_AUTO = 0,
+    PRISM_PATH_SIMPLE = 1,  /* plain FMA kernel: any M, K, N; the only path for PRISM_F32 */
+    PRISM_PATH_DECODE = 2,  /* few rows: W streamed once, split-K over wavefronts and workgroups */
+    PRISM_PATH_PREFILL = 3  /* many rows: LDS-tiled bf16 MFMA GEMM */
+} prism_path_t;
+
+/* What the dispatcher does for one call (filled by prism_plan). */
+typedef struct {
+    int32_t path;            /* prism_path_t actually used */
+    int32_t split_k;         /* K-slices reduced across workgroups (1 = none) */
+    int32_t tile_m, tile_n;  /* output tile of one workgroup */
+    int32_t grid_x, grid_y;  /* launch grid */
+    int32_t block;           /* threads per workgroup */
+    int32_t reserved;
+    uint64_t workspace_bytes; /* workspace the call needs (0 = none) */
+} prism_plan_t;
+
+/*
+ * Y[M,N] = rms_norm(X[M,K]; g[K], eps) . W[K,N]         (paper Section 7.1, workload "RMSNorm";
+ * gain g and eps are this library's additions, see the conventions above).
+ * Returns PRISM_OK once the work is enqueued.
+ */
+prism_status_t prism_rmsnorm_matmul(const void* X, const void* g, const void* W, void* Y,
+                                    int64_t M, int64_t K, int64_t N, float eps,
+                                    prism_dtype_t dtype, hipStream_t stream);
+
+/*
+ * Y[M,N] = silu(Nrm . W1) * (Nrm . W2),  Nrm = rms_norm(X; g, eps),  silu(a) = a / (1 + exp(-a)).
+ * W1 is the gate branch (paper Section 7.1, workloads "RMSNorm-MLP" and "SwiGLU").
+ * W1 and W2 are both [K,N].  The 1/rms scale is applied to both products before the activation.
+ */
+prism_status_t prism_rmsnorm_gated_mlp(const void* X, const void* g, const void* W1, const void* W2,
+                                       void* Y, int64_t M, int64_t K, int64_t N, float eps,
+                                       prism_dtype_t dtype, hipStream_t stream);
+
+/* The same two operations with the storage type in the name instead of an argument. */
+prism_status_t prism_rmsnorm_matmul_bf16(const void* X, const void* g, const void* W, void* Y,
+                                         int64_t M, int64_t K, int64_t N, float eps, hipStream_t stream);
+prism_status_t prism_rmsnorm_matmul_f32(const void* X, const void* g, const void* W, void* Y,
+                                        int64_t M, int64_t K, int64_t N, float eps, hipStream_t stream);
+prism_status_t prism_rmsnorm_gated_mlp_bf16(const void* X, const void* g, const void* W1, const void* W2,
+                                            void* Y, int64_t M, int64_t K, int64_t N, float eps,
+                                            hipStream_t stream);
+prism_status_t prism_rmsnorm_gated_mlp_f32(const void* X, const void* g, const void* W1, const void* W2,
+                                           void* Y, int64_t M, int64_t K, int64_t N, float eps,
+                                           hipStream_t stream);
+
+/*
+ * Split-K workspace (paper Table 1, "parallelized matmul (reduction)": the K-slices of one
+ * output tile are summed before the 1/rms scale and the activation).
+ *
+ * prism_workspace_bytes: bytes the given call needs under the current override (0 if none).
+ * prism_set_workspace: registers caller-owned DEVICE memory (256-byte aligned) for the current
+ *   HIP device.  The first PRISM_WORKSPACE_HEADER_BYTES hold per-tile arrival counters that
+ *   must be zero between calls: this function zeroes them with a blocking hipMemset (the one
+ *   place the library waits on the device) and every kernel leaves them zero again.  The
+ *   memory must outlive all enqueued work.  Calls that use the workspace must not overlap in
+ *   time on one device (use one stream, or order the streams).  Passing NULL/0 unregisters.
+ */
+#define PRISM_WORKSPACE_HEADER_BYTES 262144u
+uint64_t prism_workspace_bytes(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype);
+prism_status_t prism_set_workspace(void* dev_ptr, uint64_t bytes);
+
+/*
+ * Host-side query: fills *plan with the kernel family, split factor, tile and grid the
+ * dispatcher would use for this shape under the current override.  Touches no device.
+ */
+prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype,
+                          prism_plan_t* plan);
+
+/*
+ * Process-wide override for tests and tuning: force a kernel family and/or a split-K factor and
+ * a tile variant (0 = automatic for each).  A forced path that cannot run a shape makes the call
+ * return PRISM_ERR_UNSUPPORTED.  The kernels are correct for every admissible value (the paper's
+ * notion of a mapping that is correct for all parameter values, Section 2).
+ */
+prism_status_t prism_set_override(int32_t path, int32_t split_k, int32_t variant);
+
+const char* prism_status_string(prism_status_t status);
+int32_t prism_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PRISM_H */

@@ -1,0 +1,29 @@
+"""Thin Python binding of libprism (fused RMSNorm -> MatMul family for MI355X).
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels behind the C ABI declared in ``include/prism.h``.  There is no CPU or
+PyTorch fallback; if the shared library is missing the import fails.
+"""
+from .binding import (  # noqa: F401
+    PRISM_BF16,
+    PRISM_F32,
+    PRISM_OP_RMSNORM_GATED_MLP,
+    PRISM_OP_RMSNORM_MATMUL,
+    PRISM_PATH_AUTO,
+    PRISM_PATH_DECODE,
+    PRISM_PATH_PREFILL,
+    PRISM_PATH_SIMPLE,
+    PrismError,
+    Plan,
+    ensure_workspace,
+    lib,
+    library_path,
+    prism_plan,
+    prism_rmsnorm_gated_mlp,
+    prism_rmsnorm_matmul,
+    prism_set_override,
+    prism_set_workspace,
+    prism_status_string,
+    prism_version,
+    prism_workspace_bytes,
+)

@@ -1,0 +1,180 @@
+"""ctypes marshalling for the C ABI in include/prism.h."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libprism.so")
+
+PRISM_F32, PRISM_BF16 = 0, 1
+PRISM_OP_RMSNORM_MATMUL, PRISM_OP_RMSNORM_GATED_MLP = 0, 1
+PRISM_PATH_AUTO, PRISM_PATH_SIMPLE, PRISM_PATH_DECODE, PRISM_PATH_PREFILL = 0, 1, 2, 3
+WORKSPACE_HEADER_BYTES = 262144
+
+
+class PrismError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = int(status)
+        super().__init__(f"{what}: {prism_status_string(status)} (status {int(status)})")
+
+
+class Plan(ctypes.Structure):
+    _fields_ = [
+        ("path", ctypes.c_int32), ("split_k", ctypes.c_int32),
+        ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
+        ("grid_x", ctypes.c_int32), ("grid_y", ctypes.c_int32),
+        ("block", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("workspace_bytes", ctypes.c_uint64),
+    ]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "reserved"}
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def _load():
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2604_15272_amd.build` "
+            "(there is no fallback implementation)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i64, f32, i32, u64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_uint64
+    L.prism_rmsnorm_matmul.argtypes = [vp, vp, vp, vp, i64, i64, i64, f32, i32, vp]
+    L.prism_rmsnorm_gated_mlp.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, i32, vp]
+    for sfx in ("bf16", "f32"):
+        getattr(L, f"prism_rmsnorm_matmul_{sfx}").argtypes = [vp, vp, vp, vp, i64, i64, i64, f32, vp]
+        getattr(L, f"prism_rmsnorm_gated_mlp_{sfx}").argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, vp]
+        getattr(L, f"prism_rmsnorm_matmul_{sfx}").restype = i32
+        getattr(L, f"prism_rmsnorm_gated_mlp_{sfx}").restype = i32
+    L.prism_rmsnorm_matmul.restype = i32
+    L.prism_rmsnorm_gated_mlp.restype = i32
+    L.prism_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
+    L.prism_workspace_bytes.restype = u64
+    L.prism_set_workspace.argtypes = [vp, u64]
+    L.prism_set_workspace.restype = i32
+    L.prism_plan.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
+    L.prism_plan.restype = i32
+    L.prism_set_override.argtypes = [i32, i32, i32]
+    L.prism_set_override.restype = i32
+    L.prism_status_string.argtypes = [i32]
+    L.prism_status_string.restype = ctypes.c_char_p
+    L.prism_version.argtypes = []
+    L.prism_version.restype = i32
+    return L
+
+
+lib = _load()
+
+
+def prism_status_string(status):
+    return lib.prism_status_string(int(status)).decode()
+
+
+def prism_version():
+    return int(lib.prism_version())
+
+
+def _ptr(t):
+    """Device address of a torch tensor (or a plain integer address)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    return t.data_ptr()
+
+
+def _stream_handle(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _dtype_of(t, dtype):
+    if dtype is not None:
+        return int(dtype)
+    import torch
+    if t.dtype == torch.float32:
+        return PRISM_F32
+    if t.dtype == torch.bfloat16:
+        return PRISM_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def prism_workspace_bytes(op, M, K, N, dtype):
+    return int(lib.prism_workspace_bytes(int(op), int(M), int(K), int(N), int(dtype)))
+
+
+def prism_set_workspace(dev_ptr, nbytes):
+    st = lib.prism_set_workspace(dev_ptr, int(nbytes))
+    if st != 0:
+        raise PrismError(st, "prism_set_workspace")
+
+
+def prism_plan(op, M, K, N, dtype):
+    p = Plan()
+    st = lib.prism_plan(int(op), int(M), int(K), int(N), int(dtype), ctypes.byref(p))
+    if st != 0:
+        raise PrismError(st, "prism_plan")
+    return p.as_dict()
+
+
+def prism_set_override(path=0, split_k=0, variant=0):
+    st = lib.prism_set_override(int(path), int(split_k), int(variant))
+    if st != 0:
+        raise PrismError(st, "prism_set_override")
+
+
+# Device memory for the split-K workspace comes from torch (one tensor per device, grown on demand).
+_workspaces = {}
+
+
+def ensure_workspace(nbytes, device=None):
+    """Make sure the current device has a registered workspace of at least nbytes."""
+    import torch
+    dev = torch.cuda.current_device() if device is None else torch.device(device).index
+    cur = _workspaces.get(dev)
+    if nbytes <= 0 or (cur is not None and cur.numel() >= nbytes):
+        return
+    torch.cuda.synchronize(dev)
+    size = max(int(nbytes), 2 * WORKSPACE_HEADER_BYTES)
+    buf = torch.empty(size, dtype=torch.uint8, device=f"cuda:{dev}")
+    with torch.cuda.device(dev):
+        prism_set_workspace(buf.data_ptr(), size)
+    _workspaces[dev] = buf
+
+
+def prism_rmsnorm_matmul(X, g, W, Y, M=None, K=None, N=None, eps=1e-6, dtype=None, stream=None):
+    """Y[M,N] = rms_norm(X; g, eps) @ W on the GPU.  Tensors are torch CUDA tensors or addresses."""
+    if M is None:
+        M, K = X.shape
+        N = W.shape[1]
+    dt = _dtype_of(X, dtype)
+    if not isinstance(X, int):
+        ensure_workspace(prism_workspace_bytes(PRISM_OP_RMSNORM_MATMUL, M, K, N, dt))
+    st = lib.prism_rmsnorm_matmul(_ptr(X), _ptr(g), _ptr(W), _ptr(Y), int(M), int(K), int(N), float(eps), dt,
+                                  _stream_handle(stream))
+    if st != 0:
+        raise PrismError(st, "prism_rmsnorm_matmul")
+    return Y
+
+
+def prism_rmsnorm_gated_mlp(X, g, W1, W2, Y, M=None, K=None, N=None, eps=1e-6, dtype=None, stream=None):
+    """Y[M,N] = silu(Nrm @ W1) * (Nrm @ W2), Nrm = rms_norm(X; g, eps), on the GPU."""
+    if M is None:
+        M, K = X.shape
+        N = W1.shape[1]
+    dt = _dtype_of(X, dtype)
+    if not isinstance(X, int):
+        ensure_workspace(prism_workspace_bytes(PRISM_OP_RMSNORM_GATED_MLP, M, K, N, dt))
+    st = lib.prism_rmsnorm_gated_mlp(_ptr(X), _ptr(g), _ptr(W1), _ptr(W2), _ptr(Y), int(M), int(K), int(N),
+                                     float(eps), dt, _stream_handle(stream))
+    if st != 0:
+        raise PrismError(st, "prism_rmsnorm_gated_mlp")
+    return Y

@@ -1,0 +1,305 @@
+// Decode path: at most 16 rows of X against a large W, bound by streaming W from HBM once.
+//
+// Work decomposition (paper Table 1: "parallelized matmul (column partition)" across the grid's x,
+// "parallelized matmul (reduction)" and the compound parallelized sums across the grid's y, the
+// wavefronts of a workgroup and the four lane groups of a wavefront):
+//   - a workgroup owns 128 columns of W (and of W2 when gated) and one K-slice;
+//   - its wavefronts take the slice's 32-deep K-blocks round-robin;
+//   - per K-block a wavefront reads a 32 x 128 piece of W with eight 16-byte loads per lane
+//     (lane (q, c), q = lane / 16, c = lane % 16, reads rows 8q..8q+7, columns 8c..8c+7), turns
+//     its 8 x 8 sub-block into eight MFMA B operands with byte permutes, and issues eight
+//     16x16x32 bf16 MFMAs against the A operand (X * g, rounded to bf16, rows padded to 16);
+//   - the raw squares of X are summed per lane in the same loop.
+// Afterwards the partial products and partial sums of squares are reduced across wavefronts in
+// LDS, and, when the grid splits K, across workgroups through the workspace: every workgroup
+// stores its partial, takes a ticket, and the last arrival of a tile sums the partials in slice
+// order (so the result does not depend on arrival order), applies 1/rms (and the SiLU gate) and
+// stores Y.  The normalised X never exists in memory.
+#include "device_utils.h"
+#include "prism_internal.h"
+
+namespace prism {
+
+namespace {
+
+constexpr int TN = kDecodeTileN;   // 128
+constexpr int KB = kDecodeKBlock;  // 32
+
+struct WRows {
+    u32x4 r[8];
+};
+
+__device__ __forceinline__ void load_w_block(WRows& w, __amdgpu_buffer_rsrc_t rs, u32 voff, u32 row_bytes) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w.r[i] = load16(rs, voff + (u32)i * row_bytes);
+}
+
+// B operand j (j = 0..7) of a lane: column 8c + j of its 8 x 8 sub-block, eight K values.
+template <int J>
+__device__ __forceinline__ bf16x8 b_operand(const WRows& w) {
+    constexpr int d = J >> 1;
+    constexpr u32 sel = (J & 1) ? 0x07060302u : 0x05040100u;
+    u32x4 b;
+    b[0] = __builtin_amdgcn_perm(w.r[1][d], w.r[0][d], sel);
+    b[1] = __builtin_amdgcn_perm(w.r[3][d], w.r[2][d], sel);
+    b[2] = __builtin_amdgcn_perm(w.r[5][d], w.r[4][d], sel);
+    b[3] = __builtin_amdgcn_perm(w.r[7][d], w.r[6][d], sel);
+    return __builtin_bit_cast(bf16x8, b);
+}
+
+__device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], bf16x8 a, const WRows& w) {
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<0>(w), acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<1>(w), acc[1], 0, 0, 0);
+    acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<2>(w), acc[2], 0, 0, 0);
+    acc[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<3>(w), acc[3], 0, 0, 0);
+    acc[4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<4>(w), acc[4], 0, 0, 0);
+    acc[5] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<5>(w), acc[5], 0, 0, 0);
+    acc[6] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<6>(w), acc[6], 0, 0, 0);
+    acc[7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<7>(w), acc[7], 0, 0, 0);
+}
+
+// A operand of a lane: X[m = c][8 K values] * g, rounded to bf16; adds the raw squares to ss.
+__device__ __forceinline__ bf16x8 a_operand(u32x4 x, u32x4 gg, float& ss) {
+    u32x4 a;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const float x0 = bf16_lo(x[d]), x1 = bf16_hi(x[d]);
+        ss = fmaf(x0, x0, ss);
+        ss = fmaf(x1, x1, ss);
+        a[d] = pack_bf16(x0 * bf16_lo(gg[d]), x1 * bf16_hi(gg[d]));
+    }
+    return __builtin_bit_cast(bf16x8, a);
+}
+
+}  // namespace
+
+// LDS: per wavefront a 16 x 128 fp32 tile, plus 16 sums of squares.
+template <int NW, bool GATED>
+__global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restrict__ X,
+                                                         const uint16_t* __restrict__ g,
+                                                         const uint16_t* __restrict__ W1,
+                                                         const uint16_t* __restrict__ W2,
+                                                         uint16_t* __restrict__ Y, float* __restrict__ acc_part,
+                                                         float* __restrict__ ss_part, unsigned* __restrict__ tickets,
+                                                         int M, int K, int N, float eps, int S) {
+    constexpr int G = GATED ? 2 : 1;
+    constexpr int NT = NW * 64;
+    constexpr int CPT = 16 * TN / NT;  // columns per thread in the epilogue (4 for 8 wavefronts)
+    constexpr int TPR = TN / CPT;      // threads per output row
+    static_assert(CPT >= 1 && CPT <= 8 && (CPT & (CPT - 1)) == 0, "epilogue mapping");
+
+    extern __shared__ float lds[];
+    float* red = lds;                    // [NW][16][TN], used once per weight matrix
+    float* ss_red = lds + NW * 16 * TN;  // [NW][16]
+    __shared__ int is_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = lane >> 4, c = lane & 15;
+    const int ntile = blockIdx.x, split = blockIdx.y;
+    const int n0 = ntile * TN;
+
+    // This workgroup's K-blocks: [b_beg, b_beg + b_cnt).
+    const int kblocks = (K + KB - 1) / KB;
+    const int per = kblocks / S, rem = kblocks % S;
+    const int b_beg = split * per + min(split, rem);
+    const int b_cnt = per + (split < rem ? 1 : 0);
+
+    // Buffer descriptors.  W starts at this workgroup's first row and first column; its end is the
+    // end of the matrix, so rows past K read as zero.
+    const u32 row_bytes = (u32)N * 2u;
+    const size_t w_first = (size_t)b_beg * KB * N + n0;
+    const size_t w_total = (size_t)K * N;
+    const size_t w_left = (w_first < w_total ? w_total - w_first : 0) * 2;
+    const u32 w_bytes = (u32)(w_left < 0x7FFFFFFFull ? w_left : 0x7FFFFFFFull);
+    const __amdgpu_buffer_rsrc_t rw1 = make_rsrc(W1 + w_first, w_bytes);
+    const __amdgpu_buffer_rsrc_t rw2 = make_rsrc((GATED ? W2 : W1) + w_first, w_bytes);
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(X, (u32)((size_t)M * K * 2));
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc(g, (u32)K * 2u);
+
+    const bool col_ok = (n0 + 8 * c) < N;
+    const u32 w_lane = col_ok ? ((u32)(8 * q) * row_bytes + (u32)(16 * c)) : kOutOfRange;
+    const bool row_ok = c < M;
+
+    f32x4 acc1[8], acc2[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        acc1[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc2[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    float ss = 0.f;
+
+    // U K-blocks per trip, so that sixteen 16-byte row loads of W are in flight per lane.
+    constexpr int U = GATED ? 1 : 2;
+    for (int i = wave; i < b_cnt; i += U * NW) {
+        WRows w1[U], w2[U];
+        u32x4 xr[U], gr[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int ib = i + u * NW;
+            const bool has = ib < b_cnt;
+            const u32 woff = has ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange;
+            const int k = (b_beg + ib) * KB + 8 * q;
+            const bool k_ok = has && k < K;
+            load_w_block(w1[u], rw1, woff, row_bytes);
+            if (GATED) load_w_block(w2[u], rw2, woff, row_bytes);
+            xr[u] = load16(rx, (row_ok && k_ok) ? (u32)(((size_t)c * K + k) * 2) : kOutOfRange);
+            gr[u] = load16(rg, k_ok ? (u32)k * 2u : kOutOfRange);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bf16x8 a = a_operand(xr[u], gr[u], ss);
+            mfma_block(acc1, a, w1[u]);
+            if (GATED) mfma_block(acc2, a, w2[u]);
+        }
+    }
+
+    // Sum of squares of row c: the four lane groups hold different K values.
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+
+    // Epilogue mapping: thread -> (row m, CPT consecutive columns).
+    const int m = tid / TPR;
+    const int col = (tid % TPR) * CPT;
+    const int n = n0 + col;
+    const bool out_ok = (m < M) && (n < N);  // N % 8 == 0 and CPT | 8: all CPT columns valid together
+
+    // Reduce across wavefronts through LDS, one weight matrix at a time (the tile of W2 reuses the
+    // space).  Accumulator j, element i of lane (q, c) is row 4q + i, column 8c + j of the tile.
+    float v1[CPT], v2[CPT];
+    float ssum = 0.f;
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        if (gi == 1) __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float* dst = red + (wave * 16 + (4 * q + i)) * TN + 8 * c;
+            if (gi == 0) {
+                *(f32x4*)(dst) = f32x4{acc1[0][i], acc1[1][i], acc1[2][i], acc1[3][i]};
+                *(f32x4*)(dst + 4) = f32x4{acc1[4][i], acc1[5][i], acc1[6][i], acc1[7][i]};
+            } else {
+                *(f32x4*)(dst) = f32x4{acc2[0][i], acc2[1][i], acc2[2][i], acc2[3][i]};
+                *(f32x4*)(dst + 4) = f32x4{acc2[4][i], acc2[5][i], acc2[6][i], acc2[7][i]};
+            }
+        }
+        if (gi == 0 && q == 0) ss_red[wave * 16 + c] = ss;
+        __syncthreads();
+        float v[CPT];
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) v[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float* src = red + (w * 16 + m) * TN + col;
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) v[e] += src[e];
+            if (gi == 0) ssum += ss_red[w * 16 + m];
+        }
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) {
+            if (gi == 0) v1[e] = v[e];
+            else v2[e] = v[e];
+        }
+    }
+    if (!GATED) {
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) v2[e] = 0.f;
+    }
+
+    if (S > 1) {
+        // Publish this slice's partial, then find out whether every other slice has arrived.
+        if (out_ok) {
+            float* p = acc_part + (((size_t)split * G) * M + m) * N + n;
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) {
+                p[e] = v1[e];
+                if (GATED) p[(size_t)M * N + e] = v2[e];
+            }
+        }
+        if (col == 0) ss_part[((size_t)ntile * S + split) * 16 + m] = ssum;
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned prev = atomicAdd(&tickets[ntile], 1u);
+            is_last = (prev == (unsigned)(S - 1));
+        }
+        __syncthreads();
+        if (!is_last) return;
+        __threadfence();
+        if (tid == 0) tickets[ntile] = 0u;  // ready for the next call on this workspace
+
+        ssum = 0.f;
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) { v1[e] = 0.f; v2[e] = 0.f; }
+        for (int s = 0; s < S; ++s) {
+            ssum += ss_part[((size_t)ntile * S + s) * 16 + m];
+            if (out_ok) {
+                const float* p = acc_part + (((size_t)s * G) * M + m) * N + n;
+#pragma unroll
+                for (int e = 0; e < CPT; ++e) {
+                    v1[e] += p[e];
+                    if (GATED) v2[e] += p[(size_t)M * N + e];
+                }
+            }
+        }
+    }
+
+    if (!out_ok) return;
+    const float rinv = __builtin_amdgcn_rsqf(ssum / (float)K + eps);
+    float y[CPT];
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) {
+        y[e] = v1[e] * rinv;
+        if (GATED) y[e] = silu_f32(y[e]) * (v2[e] * rinv);
+    }
+    uint16_t* out = Y + (size_t)m * N + n;
+    if (CPT == 1) {
+        out[0] = (uint16_t)(pack_bf16(y[0], 0.f) & 0xFFFFu);
+    } else {
+        u32 packed[CPT / 2 > 0 ? CPT / 2 : 1];
+#pragma unroll
+        for (int e = 0; e < CPT / 2; ++e) packed[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
+        if (CPT == 2) *(u32*)out = packed[0];
+        if (CPT == 4) *(u32x2*)out = u32x2{packed[0], packed[1]};
+        if (CPT == 8) *(u32x4*)out = u32x4{packed[0], packed[1], packed[2], packed[3]};
+    }
+}
+
+template <int NW>
+static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& ws) {
+    const int n_tiles = (c.N + TN - 1) / TN;
+    dim3 grid(n_tiles, S), block(NW * 64);
+    const size_t lds = (size_t)(NW * 16 * TN + NW * 16) * sizeof(float);
+    auto* X = (const uint16_t*)c.X;
+    auto* g = (const uint16_t*)c.g;
+    auto* W1 = (const uint16_t*)c.W1;
+    auto* W2 = (const uint16_t*)c.W2;
+    auto* Y = (uint16_t*)c.Y;
+    if (c.gated) {
+        auto kern = decode_kernel<NW, true>;
+        if (lds > 65536) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W2, Y, ws.acc_part, ws.ss_part, ws.tickets,
+                           c.M, c.K, c.N, c.eps, S);
+    } else {
+        auto kern = decode_kernel<NW, false>;
+        if (lds > 65536) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W1, Y, ws.acc_part, ws.ss_part, ws.tickets,
+                           c.M, c.K, c.N, c.eps, S);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_bf16(const Call& c, int split_k, int waves, const DecodeWorkspace& ws) {
+    switch (waves) {
+        case 4: return launch_decode_nw<4>(c, split_k, ws);
+        case 8: return launch_decode_nw<8>(c, split_k, ws);
+        case 16: return launch_decode_nw<16>(c, split_k, ws);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace prism

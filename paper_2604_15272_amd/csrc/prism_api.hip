@@ -1,0 +1,295 @@
+// C ABI of the library: argument checks, shape -> kernel dispatch, workspace bookkeeping.
+#include <atomic>
+#include <cmath>
+#include <cstring>
+
+#include "prism_internal.h"
+
+namespace prism {
+namespace {
+
+constexpr int kMaxDevices = 64;
+constexpr uint64_t kTwoGiB = 0x7FFFFFFFull;
+
+struct Override {
+    std::atomic<int32_t> path{0}, split_k{0}, variant{0};
+};
+Override g_override;
+
+struct Workspace {
+    void* ptr;
+    uint64_t bytes;
+};
+Workspace g_workspace[kMaxDevices];  // indexed by HIP device ordinal
+
+uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+struct Plan {
+    prism_plan_t pub;
+    int waves;          // decode: wavefronts per workgroup
+    uint64_t ss_bytes;  // decode: bytes of the partial sums of squares (rounded)
+};
+
+bool bf16_vector_ok(int64_t K, int64_t N) { return K % 8 == 0 && N % 8 == 0; }
+
+// Prefill tile choice: fewest "rounds" of 256 workgroups, weighted by how well a tile shape feeds
+// the matrix cores (bigger tiles re-read less from LDS per MFMA).
+struct Tile {
+    int bm, bn;
+    double eff;
+};
+
+void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm, int* bn) {
+    static const Tile plain[] = {{256, 256, 1.0}, {256, 192, 0.95}, {128, 128, 0.75}, {64, 64, 0.35}};
+    static const Tile gate[] = {{256, 256, 1.0}, {128, 256, 0.85}, {128, 128, 0.6}};
+    const Tile* t = gated ? gate : plain;
+    const int nt = gated ? 3 : 4;
+    if (variant > 0) {
+        *bm = variant / 1000;
+        *bn = variant % 1000;
+        return;
+    }
+    double best = 1e300;
+    for (int i = 0; i < nt; ++i) {
+        const int cw = gated ? t[i].bn / 2 : t[i].bn;
+        const double tiles = (double)((M + t[i].bm - 1) / t[i].bm) * (double)((N + cw - 1) / cw);
+        const double rounds = std::ceil(tiles / 256.0);
+        const double cost = rounds * t[i].bm * t[i].bn / t[i].eff;
+        if (cost < best) {
+            best = cost;
+            *bm = t[i].bm;
+            *bn = t[i].bn;
+        }
+    }
+}
+
+bool prefill_tile_known(bool gated, int bm, int bn) {
+    if (gated) return (bm == 256 && bn == 256) || (bm == 128 && bn == 256) || (bm == 128 && bn == 128);
+    return (bm == 256 && bn == 256) || (bm == 256 && bn == 192) || (bm == 128 && bn == 128) || (bm == 64 && bn == 64);
+}
+
+prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Plan* out) {
+    if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP) return PRISM_ERR_UNSUPPORTED;
+    if (dtype != PRISM_F32 && dtype != PRISM_BF16) return PRISM_ERR_UNSUPPORTED;
+    if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
+    if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return PRISM_ERR_UNSUPPORTED;
+    const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
+    const int forced = g_override.path.load();
+    const int forced_split = g_override.split_k.load();
+    const int variant = g_override.variant.load();
+    std::memset(out, 0, sizeof(*out));
+    prism_plan_t& p = out->pub;
+    p.split_k = 1;
+
+    int path = forced;
+    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL) return PRISM_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return PRISM_OK;  // empty problem: nothing is launched
+    const bool fast_ok = dtype == PRISM_BF16 && bf16_vector_ok(K, N);
+    if (path == PRISM_PATH_AUTO) {
+        if (!fast_ok) path = PRISM_PATH_SIMPLE;
+        else path = (M <= kDecodeMaxRows) ? PRISM_PATH_DECODE : PRISM_PATH_PREFILL;
+        // Shapes whose byte offsets do not fit the 32-bit buffer addressing fall back.
+        if (path == PRISM_PATH_PREFILL && (uint64_t)K * N * 2 >= kTwoGiB) path = PRISM_PATH_SIMPLE;
+        if (path == PRISM_PATH_DECODE && (uint64_t)M * K * 2 >= kTwoGiB) path = PRISM_PATH_SIMPLE;
+    }
+    p.path = path;
+
+    if (path == PRISM_PATH_SIMPLE) {
+        p.tile_m = 8;
+        p.tile_n = 256;
+        p.grid_x = (int32_t)((N + 255) / 256);
+        p.grid_y = (int32_t)((M + 7) / 8);
+        p.block = 256;
+        if (p.grid_y > 65535) return PRISM_ERR_UNSUPPORTED;
+        return PRISM_OK;
+    }
+    if (!fast_ok) return PRISM_ERR_UNSUPPORTED;
+
+    if (path == PRISM_PATH_DECODE) {
+        if (M > kDecodeMaxRows || (uint64_t)M * K * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
+        int waves = (variant > 0) ? variant : (gated ? 4 : 8);
+        if (waves != 4 && waves != 8 && waves != 16) return PRISM_ERR_UNSUPPORTED;
+        const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
+        const int64_t kblocks = (K + kDecodeKBlock - 1) / kDecodeKBlock;
+        if (n_tiles > kMaxTickets) return PRISM_ERR_UNSUPPORTED;
+        int64_t S = forced_split;
+        if (S <= 0) {
+            // Enough workgroups to keep every CU streaming, each wavefront with at least two K-blocks.
+            const int64_t target = 512;
+            S = (target + n_tiles / 2) / n_tiles;
+            const int64_t s_max = kblocks / (2 * waves);
+            if (S > s_max) S = s_max;
+            if (S < 1) S = 1;
+        }
+        if (S > kblocks) S = kblocks;
+        if (S > 65535) return PRISM_ERR_UNSUPPORTED;
+        // Byte offsets inside one K-slice must fit in 31 bits.
+        const uint64_t slice_rows = (uint64_t)((kblocks + S - 1) / S) * kDecodeKBlock + 8;
+        if (slice_rows * (uint64_t)N * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
+        out->waves = waves;
+        p.split_k = (int32_t)S;
+        p.tile_m = kDecodeMaxRows;
+        p.tile_n = kDecodeTileN;
+        p.grid_x = (int32_t)n_tiles;
+        p.grid_y = (int32_t)S;
+        p.block = waves * 64;
+        if (S > 1) {
+            out->ss_bytes = round_up((uint64_t)n_tiles * S * 16 * 4, 256);
+            p.workspace_bytes = PRISM_WORKSPACE_HEADER_BYTES + out->ss_bytes +
+                                (uint64_t)S * (gated ? 2 : 1) * M * N * 4;
+        }
+        return PRISM_OK;
+    }
+
+    // PRISM_PATH_PREFILL
+    if ((uint64_t)K * N * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
+    int bm = 0, bn = 0;
+    choose_prefill_tile(gated, M, N, variant, &bm, &bn);
+    if (!prefill_tile_known(gated, bm, bn)) return PRISM_ERR_UNSUPPORTED;
+    const int cw = gated ? bn / 2 : bn;
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + cw - 1) / cw);
+    if (tiles > 0x7FFFFFFF) return PRISM_ERR_UNSUPPORTED;
+    p.tile_m = bm;
+    p.tile_n = bn;
+    p.grid_x = (int32_t)tiles;
+    p.grid_y = 1;
+    p.block = 256;
+    return PRISM_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, const void* W2, void* Y, int64_t M,
+                   int64_t K, int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream) {
+    const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
+    if (dtype != PRISM_F32 && dtype != PRISM_BF16) return PRISM_ERR_UNSUPPORTED;
+    if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
+    if (!(eps >= 0.0f) || !std::isfinite(eps)) return PRISM_ERR_INVALID_ARG;
+    if (!X || !g || !W1 || !Y || (gated && !W2)) return PRISM_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(g) || !aligned16(W1) || !aligned16(Y) || (gated && !aligned16(W2)))
+        return PRISM_ERR_INVALID_ARG;
+    Plan plan;
+    const prism_status_t st = make_plan(op, M, K, N, dtype, &plan);
+    if (st != PRISM_OK) return st;
+    if (M == 0 || N == 0) return PRISM_OK;
+
+    Call c{X, g, W1, gated ? W2 : nullptr, Y, (int)M, (int)K, (int)N, eps, gated, stream};
+    hipError_t err = hipSuccess;
+    switch (plan.pub.path) {
+        case PRISM_PATH_SIMPLE:
+            err = (dtype == PRISM_F32) ? launch_simple_f32(c) : launch_simple_bf16(c);
+            break;
+        case PRISM_PATH_DECODE: {
+            DecodeWorkspace ws{nullptr, nullptr, nullptr};
+            if (plan.pub.split_k > 1) {
+                int dev = 0;
+                if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+                if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
+                const Workspace w = g_workspace[dev];
+                if (!w.ptr || w.bytes < plan.pub.workspace_bytes) return PRISM_ERR_WORKSPACE;
+                char* base = (char*)w.ptr;
+                ws.tickets = (unsigned*)base;
+                ws.ss_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES);
+                ws.acc_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES + plan.ss_bytes);
+            }
+            err = launch_decode_bf16(c, plan.pub.split_k, plan.waves, ws);
+            break;
+        }
+        case PRISM_PATH_PREFILL:
+            err = launch_prefill_bf16(c, plan.pub.tile_m, plan.pub.tile_n);
+            break;
+        default:
+            return PRISM_ERR_UNSUPPORTED;
+    }
+    return err == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
+}
+
+}  // namespace
+}  // namespace prism
+
+using namespace prism;
+
+extern "C" {
+
+prism_status_t prism_rmsnorm_matmul(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K,
+                                    int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_MATMUL, X, g, W, nullptr, Y, M, K, N, eps, dtype, stream);
+}
+
+prism_status_t prism_rmsnorm_gated_mlp(const void* X, const void* g, const void* W1, const void* W2, void* Y,
+                                       int64_t M, int64_t K, int64_t N, float eps, prism_dtype_t dtype,
+                                       hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_GATED_MLP, X, g, W1, W2, Y, M, K, N, eps, dtype, stream);
+}
+
+prism_status_t prism_rmsnorm_matmul_bf16(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K,
+                                         int64_t N, float eps, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_MATMUL, X, g, W, nullptr, Y, M, K, N, eps, PRISM_BF16, stream);
+}
+
+prism_status_t prism_rmsnorm_matmul_f32(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K,
+                                        int64_t N, float eps, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_MATMUL, X, g, W, nullptr, Y, M, K, N, eps, PRISM_F32, stream);
+}
+
+prism_status_t prism_rmsnorm_gated_mlp_bf16(const void* X, const void* g, const void* W1, const void* W2, void* Y,
+                                            int64_t M, int64_t K, int64_t N, float eps, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_GATED_MLP, X, g, W1, W2, Y, M, K, N, eps, PRISM_BF16, stream);
+}
+
+prism_status_t prism_rmsnorm_gated_mlp_f32(const void* X, const void* g, const void* W1, const void* W2, void* Y,
+                                           int64_t M, int64_t K, int64_t N, float eps, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_GATED_MLP, X, g, W1, W2, Y, M, K, N, eps, PRISM_F32, stream);
+}
+
+uint64_t prism_workspace_bytes(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype) {
+    Plan plan;
+    if (make_plan(op, M, K, N, dtype, &plan) != PRISM_OK) return 0;
+    return plan.pub.workspace_bytes;
+}
+
+prism_status_t prism_set_workspace(void* dev_ptr, uint64_t bytes) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_UNSUPPORTED;
+    if (!dev_ptr || bytes == 0) {
+        g_workspace[dev] = Workspace{nullptr, 0};
+        return PRISM_OK;
+    }
+    if (((uintptr_t)dev_ptr & 255u) != 0 || bytes < PRISM_WORKSPACE_HEADER_BYTES) return PRISM_ERR_INVALID_ARG;
+    if (hipMemset(dev_ptr, 0, PRISM_WORKSPACE_HEADER_BYTES) != hipSuccess) return PRISM_ERR_HIP;
+    if (hipDeviceSynchronize() != hipSuccess) return PRISM_ERR_HIP;
+    g_workspace[dev] = Workspace{dev_ptr, bytes};
+    return PRISM_OK;
+}
+
+prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, prism_plan_t* plan) {
+    if (!plan) return PRISM_ERR_INVALID_ARG;
+    Plan p;
+    const prism_status_t st = make_plan(op, M, K, N, dtype, &p);
+    if (st == PRISM_OK) *plan = p.pub;
+    return st;
+}
+
+prism_status_t prism_set_override(int32_t path, int32_t split_k, int32_t variant) {
+    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL || split_k < 0 || variant < 0) return PRISM_ERR_INVALID_ARG;
+    g_override.path.store(path);
+    g_override.split_k.store(split_k);
+    g_override.variant.store(variant);
+    return PRISM_OK;
+}
+
+const char* prism_status_string(prism_status_t status) {
+    switch (status) {
+        case PRISM_OK: return "ok";
+        case PRISM_ERR_INVALID_ARG: return "invalid argument";
+        case PRISM_ERR_UNSUPPORTED: return "unsupported dtype, path or shape";
+        case PRISM_ERR_WORKSPACE: return "workspace missing or too small";
+        case PRISM_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int32_t prism_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,40 @@
+// Internal declarations shared by the C-ABI file and the kernel files (host side only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "prism.h"
+
+namespace prism {
+
+struct Call {
+    const void* X;
+    const void* g;
+    const void* W1;
+    const void* W2;  // null unless gated
+    void* Y;
+    int M, K, N;
+    float eps;
+    bool gated;
+    hipStream_t stream;
+};
+
+// Geometry of the decode (few-row) path.
+constexpr int kDecodeMaxRows = 16;     // one 16-row MFMA block
+constexpr int kDecodeTileN = 128;      // columns of W per workgroup
+constexpr int kDecodeKBlock = 32;      // K depth of one MFMA
+constexpr int kDecodeWaves = 8;        // wavefronts per workgroup (default variant)
+constexpr int kMaxTickets = PRISM_WORKSPACE_HEADER_BYTES / 4;
+
+struct DecodeWorkspace {
+    unsigned* tickets;  // [n_tiles] arrival counters, zero between calls
+    float* ss_part;     // [n_tiles][S][16] partial sums of squares
+    float* acc_part;    // [S][G][M][N] partial products (G = 2 if gated)
+};
+
+hipError_t launch_simple_f32(const Call& c);
+hipError_t launch_simple_bf16(const Call& c);
+hipError_t launch_decode_bf16(const Call& c, int split_k, int waves, const DecodeWorkspace& ws);
+hipError_t launch_prefill_bf16(const Call& c, int tile_m, int tile_n);
+
+}  // namespace prism

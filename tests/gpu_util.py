@@ -1,0 +1,72 @@
+"""Helpers shared by the GPU tests: move stored inputs to the device, run the library, read back."""
+import numpy as np
+
+import prism_inputs as pi
+
+
+def to_device(stored, dtype):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(stored)).cuda()
+    return t.view(torch.bfloat16) if dtype == pi.BF16 else t
+
+
+def from_device(t, dtype):
+    import torch
+    if dtype == pi.BF16:
+        return pi.to_f64(t.view(torch.uint16).cpu().numpy(), pi.BF16)
+    return t.cpu().numpy().astype(np.float64)
+
+
+def run_gpu(stored, dtype, gated, eps, poison=True):
+    """One library call on the current device; returns Y as float64 (exact widening of what was stored)."""
+    import torch
+    import paper_2604_15272_amd as P
+    X = to_device(stored["X"], dtype)
+    g = to_device(stored["g"], dtype)
+    M = X.shape[0]
+    tdt = torch.bfloat16 if dtype == pi.BF16 else torch.float32
+    if gated:
+        W1, W2 = to_device(stored["W1"], dtype), to_device(stored["W2"], dtype)
+        N = W1.shape[1]
+        Y = torch.full((M, N), float("nan"), dtype=tdt, device="cuda") if poison else torch.empty(
+            (M, N), dtype=tdt, device="cuda")
+        P.prism_rmsnorm_gated_mlp(X, g, W1, W2, Y, eps=eps)
+    else:
+        W = to_device(stored["W"], dtype)
+        N = W.shape[1]
+        Y = torch.full((M, N), float("nan"), dtype=tdt, device="cuda") if poison else torch.empty(
+            (M, N), dtype=tdt, device="cuda")
+        P.prism_rmsnorm_matmul(X, g, W, Y, eps=eps)
+    torch.cuda.synchronize()
+    return from_device(Y, dtype)
+
+
+def run_oracle(stored, dtype, gated, eps, rows=None):
+    import oracle
+    X = pi.to_f64(stored["X"], dtype)
+    if rows is not None:
+        X = X[rows]
+    g = pi.to_f64(stored["g"], dtype)
+    if gated:
+        return oracle.rmsnorm_gated_mlp(X, g, pi.to_f64(stored["W1"], dtype), pi.to_f64(stored["W2"], dtype), eps)
+    return oracle.rmsnorm_matmul(X, g, pi.to_f64(stored["W"], dtype), eps)
+
+
+TOL = {pi.F32: 1e-5, pi.BF16: 2e-2}
+
+
+def worst_error(y, yhat):
+    """max |y - yhat| / (|yhat| + 1): the parity bar is this <= 1e-5 (fp32) or 2e-2 (bf16)."""
+    y = np.asarray(y, dtype=np.float64)
+    yhat = np.asarray(yhat, dtype=np.float64)
+    assert y.shape == yhat.shape
+    if y.size == 0:
+        return 0.0
+    err = np.abs(y - yhat) / (np.abs(yhat) + 1.0)
+    return float(np.nanmax(np.where(np.isnan(err), np.inf, err)))
+
+
+def assert_parity(y, yhat, dtype, what=""):
+    w = worst_error(y, yhat)
+    assert w <= TOL[dtype], f"{what}: worst |y-yhat|/(|yhat|+1) = {w:.3e} > {TOL[dtype]:.0e}"
+    return w

@@ -1,0 +1,107 @@
+"""CPU-only checks: the library loads, exports what the header declares, and validates arguments."""
+import ctypes
+import os
+import re
+
+import pytest
+
+
+@pytest.fixture(scope="module")
+def P(repo_root):
+    lib = os.path.join(repo_root, "paper_2604_15272_amd", "libprism.so")
+    if not os.path.exists(lib):
+        from paper_2604_15272_amd.build import build_library  # imports nothing that needs the library
+        build_library()
+    import paper_2604_15272_amd as P
+    yield P
+    P.prism_set_override(0, 0, 0)
+
+
+def test_every_declared_symbol_is_exported(P, repo_root):
+    text = open(os.path.join(repo_root, "include", "prism.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(prism_[a-z0-9_]+)\s*\(", text))
+    assert {"prism_rmsnorm_matmul", "prism_rmsnorm_gated_mlp", "prism_set_workspace", "prism_plan"} <= names
+    L = ctypes.CDLL(P.library_path())
+    for n in sorted(names):
+        assert hasattr(L, n), f"{n} is declared in prism.h but not exported"
+    assert P.prism_version() >= 100
+
+
+def test_status_strings(P):
+    assert P.prism_status_string(0) == "ok"
+    assert len({P.prism_status_string(i) for i in range(5)}) == 5
+
+
+def test_argument_validation_needs_no_device(P):
+    L = P.lib
+    a = 0x1000  # aligned, never dereferenced: every call below fails before any launch
+    ok = lambda **kw: None
+    call = lambda X=a, g=a, W=a, Y=a, M=4, K=64, N=64, eps=1e-6, dt=1: L.prism_rmsnorm_matmul(
+        X, g, W, Y, M, K, N, eps, dt, None)
+    assert call(X=None) == 1 and call(g=None) == 1 and call(W=None) == 1 and call(Y=None) == 1
+    assert call(X=a + 2) == 1                       # misaligned
+    assert call(M=-1) == 1 and call(N=-1) == 1 and call(K=0) == 1 and call(K=-8) == 1
+    assert call(eps=-1.0) == 1 and call(eps=float("nan")) == 1 and call(eps=float("inf")) == 1
+    assert call(dt=7) == 2
+    assert call(M=0) == 0 and call(N=0) == 0        # empty problem: success, no launch
+    gcall = lambda W2=a, **kw: L.prism_rmsnorm_gated_mlp(a, a, a, W2, a, 4, 64, 64, 1e-6, 1, None)
+    assert gcall(W2=None) == 1
+
+
+def test_plan_picks_paths_by_shape(P):
+    f32, bf16 = P.PRISM_F32, P.PRISM_BF16
+    assert P.prism_plan(0, 8, 256, 512, f32)["path"] == P.PRISM_PATH_SIMPLE
+    d = P.prism_plan(0, 16, 4096, 4096, bf16)
+    assert d["path"] == P.PRISM_PATH_DECODE and d["split_k"] >= 1 and d["grid_x"] == 32
+    assert d["workspace_bytes"] == P.prism_workspace_bytes(0, 16, 4096, 4096, bf16)
+    p = P.prism_plan(0, 2048, 4096, 6144, bf16)
+    assert p["path"] == P.PRISM_PATH_PREFILL and p["workspace_bytes"] == 0
+    assert p["grid_x"] == -(-2048 // p["tile_m"]) * -(-6144 // p["tile_n"])
+    pg = P.prism_plan(1, 4096, 4096, 14336, bf16)
+    assert pg["path"] == P.PRISM_PATH_PREFILL
+    assert pg["grid_x"] == -(-4096 // pg["tile_m"]) * -(-14336 // (pg["tile_n"] // 2))
+    # unaligned bf16 shapes go to the plain kernel
+    assert P.prism_plan(0, 16, 4100, 4096, bf16)["path"] == P.PRISM_PATH_SIMPLE
+    assert P.prism_plan(0, 16, 4096, 4100, bf16)["path"] == P.PRISM_PATH_SIMPLE
+
+
+def test_override_and_workspace_size(P):
+    bf16 = P.PRISM_BF16
+    P.prism_set_override(P.PRISM_PATH_DECODE, 4, 8)
+    d = P.prism_plan(1, 8, 4096, 14336, bf16)
+    assert d["split_k"] == 4 and d["block"] == 512 and d["grid_y"] == 4
+    n_tiles = 14336 // 128
+    expect = 262144 + -(-n_tiles * 4 * 16 * 4 // 256) * 256 + 4 * 2 * 8 * 14336 * 4
+    assert d["workspace_bytes"] == expect
+    P.prism_set_override(P.PRISM_PATH_DECODE, 1, 0)
+    assert P.prism_plan(0, 16, 4096, 4096, bf16)["workspace_bytes"] == 0
+    # a forced path that cannot run the shape is refused, not silently replaced
+    P.prism_set_override(P.PRISM_PATH_DECODE, 0, 0)
+    with pytest.raises(P.PrismError):
+        P.prism_plan(0, 64, 4096, 4096, bf16)
+    with pytest.raises(P.PrismError):
+        P.prism_plan(0, 8, 256, 512, P.PRISM_F32)
+    P.prism_set_override(P.PRISM_PATH_PREFILL, 0, 999999)
+    with pytest.raises(P.PrismError):
+        P.prism_plan(0, 64, 4096, 4096, bf16)
+    P.prism_set_override(0, 0, 0)
+    with pytest.raises(P.PrismError):
+        P.prism_set_override(9, 0, 0)
+
+
+def test_inputs_are_deterministic_and_bf16_exact():
+    import numpy as np
+    import prism_inputs as pi
+    a = pi.draw(pi.BF16, 4, 64, 32, True, 5)
+    b = pi.draw(pi.BF16, 4, 64, 32, True, 5)
+    assert all(np.array_equal(a[k], b[k]) for k in a) and set(a) == {"X", "g", "W1", "W2"}
+    assert not np.array_equal(a["W1"], a["W2"])
+    # round-to-nearest-even on exact ties
+    ties = np.array([1.00390625, 1.01171875, -1.00390625], dtype=np.float32)  # 1 + 2^-8, 1 + 3*2^-8
+    assert list(pi.f32_to_bf16_bits(ties)) == [0x3F80, 0x3F82, 0xBF80]
+    x = pi.bf16_bits_to_f32(a["X"])
+    assert np.array_equal(pi.f32_to_bf16_bits(x), a["X"])
+    g = pi.to_f64(a["g"], pi.BF16)
+    assert g.min() >= 0.5 and g.max() <= 1.5
+    assert len(pi.WORKLOADS) == 5 and pi.WORKLOADS[1].N == 4096 and pi.WORKLOADS[3].gated
