@@ -26,7 +26,7 @@
  *   - Pointers must be 16-byte aligned.
  *   - Work is enqueued on `stream` and the call returns without waiting for it.
  *   - Errors are reported by return code only; nothing is printed or thrown.
- *     M == 0 or N == 0 returns PRISM_OK without a launch.
+ *     M == 0 or N == 0 returns PRISM_OK without a launch and without looking at the pointers.
  */
 #ifndef PRISM_H
 #define PRISM_H

@@ -165,13 +165,13 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
     if (dtype != PRISM_F32 && dtype != PRISM_BF16) return PRISM_ERR_UNSUPPORTED;
     if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
     if (!(eps >= 0.0f) || !std::isfinite(eps)) return PRISM_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return PRISM_OK;  // empty problem: pointers are not looked at
     if (!X || !g || !W1 || !Y || (gated && !W2)) return PRISM_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(g) || !aligned16(W1) || !aligned16(Y) || (gated && !aligned16(W2)))
         return PRISM_ERR_INVALID_ARG;
     Plan plan;
     const prism_status_t st = make_plan(op, M, K, N, dtype, &plan);
     if (st != PRISM_OK) return st;
-    if (M == 0 || N == 0) return PRISM_OK;
 
     Call c{X, g, W1, gated ? W2 : nullptr, Y, (int)M, (int)K, (int)N, eps, gated, stream};
     hipError_t err = hipSuccess;
