@@ -86,7 +86,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     constexpr int NT = NW * 64;
     constexpr int CPT = 16 * TN / NT;  // columns per thread in the epilogue (4 for 8 wavefronts)
     constexpr int TPR = TN / CPT;      // threads per output row
-    static_assert(CPT >= 1 && CPT <= 8 && (CPT & (CPT - 1)) == 0, "epilogue mapping");
+    static_assert(CPT >= 2 && CPT <= 8 && (CPT & (CPT - 1)) == 0, "epilogue mapping");
 
     extern __shared__ float lds[];
     float* red = lds;                    // [NW][16][TN], used once per weight matrix
@@ -206,37 +206,47 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 
     if (S > 1) {
         // Publish this slice's partial, then find out whether every other slice has arrived.
+        // The partials travel between workgroups that may sit on different XCDs (different L2s).
+        // They are written and read with device-coherent accesses (relaxed atomics of agent scope:
+        // stores write through, loads do not hit a stale L2 line), so that no whole-cache
+        // write-back or invalidate is needed: a workgroup waits until its stores are acknowledged,
+        // then takes its ticket; whoever draws the last ticket reads after that.
         if (out_ok) {
             float* p = acc_part + (((size_t)split * G) * M + m) * N + n;
 #pragma unroll
-            for (int e = 0; e < CPT; ++e) {
-                p[e] = v1[e];
-                if (GATED) p[(size_t)M * N + e] = v2[e];
+            for (int e = 0; e < CPT; e += 2) {
+                store_coherent2(p + e, v1[e], v1[e + 1]);
+                if (GATED) store_coherent2(p + (size_t)M * N + e, v2[e], v2[e + 1]);
             }
         }
-        if (col == 0) ss_part[((size_t)ntile * S + split) * 16 + m] = ssum;
-        __threadfence();
+        if (col == 0) store_coherent(ss_part + ((size_t)ntile * S + split) * 16 + m, ssum);
+        wait_stores_acknowledged();
         __syncthreads();
         if (tid == 0) {
-            const unsigned prev = atomicAdd(&tickets[ntile], 1u);
+            const unsigned prev = __hip_atomic_fetch_add(&tickets[ntile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             is_last = (prev == (unsigned)(S - 1));
         }
         __syncthreads();
         if (!is_last) return;
-        __threadfence();
         if (tid == 0) tickets[ntile] = 0u;  // ready for the next call on this workspace
 
         ssum = 0.f;
 #pragma unroll
         for (int e = 0; e < CPT; ++e) { v1[e] = 0.f; v2[e] = 0.f; }
         for (int s = 0; s < S; ++s) {
-            ssum += ss_part[((size_t)ntile * S + s) * 16 + m];
+            ssum += load_coherent(ss_part + ((size_t)ntile * S + s) * 16 + m);
             if (out_ok) {
                 const float* p = acc_part + (((size_t)s * G) * M + m) * N + n;
 #pragma unroll
-                for (int e = 0; e < CPT; ++e) {
-                    v1[e] += p[e];
-                    if (GATED) v2[e] += p[(size_t)M * N + e];
+                for (int e = 0; e < CPT; e += 2) {
+                    const f32x2 a = load_coherent2(p + e);
+                    v1[e] += a[0];
+                    v1[e + 1] += a[1];
+                    if (GATED) {
+                        const f32x2 b = load_coherent2(p + (size_t)M * N + e);
+                        v2[e] += b[0];
+                        v2[e + 1] += b[1];
+                    }
                 }
             }
         }
@@ -275,18 +285,14 @@ static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& 
     auto* Y = (uint16_t*)c.Y;
     if (c.gated) {
         auto kern = decode_kernel<NW, true>;
-        if (lds > 65536) {
-            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        static std::atomic<uint64_t> opted{0};
+        if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W2, Y, ws.acc_part, ws.ss_part, ws.tickets,
                            c.M, c.K, c.N, c.eps, S);
     } else {
         auto kern = decode_kernel<NW, false>;
-        if (lds > 65536) {
-            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-        }
+        static std::atomic<uint64_t> opted{0};
+        if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W1, Y, ws.acc_part, ws.ss_part, ws.tickets,
                            c.M, c.K, c.N, c.eps, S);
     }

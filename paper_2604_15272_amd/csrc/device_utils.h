@@ -36,6 +36,28 @@ __device__ __forceinline__ u32x4 load16(__amdgpu_buffer_rsrc_t r, u32 voff) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
 }
 
+// Device-coherent accesses for data handed from one workgroup to another inside a kernel.  On a
+// multi-XCD part every XCD has its own L2: these accesses go through to the memory side instead
+// of living in (or being served from) the issuing XCD's L2.
+__device__ __forceinline__ void store_coherent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_coherent2(float* p, float a, float b) {
+    const f32x2 v = {a, b};
+    __hip_atomic_store((unsigned long long*)p, __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float load_coherent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x2 load_coherent2(const float* p) {
+    const unsigned long long v =
+        __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(f32x2, v);
+}
+// Blocks until every store this wavefront issued has been acknowledged by the memory system.
+__device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ float silu_f32(float a) {
     // a / (1 + exp(-a)); exp(-a) -> inf for very negative a gives a * 0 = -0.
     return a * __builtin_amdgcn_rcpf(1.0f + __expf(-a));

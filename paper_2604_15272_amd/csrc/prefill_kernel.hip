@@ -236,10 +236,8 @@ static hipError_t launch_tile(const Call& c) {
     const int tiles_m = (c.M + BM - 1) / BM, tiles_n = (c.N + CW - 1) / CW;
     const size_t lds = (size_t)(2 * KCH * (BM + PAD) + 2 * KCH * (BN + PAD)) * 16 + (size_t)BM * 4;
     auto kern = prefill_kernel<BM, BN, GATED>;
-    if (lds > 65536) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-    }
+    static std::atomic<uint64_t> opted{0};
+    if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds, c.stream, (const uint16_t*)c.X,
                        (const uint16_t*)c.g, (const uint16_t*)c.W1, (const uint16_t*)(c.gated ? c.W2 : c.W1),
                        (uint16_t*)c.Y, c.M, c.K, c.N, c.eps, tiles_m, tiles_n);

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "prism.h"
 
 namespace prism {
@@ -31,6 +33,20 @@ struct DecodeWorkspace {
     float* ss_part;     // [n_tiles][S][16] partial sums of squares
     float* acc_part;    // [S][G][M][N] partial products (G = 2 if gated)
 };
+
+// Kernels with more than 64 KiB of dynamic LDS must be opted in once per device; `done` remembers
+// which devices (bit = ordinal) have been.
+inline hipError_t allow_large_lds(const void* kernel, size_t bytes, std::atomic<uint64_t>& done) {
+    if (bytes <= 65536) return hipSuccess;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_relaxed) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_relaxed);
+    return e;
+}
 
 hipError_t launch_simple_f32(const Call& c);
 hipError_t launch_simple_bf16(const Call& c);
