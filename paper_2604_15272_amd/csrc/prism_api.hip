@@ -107,17 +107,18 @@ prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_d
 
     if (path == PRISM_PATH_DECODE) {
         if (M > kDecodeMaxRows || (uint64_t)M * K * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
-        int waves = (variant > 0) ? variant : (gated ? 4 : 8);
+        int waves = (variant > 0) ? variant : 8;
         if (waves != 4 && waves != 8 && waves != 16) return PRISM_ERR_UNSUPPORTED;
         const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
         const int64_t kblocks = (K + kDecodeKBlock - 1) / kDecodeKBlock;
         if (n_tiles > kMaxTickets) return PRISM_ERR_UNSUPPORTED;
         int64_t S = forced_split;
         if (S <= 0) {
-            // Enough workgroups to keep every CU streaming, each wavefront with at least two K-blocks.
-            const int64_t target = 512;
+            // About one workgroup per CU (measured best on MI355X: more slices only add partial-sum
+            // traffic and tickets), each wavefront keeping at least one K-block.
+            const int64_t target = 256;
             S = (target + n_tiles / 2) / n_tiles;
-            const int64_t s_max = kblocks / (2 * waves);
+            const int64_t s_max = kblocks / waves;
             if (S > s_max) S = s_max;
             if (S < 1) S = 1;
         }
