@@ -1,19 +1,28 @@
 // Prefill path: many rows of X, a compute-bound dense contraction on the bf16 matrix cores.
 //
 // A workgroup of four wavefronts (2 x 2) owns a BM x BN output tile and walks K in steps of 64.
-// Per step it stages a BM x 64 tile of X and a 64 x BN tile of W in LDS (double-buffered: the
-// next step's global loads are issued before the current step's MFMAs and written to the other
-// buffer after them).  On the way to LDS
+// LDS holds two stages of a BM x 64 tile of X and a 64 x BN tile of W, both as
+// [k / 8][row or column][8 k values], so that an MFMA operand is one 16-byte read and 32 consecutive
+// lanes read 512 consecutive bytes.  On the way to LDS
 //   - X is multiplied by the gain and re-rounded to bf16, and its raw squares are summed per row
 //     (the row reduction lives in the K-loop: paper Figure 1(b), Accum beside Matmul);
 //   - W, which arrives N-contiguous, is turned K-contiguous with byte permutes on 8 x 8 blocks.
-// Both tiles sit in LDS as [k / 8][row or column][8 k values] so that an MFMA operand is one
-// 16-byte read and 32 consecutive lanes read 512 consecutive bytes.
 // The MFMA is issued "transposed" (W supplies the instruction's A operand, X its B operand), so a
 // lane ends up with four consecutive output columns of one row, and its 1/rms factor (Table 1,
 // "matmul commutes with div denominator") is one scalar per 32 x 32 block.
 // The gated variant puts BN/2 columns of W1 and the same BN/2 columns of W2 side by side in the
 // W tile; each wavefront holds matching W1 and W2 accumulators and applies SiLU(a) * b in registers.
+//
+// Software pipeline of one K step (four 16-deep MFMA phases), all in one wavefront's instruction
+// stream because a 256 x 256 tile leaves one wavefront per SIMD:
+//   phase 0..2: MFMAs of phase p run on operands read from LDS during phase p - 1, while the
+//               operands of phase p + 1 are read, and a share of the NEXT tile is staged
+//               (registers -> gain / squares / permutes -> the other LDS stage); each register set is
+//               refilled from global memory with the tile after next as soon as it has been staged;
+//   barrier;
+//   phase 3:    MFMAs, while the first operands of the next tile are read from the other stage.
+#include <type_traits>
+
 #include "device_utils.h"
 #include "prism_internal.h"
 
@@ -36,10 +45,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
                                                       const uint16_t* __restrict__ W1,
                                                       const uint16_t* __restrict__ W2, uint16_t* __restrict__ Y,
                                                       int M, int K, int N, float eps, int tiles_m, int tiles_n) {
-    constexpr int WTM = BM / 2, WTN = BN / 2;      // wavefront tile
+    constexpr int WTM = BM / 2, WTN = BN / 2;        // wavefront tile
     constexpr int TM32 = WTM / 32, TN32 = WTN / 32;  // 32 x 32 MFMA blocks per wavefront
-    constexpr int CW = GATED ? BN / 2 : BN;        // output columns per workgroup
-    constexpr int XI = BM / 32;                    // 16-byte X loads per thread per stage
+    constexpr int CW = GATED ? BN / 2 : BN;          // output columns per workgroup
+    constexpr int XI = BM / 32;                      // 16-byte X loads per thread per stage
     constexpr int A_PLANE = BM + PAD, B_PLANE = BN + PAD;  // slots per chunk plane
     constexpr int A_SLOTS = KCH * A_PLANE, B_SLOTS = KCH * B_PLANE;
     static_assert(BM % 64 == 0 && BN % 64 == 0 && BN <= 256, "tile shape");
@@ -47,8 +56,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     static_assert(CW % 64 == 0, "a wavefront loads from one weight matrix only");
 
     extern __shared__ u32x4 lds[];
-    u32x4* As = lds;                 // [2][KCH][A_PLANE]
-    u32x4* Bs = lds + 2 * A_SLOTS;   // [2][KCH][B_PLANE]
+    u32x4* As = lds;                // [2][KCH][A_PLANE]
+    u32x4* Bs = lds + 2 * A_SLOTS;  // [2][KCH][B_PLANE]
     float* rscale = (float*)(lds + 2 * A_SLOTS + 2 * B_SLOTS);  // [BM]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -67,9 +76,10 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     const size_t x_left = ((size_t)M * K - x_first) * 2;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + x_first, (u32)(x_left < 0x7FFFFFFFull ? x_left : 0x7FFFFFFFull));
     const __amdgpu_buffer_rsrc_t rg = make_rsrc(g, (u32)K * 2u);
-    // W: thread t owns one 8 (k) x 8 (n) block of the stage.
+    // W: thread t owns one 8 (k) x 8 (n) block of the stage.  Which matrix a wavefront reads is the
+    // same for all its lanes (CW is a multiple of 64); say so, to keep the descriptor in SGPRs.
     constexpr int NB8 = CW / 8;  // 8-column groups per weight matrix
-    const int wmat = GATED ? (tid / CW) & 1 : 0;  // wavefront-uniform: CW is a multiple of 64
+    const int wmat = GATED ? __builtin_amdgcn_readfirstlane((tid / CW) & 1) : 0;
     const int wt = GATED ? tid % CW : tid;
     const bool w_active = tid < BN;
     const int wkb = wt / NB8, wnb = wt % NB8;
@@ -80,66 +90,68 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     const u32 row_bytes = (u32)N * 2u;
     const u32 w_lane = w_col_ok ? ((u32)(8 * wkb) * row_bytes + (u32)(16 * wnb)) : kOutOfRange;
     const int w_lds_col = wmat * (BN / 2) + 8 * wnb;  // first LDS column of the block
+    // LDS slot of column j of the block, within a stage.  Threads without a block (tiles narrower than
+    // 256) store to a padding slot instead of branching, which keeps the K loop one basic block.
+    int w_dst[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) w_dst[j] = w_active ? wkb * B_PLANE + swz(w_lds_col + j) : BN;
 
-    u32x4 xreg[XI], greg;
-    u32x4 wreg[8];
+    u32x4 xreg[XI], wreg[8], g_cur, g_nxt;
     float ssq[XI];
 #pragma unroll
     for (int i = 0; i < XI; ++i) ssq[i] = 0.f;
 
-    auto issue_loads = [&](int kt) {
+    // Global loads of K step kt (k past the end read as zero: X by predicate, g and W by the descriptor).
+    auto load_g = [&](int kt) {
         const int k = kt * BK + 8 * xc;
-        const bool k_ok = k < K;
-        greg = load16(rg, k_ok ? (u32)k * 2u : kOutOfRange);
-#pragma unroll
-        for (int i = 0; i < XI; ++i) {
-            const int r = xr0 + 32 * i;
-            xreg[i] = load16(rx, k_ok ? (u32)(((size_t)r * K + k) * 2) : kOutOfRange);
-        }
+        return load16(rg, (u32)k * 2u);  // k < 2^30: past K is past the descriptor
+    };
+    auto load_x = [&](int kt, int i) {
+        const int k = kt * BK + 8 * xc;
+        xreg[i] = load16(rx, (k < K) ? (u32)(((size_t)(xr0 + 32 * i) * K + k) * 2) : kOutOfRange);
+    };
+    auto load_w = [&](int kt) {
         const u32 woff = w_lane + (u32)kt * BK * row_bytes;
 #pragma unroll
         for (int r = 0; r < 8; ++r) wreg[r] = load16(rw, woff + (u32)r * row_bytes);
     };
 
-    auto stage_to_lds = [&](int buf) {
-        u32x4* a_dst = As + buf * A_SLOTS + xc * A_PLANE;
-        float gf[8];
+    auto load_w_rows = [&](int kt, int r0) {  // two of the eight rows
+        const u32 woff = w_lane + (u32)kt * BK * row_bytes;
+        wreg[r0] = load16(rw, woff + (u32)r0 * row_bytes);
+        wreg[r0 + 1] = load16(rw, woff + (u32)(r0 + 1) * row_bytes);
+    };
+
+    // Staging of X chunk i, in four pieces (one dword = two elements each): gain, squares, rounding;
+    // the fourth piece stores the 16 bytes to LDS.
+    u32x4 xa[XI];
+    auto stage_x_piece = [&](u32x4* a_stage, int i, int d, const float (&gf)[8]) {
+        const u32 xx = xreg[i][d];
+        ssq[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xx), __builtin_bit_cast(bf16x2, xx),
+                                                 ssq[i], false);
+        xa[i][d] = pack_bf16(bf16_lo(xx) * gf[2 * d], bf16_hi(xx) * gf[2 * d + 1]);
+        if (d == 3) a_stage[xc * A_PLANE + xr0 + 32 * i] = xa[i];
+    };
+    // Staging of W column j of the thread's 8 x 8 block.
+    auto stage_w = [&](u32x4* b_stage, int j) {
+        const int d = j >> 1;
+        const u32 sel = (j & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 b;
+        b[0] = __builtin_amdgcn_perm(wreg[1][d], wreg[0][d], sel);
+        b[1] = __builtin_amdgcn_perm(wreg[3][d], wreg[2][d], sel);
+        b[2] = __builtin_amdgcn_perm(wreg[5][d], wreg[4][d], sel);
+        b[3] = __builtin_amdgcn_perm(wreg[7][d], wreg[6][d], sel);
+        b_stage[w_dst[j]] = b;
+    };
+    auto unpack_g = [&](u32x4 gg, float (&gf)[8]) {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) { gf[2 * d] = bf16_lo(greg[d]); gf[2 * d + 1] = bf16_hi(greg[d]); }
-#pragma unroll
-        for (int i = 0; i < XI; ++i) {
-            u32x4 a;
-            float s = ssq[i];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const float x0 = bf16_lo(xreg[i][d]), x1 = bf16_hi(xreg[i][d]);
-                s = fmaf(x0, x0, s);
-                s = fmaf(x1, x1, s);
-                a[d] = pack_bf16(x0 * gf[2 * d], x1 * gf[2 * d + 1]);
-            }
-            ssq[i] = s;
-            a_dst[xr0 + 32 * i] = a;
-        }
-        if (w_active) {
-            u32x4* b_dst = Bs + buf * B_SLOTS + wkb * B_PLANE;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int d = j >> 1;
-                const u32 sel = (j & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 b;
-                b[0] = __builtin_amdgcn_perm(wreg[1][d], wreg[0][d], sel);
-                b[1] = __builtin_amdgcn_perm(wreg[3][d], wreg[2][d], sel);
-                b[2] = __builtin_amdgcn_perm(wreg[5][d], wreg[4][d], sel);
-                b[3] = __builtin_amdgcn_perm(wreg[7][d], wreg[6][d], sel);
-                b_dst[swz(w_lds_col + j)] = b;
-            }
-        }
+        for (int d = 0; d < 4; ++d) { gf[2 * d] = bf16_lo(gg[d]); gf[2 * d + 1] = bf16_hi(gg[d]); }
     };
 
     // ---- LDS -> MFMA operand maps --------------------------------------------------------------
     int a_slot[TM32];  // X operand: row of the tile
 #pragma unroll
-    for (int ib = 0; ib < TM32; ++ib) a_slot[ib] = wm * WTM + 32 * ib + l32;
+    for (int ib = 0; ib < TM32; ++ib) a_slot[ib] = lh * A_PLANE + wm * WTM + 32 * ib + l32;
     int b_slot[TN32];  // W operand: swizzled column of the tile
 #pragma unroll
     for (int jb = 0; jb < TN32; ++jb) {
@@ -150,8 +162,15 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         } else {
             col = wn * WTN + 32 * jb;
         }
-        b_slot[jb] = swz(col + l32);
+        b_slot[jb] = lh * B_PLANE + swz(col + l32);
     }
+    // Operands of 16-deep phase kk of a stage: chunk plane 2 kk + lh.
+    auto read_frags = [&](const u32x4* a_stage, const u32x4* b_stage, int kk, bf16x8 (&xf)[TM32], bf16x8 (&wf)[TN32]) {
+#pragma unroll
+        for (int ib = 0; ib < TM32; ++ib) xf[ib] = __builtin_bit_cast(bf16x8, a_stage[2 * kk * A_PLANE + a_slot[ib]]);
+#pragma unroll
+        for (int jb = 0; jb < TN32; ++jb) wf[jb] = __builtin_bit_cast(bf16x8, b_stage[2 * kk * B_PLANE + b_slot[jb]]);
+    };
 
     f32x16 acc[TN32][TM32];
 #pragma unroll
@@ -160,36 +179,102 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         for (int ib = 0; ib < TM32; ++ib)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[jb][ib][v] = 0.f;
+    constexpr int MF = TM32 * TN32;   // MFMAs per 16-deep phase
+    constexpr int RD = TM32 + TN32;   // operand reads per phase
+    constexpr int RPS = (RD + MF - 1) / MF;  // operand reads per MFMA slot (front-loaded)
 
+    // One phase, as MF slots.  Slot q issues MFMA q on the operands read during the previous phase,
+    // reads its share of the next operands (from `a_rd`/`b_rd`, 16-deep phase `kk_rd`), and does its
+    // share of the staging work items of this phase, in order: NXD pieces of X chunks starting at
+    // chunk X0 (each finished chunk is refilled from the tile after next), NW columns of W starting
+    // at column W0, and, if TAIL, the refill of the W registers in four pairs of rows.
+    // A scheduling barrier closes every slot: the order written here is the order executed.
+    auto phase = [&](auto x0_c, auto nx_c, auto w0_c, auto nw_c, auto tail_c, const u32x4* a_rd, const u32x4* b_rd,
+                     int kk_rd, const bf16x8 (&xf)[TM32], const bf16x8 (&wf)[TN32], bf16x8 (&xf_n)[TM32],
+                     bf16x8 (&wf_n)[TN32], u32x4* a_nxt, u32x4* b_nxt, const float (&gf)[8], int kt_load) {
+        constexpr int X0 = decltype(x0_c)::value, NX = decltype(nx_c)::value, W0 = decltype(w0_c)::value,
+                      NW = decltype(nw_c)::value, TAIL = decltype(tail_c)::value;
+        constexpr int ITEMS = 4 * NX + NW + (TAIL ? 4 : 0);
+#pragma unroll
+        for (int q = 0; q < MF; ++q) {
+            const int jb = q / TM32, ib = q % TM32;
+            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[jb], xf[ib], acc[jb][ib], 0, 0, 0);
+#pragma unroll
+            for (int r = q * RPS; r < (q + 1) * RPS && r < RD; ++r) {
+                if (r < TM32) xf_n[r] = __builtin_bit_cast(bf16x8, a_rd[2 * kk_rd * A_PLANE + a_slot[r]]);
+                else wf_n[r - TM32] = __builtin_bit_cast(bf16x8, b_rd[2 * kk_rd * B_PLANE + b_slot[r - TM32]]);
+            }
+#pragma unroll
+            for (int it = (q * ITEMS) / MF; it < ((q + 1) * ITEMS) / MF; ++it) {
+                if (it < 4 * NX) {
+                    const int i = X0 + it / 4, d = it % 4;
+                    stage_x_piece(a_nxt, i, d, gf);
+                    if (d == 3) load_x(kt_load, i);
+                } else if (it < 4 * NX + NW) {
+                    stage_w(b_nxt, W0 + it - 4 * NX);
+                } else {
+                    const int r0 = 2 * (it - 4 * NX - NW);
+                    load_w_rows(kt_load, r0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using std::integral_constant;
+
+    constexpr int xs0 = 0, xs1 = XI / 2, xs2 = (3 * XI) / 4, xs3 = XI;
+    constexpr int ws0 = 0, ws1 = 0, ws2 = 4, ws3 = 8;
     const int KT = (K + BK - 1) / BK;
-    issue_loads(0);
-    stage_to_lds(0);
+
+    // ---- prologue: tile 0 to stage 0, tile 1 into registers, first operands ----------------------
+    {
+        g_cur = load_g(0);
+#pragma unroll
+        for (int i = 0; i < XI; ++i) load_x(0, i);
+        load_w(0);
+        float gf[8];
+        unpack_g(g_cur, gf);
+#pragma unroll
+        for (int i = 0; i < XI; ++i)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) stage_x_piece(As, i, d, gf);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) stage_w(Bs, j);
+        g_cur = load_g(1);
+#pragma unroll
+        for (int i = 0; i < XI; ++i) load_x(1, i);
+        load_w(1);
+    }
     __syncthreads();
+    bf16x8 xfA[TM32], wfA[TN32], xfB[TM32], wfB[TN32];
+    read_frags(As, Bs, 0, xfA, wfA);
 
     for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        const bool more = (kt + 1) < KT;
-        if (more) issue_loads(kt + 1);
+        const int cur = kt & 1;
+        const u32x4* a_cur = As + cur * A_SLOTS;
+        const u32x4* b_cur = Bs + cur * B_SLOTS;
+        u32x4* a_nxt = As + (cur ^ 1) * A_SLOTS;
+        u32x4* b_nxt = Bs + (cur ^ 1) * B_SLOTS;
+        float gf[8];
+        unpack_g(g_cur, gf);       // gain of tile kt + 1 (being staged)
+        g_nxt = load_g(kt + 2);    // gain of the tile after next
 
-        const u32x4* a_src = As + buf * A_SLOTS;
-        const u32x4* b_src = Bs + buf * B_SLOTS;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int ch = 2 * kk + lh;
-            bf16x8 xf[TM32], wf[TN32];
-#pragma unroll
-            for (int ib = 0; ib < TM32; ++ib) xf[ib] = __builtin_bit_cast(bf16x8, a_src[ch * A_PLANE + a_slot[ib]]);
-#pragma unroll
-            for (int jb = 0; jb < TN32; ++jb) wf[jb] = __builtin_bit_cast(bf16x8, b_src[ch * B_PLANE + b_slot[jb]]);
-#pragma unroll
-            for (int jb = 0; jb < TN32; ++jb)
-#pragma unroll
-                for (int ib = 0; ib < TM32; ++ib)
-                    acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[jb], xf[ib], acc[jb][ib], 0, 0, 0);
-        }
-
-        if (more) stage_to_lds(buf ^ 1);
-        __syncthreads();
+        // Shares of the next tile per phase: X chunks [xs_p, xs_p+1), W columns [ws_p, ws_p+1).  W comes
+        // late: its registers are refilled last, so its loads have had the least time.
+        phase(integral_constant<int, xs0>{}, integral_constant<int, xs1 - xs0>{}, integral_constant<int, ws0>{},
+              integral_constant<int, ws1 - ws0>{}, integral_constant<int, 0>{}, a_cur, b_cur, 1, xfA, wfA, xfB, wfB,
+              a_nxt, b_nxt, gf, kt + 2);
+        phase(integral_constant<int, xs1>{}, integral_constant<int, xs2 - xs1>{}, integral_constant<int, ws1>{},
+              integral_constant<int, ws2 - ws1>{}, integral_constant<int, 0>{}, a_cur, b_cur, 2, xfB, wfB, xfA, wfA,
+              a_nxt, b_nxt, gf, kt + 2);
+        phase(integral_constant<int, xs2>{}, integral_constant<int, xs3 - xs2>{}, integral_constant<int, ws2>{},
+              integral_constant<int, ws3 - ws2>{}, integral_constant<int, 1>{}, a_cur, b_cur, 3, xfA, wfA, xfB, wfB,
+              a_nxt, b_nxt, gf, kt + 2);
+        __syncthreads();  // the next tile is complete in LDS; nobody reads the current stage any more
+        phase(integral_constant<int, 0>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{},
+              integral_constant<int, 0>{}, integral_constant<int, 0>{}, a_nxt, b_nxt, 0, xfB, wfB, xfA, wfA, a_nxt,
+              b_nxt, gf, kt + 2);
+        g_cur = g_nxt;
     }
 
     // ---- 1/rms per row: the eight threads that shared a row combine their partial sums -----------
