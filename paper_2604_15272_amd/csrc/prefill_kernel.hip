@@ -4,9 +4,14 @@
 // LDS holds two stages of a BM x 64 tile of X and a 64 x BN tile of W, both as
 // [k / 8][row or column][8 k values], so that an MFMA operand is one 16-byte read and 32 consecutive
 // lanes read 512 consecutive bytes.  On the way to LDS
-//   - X is multiplied by the gain and re-rounded to bf16, and its raw squares are summed per row
-//     (the row reduction lives in the K-loop: paper Figure 1(b), Accum beside Matmul);
-//   - W, which arrives N-contiguous, is turned K-contiguous with byte permutes on 8 x 8 blocks.
+//   - the raw squares of X are summed per row (the row reduction lives in the K-loop: paper
+//     Figure 1(b), Accum beside Matmul);
+//   - W, which arrives N-contiguous, is turned K-contiguous on 8 x 8 blocks held by one thread, and
+//     the gain is folded in on the way: (X * g) W = X (g * W) row by row of W, so the multiply and
+//     the re-rounding to bf16 ride on the transposition that W needs anyway (an element is
+//     extracted, scaled by the gain of its row k and packed next to its K neighbour).  X then needs
+//     no arithmetic besides its squares, which matters because only about four vector
+//     instructions fit under one MFMA.
 // The MFMA is issued "transposed" (W supplies the instruction's A operand, X its B operand), so a
 // lane ends up with four consecutive output columns of one row, and its 1/rms factor (Table 1,
 // "matmul commutes with div denominator") is one scalar per 32 x 32 block.
@@ -32,7 +37,8 @@ namespace {
 
 constexpr int BK = 64;       // K depth of one LDS stage
 constexpr int KCH = BK / 8;  // 16-byte K chunks per row of a stage
-constexpr int PAD = 2;       // slots of padding per chunk plane (spreads the X stores over banks)
+constexpr int PAD = 1;       // slots of padding per chunk plane: eight planes then start 16 bytes apart mod 128,
+                             // the spacing at which the eight-lanes-per-row X stores run at full LDS write rate
 
 // Column swizzle of the W tile: a bijection on every aligned group of 16 columns (given the
 // higher bits), chosen so that the permuted 8 x 8 blocks store without bank conflicts.
@@ -102,9 +108,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     for (int i = 0; i < XI; ++i) ssq[i] = 0.f;
 
     // Global loads of K step kt (k past the end read as zero: X by predicate, g and W by the descriptor).
-    auto load_g = [&](int kt) {
-        const int k = kt * BK + 8 * xc;
-        return load16(rg, (u32)k * 2u);  // k < 2^30: past K is past the descriptor
+    auto load_g = [&](int kt) {  // gain of the eight rows (k values) of the thread's W block
+        const int k = kt * BK + 8 * wkb;
+        return load16(rg, (u32)k * 2u);  // past K is past the descriptor: zero
     };
     auto load_x = [&](int kt, int i) {
         const int k = kt * BK + 8 * xc;
@@ -116,32 +122,29 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         for (int r = 0; r < 8; ++r) wreg[r] = load16(rw, woff + (u32)r * row_bytes);
     };
 
-    auto load_w_rows = [&](int kt, int r0) {  // two of the eight rows
-        const u32 woff = w_lane + (u32)kt * BK * row_bytes;
-        wreg[r0] = load16(rw, woff + (u32)r0 * row_bytes);
-        wreg[r0 + 1] = load16(rw, woff + (u32)(r0 + 1) * row_bytes);
+    auto load_w_row = [&](int kt, int r) {
+        wreg[r] = load16(rw, w_lane + (u32)kt * BK * row_bytes + (u32)r * row_bytes);
     };
 
-    // Staging of X chunk i, in four pieces (one dword = two elements each): gain, squares, rounding;
-    // the fourth piece stores the 16 bytes to LDS.
-    u32x4 xa[XI];
-    auto stage_x_piece = [&](u32x4* a_stage, int i, int d, const float (&gf)[8]) {
+    // Staging of X chunk i, in four pieces (one dword = two elements each): the squares; the fourth
+    // piece stores the 16 raw bytes to LDS.
+    auto stage_x_piece = [&](u32x4* a_stage, int i, int d) {
         const u32 xx = xreg[i][d];
         ssq[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xx), __builtin_bit_cast(bf16x2, xx),
                                                  ssq[i], false);
-        xa[i][d] = pack_bf16(bf16_lo(xx) * gf[2 * d], bf16_hi(xx) * gf[2 * d + 1]);
-        if (d == 3) a_stage[xc * A_PLANE + xr0 + 32 * i] = xa[i];
+        if (d == 3) a_stage[xc * A_PLANE + xr0 + 32 * i] = xreg[i];
     };
-    // Staging of W column j of the thread's 8 x 8 block.
-    auto stage_w = [&](u32x4* b_stage, int j) {
+    // Staging of W column j of the thread's 8 x 8 block, in four pieces: piece t scales elements
+    // (2t, j) and (2t + 1, j) by the gains of their rows and packs them as K neighbours (this is the
+    // transposition); the fourth piece stores the 16 bytes to LDS.
+    u32x4 wb;
+    auto stage_w_piece = [&](u32x4* b_stage, int j, int t, const float (&gf)[8]) {
         const int d = j >> 1;
-        const u32 sel = (j & 1) ? 0x07060302u : 0x05040100u;
-        u32x4 b;
-        b[0] = __builtin_amdgcn_perm(wreg[1][d], wreg[0][d], sel);
-        b[1] = __builtin_amdgcn_perm(wreg[3][d], wreg[2][d], sel);
-        b[2] = __builtin_amdgcn_perm(wreg[5][d], wreg[4][d], sel);
-        b[3] = __builtin_amdgcn_perm(wreg[7][d], wreg[6][d], sel);
-        b_stage[w_dst[j]] = b;
+        const u32 w0 = wreg[2 * t][d], w1 = wreg[2 * t + 1][d];
+        const float e0 = (j & 1) ? bf16_hi(w0) : bf16_lo(w0);
+        const float e1 = (j & 1) ? bf16_hi(w1) : bf16_lo(w1);
+        wb[t] = pack_bf16(e0 * gf[2 * t], e1 * gf[2 * t + 1]);
+        if (t == 3) b_stage[w_dst[j]] = wb;
     };
     auto unpack_g = [&](u32x4 gg, float (&gf)[8]) {
 #pragma unroll
@@ -185,16 +188,17 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 
     // One phase, as MF slots.  Slot q issues MFMA q on the operands read during the previous phase,
     // reads its share of the next operands (from `a_rd`/`b_rd`, 16-deep phase `kk_rd`), and does its
-    // share of the staging work items of this phase, in order: NXD pieces of X chunks starting at
-    // chunk X0 (each finished chunk is refilled from the tile after next), NW columns of W starting
-    // at column W0, and, if TAIL, the refill of the W registers in four pairs of rows.
+    // share of this phase's staging of the next tile: X pieces [XP0, XP0 + NXP) (piece = 4 * chunk +
+    // dword; a finished chunk is refilled from the tile after next), W pieces [WP0, WP0 + NWP)
+    // (piece = 4 * column + K pair), and, if TAIL, the refill of the W registers in the last slots.
     // A scheduling barrier closes every slot: the order written here is the order executed.
-    auto phase = [&](auto x0_c, auto nx_c, auto w0_c, auto nw_c, auto tail_c, const u32x4* a_rd, const u32x4* b_rd,
+    auto phase = [&](auto xp0_c, auto nxp_c, auto wp0_c, auto nwp_c, auto tail_c, const u32x4* a_rd, const u32x4* b_rd,
                      int kk_rd, const bf16x8 (&xf)[TM32], const bf16x8 (&wf)[TN32], bf16x8 (&xf_n)[TM32],
                      bf16x8 (&wf_n)[TN32], u32x4* a_nxt, u32x4* b_nxt, const float (&gf)[8], int kt_load) {
-        constexpr int X0 = decltype(x0_c)::value, NX = decltype(nx_c)::value, W0 = decltype(w0_c)::value,
-                      NW = decltype(nw_c)::value, TAIL = decltype(tail_c)::value;
-        constexpr int ITEMS = 4 * NX + NW + (TAIL ? 4 : 0);
+        constexpr int XP0 = decltype(xp0_c)::value, NXP = decltype(nxp_c)::value, WP0 = decltype(wp0_c)::value,
+                      NWP = decltype(nwp_c)::value, TAIL = decltype(tail_c)::value;
+        constexpr int TAIL_SLOTS = TAIL ? (MF >= 8 ? 4 : 1) : 0;  // slots at the end that refill W rows
+        constexpr int WS = MF - TAIL_SLOTS > 0 ? MF - TAIL_SLOTS : 1;  // slots that stage W pieces
 #pragma unroll
         for (int q = 0; q < MF; ++q) {
             const int jb = q / TM32, ib = q % TM32;
@@ -205,25 +209,30 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
                 else wf_n[r - TM32] = __builtin_bit_cast(bf16x8, b_rd[2 * kk_rd * B_PLANE + b_slot[r - TM32]]);
             }
 #pragma unroll
-            for (int it = (q * ITEMS) / MF; it < ((q + 1) * ITEMS) / MF; ++it) {
-                if (it < 4 * NX) {
-                    const int i = X0 + it / 4, d = it % 4;
-                    stage_x_piece(a_nxt, i, d, gf);
-                    if (d == 3) load_x(kt_load, i);
-                } else if (it < 4 * NX + NW) {
-                    stage_w(b_nxt, W0 + it - 4 * NX);
-                } else {
-                    const int r0 = 2 * (it - 4 * NX - NW);
-                    load_w_rows(kt_load, r0);
-                }
+            for (int it = (q * NXP) / MF; it < ((q + 1) * NXP) / MF; ++it) {
+                const int i = (XP0 + it) / 4, d = (XP0 + it) % 4;
+                stage_x_piece(a_nxt, i, d);
+                if (d == 3) load_x(kt_load, i);
+            }
+            if (q < WS) {
+#pragma unroll
+                for (int it = (q * NWP) / WS; it < ((q + 1) * NWP) / WS; ++it)
+                    stage_w_piece(b_nxt, (WP0 + it) / 4, (WP0 + it) % 4, gf);
+            }
+            if (TAIL && q >= MF - TAIL_SLOTS) {  // after the last W piece: refill the W rows
+                constexpr int RPT = TAIL_SLOTS ? 8 / TAIL_SLOTS : 0;
+#pragma unroll
+                for (int r = (q - (MF - TAIL_SLOTS)) * RPT; r < (q - (MF - TAIL_SLOTS) + 1) * RPT; ++r)
+                    load_w_row(kt_load, r);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     using std::integral_constant;
 
-    constexpr int xs0 = 0, xs1 = XI / 2, xs2 = (3 * XI) / 4, xs3 = XI;
-    constexpr int ws0 = 0, ws1 = 0, ws2 = 4, ws3 = 8;
+    // X pieces (4 per chunk) and W pieces (4 per column) staged in phases 0, 1, 2.
+    constexpr int xp0 = 0, xp1 = 2 * XI, xp2 = 3 * XI, xp3 = 4 * XI;
+    constexpr int wp0 = 0, wp1 = 0, wp2 = 16, wp3 = 32;
     const int KT = (K + BK - 1) / BK;
 
     // ---- prologue: tile 0 to stage 0, tile 1 into registers, first operands ----------------------
@@ -237,9 +246,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #pragma unroll
         for (int i = 0; i < XI; ++i)
 #pragma unroll
-            for (int d = 0; d < 4; ++d) stage_x_piece(As, i, d, gf);
+            for (int d = 0; d < 4; ++d) stage_x_piece(As, i, d);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) stage_w(Bs, j);
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) stage_w_piece(Bs, j, t, gf);
         g_cur = load_g(1);
 #pragma unroll
         for (int i = 0; i < XI; ++i) load_x(1, i);
@@ -259,16 +270,16 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         unpack_g(g_cur, gf);       // gain of tile kt + 1 (being staged)
         g_nxt = load_g(kt + 2);    // gain of the tile after next
 
-        // Shares of the next tile per phase: X chunks [xs_p, xs_p+1), W columns [ws_p, ws_p+1).  W comes
+        // Shares of the next tile per phase: X pieces [xp_p, xp_p+1), W pieces [wp_p, wp_p+1).  W starts
         // late: its registers are refilled last, so its loads have had the least time.
-        phase(integral_constant<int, xs0>{}, integral_constant<int, xs1 - xs0>{}, integral_constant<int, ws0>{},
-              integral_constant<int, ws1 - ws0>{}, integral_constant<int, 0>{}, a_cur, b_cur, 1, xfA, wfA, xfB, wfB,
+        phase(integral_constant<int, xp0>{}, integral_constant<int, xp1 - xp0>{}, integral_constant<int, wp0>{},
+              integral_constant<int, wp1 - wp0>{}, integral_constant<int, 0>{}, a_cur, b_cur, 1, xfA, wfA, xfB, wfB,
               a_nxt, b_nxt, gf, kt + 2);
-        phase(integral_constant<int, xs1>{}, integral_constant<int, xs2 - xs1>{}, integral_constant<int, ws1>{},
-              integral_constant<int, ws2 - ws1>{}, integral_constant<int, 0>{}, a_cur, b_cur, 2, xfB, wfB, xfA, wfA,
+        phase(integral_constant<int, xp1>{}, integral_constant<int, xp2 - xp1>{}, integral_constant<int, wp1>{},
+              integral_constant<int, wp2 - wp1>{}, integral_constant<int, 0>{}, a_cur, b_cur, 2, xfB, wfB, xfA, wfA,
               a_nxt, b_nxt, gf, kt + 2);
-        phase(integral_constant<int, xs2>{}, integral_constant<int, xs3 - xs2>{}, integral_constant<int, ws2>{},
-              integral_constant<int, ws3 - ws2>{}, integral_constant<int, 1>{}, a_cur, b_cur, 3, xfA, wfA, xfB, wfB,
+        phase(integral_constant<int, xp2>{}, integral_constant<int, xp3 - xp2>{}, integral_constant<int, wp2>{},
+              integral_constant<int, wp3 - wp2>{}, integral_constant<int, 1>{}, a_cur, b_cur, 3, xfA, wfA, xfB, wfB,
               a_nxt, b_nxt, gf, kt + 2);
         __syncthreads();  // the next tile is complete in LDS; nobody reads the current stage any more
         phase(integral_constant<int, 0>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{},
