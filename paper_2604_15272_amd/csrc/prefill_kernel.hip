@@ -1,17 +1,27 @@
 // Prefill path: many rows of X, a compute-bound dense contraction on the bf16 matrix cores.
 //
 // A workgroup of four wavefronts (2 x 2) owns a BM x BN output tile and walks K in steps of 64.
-// LDS holds two stages of a BM x 64 tile of X and a 64 x BN tile of W, both as
-// [k / 8][row or column][8 k values], so that an MFMA operand is one 16-byte read and 32 consecutive
-// lanes read 512 consecutive bytes.  On the way to LDS
-//   - the raw squares of X are summed per row (the row reduction lives in the K-loop: paper
-//     Figure 1(b), Accum beside Matmul);
+// LDS holds two stages of a BM x 64 tile of X and a 64 x BN tile of W; an MFMA operand (8 K values of
+// one row or column) is one 16-byte read.
+//   - X goes from global memory straight into LDS (buffer loads with the LDS flag: no registers, no
+//     vector instructions, no LDS store instructions).  Such a load writes the 64 lanes' 16 bytes
+//     back to back, so a stage is row-major (8 rows = 1 KiB per wavefront instruction); to keep the
+//     operand reads (32 consecutive rows, same K chunk) off each other's banks, the K chunks of row r
+//     are rotated by r % 8 (done on the global address, which is free) and every group of 8 rows
+//     is followed by 128 bytes of padding.
+//   - W sits in LDS as [k / 8][column][8 k values].
 //   - W, which arrives N-contiguous, is turned K-contiguous on 8 x 8 blocks held by one thread, and
 //     the gain is folded in on the way: (X * g) W = X (g * W) row by row of W, so the multiply and
 //     the re-rounding to bf16 ride on the transposition that W needs anyway (an element is
 //     extracted, scaled by the gain of its row k and packed next to its K neighbour).  X then needs
-//     no arithmetic besides its squares, which matters because only about four vector
-//     instructions fit under one MFMA.
+//     no vector arithmetic at all, which matters because only about four vector instructions fit
+//     under one MFMA.
+// The row sums of squares live in the K-loop too (paper Figure 1(b), Accum beside Matmul), but on the
+// matrix cores: a 4x4x4 MFMA fed the same X operand registers on both sides yields, on its diagonal,
+// the squares of four K values per lane, and accumulates them.  (A dot-product instruction would be
+// one vector op per two elements, but measured here it cannot overlap with a running MFMA and cost
+// 13 % of the kernel; two small MFMAs per operand cost 16 cycles of the matrix pipe.)  The two
+// wavefronts that share rows take alternate 16-deep phases.
 // The MFMA is issued "transposed" (W supplies the instruction's A operand, X its B operand), so a
 // lane ends up with four consecutive output columns of one row, and its 1/rms factor (Table 1,
 // "matmul commutes with div denominator") is one scalar per 32 x 32 block.
@@ -21,11 +31,12 @@
 // Software pipeline of one K step (four 16-deep MFMA phases), all in one wavefront's instruction
 // stream because a 256 x 256 tile leaves one wavefront per SIMD:
 //   phase 0..2: MFMAs of phase p run on operands read from LDS during phase p - 1, while the
-//               operands of phase p + 1 are read, and a share of the NEXT tile is staged
-//               (registers -> gain / squares / permutes -> the other LDS stage); each register set is
-//               refilled from global memory with the tile after next as soon as it has been staged;
-//   barrier;
-//   phase 3:    MFMAs, while the first operands of the next tile are read from the other stage.
+//               operands of phase p + 1 are read and the W part of the NEXT tile is staged
+//               (registers -> gain, transposition -> the other LDS stage); at the end the W registers
+//               are refilled from the tile after next;
+//   barrier     (the next tile is complete: its X part was requested a whole step earlier);
+//   phase 3:    MFMAs, while the first operands of the next tile are read from the other stage and
+//               the X part of the tile after next is requested into the stage just vacated.
 #include <type_traits>
 
 #include "device_utils.h"
@@ -37,8 +48,8 @@ namespace {
 
 constexpr int BK = 64;       // K depth of one LDS stage
 constexpr int KCH = BK / 8;  // 16-byte K chunks per row of a stage
-constexpr int PAD = 1;       // slots of padding per chunk plane: eight planes then start 16 bytes apart mod 128,
-                             // the spacing at which the eight-lanes-per-row X stores run at full LDS write rate
+constexpr int PAD = 1;       // 16-byte slots of padding per K-chunk plane of the W stage
+constexpr int XGS = 72;      // 16-byte slots per group of 8 rows of the X stage: 64 of data, 8 of padding
 
 // Column swizzle of the W tile: a bijection on every aligned group of 16 columns (given the
 // higher bits), chosen so that the permuted 8 x 8 blocks store without bank conflicts.
@@ -55,14 +66,14 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     constexpr int TM32 = WTM / 32, TN32 = WTN / 32;  // 32 x 32 MFMA blocks per wavefront
     constexpr int CW = GATED ? BN / 2 : BN;          // output columns per workgroup
     constexpr int XI = BM / 32;                      // 16-byte X loads per thread per stage
-    constexpr int A_PLANE = BM + PAD, B_PLANE = BN + PAD;  // slots per chunk plane
-    constexpr int A_SLOTS = KCH * A_PLANE, B_SLOTS = KCH * B_PLANE;
+    constexpr int B_PLANE = BN + PAD;                      // slots per chunk plane of W
+    constexpr int A_SLOTS = (BM / 8) * XGS, B_SLOTS = KCH * B_PLANE;  // slots per stage
     static_assert(BM % 64 == 0 && BN % 64 == 0 && BN <= 256, "tile shape");
     static_assert(!GATED || (WTN % 64 == 0), "gated tiles pair 32-column blocks of W1 and W2");
     static_assert(CW % 64 == 0, "a wavefront loads from one weight matrix only");
 
     extern __shared__ u32x4 lds[];
-    u32x4* As = lds;                // [2][KCH][A_PLANE]
+    u32x4* As = lds;                // [2][BM / 8][XGS]
     u32x4* Bs = lds + 2 * A_SLOTS;  // [2][KCH][B_PLANE]
     float* rscale = (float*)(lds + 2 * A_SLOTS + 2 * B_SLOTS);  // [BM]
 
@@ -102,59 +113,45 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #pragma unroll
     for (int j = 0; j < 8; ++j) w_dst[j] = w_active ? wkb * B_PLANE + swz(w_lds_col + j) : BN;
 
-    u32x4 xreg[XI], wreg[8], g_cur, g_nxt;
-    float ssq[XI];
-#pragma unroll
-    for (int i = 0; i < XI; ++i) ssq[i] = 0.f;
+    u32x4 wreg[8];       // eight rows of the thread's 8 x 8 block of W
+    u32x4 g_cur, g_nxt;  // gain of those eight rows: tile being staged, tile after it
 
     // Global loads of K step kt (k past the end read as zero: X by predicate, g and W by the descriptor).
-    auto load_g = [&](int kt) {  // gain of the eight rows (k values) of the thread's W block
-        const int k = kt * BK + 8 * wkb;
-        return load16(rg, (u32)k * 2u);  // past K is past the descriptor: zero
-    };
-    auto load_x = [&](int kt, int i) {
-        const int k = kt * BK + 8 * xc;
-        xreg[i] = load16(rx, (k < K) ? (u32)(((size_t)(xr0 + 32 * i) * K + k) * 2) : kOutOfRange);
-    };
-    auto load_w = [&](int kt) {
-        const u32 woff = w_lane + (u32)kt * BK * row_bytes;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) wreg[r] = load16(rw, woff + (u32)r * row_bytes);
-    };
-
+    auto load_g = [&](int kt) { return load16(rg, (u32)(kt * BK + 8 * wkb) * 2u); };
     auto load_w_row = [&](int kt, int r) {
         wreg[r] = load16(rw, w_lane + (u32)kt * BK * row_bytes + (u32)r * row_bytes);
     };
-
-    // Staging of X chunk i, in four pieces (one dword = two elements each): the squares; the fourth
-    // piece stores the 16 raw bytes to LDS.
-    auto stage_x_piece = [&](u32x4* a_stage, int i, int d) {
-        const u32 xx = xreg[i][d];
-        ssq[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, xx), __builtin_bit_cast(bf16x2, xx),
-                                                 ssq[i], false);
-        if (d == 3) a_stage[xc * A_PLANE + xr0 + 32 * i] = xreg[i];
+    // X, request i of K step kt: this wavefront moves rows 8 * wave + 32 i .. + 7 (64 K values each)
+    // into group wave + 4 i of the stage; lane l = 8 r + p fetches chunk p ^ r of its row.
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const int x_chunk = (lane & 7) ^ (lane >> 3);
+    auto request_x = [&](u32x4* a_stage, int kt, int i) {
+        const int k = kt * BK + 8 * x_chunk;
+        const u32 voff = (k < K) ? (u32)(((size_t)(xr0 + 32 * i) * K + k) * 2) : kOutOfRange;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (__attribute__((address_space(3))) void*)(a_stage + (wave_s + 4 * i) * XGS),
+                                                 16, (int)voff, 0, 0, 0);
     };
+
     // Staging of W column j of the thread's 8 x 8 block, in four pieces: piece t scales elements
     // (2t, j) and (2t + 1, j) by the gains of their rows and packs them as K neighbours (this is the
     // transposition); the fourth piece stores the 16 bytes to LDS.
     u32x4 wb;
-    auto stage_w_piece = [&](u32x4* b_stage, int j, int t, const float (&gf)[8]) {
+    auto stage_w_piece = [&](u32x4* b_stage, int j, int t) {
         const int d = j >> 1;
-        const u32 w0 = wreg[2 * t][d], w1 = wreg[2 * t + 1][d];
+        const u32 w0 = wreg[2 * t][d], w1 = wreg[2 * t + 1][d], gg = g_cur[t];
         const float e0 = (j & 1) ? bf16_hi(w0) : bf16_lo(w0);
         const float e1 = (j & 1) ? bf16_hi(w1) : bf16_lo(w1);
-        wb[t] = pack_bf16(e0 * gf[2 * t], e1 * gf[2 * t + 1]);
+        wb[t] = pack_bf16(e0 * bf16_lo(gg), e1 * bf16_hi(gg));
         if (t == 3) b_stage[w_dst[j]] = wb;
-    };
-    auto unpack_g = [&](u32x4 gg, float (&gf)[8]) {
-#pragma unroll
-        for (int d = 0; d < 4; ++d) { gf[2 * d] = bf16_lo(gg[d]); gf[2 * d + 1] = bf16_hi(gg[d]); }
     };
 
     // ---- LDS -> MFMA operand maps --------------------------------------------------------------
-    int a_slot[TM32];  // X operand: row of the tile
+    // X operand of 32-row block ib in 16-deep phase kk: row R = wm * WTM + 32 ib + l32, chunk 2 kk + lh,
+    // which sits at position (2 kk + lh) ^ (R % 8) of its row: slot a_slot[kk] + 4 * XGS * ib.
+    int a_slot[BK / 16];
 #pragma unroll
-    for (int ib = 0; ib < TM32; ++ib) a_slot[ib] = lh * A_PLANE + wm * WTM + 32 * ib + l32;
+    for (int kk = 0; kk < BK / 16; ++kk)
+        a_slot[kk] = (wm * (WTM / 8) + (l32 >> 3)) * XGS + (l32 & 7) * 8 + ((2 * kk + lh) ^ (l32 & 7));
     int b_slot[TN32];  // W operand: swizzled column of the tile
 #pragma unroll
     for (int jb = 0; jb < TN32; ++jb) {
@@ -168,11 +165,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         b_slot[jb] = lh * B_PLANE + swz(col + l32);
     }
     // Operands of 16-deep phase kk of a stage: chunk plane 2 kk + lh.
-    auto read_frags = [&](const u32x4* a_stage, const u32x4* b_stage, int kk, bf16x8 (&xf)[TM32], bf16x8 (&wf)[TN32]) {
+    auto read_frags = [&](const u32x4* a_stage, const u32x4* b_stage, int kk, u32x4 (&xf)[TM32], u32x4 (&wf)[TN32]) {
 #pragma unroll
-        for (int ib = 0; ib < TM32; ++ib) xf[ib] = __builtin_bit_cast(bf16x8, a_stage[2 * kk * A_PLANE + a_slot[ib]]);
+        for (int ib = 0; ib < TM32; ++ib) xf[ib] = a_stage[a_slot[kk] + 4 * XGS * ib];
 #pragma unroll
-        for (int jb = 0; jb < TN32; ++jb) wf[jb] = __builtin_bit_cast(bf16x8, b_stage[2 * kk * B_PLANE + b_slot[jb]]);
+        for (int jb = 0; jb < TN32; ++jb) wf[jb] = b_stage[2 * kk * B_PLANE + b_slot[jb]];
     };
 
     f32x16 acc[TN32][TM32];
@@ -182,120 +179,142 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         for (int ib = 0; ib < TM32; ++ib)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[jb][ib][v] = 0.f;
-    constexpr int MF = TM32 * TN32;   // MFMAs per 16-deep phase
-    constexpr int RD = TM32 + TN32;   // operand reads per phase
+    // Sums of squares: gram[ib][lane % 4] accumulates the squares of the K values this lane's operand
+    // registers have held for row 32 ib + lane % 32 (in the phases this wavefront is in charge of).
+    f32x4 gram[TM32];
+#pragma unroll
+    for (int ib = 0; ib < TM32; ++ib) gram[ib] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int wn_s = __builtin_amdgcn_readfirstlane(wn);
+
+    constexpr int MF = TM32 * TN32;          // MFMAs per 16-deep phase
+    constexpr int RD = TM32 + TN32;          // operand reads per phase
     constexpr int RPS = (RD + MF - 1) / MF;  // operand reads per MFMA slot (front-loaded)
 
     // One phase, as MF slots.  Slot q issues MFMA q on the operands read during the previous phase,
     // reads its share of the next operands (from `a_rd`/`b_rd`, 16-deep phase `kk_rd`), and does its
-    // share of this phase's staging of the next tile: X pieces [XP0, XP0 + NXP) (piece = 4 * chunk +
-    // dword; a finished chunk is refilled from the tile after next), W pieces [WP0, WP0 + NWP)
-    // (piece = 4 * column + K pair), and, if TAIL, the refill of the W registers in the last slots.
-    // A scheduling barrier closes every slot: the order written here is the order executed.
-    auto phase = [&](auto xp0_c, auto nxp_c, auto wp0_c, auto nwp_c, auto tail_c, const u32x4* a_rd, const u32x4* b_rd,
-                     int kk_rd, const bf16x8 (&xf)[TM32], const bf16x8 (&wf)[TN32], bf16x8 (&xf_n)[TM32],
-                     bf16x8 (&wf_n)[TN32], u32x4* a_nxt, u32x4* b_nxt, const float (&gf)[8], int kt_load) {
-        constexpr int XP0 = decltype(xp0_c)::value, NXP = decltype(nxp_c)::value, WP0 = decltype(wp0_c)::value,
-                      NWP = decltype(nwp_c)::value, TAIL = decltype(tail_c)::value;
-        constexpr int TAIL_SLOTS = TAIL ? (MF >= 8 ? 4 : 1) : 0;  // slots at the end that refill W rows
-        constexpr int WS = MF - TAIL_SLOTS > 0 ? MF - TAIL_SLOTS : 1;  // slots that stage W pieces
+    // share of this phase's work on the tiles to come: X requests [X0, X0 + NX) of the tile after next
+    // are issued into stage `a_x`; W pieces [WP0, WP0 + NWP)
+    // (piece = 4 * column + K pair) of the next tile are staged; rows [R0, R0 + NR) of
+    // the tile after next are loaded (only after the last W piece of the step: they overwrite what
+    // the pieces read).  A scheduling barrier closes every slot: the order written here is the
+    // order executed.
+    auto phase = [&](auto kk_c, auto x0_c, auto nx_c, auto wp0_c, auto nwp_c, auto r0_c, auto nr_c, const u32x4* a_rd,
+                     const u32x4* b_rd, int kk_rd, const u32x4 (&xf)[TM32], const u32x4 (&wf)[TN32],
+                     u32x4 (&xf_n)[TM32], u32x4 (&wf_n)[TN32], u32x4* a_x, u32x4* b_nxt, int kt_load) {
+        constexpr int KK = decltype(kk_c)::value, X0 = decltype(x0_c)::value, NX = decltype(nx_c)::value,
+                      WP0 = decltype(wp0_c)::value, NWP = decltype(nwp_c)::value, R0 = decltype(r0_c)::value,
+                      NR = decltype(nr_c)::value;
+        // Sums of squares on the matrix cores, in the phases this wavefront is in charge of.  Written
+        // as assembly so that these accumulators stay in ordinary vector registers: the 256
+        // accumulators of the product fill the accumulation registers, and the compiler would shuttle
+        // them out and back to make room.  The trailing wait states cover a dependent MFMA that
+        // follows at once (same accumulator, next K half) when a wavefront has few row blocks.
+        if (wn_s == (KK & 1)) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int ib = 0; ib < TM32; ++ib) {
+                    const u32x2 v = {xf[ib][2 * h], xf[ib][2 * h + 1]};
+                    if constexpr (TM32 >= 4)  // three other MFMAs separate the two uses of an accumulator
+                        asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %1, %0" : "+v"(gram[ib]) : "v"(v));
+                    else
+                        asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %1, %0\n\ts_nop 4" : "+v"(gram[ib]) : "v"(v));
+                }
+        }
 #pragma unroll
         for (int q = 0; q < MF; ++q) {
             const int jb = q / TM32, ib = q % TM32;
-            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[jb], xf[ib], acc[jb][ib], 0, 0, 0);
+            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[jb]),
+                                                                  __builtin_bit_cast(bf16x8, xf[ib]), acc[jb][ib], 0, 0, 0);
 #pragma unroll
             for (int r = q * RPS; r < (q + 1) * RPS && r < RD; ++r) {
-                if (r < TM32) xf_n[r] = __builtin_bit_cast(bf16x8, a_rd[2 * kk_rd * A_PLANE + a_slot[r]]);
-                else wf_n[r - TM32] = __builtin_bit_cast(bf16x8, b_rd[2 * kk_rd * B_PLANE + b_slot[r - TM32]]);
+                if (r < TM32) xf_n[r] = a_rd[a_slot[kk_rd] + 4 * XGS * r];
+                else wf_n[r - TM32] = b_rd[2 * kk_rd * B_PLANE + b_slot[r - TM32]];
             }
 #pragma unroll
-            for (int it = (q * NXP) / MF; it < ((q + 1) * NXP) / MF; ++it) {
-                const int i = (XP0 + it) / 4, d = (XP0 + it) % 4;
-                stage_x_piece(a_nxt, i, d);
-                if (d == 3) load_x(kt_load, i);
-            }
+            for (int it = (q * NX) / MF; it < ((q + 1) * NX) / MF; ++it) request_x(a_x, kt_load, X0 + it);
+            constexpr int TS = NR > 0 ? (MF >= 8 ? 4 : 1) : 0;  // slots at the end that refill W rows
+            constexpr int WS = MF - TS > 0 ? MF - TS : 1;       // slots that stage W pieces
             if (q < WS) {
 #pragma unroll
                 for (int it = (q * NWP) / WS; it < ((q + 1) * NWP) / WS; ++it)
-                    stage_w_piece(b_nxt, (WP0 + it) / 4, (WP0 + it) % 4, gf);
+                    stage_w_piece(b_nxt, (WP0 + it) / 4, (WP0 + it) % 4);
             }
-            if (TAIL && q >= MF - TAIL_SLOTS) {  // after the last W piece: refill the W rows
-                constexpr int RPT = TAIL_SLOTS ? 8 / TAIL_SLOTS : 0;
+            if (NR > 0 && q >= MF - TS) {
 #pragma unroll
-                for (int r = (q - (MF - TAIL_SLOTS)) * RPT; r < (q - (MF - TAIL_SLOTS) + 1) * RPT; ++r)
-                    load_w_row(kt_load, r);
+                for (int it = ((q - (MF - TS)) * NR) / TS; it < ((q - (MF - TS) + 1) * NR) / TS; ++it)
+                    load_w_row(kt_load, R0 + it);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     using std::integral_constant;
 
-    // X pieces (4 per chunk) and W pieces (4 per column) staged in phases 0, 1, 2.
-    constexpr int xp0 = 0, xp1 = 2 * XI, xp2 = 3 * XI, xp3 = 4 * XI;
-    constexpr int wp0 = 0, wp1 = 0, wp2 = 16, wp3 = 32;
+    // W pieces (4 per column) staged in phases 0, 1, 2; W rows refilled at the end of phase 2; the X
+    // requests go out in phase 3.
+    constexpr int wp1 = 4, wp2 = 18, wp3 = 32;   // W starts late: its loads have had the least time
+    constexpr int rs1 = 0, rs2 = 0, rs3 = 8;     // W rows are refilled once every piece has been staged
     const int KT = (K + BK - 1) / BK;
 
-    // ---- prologue: tile 0 to stage 0, tile 1 into registers, first operands ----------------------
-    {
-        g_cur = load_g(0);
-#pragma unroll
-        for (int i = 0; i < XI; ++i) load_x(0, i);
-        load_w(0);
-        float gf[8];
-        unpack_g(g_cur, gf);
-#pragma unroll
-        for (int i = 0; i < XI; ++i)
-#pragma unroll
-            for (int d = 0; d < 4; ++d) stage_x_piece(As, i, d);
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) stage_w_piece(Bs, j, t, gf);
-        g_cur = load_g(1);
-#pragma unroll
-        for (int i = 0; i < XI; ++i) load_x(1, i);
-        load_w(1);
-    }
-    __syncthreads();
-    bf16x8 xfA[TM32], wfA[TN32], xfB[TM32], wfB[TN32];
-    read_frags(As, Bs, 0, xfA, wfA);
+    u32x4 xfA[TM32], wfA[TN32], xfB[TM32], wfB[TN32];
 
-    for (int kt = 0; kt < KT; ++kt) {
+    // One K step: MFMAs on stage kt % 2; the next tile goes from the registers to the other stage; the
+    // tile after next goes from memory to the registers.
+    auto k_step = [&](int kt) {
         const int cur = kt & 1;
         const u32x4* a_cur = As + cur * A_SLOTS;
         const u32x4* b_cur = Bs + cur * B_SLOTS;
-        u32x4* a_nxt = As + (cur ^ 1) * A_SLOTS;
+        const u32x4* a_nxt = As + (cur ^ 1) * A_SLOTS;
+        u32x4* a_x = As + cur * A_SLOTS;  // free after the barrier: receives the X part of tile kt + 2
         u32x4* b_nxt = Bs + (cur ^ 1) * B_SLOTS;
-        float gf[8];
-        unpack_g(g_cur, gf);       // gain of tile kt + 1 (being staged)
-        g_nxt = load_g(kt + 2);    // gain of the tile after next
-
-        // Shares of the next tile per phase: X pieces [xp_p, xp_p+1), W pieces [wp_p, wp_p+1).  W starts
-        // late: its registers are refilled last, so its loads have had the least time.
-        phase(integral_constant<int, xp0>{}, integral_constant<int, xp1 - xp0>{}, integral_constant<int, wp0>{},
-              integral_constant<int, wp1 - wp0>{}, integral_constant<int, 0>{}, a_cur, b_cur, 1, xfA, wfA, xfB, wfB,
-              a_nxt, b_nxt, gf, kt + 2);
-        phase(integral_constant<int, xp1>{}, integral_constant<int, xp2 - xp1>{}, integral_constant<int, wp1>{},
-              integral_constant<int, wp2 - wp1>{}, integral_constant<int, 0>{}, a_cur, b_cur, 2, xfB, wfB, xfA, wfA,
-              a_nxt, b_nxt, gf, kt + 2);
-        phase(integral_constant<int, xp2>{}, integral_constant<int, xp3 - xp2>{}, integral_constant<int, wp2>{},
-              integral_constant<int, wp3 - wp2>{}, integral_constant<int, 1>{}, a_cur, b_cur, 3, xfA, wfA, xfB, wfB,
-              a_nxt, b_nxt, gf, kt + 2);
+        g_nxt = load_g(kt + 2);
+#define IC(v) integral_constant<int, (v)> {}
+        phase(IC(0), IC(0), IC(0), IC(0), IC(wp1), IC(0), IC(rs1), a_cur, b_cur, 1, xfA, wfA, xfB, wfB, a_x, b_nxt,
+              kt + 2);
+        phase(IC(1), IC(0), IC(0), IC(wp1), IC(wp2 - wp1), IC(rs1), IC(rs2 - rs1), a_cur, b_cur, 2, xfB, wfB, xfA, wfA,
+              a_x, b_nxt, kt + 2);
+        phase(IC(2), IC(0), IC(0), IC(wp2), IC(wp3 - wp2), IC(rs2), IC(rs3 - rs2), a_cur, b_cur, 3, xfA, wfA, xfB, wfB,
+              a_x, b_nxt, kt + 2);
         __syncthreads();  // the next tile is complete in LDS; nobody reads the current stage any more
-        phase(integral_constant<int, 0>{}, integral_constant<int, 0>{}, integral_constant<int, 0>{},
-              integral_constant<int, 0>{}, integral_constant<int, 0>{}, a_nxt, b_nxt, 0, xfB, wfB, xfA, wfA, a_nxt,
-              b_nxt, gf, kt + 2);
+        phase(IC(3), IC(0), IC(XI), IC(0), IC(0), IC(0), IC(0), a_nxt, b_nxt, 0, xfB, wfB, xfA, wfA,
+              a_x, b_nxt, kt + 2);
+#undef IC
         g_cur = g_nxt;
-    }
+    };
 
-    // ---- 1/rms per row: the eight threads that shared a row combine their partial sums -----------
+    // ---- prologue: X tiles 0 and 1 requested, W tile 0 staged, W tile 1 into registers -------------
 #pragma unroll
-    for (int i = 0; i < XI; ++i) {
-        float s = ssq[i];
-        s += __shfl_xor(s, 1, 64);
-        s += __shfl_xor(s, 2, 64);
-        s += __shfl_xor(s, 4, 64);
-        if (xc == 0) rscale[xr0 + 32 * i] = __builtin_amdgcn_rsqf(s / (float)K + eps);
+    for (int i = 0; i < XI; ++i) request_x(As, 0, i);
+#pragma unroll
+    for (int i = 0; i < XI; ++i) request_x(As + A_SLOTS, 1, i);
+    g_cur = load_g(0);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) load_w_row(0, r);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) stage_w_piece(Bs, j, t);
+    g_cur = load_g(1);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) load_w_row(1, r);
+    __syncthreads();
+    read_frags(As, Bs, 0, xfA, wfA);
+
+    for (int kt = 0; kt < KT; ++kt) k_step(kt);
+
+    // ---- 1/rms per row: four partial sums per row (two K halves of the operand x two wavefronts) ----
+    __syncthreads();  // the stages are free: reuse the first one for the partials
+    float* ss_part = (float*)As;  // [2 wn][2 lh][BM]
+#pragma unroll
+    for (int ib = 0; ib < TM32; ++ib) {
+        const int sel = lane & 3;
+        const float v = sel == 0 ? gram[ib][0] : sel == 1 ? gram[ib][1] : sel == 2 ? gram[ib][2] : gram[ib][3];
+        ss_part[(wn * 2 + lh) * BM + wm * WTM + 32 * ib + l32] = v;
+    }
+    __syncthreads();
+    if (tid < BM) {
+        const float s = ss_part[tid] + ss_part[BM + tid] + ss_part[2 * BM + tid] + ss_part[3 * BM + tid];
+        rscale[tid] = __builtin_amdgcn_rsqf(s / (float)K + eps);
     }
     __syncthreads();
 
@@ -330,7 +349,7 @@ template <int BM, int BN, bool GATED>
 static hipError_t launch_tile(const Call& c) {
     constexpr int CW = GATED ? BN / 2 : BN;
     const int tiles_m = (c.M + BM - 1) / BM, tiles_n = (c.N + CW - 1) / CW;
-    const size_t lds = (size_t)(2 * KCH * (BM + PAD) + 2 * KCH * (BN + PAD)) * 16 + (size_t)BM * 4;
+    const size_t lds = (size_t)(2 * (BM / 8) * XGS + 2 * KCH * (BN + PAD)) * 16 + (size_t)BM * 4;
     auto kern = prefill_kernel<BM, BN, GATED>;
     static std::atomic<uint64_t> opted{0};
     if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
