@@ -42,6 +42,10 @@
 #include "device_utils.h"
 #include "prism_internal.h"
 
+#ifndef PREFILL_P3
+#define PREFILL_P3 8
+#endif
+
 namespace prism {
 
 namespace {
@@ -81,14 +85,32 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, lh = lane >> 5;
 
-    // Tile order: consecutive workgroups share a column tile of W and walk down the rows.
-    const int tile = blockIdx.x;
-    const int tm = tile % tiles_m, tn = tile / tiles_m;
+    // Tile order.  Workgroups are dealt to the 8 XCDs round-robin and each XCD has its own L2, so
+    // the 32 workgroups that run together on one XCD should share as much of X and W as they can: a
+    // block of 4 row tiles x 8 column tiles needs 12 tile streams instead of the 18 or more of a strip.
+    //   1. position: within each full round of 256 workgroups, XCD x (ids = x mod 8) takes the 32
+    //      consecutive positions 32 x .. 32 x + 31 (a partial last round is split into 8 equal runs,
+    //      its remainder keeps the identity);
+    //   2. tile: positions fill bands of 8 column tiles row by row, so 32 consecutive positions are
+    //      such a 4 x 8 block.
+    int pos = blockIdx.x;
+    {
+        const int total = tiles_m * tiles_n, full = total & ~255;
+        if (pos < full) {
+            pos = (pos & ~255) + (pos & 7) * 32 + ((pos & 255) >> 3);
+        } else {
+            const int run = (total - full) >> 3, b = pos - full;
+            if (b < 8 * run) pos = full + (b & 7) * run + (b >> 3);
+        }
+    }
+    const int band = pos / (8 * tiles_m), in_band = pos % (8 * tiles_m);
+    const int band_w = tiles_n - 8 * band < 8 ? tiles_n - 8 * band : 8;
+    const int tm = in_band / band_w, tn = 8 * band + in_band % band_w;
     const int m0 = tm * BM, n0 = tn * CW;
 
     // ---- global -> register staging maps -------------------------------------------------------
-    // X: thread t loads row (t / 8 + 32 i), K chunk (t % 8) of the stage.
-    const int xr0 = tid >> 3, xc = tid & 7;
+    // X: thread t requests row (t / 8 + 32 i) of the stage.
+    const int xr0 = tid >> 3;
     const size_t x_first = (size_t)m0 * K;
     const size_t x_left = ((size_t)M * K - x_first) * 2;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + x_first, (u32)(x_left < 0x7FFFFFFFull ? x_left : 0x7FFFFFFFull));
@@ -113,14 +135,21 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #pragma unroll
     for (int j = 0; j < 8; ++j) w_dst[j] = w_active ? wkb * B_PLANE + swz(w_lds_col + j) : BN;
 
-    u32x4 wreg[8];       // eight rows of the thread's 8 x 8 block of W
-    u32x4 g_cur, g_nxt;  // gain of those eight rows: tile being staged, tile after it
+    // Two register sets for W: while one is being staged into LDS, the other already holds the tile
+    // after it, so a tile's loads have more than a whole K step to arrive.
+    struct WSet {
+        u32x4 w[8];  // eight rows of the thread's 8 x 8 block of W
+        u32x4 g;     // gain of those eight rows
+    };
+    WSet ws_a, ws_b;
 
     // Global loads of K step kt (k past the end read as zero: X by predicate, g and W by the descriptor).
-    auto load_g = [&](int kt) { return load16(rg, (u32)(kt * BK + 8 * wkb) * 2u); };
-    auto load_w_row = [&](int kt, int r) {
-        wreg[r] = load16(rw, w_lane + (u32)kt * BK * row_bytes + (u32)r * row_bytes);
+    // Load 0 of a set is the gain, loads 1..8 are the rows.
+    auto load_w = [&](WSet& s, int kt, int i) {
+        if (i == 0) s.g = load16(rg, (u32)(kt * BK + 8 * wkb) * 2u);
+        else s.w[i - 1] = load16(rw, w_lane + (u32)kt * BK * row_bytes + (u32)(i - 1) * row_bytes);
     };
+    constexpr int NWL = 9;  // loads per set
     // X, request i of K step kt: this wavefront moves rows 8 * wave + 32 i .. + 7 (64 K values each)
     // into group wave + 4 i of the stage; lane l = 8 r + p fetches chunk p ^ r of its row.
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -136,9 +165,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     // (2t, j) and (2t + 1, j) by the gains of their rows and packs them as K neighbours (this is the
     // transposition); the fourth piece stores the 16 bytes to LDS.
     u32x4 wb;
-    auto stage_w_piece = [&](u32x4* b_stage, int j, int t) {
+    auto stage_w_piece = [&](const WSet& s, u32x4* b_stage, int j, int t) {
         const int d = j >> 1;
-        const u32 w0 = wreg[2 * t][d], w1 = wreg[2 * t + 1][d], gg = g_cur[t];
+        const u32 w0 = s.w[2 * t][d], w1 = s.w[2 * t + 1][d], gg = s.g[t];
         const float e0 = (j & 1) ? bf16_hi(w0) : bf16_lo(w0);
         const float e1 = (j & 1) ? bf16_hi(w1) : bf16_lo(w1);
         wb[t] = pack_bf16(e0 * bf16_lo(gg), e1 * bf16_hi(gg));
@@ -192,18 +221,18 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 
     // One phase, as MF slots.  Slot q issues MFMA q on the operands read during the previous phase,
     // reads its share of the next operands (from `a_rd`/`b_rd`, 16-deep phase `kk_rd`), and does its
-    // share of this phase's work on the tiles to come: X requests [X0, X0 + NX) of the tile after next
-    // are issued into stage `a_x`; W pieces [WP0, WP0 + NWP)
-    // (piece = 4 * column + K pair) of the next tile are staged; rows [R0, R0 + NR) of
-    // the tile after next are loaded (only after the last W piece of the step: they overwrite what
-    // the pieces read).  A scheduling barrier closes every slot: the order written here is the
-    // order executed.
-    auto phase = [&](auto kk_c, auto x0_c, auto nx_c, auto wp0_c, auto nwp_c, auto r0_c, auto nr_c, const u32x4* a_rd,
-                     const u32x4* b_rd, int kk_rd, const u32x4 (&xf)[TM32], const u32x4 (&wf)[TN32],
-                     u32x4 (&xf_n)[TM32], u32x4 (&wf_n)[TN32], u32x4* a_x, u32x4* b_nxt, int kt_load) {
-        constexpr int KK = decltype(kk_c)::value, X0 = decltype(x0_c)::value, NX = decltype(nx_c)::value,
-                      WP0 = decltype(wp0_c)::value, NWP = decltype(nwp_c)::value, R0 = decltype(r0_c)::value,
-                      NR = decltype(nr_c)::value;
+    // share of this phase's work on the tiles to come: NX X requests of K step `kt_x` go into stage
+    // `a_x`, then NL loads of K step `kt_w` go into the set `w_ld` (requests before loads: a wait for
+    // the requests then leaves the loads in flight); W pieces [WP0, WP0 + NWP) (piece = 4 * column +
+    // K pair) of the set `w_st` are staged into `b_st`.  A scheduling barrier closes every slot: the
+    // order written here is the order executed.
+    auto phase = [&](auto kk_c, auto nx_c, auto nl_c, auto wp0_c, auto nwp_c, const u32x4* a_rd, const u32x4* b_rd,
+                     int kk_rd, const u32x4 (&xf)[TM32], const u32x4 (&wf)[TN32], u32x4 (&xf_n)[TM32],
+                     u32x4 (&wf_n)[TN32], u32x4* a_x, int kt_x, WSet& w_ld, int kt_w, const WSet& w_st,
+                     u32x4* b_st) {
+        constexpr int KK = decltype(kk_c)::value, NX = decltype(nx_c)::value, NL = decltype(nl_c)::value,
+                      WP0 = decltype(wp0_c)::value, NWP = decltype(nwp_c)::value;
+        constexpr int NI = NX + NL;  // global-memory instructions of this phase, spread over its slots
         // Sums of squares on the matrix cores, in the phases this wavefront is in charge of.  Written
         // as assembly so that these accumulators stay in ordinary vector registers: the 256
         // accumulators of the product fill the accumulation registers, and the compiler would shuttle
@@ -232,75 +261,81 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
                 else wf_n[r - TM32] = b_rd[2 * kk_rd * B_PLANE + b_slot[r - TM32]];
             }
 #pragma unroll
-            for (int it = (q * NX) / MF; it < ((q + 1) * NX) / MF; ++it) request_x(a_x, kt_load, X0 + it);
-            constexpr int TS = NR > 0 ? (MF >= 8 ? 4 : 1) : 0;  // slots at the end that refill W rows
-            constexpr int WS = MF - TS > 0 ? MF - TS : 1;       // slots that stage W pieces
-            if (q < WS) {
-#pragma unroll
-                for (int it = (q * NWP) / WS; it < ((q + 1) * NWP) / WS; ++it)
-                    stage_w_piece(b_nxt, (WP0 + it) / 4, (WP0 + it) % 4);
+            for (int i = 0; i < NI; ++i) {
+                if ((i * MF) / (NI > 0 ? NI : 1) != q) continue;
+                if (i < NX) request_x(a_x, kt_x, i);
+                else load_w(w_ld, kt_w, i - NX);
             }
-            if (NR > 0 && q >= MF - TS) {
 #pragma unroll
-                for (int it = ((q - (MF - TS)) * NR) / TS; it < ((q - (MF - TS) + 1) * NR) / TS; ++it)
-                    load_w_row(kt_load, R0 + it);
-            }
+            for (int it = (q * NWP) / MF; it < ((q + 1) * NWP) / MF; ++it)
+                stage_w_piece(w_st, b_st, (WP0 + it) / 4, (WP0 + it) % 4);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
     using std::integral_constant;
 
-    // W pieces (4 per column) staged in phases 0, 1, 2; W rows refilled at the end of phase 2; the X
-    // requests go out in phase 3.
-    constexpr int wp1 = 4, wp2 = 18, wp3 = 32;   // W starts late: its loads have had the least time
-    constexpr int rs1 = 0, rs2 = 0, rs3 = 8;     // W rows are refilled once every piece has been staged
+    // W pieces (4 per column, 32 per tile): the first P3 are staged a step early, in phase 3 (after the
+    // barrier, into the stage just vacated); the rest in phases 0, 1, 2.
+    constexpr int P3 = PREFILL_P3;
+    constexpr int wp1 = P3 + (32 - P3) / 3, wp2 = P3 + 2 * (32 - P3) / 3;
     const int KT = (K + BK - 1) / BK;
+    const int KT2 = (KT + 1) & ~1;  // the loop body holds two steps (one per register set); an odd
+                                    // count is padded with a step whose X and W read as zero
 
     u32x4 xfA[TM32], wfA[TN32], xfB[TM32], wfB[TN32];
 
-    // One K step: MFMAs on stage kt % 2; the next tile goes from the registers to the other stage; the
-    // tile after next goes from memory to the registers.
-    auto k_step = [&](int kt) {
+    // One K step: MFMAs on stage kt % 2.  On entry `ws` holds W of step kt + 1, its first P3 pieces
+    // already in the other stage, and `wo` holds W of step kt + 2.  On exit `ws` is being refilled with
+    // step kt + 3 and the first P3 pieces of `wo` are staged.
+    auto k_step = [&](int kt, WSet& ws, WSet& wo) {
         const int cur = kt & 1;
         const u32x4* a_cur = As + cur * A_SLOTS;
         const u32x4* b_cur = Bs + cur * B_SLOTS;
         const u32x4* a_nxt = As + (cur ^ 1) * A_SLOTS;
-        u32x4* a_x = As + cur * A_SLOTS;  // free after the barrier: receives the X part of tile kt + 2
+        u32x4* a_x = As + cur * A_SLOTS;  // free after the barrier: receive the parts of tile kt + 2
+        u32x4* b_x = Bs + cur * B_SLOTS;
         u32x4* b_nxt = Bs + (cur ^ 1) * B_SLOTS;
-        g_nxt = load_g(kt + 2);
 #define IC(v) integral_constant<int, (v)> {}
-        phase(IC(0), IC(0), IC(0), IC(0), IC(wp1), IC(0), IC(rs1), a_cur, b_cur, 1, xfA, wfA, xfB, wfB, a_x, b_nxt,
-              kt + 2);
-        phase(IC(1), IC(0), IC(0), IC(wp1), IC(wp2 - wp1), IC(rs1), IC(rs2 - rs1), a_cur, b_cur, 2, xfB, wfB, xfA, wfA,
-              a_x, b_nxt, kt + 2);
-        phase(IC(2), IC(0), IC(0), IC(wp2), IC(wp3 - wp2), IC(rs2), IC(rs3 - rs2), a_cur, b_cur, 3, xfA, wfA, xfB, wfB,
-              a_x, b_nxt, kt + 2);
+        phase(IC(0), IC(0), IC(0), IC(P3), IC(wp1 - P3), a_cur, b_cur, 1, xfA, wfA, xfB, wfB, a_x, 0, ws, 0, ws, b_nxt);
+        phase(IC(1), IC(0), IC(0), IC(wp1), IC(wp2 - wp1), a_cur, b_cur, 2, xfB, wfB, xfA, wfA, a_x, 0, ws, 0, ws, b_nxt);
+        phase(IC(2), IC(0), IC(0), IC(wp2), IC(32 - wp2), a_cur, b_cur, 3, xfA, wfA, xfB, wfB, a_x, 0, ws, 0, ws, b_nxt);
+        // The X part of tile kt + 1 was requested one step ago; the only global-memory instructions
+        // issued since are the NWL loads of a W set, and loads complete in order.
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NWL) : "memory");
         __syncthreads();  // the next tile is complete in LDS; nobody reads the current stage any more
-        phase(IC(3), IC(0), IC(XI), IC(0), IC(0), IC(0), IC(0), a_nxt, b_nxt, 0, xfB, wfB, xfA, wfA,
-              a_x, b_nxt, kt + 2);
+        phase(IC(3), IC(XI), IC(NWL), IC(0), IC(P3), a_nxt, b_nxt, 0, xfB, wfB, xfA, wfA, a_x, kt + 2, ws, kt + 3, wo, b_x);
 #undef IC
-        g_cur = g_nxt;
     };
 
-    // ---- prologue: X tiles 0 and 1 requested, W tile 0 staged, W tile 1 into registers -------------
+    // ---- prologue ----------------------------------------------------------------------------------
+    // The global-memory instructions are issued in the order the loop issues them (requests of a
+    // tile, then the loads of the W set two tiles later), so that the wait counts computed for the loop
+    // body hold on entry as well: X 0, W 0, W 1, [stage W 0], X 1, W 2.
 #pragma unroll
     for (int i = 0; i < XI; ++i) request_x(As, 0, i);
 #pragma unroll
+    for (int i = 0; i < NWL; ++i) load_w(ws_b, 0, i);
+#pragma unroll
+    for (int i = 0; i < NWL; ++i) load_w(ws_a, 1, i);
+#pragma unroll
+    for (int p = 0; p < 32; ++p) stage_w_piece(ws_b, Bs, p / 4, p % 4);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
     for (int i = 0; i < XI; ++i) request_x(As + A_SLOTS, 1, i);
-    g_cur = load_g(0);
 #pragma unroll
-    for (int r = 0; r < 8; ++r) load_w_row(0, r);
+    for (int i = 0; i < NWL; ++i) load_w(ws_b, 2, i);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) stage_w_piece(Bs, j, t);
-    g_cur = load_g(1);
-#pragma unroll
-    for (int r = 0; r < 8; ++r) load_w_row(1, r);
+    for (int p = 0; p < P3; ++p) stage_w_piece(ws_a, Bs + B_SLOTS, p / 4, p % 4);
+    // X of tile 0 is older than everything but its own requests.
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * NWL + XI) : "memory");
     __syncthreads();
     read_frags(As, Bs, 0, xfA, wfA);
 
-    for (int kt = 0; kt < KT; ++kt) k_step(kt);
+    for (int kt = 0; kt < KT2; kt += 2) {
+        k_step(kt, ws_a, ws_b);
+        k_step(kt + 1, ws_b, ws_a);
+    }
 
     // ---- 1/rms per row: four partial sums per row (two K halves of the operand x two wavefronts) ----
     __syncthreads();  // the stages are free: reuse the first one for the partials
