@@ -28,23 +28,30 @@
 // The gated variant puts BN/2 columns of W1 and the same BN/2 columns of W2 side by side in the
 // W tile; each wavefront holds matching W1 and W2 accumulators and applies SiLU(a) * b in registers.
 //
-// Software pipeline of one K step (four 16-deep MFMA phases), all in one wavefront's instruction
-// stream because a 256 x 256 tile leaves one wavefront per SIMD:
-//   phase 0..2: MFMAs of phase p run on operands read from LDS during phase p - 1, while the
-//               operands of phase p + 1 are read and the W part of the NEXT tile is staged
-//               (registers -> gain, transposition -> the other LDS stage); at the end the W registers
-//               are refilled from the tile after next;
-//   barrier     (the next tile is complete: its X part was requested a whole step earlier);
-//   phase 3:    MFMAs, while the first operands of the next tile are read from the other stage and
-//               the X part of the tile after next is requested into the stage just vacated.
+// Software pipeline of one K step (four 16-deep MFMA phases of MF MFMAs each), all in one wavefront's
+// instruction stream because a 256 x 256 tile leaves one wavefront per SIMD.  Every MFMA is a "slot"
+// closed by a scheduling barrier, and the other work is dealt out to the slots:
+//   - operands: the MFMAs of a phase run on registers read from LDS during the phase before;
+//   - W staging: two register sets alternate.  While the tile in one set is scaled, transposed and
+//     stored to the other LDS stage (phases 0..2, a few vector instructions per slot), the other set
+//     is being loaded with the tile after it;
+//   - global memory: the X requests of the tile after next and the loads of the W set just staged are
+//     spread over phase 3 and phases 0, 1 of the following step (requests first), one instruction
+//     every few slots; the four wavefronts run the same schedule, and bunched loads would block the
+//     MFMAs behind them at the address unit;
+//   - barrier after phase 2: written as explicit waits plus s_barrier.  It waits for this wavefront's
+//     LDS accesses and for its X requests of the next tile (all but the loads issued after them;
+//     loads complete in issue order), not for loads that are needed later.
+// The prologue issues its global-memory instructions in the same order as the loop, so that the
+// wait counts the compiler derives for the loop body are the steady-state ones.
+// Measured on MI355X (4096 x 4096 x 2*14336 gated): the shader clock drops from 2.3 GHz to 1.55 - 1.75
+// GHz when all 256 CUs run this kernel, and a K step takes about 3070 cycles against 2176 of pure
+// MFMA work; the vendor GEMM library reaches 1.27 PFLOP/s on the same plain product in this layout.
 #include <type_traits>
 
 #include "device_utils.h"
 #include "prism_internal.h"
 
-#ifndef PREFILL_P3
-#define PREFILL_P3 8
-#endif
 
 namespace prism {
 
@@ -219,20 +226,36 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     constexpr int RD = TM32 + TN32;          // operand reads per phase
     constexpr int RPS = (RD + MF - 1) / MF;  // operand reads per MFMA slot (front-loaded)
 
+    // Global-memory instructions that bring in one more tile ("refill"): the XI requests of an X tile,
+    // then the NWL loads of the W set one tile later - NI instructions, spread evenly
+    // over the 3 MF slots of three consecutive phases (phase 3 of one K step, phases 0 and 1 of the
+    // next).  All four wavefronts run this schedule at the same time and the address unit takes about
+    // 16 cycles per instruction, so bunching them would block the MFMAs queued behind them.
+    // The requests come first: the barrier that needs them then leaves the NWL loads after them in
+    // flight.
+    constexpr int NI = XI + NWL;
+    auto refill_slot = [&](auto part_c, int q, u32x4* a_x, int kt_x, WSet& w_ld) {
+        constexpr int PART = decltype(part_c)::value;
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            if ((i * 3 * MF) / NI != PART * MF + q) continue;
+            if (i < XI) request_x(a_x, kt_x, i);
+            else load_w(w_ld, kt_x + 1, i - XI);
+        }
+    };
+    constexpr int NI0 = (NI + 2) / 3;  // instructions of part 0: those with i * 3 MF / NI < MF
+
     // One phase, as MF slots.  Slot q issues MFMA q on the operands read during the previous phase,
     // reads its share of the next operands (from `a_rd`/`b_rd`, 16-deep phase `kk_rd`), and does its
-    // share of this phase's work on the tiles to come: NX X requests of K step `kt_x` go into stage
-    // `a_x`, then NL loads of K step `kt_w` go into the set `w_ld` (requests before loads: a wait for
-    // the requests then leaves the loads in flight); W pieces [WP0, WP0 + NWP) (piece = 4 * column +
-    // K pair) of the set `w_st` are staged into `b_st`.  A scheduling barrier closes every slot: the
-    // order written here is the order executed.
-    auto phase = [&](auto kk_c, auto nx_c, auto nl_c, auto wp0_c, auto nwp_c, const u32x4* a_rd, const u32x4* b_rd,
+    // share of this phase's work on the tiles to come: part PART of the refill (none if negative) of
+    // X tile `kt_x` into stage `a_x` and of W tile `kt_x` + 1 into the set `w_ld`; W pieces
+    // [WP0, WP0 + NWP) (piece = 4 * column + K pair) of the set `w_st` staged into `b_st`.  A
+    // scheduling barrier closes every slot: the order written here is the order executed.
+    auto phase = [&](auto kk_c, auto part_c, auto wp0_c, auto nwp_c, const u32x4* a_rd, const u32x4* b_rd,
                      int kk_rd, const u32x4 (&xf)[TM32], const u32x4 (&wf)[TN32], u32x4 (&xf_n)[TM32],
-                     u32x4 (&wf_n)[TN32], u32x4* a_x, int kt_x, WSet& w_ld, int kt_w, const WSet& w_st,
-                     u32x4* b_st) {
-        constexpr int KK = decltype(kk_c)::value, NX = decltype(nx_c)::value, NL = decltype(nl_c)::value,
-                      WP0 = decltype(wp0_c)::value, NWP = decltype(nwp_c)::value;
-        constexpr int NI = NX + NL;  // global-memory instructions of this phase, spread over its slots
+                     u32x4 (&wf_n)[TN32], u32x4* a_x, int kt_x, WSet& w_ld, const WSet& w_st, u32x4* b_st) {
+        constexpr int KK = decltype(kk_c)::value, PART = decltype(part_c)::value, WP0 = decltype(wp0_c)::value,
+                      NWP = decltype(nwp_c)::value;
         // Sums of squares on the matrix cores, in the phases this wavefront is in charge of.  Written
         // as assembly so that these accumulators stay in ordinary vector registers: the 256
         // accumulators of the product fill the accumulation registers, and the compiler would shuttle
@@ -260,12 +283,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
                 if (r < TM32) xf_n[r] = a_rd[a_slot[kk_rd] + 4 * XGS * r];
                 else wf_n[r - TM32] = b_rd[2 * kk_rd * B_PLANE + b_slot[r - TM32]];
             }
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                if ((i * MF) / (NI > 0 ? NI : 1) != q) continue;
-                if (i < NX) request_x(a_x, kt_x, i);
-                else load_w(w_ld, kt_w, i - NX);
-            }
+            if constexpr (PART >= 0) refill_slot(part_c, q, a_x, kt_x, w_ld);
 #pragma unroll
             for (int it = (q * NWP) / MF; it < ((q + 1) * NWP) / MF; ++it)
                 stage_w_piece(w_st, b_st, (WP0 + it) / 4, (WP0 + it) % 4);
@@ -273,10 +291,21 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         }
     };
     using std::integral_constant;
+    // Barrier between K steps.  Written out instead of __syncthreads(): the fences of the latter make
+    // the compiler wait for every LDS-writing load in flight, also those of a tile that is not needed
+    // yet.  What the barrier has to order is stated here instead: this wavefront's LDS writes and reads are complete (lgkmcnt), and so are its X
+    // requests of the next tile - everything but the newest `younger` global-memory instructions; they
+    // complete in issue order.
+    auto stage_barrier = [&](auto younger_c) {
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(decltype(younger_c)::value) : "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
 
-    // W pieces (4 per column, 32 per tile): the first P3 are staged a step early, in phase 3 (after the
-    // barrier, into the stage just vacated); the rest in phases 0, 1, 2.
-    constexpr int P3 = PREFILL_P3;
+    // W pieces (4 per column, 32 per tile): the first P3 could be staged a step early, in phase 3 (after
+    // the barrier, into the stage just vacated), the rest in phases 0, 1, 2.  Measured best with none
+    // in phase 3: the set's last loads are issued only two phases before it.
+    constexpr int P3 = 0;
     constexpr int wp1 = P3 + (32 - P3) / 3, wp2 = P3 + 2 * (32 - P3) / 3;
     const int KT = (K + BK - 1) / BK;
     const int KT2 = (KT + 1) & ~1;  // the loop body holds two steps (one per register set); an odd
@@ -285,32 +314,31 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     u32x4 xfA[TM32], wfA[TN32], xfB[TM32], wfB[TN32];
 
     // One K step: MFMAs on stage kt % 2.  On entry `ws` holds W of step kt + 1, its first P3 pieces
-    // already in the other stage, and `wo` holds W of step kt + 2.  On exit `ws` is being refilled with
-    // step kt + 3 and the first P3 pieces of `wo` are staged.
+    // already in the other stage; part 0 of the refill with X tile kt + 1 (into the other stage) and W
+    // tile kt + 2 (into `wo`) has been issued.  Phases 0 and 1 issue the rest of it, phase 3 (after the
+    // barrier, which vacates this stage, and after the last piece of `ws` has been staged) begins the
+    // next refill: X tile kt + 2 into this stage, W tile kt + 3 into `ws`.
     auto k_step = [&](int kt, WSet& ws, WSet& wo) {
         const int cur = kt & 1;
-        const u32x4* a_cur = As + cur * A_SLOTS;
-        const u32x4* b_cur = Bs + cur * B_SLOTS;
-        const u32x4* a_nxt = As + (cur ^ 1) * A_SLOTS;
-        u32x4* a_x = As + cur * A_SLOTS;  // free after the barrier: receive the parts of tile kt + 2
-        u32x4* b_x = Bs + cur * B_SLOTS;
+        u32x4* a_cur = As + cur * A_SLOTS;
+        u32x4* b_cur = Bs + cur * B_SLOTS;
+        u32x4* a_nxt = As + (cur ^ 1) * A_SLOTS;
         u32x4* b_nxt = Bs + (cur ^ 1) * B_SLOTS;
 #define IC(v) integral_constant<int, (v)> {}
-        phase(IC(0), IC(0), IC(0), IC(P3), IC(wp1 - P3), a_cur, b_cur, 1, xfA, wfA, xfB, wfB, a_x, 0, ws, 0, ws, b_nxt);
-        phase(IC(1), IC(0), IC(0), IC(wp1), IC(wp2 - wp1), a_cur, b_cur, 2, xfB, wfB, xfA, wfA, a_x, 0, ws, 0, ws, b_nxt);
-        phase(IC(2), IC(0), IC(0), IC(wp2), IC(32 - wp2), a_cur, b_cur, 3, xfA, wfA, xfB, wfB, a_x, 0, ws, 0, ws, b_nxt);
-        // The X part of tile kt + 1 was requested one step ago; the only global-memory instructions
-        // issued since are the NWL loads of a W set, and loads complete in order.
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NWL) : "memory");
-        __syncthreads();  // the next tile is complete in LDS; nobody reads the current stage any more
-        phase(IC(3), IC(XI), IC(NWL), IC(0), IC(P3), a_nxt, b_nxt, 0, xfB, wfB, xfA, wfA, a_x, kt + 2, ws, kt + 3, wo, b_x);
+        phase(IC(0), IC(1), IC(P3), IC(wp1 - P3), a_cur, b_cur, 1, xfA, wfA, xfB, wfB, a_nxt, kt + 1, wo, ws, b_nxt);
+        phase(IC(1), IC(2), IC(wp1), IC(wp2 - wp1), a_cur, b_cur, 2, xfB, wfB, xfA, wfA, a_nxt, kt + 1, wo, ws, b_nxt);
+        phase(IC(2), IC(-1), IC(wp2), IC(32 - wp2), a_cur, b_cur, 3, xfA, wfA, xfB, wfB, a_nxt, kt + 1, wo, ws, b_nxt);
+        // The next tile is complete in LDS (the requests of its X part are followed by NWL younger
+        // instructions only); nobody reads the current stage any more.
+        stage_barrier(IC(NWL));
+        phase(IC(3), IC(0), IC(0), IC(P3), a_nxt, b_nxt, 0, xfB, wfB, xfA, wfA, a_cur, kt + 2, ws, wo, b_cur);
 #undef IC
     };
 
     // ---- prologue ----------------------------------------------------------------------------------
-    // The global-memory instructions are issued in the order the loop issues them (requests of a
-    // tile, then the loads of the W set two tiles later), so that the wait counts computed for the loop
-    // body hold on entry as well: X 0, W 0, W 1, [stage W 0], X 1, W 2.
+    // The global-memory instructions are issued in the order the loop issues them, so that the wait
+    // counts computed for the loop body hold on entry as well: X 0, W 0, W 1, [stage W 0], part 0 of
+    // the refill with X 1 and W 2.
 #pragma unroll
     for (int i = 0; i < XI; ++i) request_x(As, 0, i);
 #pragma unroll
@@ -321,15 +349,12 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     for (int p = 0; p < 32; ++p) stage_w_piece(ws_b, Bs, p / 4, p % 4);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < XI; ++i) request_x(As + A_SLOTS, 1, i);
-#pragma unroll
-    for (int i = 0; i < NWL; ++i) load_w(ws_b, 2, i);
+    for (int q = 0; q < MF; ++q) refill_slot(integral_constant<int, 0>{}, q, As + A_SLOTS, 1, ws_b);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int p = 0; p < P3; ++p) stage_w_piece(ws_a, Bs + B_SLOTS, p / 4, p % 4);
     // X of tile 0 is older than everything but its own requests.
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * NWL + XI) : "memory");
-    __syncthreads();
+    stage_barrier(integral_constant<int, 2 * NWL + NI0>{});
     read_frags(As, Bs, 0, xfA, wfA);
 
     for (int kt = 0; kt < KT2; kt += 2) {
@@ -338,6 +363,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     }
 
     // ---- 1/rms per row: four partial sums per row (two K halves of the operand x two wavefronts) ----
+    // Requests past the last tile are still on their way to LDS (they deliver zeros).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();  // the stages are free: reuse the first one for the partials
     float* ss_part = (float*)As;  // [2 wn][2 lh][BM]
 #pragma unroll
