@@ -185,6 +185,27 @@ def cpu_baseline(runner):
     }
 
 
+COPY_CALIBRATION_BYTES = 256 << 20
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch of the workload's kernel, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    and recorded in profiles/hbm_traffic.md (one line per workload: `traffic <workload> fetch_bytes=...
+    write_bytes=...`).  bench.py cannot collect counters itself; None if no measurement is recorded."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.md")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 4 and f[0] == "traffic" and f[1] == workload:
+                kv = dict(x.split("=") for x in f[2:] if "=" in x)
+                return {"fetch_bytes": float(kv["fetch_bytes"]), "write_bytes": float(kv["write_bytes"]),
+                        "bytes": float(kv["fetch_bytes"]) + float(kv["write_bytes"]),
+                        "source": "profiles/hbm_traffic.md (rocprofv3 --pmc, scaled by a copy of known size)"}
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -193,6 +214,9 @@ def main():
     ap.add_argument("--workload", type=int, default=1, help="benchmark configuration index (1..4)")
     ap.add_argument("--no-extra", action="store_true", help="time only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch one device-to-device copy of 256 MiB (outside the timed region): under "
+                         "rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE reading calibrates the counters")
     a = ap.parse_args()
     if a.gpus != 1:
         log("bench.py measures one GPU: this build has no multi-GPU path (no collectives, no sharding); "
@@ -204,6 +228,15 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    if a.calibrate_copy:
+        src = torch.full((COPY_CALIBRATION_BYTES // 2,), 1.0, dtype=torch.bfloat16, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log(f"[bench] calibration copy: {COPY_CALIBRATION_BYTES} bytes read and as many written")
+        del src, dst
+
     head, runner = measure(a.workload, a.steps, a.warmup)
     out = {
         "metric": METRIC, "value": head["value"], "unit": head["unit"], "n_gpus": 1, "steps": a.steps,
@@ -212,7 +245,7 @@ def main():
         "config": {"workload": head["workload"], "M": head["M"], "K": head["K"], "N": head["N"],
                    "gated": head["gated"], "plan": head["plan"], "buffer_sets": head["buffer_sets"]},
         "roofline": {"bound": head["bound"], "achieved": head["achieved"], "peak": head["peak"],
-                     "unit": head["unit"], "frac": head["frac"], "traffic": None,
+                     "unit": head["unit"], "frac": head["frac"], "traffic": measured_traffic(head["workload"]),
                      "kernel": "prism::decode_kernel" if head["bound"] == "hbm" else "prism::prefill_kernel",
                      "kernel_ms_per_launch": head["kernel_ms"],
                      "timing": "HIP events around the timed region on the launch stream, divided by the launches"},

@@ -173,14 +173,17 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         if (gi == 1) __syncthreads();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
+            // A lane owns 32 bytes of a row; lanes c and c + 8 are 256 bytes apart, the same banks.
+            // The upper eight write their second half first, so that one store instruction covers
+            // 16 different 16-byte bank groups.
             float* dst = red + (wave * 16 + (4 * q + i)) * TN + 8 * c;
-            if (gi == 0) {
-                *(f32x4*)(dst) = f32x4{acc1[0][i], acc1[1][i], acc1[2][i], acc1[3][i]};
-                *(f32x4*)(dst + 4) = f32x4{acc1[4][i], acc1[5][i], acc1[6][i], acc1[7][i]};
-            } else {
-                *(f32x4*)(dst) = f32x4{acc2[0][i], acc2[1][i], acc2[2][i], acc2[3][i]};
-                *(f32x4*)(dst + 4) = f32x4{acc2[4][i], acc2[5][i], acc2[6][i], acc2[7][i]};
-            }
+            const f32x4 lo = (gi == 0) ? f32x4{acc1[0][i], acc1[1][i], acc1[2][i], acc1[3][i]}
+                                       : f32x4{acc2[0][i], acc2[1][i], acc2[2][i], acc2[3][i]};
+            const f32x4 hi = (gi == 0) ? f32x4{acc1[4][i], acc1[5][i], acc1[6][i], acc1[7][i]}
+                                       : f32x4{acc2[4][i], acc2[5][i], acc2[6][i], acc2[7][i]};
+            const bool upper = (c & 8) != 0;
+            *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
+            *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
         }
         if (gi == 0 && q == 0) ss_red[wave * 16 + c] = ss;
         __syncthreads();
@@ -231,22 +234,42 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         if (!is_last) return;
         if (tid == 0) tickets[ntile] = 0u;  // ready for the next call on this workspace
 
+        // Eight slices at a time: all their loads are issued before the first sum needs one (a load
+        // per trip would cost a round trip to memory per slice); the sums stay in slice order.  Slots
+        // past the last slice re-read it and are not added.
         ssum = 0.f;
 #pragma unroll
         for (int e = 0; e < CPT; ++e) { v1[e] = 0.f; v2[e] = 0.f; }
-        for (int s = 0; s < S; ++s) {
-            ssum += load_coherent(ss_part + ((size_t)ntile * S + s) * 16 + m);
-            if (out_ok) {
-                const float* p = acc_part + (((size_t)s * G) * M + m) * N + n;
+        constexpr int BATCH = 8;
+        for (int s0 = 0; s0 < S; s0 += BATCH) {
+            float sq[BATCH];
+            f32x2 pa[BATCH][CPT / 2], pb[BATCH][CPT / 2];
 #pragma unroll
-                for (int e = 0; e < CPT; e += 2) {
-                    const f32x2 a = load_coherent2(p + e);
-                    v1[e] += a[0];
-                    v1[e + 1] += a[1];
-                    if (GATED) {
-                        const f32x2 b = load_coherent2(p + (size_t)M * N + e);
-                        v2[e] += b[0];
-                        v2[e + 1] += b[1];
+            for (int j = 0; j < BATCH; ++j) {
+                const int s = min(s0 + j, S - 1);
+                sq[j] = load_coherent(ss_part + ((size_t)ntile * S + s) * 16 + m);
+                if (out_ok) {
+                    const float* p = acc_part + (((size_t)s * G) * M + m) * N + n;
+#pragma unroll
+                    for (int e = 0; e < CPT / 2; ++e) {
+                        pa[j][e] = load_coherent2(p + 2 * e);
+                        if (GATED) pb[j][e] = load_coherent2(p + (size_t)M * N + 2 * e);
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                if (s0 + j >= S) break;
+                ssum += sq[j];
+                if (out_ok) {
+#pragma unroll
+                    for (int e = 0; e < CPT / 2; ++e) {
+                        v1[2 * e] += pa[j][e][0];
+                        v1[2 * e + 1] += pa[j][e][1];
+                        if (GATED) {
+                            v2[2 * e] += pb[j][e][0];
+                            v2[2 * e + 1] += pb[j][e][1];
+                        }
                     }
                 }
             }
