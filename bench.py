@@ -136,7 +136,7 @@ def measure(idx, steps, warmup):
     res = {
         "workload": wl.name, "config_index": idx, "M": wl.M, "K": wl.K, "N": wl.N, "gated": wl.gated,
         "plan": r.plan, "steps": steps, "ms_per_step": wall_ms, "event_ms_per_step": ev_ms,
-        "kernel_ms": k_mean, "buffer_sets": sets,
+        "kernel_ms": k_mean, "buffer_sets": sets, "bytes_per_launch": nbytes, "flops_per_launch": flops,
     }
     if dec:
         res.update(value=nbytes / (wall_ms * 1e-3) / 1e9, unit="GB/s", bound="hbm",
@@ -199,8 +199,8 @@ def measured_traffic(workload):
             if len(f) >= 4 and f[0] == "traffic" and f[1] == workload:
                 kv = dict(x.split("=") for x in f[2:] if "=" in x)
                 return {"fetch_bytes": float(kv["fetch_bytes"]), "write_bytes": float(kv["write_bytes"]),
-                        "bytes": float(kv["fetch_bytes"]) + float(kv["write_bytes"]),
-                        "source": "profiles/hbm_traffic.md (rocprofv3 --pmc, scaled by a copy of known size)"}
+                        "source": "profiles/hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, each scaled "
+                                  "by its reading for a copy of known size)"}
     except (OSError, KeyError, ValueError):
         pass
     return None
@@ -238,6 +238,7 @@ def main():
         del src, dst
 
     head, runner = measure(a.workload, a.steps, a.warmup)
+    traffic = measured_traffic(head["workload"])
     out = {
         "metric": METRIC, "value": head["value"], "unit": head["unit"], "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
@@ -245,7 +246,10 @@ def main():
         "config": {"workload": head["workload"], "M": head["M"], "K": head["K"], "N": head["N"],
                    "gated": head["gated"], "plan": head["plan"], "buffer_sets": head["buffer_sets"]},
         "roofline": {"bound": head["bound"], "achieved": head["achieved"], "peak": head["peak"],
-                     "unit": head["unit"], "frac": head["frac"], "traffic": measured_traffic(head["workload"]),
+                     "unit": head["unit"], "frac": head["frac"],
+                     "traffic": None if traffic is None else traffic["fetch_bytes"] + traffic["write_bytes"],
+                     "traffic_unit": "bytes per launch", "traffic_detail": traffic,
+                     "algorithmic_bytes_per_launch": head.get("bytes_per_launch"),
                      "kernel": "prism::decode_kernel" if head["bound"] == "hbm" else "prism::prefill_kernel",
                      "kernel_ms_per_launch": head["kernel_ms"],
                      "timing": "HIP events around the timed region on the launch stream, divided by the launches"},
