@@ -10,8 +10,12 @@ import pytest
 def P(repo_root):
     lib = os.path.join(repo_root, "paper_2604_15272_amd", "libprism.so")
     if not os.path.exists(lib):
-        from paper_2604_15272_amd.build import build_library  # imports nothing that needs the library
-        build_library()
+        import importlib.util  # by path: importing the package needs the library
+        spec = importlib.util.spec_from_file_location("_prism_build",
+                                                      os.path.join(repo_root, "paper_2604_15272_amd", "build.py"))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        mod.build_library()
     import paper_2604_15272_amd as P
     yield P
     P.prism_set_override(0, 0, 0)
