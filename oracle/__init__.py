@@ -9,5 +9,7 @@ from .rmsnorm_family import (  # noqa: F401
     rms_norm,
     rmsnorm_matmul,
     rmsnorm_gated_mlp,
+    rmsnorm_glu,
+    swiglu,
     silu,
 )

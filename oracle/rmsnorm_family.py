@@ -22,6 +22,11 @@ the definition written out in the unfused order: normalise first, then
 multiply.  Every array is float64; callers widen stored bf16/fp32 inputs
 exactly before calling.  ``numpy.matmul`` is the one library step.
 
+The paper's own two gated workloads are here as written there, beside the
+target operator that combines them: ``rmsnorm_glu`` ("RMSNorm-MLP": shared
+normalisation, no activation) and ``swiglu`` ("SwiGLU": activation, no
+normalisation, no gain).
+
 Pins (tests/test_oracle_pins.py): scale invariance and unit row RMS at eps=0
 and their closed forms at eps>0, W = I, a triple-loop brute force, the
 fused-order identity, constant-row and one-hot-row closed forms, column and
@@ -96,3 +101,30 @@ def rmsnorm_gated_mlp(X, g, W1, W2, eps):
     a = np.matmul(Nrm, W1)
     b = np.matmul(Nrm, W2)
     return silu(a) * b
+
+
+def rmsnorm_glu(X, g, W1, W2, eps):
+    """Y = (Nrm @ W1) * (Nrm @ W2), Nrm = rms_norm(X; g, eps): no activation.
+
+    Paper Section 7.1, "RMSNorm-MLP": (rms_norm(X) W_up) * (rms_norm(X) W_gate),
+    the two branches being interchangeable.  The paper's operator has no gain:
+    pass g = ones.
+    """
+    W1 = _f64(W1, 2, "W1")
+    W2 = _f64(W2, 2, "W2")
+    if W1.shape != W2.shape:
+        raise ValueError("W1 and W2 must have the same shape")
+    Nrm = rms_norm(X, g, eps)
+    if W1.shape[0] != Nrm.shape[1]:
+        raise ValueError("W1/W2 must be [K,N]")
+    return np.matmul(Nrm, W1) * np.matmul(Nrm, W2)
+
+
+def swiglu(X, W_gate, W_up):
+    """Y = silu(X @ W_gate) * (X @ W_up): no normalisation, no gain.  Paper Section 7.1, "SwiGLU"."""
+    X = _f64(X, 2, "X")
+    W_gate = _f64(W_gate, 2, "W_gate")
+    W_up = _f64(W_up, 2, "W_up")
+    if W_gate.shape != W_up.shape or W_gate.shape[0] != X.shape[1]:
+        raise ValueError("W_gate and W_up must both be [K,N]")
+    return silu(np.matmul(X, W_gate)) * np.matmul(X, W_up)

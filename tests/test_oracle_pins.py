@@ -211,7 +211,59 @@ def pin_output_variance(o):
     assert abs(Y.mean()) < 0.05
 
 
-PINS = [pin_hand_worked, pin_scale_invariance, pin_unit_rms, pin_identity_weight, pin_brute_force,
+def pin_paper_variants(o):
+    """The paper's two gated workloads as written (Section 7.1): closed forms, brute force, symmetry."""
+    gv = _golden()
+    # hand-worked (tests/golden): X = [[3, 4]], W = [[1, 2], [3, 4]], W2 = diag(1, 2)
+    X = np.array([[3.0, 4.0]])
+    W = np.array([[1.0, 2.0], [3.0, 4.0]])
+    W2 = np.array([[1.0, 0.0], [0.0, 2.0]])
+    g = np.array([2.0, 0.5])
+    # case E: GLU with norm, g = [2, .5], eps = 3.5: Nrm = [1.5, .5]; Nrm W = [3, 5]; Nrm W2 = [1.5, 1]
+    np.testing.assert_allclose(o.rmsnorm_glu(X, g, W, W2, 3.5), [[4.5, 5.0]], rtol=1e-15)
+    # case F: SwiGLU without norm: X W = [15, 22], X W2 = [3, 8]
+    np.testing.assert_allclose(o.swiglu(X, W, W2), [[gv["silu15"] * 3.0, gv["silu22"] * 8.0]], rtol=1e-15)
+    # brute force, scalar loops
+    for seed, (M, K, N) in enumerate([(1, 1, 1), (3, 5, 2), (2, 7, 3)]):
+        Xr, gr, W1r, W2r = _rand(40 + seed, M, K, N)
+        a = _brute_plain(Xr.tolist(), gr.tolist(), W1r.tolist(), 0.3)
+        b = _brute_plain(Xr.tolist(), gr.tolist(), W2r.tolist(), 0.3)
+        np.testing.assert_allclose(o.rmsnorm_glu(Xr, gr, W1r, W2r, 0.3), a * b, rtol=1e-12, atol=1e-14)
+        ref = np.zeros((M, N))
+        for m in range(M):
+            for j in range(N):
+                sa = sum(Xr[m, k] * W1r[k, j] for k in range(K))
+                sb = sum(Xr[m, k] * W2r[k, j] for k in range(K))
+                ref[m, j] = sa / (1.0 + math.exp(-sa)) * sb
+        np.testing.assert_allclose(o.swiglu(Xr, W1r, W2r), ref, rtol=1e-12, atol=1e-14)
+    Xr, gr, W1r, W2r = _rand(44, 4, 24, 6)
+    # GLU: the branches are interchangeable, the result is homogeneous of degree 0 in X at eps = 0 ...
+    np.testing.assert_allclose(o.rmsnorm_glu(Xr, gr, W1r, W2r, 1e-6), o.rmsnorm_glu(Xr, gr, W2r, W1r, 1e-6), rtol=1e-14)
+    np.testing.assert_allclose(o.rmsnorm_glu(5.0 * Xr, gr, W1r, W2r, 0.0), o.rmsnorm_glu(Xr, gr, W1r, W2r, 0.0), rtol=1e-12)
+    # ... and equals the product of two plain calls
+    np.testing.assert_allclose(o.rmsnorm_glu(Xr, gr, W1r, W2r, 1e-6),
+                               o.rmsnorm_matmul(Xr, gr, W1r, 1e-6) * o.rmsnorm_matmul(Xr, gr, W2r, 1e-6), rtol=1e-13)
+    # one-hot row a e_j, eps = 0: Nrm = sign(a) sqrt(K) g_j e_j, so Y = K g_j^2 W1[j,:] W2[j,:]
+    Xo = np.zeros((1, 24))
+    Xo[0, 5] = -0.3
+    np.testing.assert_allclose(o.rmsnorm_glu(Xo, gr, W1r, W2r, 0.0), [24 * gr[5] ** 2 * W1r[5] * W2r[5]], rtol=1e-13)
+    # SwiGLU: not normalised (scaling X changes it), the branches are not interchangeable, W_gate = 0 -> 0,
+    # one-hot row picks row j of both weights
+    assert not np.allclose(o.swiglu(2.0 * Xr, W1r, W2r), o.swiglu(Xr, W1r, W2r))
+    assert not np.allclose(o.swiglu(Xr, W1r, W2r), o.swiglu(Xr, W2r, W1r))
+    assert np.all(o.swiglu(Xr, np.zeros_like(W1r), W2r) == 0.0)
+    np.testing.assert_allclose(o.swiglu(Xo, W1r, W2r), [o.silu(-0.3 * W1r[5]) * (-0.3 * W2r[5])], rtol=1e-13)
+    # relation to the target operator: dividing X by its row rms by hand, with g = 1, gives the gated MLP
+    r = 1.0 / np.sqrt(np.mean(Xr * Xr, axis=1, keepdims=True) + 1e-6)
+    np.testing.assert_allclose(o.swiglu(Xr * r, W1r, W2r), o.rmsnorm_gated_mlp(Xr, np.ones(24), W1r, W2r, 1e-6),
+                               rtol=1e-12, atol=1e-15)
+    torch = pytest.importorskip("torch")
+    tX, tW1, tW2 = (torch.from_numpy(a) for a in (Xr, W1r, W2r))
+    np.testing.assert_allclose(o.swiglu(Xr, W1r, W2r), (torch.nn.functional.silu(tX @ tW1) * (tX @ tW2)).numpy(),
+                               rtol=1e-12, atol=1e-15)
+
+
+PINS = [pin_paper_variants, pin_hand_worked, pin_scale_invariance, pin_unit_rms, pin_identity_weight, pin_brute_force,
         pin_fused_order, pin_closed_form_rows, pin_partitions, pin_gated_identities,
         pin_torch_second_opinion, pin_output_variance]
 
@@ -225,7 +277,8 @@ def test_pin(pin):
 
 def _mutant(**over):
     ns = types.SimpleNamespace(rms_norm=O.rms_norm, rmsnorm_matmul=O.rmsnorm_matmul,
-                               rmsnorm_gated_mlp=O.rmsnorm_gated_mlp, silu=O.silu)
+                               rmsnorm_gated_mlp=O.rmsnorm_gated_mlp, silu=O.silu,
+                               rmsnorm_glu=O.rmsnorm_glu, swiglu=O.swiglu)
     for k, v in over.items():
         setattr(ns, k, v)
     # rebuild the composite functions on top of the (possibly replaced) pieces
@@ -236,6 +289,13 @@ def _mutant(**over):
             n = ns.rms_norm(X, g, eps)
             return ns.silu(n @ W1) * (n @ W2)
         ns.rmsnorm_gated_mlp = gated
+    if "rmsnorm_glu" not in over:
+        def glu(X, g, W1, W2, eps):
+            n = ns.rms_norm(X, g, eps)
+            return (n @ W1) * (n @ W2)
+        ns.rmsnorm_glu = glu
+    if "swiglu" not in over:
+        ns.swiglu = lambda X, Wg, Wu: ns.silu(X @ Wg) * (X @ Wu)
     return ns
 
 
@@ -265,6 +325,12 @@ MUTANTS = {
         O.rmsnorm_matmul(X, g, W1, eps) * O.rmsnorm_matmul(X, g, W2, eps))),
     "sigmoid_not_silu": _mutant(silu=lambda a: 1.0 / (1.0 + np.exp(-np.asarray(a, dtype=np.float64)))),
     "silu_wrong_sign": _mutant(silu=lambda a: np.asarray(a) / (1.0 + np.exp(np.asarray(a, dtype=np.float64)))),
+    "glu_with_activation": _mutant(rmsnorm_glu=lambda X, g, W1, W2, eps: O.rmsnorm_gated_mlp(X, g, W1, W2, eps)),
+    "glu_sum_not_product": _mutant(rmsnorm_glu=lambda X, g, W1, W2, eps: (
+        O.rmsnorm_matmul(X, g, W1, eps) + O.rmsnorm_matmul(X, g, W2, eps))),
+    "swiglu_normalised": _mutant(swiglu=lambda X, Wg, Wu: O.rmsnorm_gated_mlp(X, np.ones(X.shape[1]), Wg, Wu, 0.0)),
+    "swiglu_silu_on_up": _mutant(swiglu=lambda X, Wg, Wu: O.swiglu(X, Wu, Wg)),
+    "swiglu_no_activation": _mutant(swiglu=lambda X, Wg, Wu: (X @ Wg) * (X @ Wu)),
     "scale_after_silu": _mutant(rmsnorm_gated_mlp=lambda X, g, W1, W2, eps: (
         O.silu((X * g) @ W1) * ((X * g) @ W2) / (np.mean(X * X, axis=1, keepdims=True) + eps))),
 }
