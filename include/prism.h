@@ -20,6 +20,8 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
  *     allocates and frees nothing.  X, g, W* are only read; Y is overwritten and
  *     must not overlap any input.
+ *   - g may be NULL: the call then has no gain tensor (g = 1), as in the paper's
+ *     own workloads, whose rms_norm takes X alone (Section 7.1, Section 7.6).
  *   - Layout: row-major, contiguous.  X[M,K], g[K], W[K,N], Y[M,N].
  *   - dtype names the storage type of X, g, W*, Y alike.  PRISM_BF16 multiplies
  *     on the bf16 matrix cores and accumulates in fp32; PRISM_F32 uses fp32 FMAs.
@@ -74,7 +76,8 @@ typedef struct {
 
 /*
  * Y[M,N] = rms_norm(X[M,K]; g[K], eps) . W[K,N]         (paper Section 7.1, workload "RMSNorm";
- * gain g and eps are this library's additions, see the conventions above).
+ * gain g and eps are this library's additions, see the conventions above; g = NULL and the
+ * paper's operator is obtained).
  * Returns PRISM_OK once the work is enqueued.
  */
 prism_status_t prism_rmsnorm_matmul(const void* X, const void* g, const void* W, void* Y,
@@ -90,7 +93,23 @@ prism_status_t prism_rmsnorm_gated_mlp(const void* X, const void* g, const void*
                                        void* Y, int64_t M, int64_t K, int64_t N, float eps,
                                        prism_dtype_t dtype, hipStream_t stream);
 
-/* The same two operations with the storage type in the name instead of an argument. */
+/*
+ * The paper's "RMSNorm-MLP" workload exactly (Section 7.1): the two products that share the
+ * normalised input, multiplied element by element, with no activation:
+ * Y[M,N] = (Nrm . W1) * (Nrm . W2),  Nrm = rms_norm(X; g, eps).  Arguments as above.
+ */
+prism_status_t prism_rmsnorm_glu(const void* X, const void* g, const void* W1, const void* W2,
+                                 void* Y, int64_t M, int64_t K, int64_t N, float eps,
+                                 prism_dtype_t dtype, hipStream_t stream);
+
+/*
+ * The paper's "SwiGLU" workload exactly (Section 7.1): Y[M,N] = silu(X . W_gate) * (X . W_up),
+ * no normalisation and no gain.  W_gate and W_up are both [K,N].
+ */
+prism_status_t prism_swiglu(const void* X, const void* W_gate, const void* W_up, void* Y,
+                            int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, hipStream_t stream);
+
+/* The first two operations with the storage type in the name instead of an argument. */
 prism_status_t prism_rmsnorm_matmul_bf16(const void* X, const void* g, const void* W, void* Y,
                                          int64_t M, int64_t K, int64_t N, float eps, hipStream_t stream);
 prism_status_t prism_rmsnorm_matmul_f32(const void* X, const void* g, const void* W, void* Y,

@@ -20,6 +20,8 @@ from .binding import (  # noqa: F401
     library_path,
     prism_plan,
     prism_rmsnorm_gated_mlp,
+    prism_rmsnorm_glu,
+    prism_swiglu,
     prism_rmsnorm_matmul,
     prism_set_override,
     prism_set_workspace,

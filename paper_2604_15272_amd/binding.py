@@ -50,6 +50,10 @@ def _load():
         getattr(L, f"prism_rmsnorm_gated_mlp_{sfx}").restype = i32
     L.prism_rmsnorm_matmul.restype = i32
     L.prism_rmsnorm_gated_mlp.restype = i32
+    L.prism_rmsnorm_glu.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, i32, vp]
+    L.prism_rmsnorm_glu.restype = i32
+    L.prism_swiglu.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp]
+    L.prism_swiglu.restype = i32
     L.prism_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
     L.prism_workspace_bytes.restype = u64
     L.prism_set_workspace.argtypes = [vp, u64]
@@ -177,4 +181,34 @@ def prism_rmsnorm_gated_mlp(X, g, W1, W2, Y, M=None, K=None, N=None, eps=1e-6, d
                                      float(eps), dt, _stream_handle(stream))
     if st != 0:
         raise PrismError(st, "prism_rmsnorm_gated_mlp")
+    return Y
+
+
+def prism_rmsnorm_glu(X, g, W1, W2, Y, M=None, K=None, N=None, eps=1e-6, dtype=None, stream=None):
+    """Y[M,N] = (Nrm @ W1) * (Nrm @ W2), Nrm = rms_norm(X; g, eps): the paper's RMSNorm-MLP (no activation)."""
+    if M is None:
+        M, K = X.shape
+        N = W1.shape[1]
+    dt = _dtype_of(X, dtype)
+    if not isinstance(X, int):
+        ensure_workspace(prism_workspace_bytes(PRISM_OP_RMSNORM_GATED_MLP, M, K, N, dt))
+    st = lib.prism_rmsnorm_glu(_ptr(X), _ptr(g), _ptr(W1), _ptr(W2), _ptr(Y), int(M), int(K), int(N), float(eps), dt,
+                               _stream_handle(stream))
+    if st != 0:
+        raise PrismError(st, "prism_rmsnorm_glu")
+    return Y
+
+
+def prism_swiglu(X, W_gate, W_up, Y, M=None, K=None, N=None, dtype=None, stream=None):
+    """Y[M,N] = silu(X @ W_gate) * (X @ W_up): the paper's SwiGLU (no normalisation, no gain)."""
+    if M is None:
+        M, K = X.shape
+        N = W_gate.shape[1]
+    dt = _dtype_of(X, dtype)
+    if not isinstance(X, int):
+        ensure_workspace(prism_workspace_bytes(PRISM_OP_RMSNORM_GATED_MLP, M, K, N, dt))
+    st = lib.prism_swiglu(_ptr(X), _ptr(W_gate), _ptr(W_up), _ptr(Y), int(M), int(K), int(N), dt,
+                          _stream_handle(stream))
+    if st != 0:
+        raise PrismError(st, "prism_swiglu")
     return Y

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
                                                          const uint16_t* __restrict__ W2,
                                                          uint16_t* __restrict__ Y, float* __restrict__ acc_part,
                                                          float* __restrict__ ss_part, unsigned* __restrict__ tickets,
-                                                         int M, int K, int N, float eps, int S) {
+                                                         int M, int K, int N, float eps, int S, int flags) {
     constexpr int G = GATED ? 2 : 1;
     constexpr int NT = NW * 64;
     constexpr int CPT = 16 * TN / NT;  // columns per thread in the epilogue (4 for 8 wavefronts)
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
             const bool k_ok = has && k < K;
             // X and g first: they come from L2 and let the A operand be ready before W lands.
             xr[u] = load16(rx, (row_ok && k_ok) ? (u32)(((size_t)c * K + k) * 2) : kOutOfRange);
-            gr[u] = load16(rg, k_ok ? (u32)k * 2u : kOutOfRange);
+            gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : bf16_ones();
             load_w_block(w1[u], rw1, woff, row_bytes);
             if (GATED) load_w_block(w2[u], rw2, woff, row_bytes);
         }
@@ -277,12 +277,12 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     }
 
     if (!out_ok) return;
-    const float rinv = __builtin_amdgcn_rsqf(ssum / (float)K + eps);
+    const float rinv = (flags & kFlagNorm) ? __builtin_amdgcn_rsqf(ssum / (float)K + eps) : 1.0f;
     float y[CPT];
 #pragma unroll
     for (int e = 0; e < CPT; ++e) {
         y[e] = v1[e] * rinv;
-        if (GATED) y[e] = silu_f32(y[e]) * (v2[e] * rinv);
+        if (GATED) y[e] = ((flags & kFlagSilu) ? silu_f32(y[e]) : y[e]) * (v2[e] * rinv);
     }
     uint16_t* out = Y + (size_t)m * N + n;
     if (CPT == 1) {
@@ -312,13 +312,13 @@ static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& 
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W2, Y, ws.acc_part, ws.ss_part, ws.tickets,
-                           c.M, c.K, c.N, c.eps, S);
+                           c.M, c.K, c.N, c.eps, S, c.flags);
     } else {
         auto kern = decode_kernel<NW, false>;
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W1, Y, ws.acc_part, ws.ss_part, ws.tickets,
-                           c.M, c.K, c.N, c.eps, S);
+                           c.M, c.K, c.N, c.eps, S, c.flags);
     }
     return hipGetLastError();
 }

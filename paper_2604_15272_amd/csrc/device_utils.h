@@ -21,6 +21,9 @@ constexpr u32 kOutOfRange = 0x80000000u;
 __device__ __forceinline__ float bf16_lo(u32 u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(u32 u) { return __builtin_bit_cast(float, u & 0xFFFF0000u); }
 
+// Eight bf16 ones (the gain of a call without a gain tensor).
+__device__ __forceinline__ u32x4 bf16_ones() { return u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u}; }
+
 // Two floats -> two bf16 (round to nearest even) in one dword, a in the low half.
 __device__ __forceinline__ u32 pack_bf16(float a, float b) {
     f32x2 v = {a, b};

@@ -72,7 +72,7 @@ template <int BM, int BN, bool GATED>
 __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ g,
                                                       const uint16_t* __restrict__ W1,
                                                       const uint16_t* __restrict__ W2, uint16_t* __restrict__ Y,
-                                                      int M, int K, int N, float eps, int tiles_m, int tiles_n) {
+                                                      int M, int K, int N, float eps, int tiles_m, int tiles_n, int flags) {
     constexpr int WTM = BM / 2, WTN = BN / 2;        // wavefront tile
     constexpr int TM32 = WTM / 32, TN32 = WTN / 32;  // 32 x 32 MFMA blocks per wavefront
     constexpr int CW = GATED ? BN / 2 : BN;          // output columns per workgroup
@@ -149,11 +149,19 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         u32x4 g;     // gain of those eight rows
     };
     WSet ws_a, ws_b;
+    const bool has_gain = (flags & kFlagGain) != 0;
 
     // Global loads of K step kt (k past the end read as zero: X by predicate, g and W by the descriptor).
     // Load 0 of a set is the gain, loads 1..8 are the rows.
     auto load_w = [&](WSet& s, int kt, int i) {
-        if (i == 0) s.g = load16(rg, (u32)(kt * BK + 8 * wkb) * 2u);
+        if (i == 0) {
+            // Without a gain tensor the load is still issued (out of range: it returns zero and touches
+            // no memory): the wait counts of the pipeline below count instructions.
+            const u32x4 v = load16(rg, has_gain ? (u32)(kt * BK + 8 * wkb) * 2u : kOutOfRange);
+            const u32x4 one = bf16_ones();
+            s.g = u32x4{has_gain ? v[0] : one[0], has_gain ? v[1] : one[1], has_gain ? v[2] : one[2],
+                        has_gain ? v[3] : one[3]};
+        }
         else s.w[i - 1] = load16(rw, w_lane + (u32)kt * BK * row_bytes + (u32)(i - 1) * row_bytes);
     };
     constexpr int NWL = 9;  // loads per set
@@ -376,12 +384,13 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     __syncthreads();
     if (tid < BM) {
         const float s = ss_part[tid] + ss_part[BM + tid] + ss_part[2 * BM + tid] + ss_part[3 * BM + tid];
-        rscale[tid] = __builtin_amdgcn_rsqf(s / (float)K + eps);
+        rscale[tid] = (flags & kFlagNorm) ? __builtin_amdgcn_rsqf(s / (float)K + eps) : 1.0f;
     }
     __syncthreads();
 
     // ---- epilogue: register v of block (jb, ib) is row 32 ib + l32, column 32 jb + 8 (v / 4) + 4 lh + v % 4
     constexpr int OB = GATED ? TN32 / 2 : TN32;  // output 32-column blocks per wavefront
+    const bool act_silu = (flags & kFlagSilu) != 0;
 #pragma unroll
     for (int ib = 0; ib < TM32; ++ib) {
         const int ml = wm * WTM + 32 * ib + l32;
@@ -399,7 +408,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     y[e] = acc[jb][ib][4 * vg + e] * r;
-                    if (GATED) y[e] = silu_f32(y[e]) * (acc[jb + OB][ib][4 * vg + e] * r);
+                    if (GATED) y[e] = (act_silu ? silu_f32(y[e]) : y[e]) * (acc[jb + OB][ib][4 * vg + e] * r);
                 }
                 *(u32x2*)(Y + (size_t)m * N + n) = u32x2{pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
             }
@@ -417,7 +426,7 @@ static hipError_t launch_tile(const Call& c) {
     if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds, c.stream, (const uint16_t*)c.X,
                        (const uint16_t*)c.g, (const uint16_t*)c.W1, (const uint16_t*)(c.gated ? c.W2 : c.W1),
-                       (uint16_t*)c.Y, c.M, c.K, c.N, c.eps, tiles_m, tiles_n);
+                       (uint16_t*)c.Y, c.M, c.K, c.N, c.eps, tiles_m, tiles_n, c.flags);
     return hipGetLastError();
 }
 

@@ -160,21 +160,25 @@ prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_d
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// One call of the family: `flags` says which optional steps it takes (gain is dropped here when g
+// is null).
 prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, const void* W2, void* Y, int64_t M,
-                   int64_t K, int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream) {
+                   int64_t K, int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream,
+                   int flags = kFlagGain | kFlagNorm | kFlagSilu) {
     const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
+    if (!g) flags &= ~kFlagGain;
     if (dtype != PRISM_F32 && dtype != PRISM_BF16) return PRISM_ERR_UNSUPPORTED;
     if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
     if (!(eps >= 0.0f) || !std::isfinite(eps)) return PRISM_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return PRISM_OK;  // empty problem: pointers are not looked at
-    if (!X || !g || !W1 || !Y || (gated && !W2)) return PRISM_ERR_INVALID_ARG;
+    if (!X || !W1 || !Y || (gated && !W2)) return PRISM_ERR_INVALID_ARG;
     if (!aligned16(X) || !aligned16(g) || !aligned16(W1) || !aligned16(Y) || (gated && !aligned16(W2)))
         return PRISM_ERR_INVALID_ARG;
     Plan plan;
     const prism_status_t st = make_plan(op, M, K, N, dtype, &plan);
     if (st != PRISM_OK) return st;
 
-    Call c{X, g, W1, gated ? W2 : nullptr, Y, (int)M, (int)K, (int)N, eps, gated, stream};
+    Call c{X, g, W1, gated ? W2 : nullptr, Y, (int)M, (int)K, (int)N, eps, gated, flags, stream};
     hipError_t err = hipSuccess;
     switch (plan.pub.path) {
         case PRISM_PATH_SIMPLE:
@@ -221,6 +225,16 @@ prism_status_t prism_rmsnorm_gated_mlp(const void* X, const void* g, const void*
                                        int64_t M, int64_t K, int64_t N, float eps, prism_dtype_t dtype,
                                        hipStream_t stream) {
     return run(PRISM_OP_RMSNORM_GATED_MLP, X, g, W1, W2, Y, M, K, N, eps, dtype, stream);
+}
+
+prism_status_t prism_rmsnorm_glu(const void* X, const void* g, const void* W1, const void* W2, void* Y, int64_t M,
+                                 int64_t K, int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_GATED_MLP, X, g, W1, W2, Y, M, K, N, eps, dtype, stream, kFlagGain | kFlagNorm);
+}
+
+prism_status_t prism_swiglu(const void* X, const void* W_gate, const void* W_up, void* Y, int64_t M, int64_t K,
+                            int64_t N, prism_dtype_t dtype, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_GATED_MLP, X, nullptr, W_gate, W_up, Y, M, K, N, 0.0f, dtype, stream, kFlagSilu);
 }
 
 prism_status_t prism_rmsnorm_matmul_bf16(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K,
@@ -291,6 +305,6 @@ const char* prism_status_string(prism_status_t status) {
     }
 }
 
-int32_t prism_version(void) { return 100; }
+int32_t prism_version(void) { return 110; }
 
 }  // extern "C"

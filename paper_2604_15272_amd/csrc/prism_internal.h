@@ -18,8 +18,14 @@ struct Call {
     int M, K, N;
     float eps;
     bool gated;
+    int flags;  // kFlag* bits
     hipStream_t stream;
 };
+
+// Members of the operator family (paper Section 7.1): which of the optional steps a call takes.
+constexpr int kFlagGain = 1;  // multiply the row by g[K] (off: g is not read)
+constexpr int kFlagNorm = 2;  // scale by 1/rms (off: the sums of squares are ignored)
+constexpr int kFlagSilu = 4;  // gated calls: SiLU on the W1 branch (off: plain product of the branches)
 
 // Geometry of the decode (few-row) path.
 constexpr int kDecodeMaxRows = 16;     // one 16-row MFMA block

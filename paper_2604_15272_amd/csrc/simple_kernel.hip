@@ -28,7 +28,7 @@ template <> __device__ __forceinline__ void store_elem<uint16_t>(uint16_t* p, si
 template <typename T, bool GATED>
 __global__ __launch_bounds__(kSimpleCols) void simple_kernel(const T* __restrict__ X, const T* __restrict__ g,
                                                            const T* __restrict__ W1, const T* __restrict__ W2,
-                                                           T* __restrict__ Y, int M, int K, int N, float eps) {
+                                                           T* __restrict__ Y, int M, int K, int N, float eps, int flags) {
     __shared__ float xs[kSimpleRows][kSimpleChunk];
     __shared__ float ss_wave[kSimpleCols / 64][kSimpleRows];
     const int t = threadIdx.x;
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kSimpleCols) void simple_kernel(const T* __restrict
     for (int kc = 0; kc < K; kc += kSimpleChunk) {
         __syncthreads();
         const int k = kc + t;
-        const float gk = (k < K) ? load_elem<T>(g, (size_t)k) : 0.f;
+        const float gk = (k < K) ? ((flags & kFlagGain) ? load_elem<T>(g, (size_t)k) : 1.f) : 0.f;
 #pragma unroll
         for (int r = 0; r < kSimpleRows; ++r) {
             const int m = m0 + r;
@@ -90,11 +90,11 @@ __global__ __launch_bounds__(kSimpleCols) void simple_kernel(const T* __restrict
         float tot = 0.f;
 #pragma unroll
         for (int w = 0; w < kSimpleCols / 64; ++w) tot += ss_wave[w][r];
-        const float rinv = 1.0f / sqrtf(tot / (float)K + eps);
+        const float rinv = (flags & kFlagNorm) ? 1.0f / sqrtf(tot / (float)K + eps) : 1.0f;
         float y = acc1[r] * rinv;
         if (GATED) {
             const float a = y;
-            y = a / (1.0f + expf(-a)) * (acc2[r] * rinv);
+            y = ((flags & kFlagSilu) ? a / (1.0f + expf(-a)) : a) * (acc2[r] * rinv);
         }
         store_elem<T>(Y, (size_t)m * N + n, y);
     }
@@ -106,10 +106,10 @@ static hipError_t launch_simple(const Call& c) {
     dim3 block(kSimpleCols);
     if (c.gated)
         hipLaunchKernelGGL((simple_kernel<T, true>), grid, block, 0, c.stream, (const T*)c.X, (const T*)c.g,
-                           (const T*)c.W1, (const T*)c.W2, (T*)c.Y, c.M, c.K, c.N, c.eps);
+                           (const T*)c.W1, (const T*)c.W2, (T*)c.Y, c.M, c.K, c.N, c.eps, c.flags);
     else
         hipLaunchKernelGGL((simple_kernel<T, false>), grid, block, 0, c.stream, (const T*)c.X, (const T*)c.g,
-                           (const T*)c.W1, (const T*)c.W1, (T*)c.Y, c.M, c.K, c.N, c.eps);
+                           (const T*)c.W1, (const T*)c.W1, (T*)c.Y, c.M, c.K, c.N, c.eps, c.flags);
     return hipGetLastError();
 }
 

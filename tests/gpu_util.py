@@ -41,6 +41,55 @@ def run_gpu(stored, dtype, gated, eps, poison=True):
     return from_device(Y, dtype)
 
 
+def run_gpu_variant(stored, dtype, variant, eps):
+    """The paper's own members of the family through their entry points.
+
+    variant: "plain_nogain" (rms_norm without gain, then W), "glu" (RMSNorm-MLP: no activation),
+    "glu_nogain", "swiglu" (no normalisation, no gain).  Returns Y as float64.
+    """
+    import torch
+    import paper_2604_15272_amd as P
+    X = to_device(stored["X"], dtype)
+    g = to_device(stored["g"], dtype)
+    M = X.shape[0]
+    tdt = torch.bfloat16 if dtype == pi.BF16 else torch.float32
+    names = ("W",) if variant == "plain_nogain" else ("W1", "W2")
+    Ws = [to_device(stored[n], dtype) for n in names]
+    N = Ws[0].shape[1]
+    Y = torch.full((M, N), float("nan"), dtype=tdt, device="cuda")
+    if variant == "plain_nogain":
+        P.prism_rmsnorm_matmul(X, None, Ws[0], Y, eps=eps)
+    elif variant == "glu":
+        P.prism_rmsnorm_glu(X, g, Ws[0], Ws[1], Y, eps=eps)
+    elif variant == "glu_nogain":
+        P.prism_rmsnorm_glu(X, None, Ws[0], Ws[1], Y, eps=eps)
+    elif variant == "swiglu":
+        P.prism_swiglu(X, Ws[0], Ws[1], Y)
+    else:
+        raise ValueError(variant)
+    torch.cuda.synchronize()
+    return from_device(Y, dtype)
+
+
+def run_oracle_variant(stored, dtype, variant, eps, rows=None):
+    import oracle
+    X = pi.to_f64(stored["X"], dtype)
+    if rows is not None:
+        X = X[rows]
+    g = pi.to_f64(stored["g"], dtype)
+    one = np.ones_like(g)
+    if variant == "plain_nogain":
+        return oracle.rmsnorm_matmul(X, one, pi.to_f64(stored["W"], dtype), eps)
+    W1, W2 = pi.to_f64(stored["W1"], dtype), pi.to_f64(stored["W2"], dtype)
+    if variant == "glu":
+        return oracle.rmsnorm_glu(X, g, W1, W2, eps)
+    if variant == "glu_nogain":
+        return oracle.rmsnorm_glu(X, one, W1, W2, eps)
+    if variant == "swiglu":
+        return oracle.swiglu(X, W1, W2)
+    raise ValueError(variant)
+
+
 def run_oracle(stored, dtype, gated, eps, rows=None):
     import oracle
     X = pi.to_f64(stored["X"], dtype)

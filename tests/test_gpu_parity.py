@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import prism_inputs as pi
-from gpu_util import assert_parity, run_gpu, run_oracle, worst_error
+from gpu_util import assert_parity, run_gpu, run_gpu_variant, run_oracle, run_oracle_variant, worst_error
 
 pytestmark = pytest.mark.gpu
 
@@ -141,6 +141,64 @@ def test_prefill_configs_full_size_sampled_rows(P, idx):
     # property that holds at any size: output variance of the i.i.d. recipe (13/12 for the plain product)
     if not wl.gated:
         assert abs(y.var() - 13.0 / 12.0) < 0.02
+
+
+# ---- the paper's own members of the family (Section 7.1), at its shapes (Section 7.1: n in {8, 16}, d in
+# ---- {1024, 4096}) and on every kernel family ----------------------------------------------------------
+
+def _variant_case(P, dtype, M, K, N, variant, seed, path=0, split=0, tile=0, x_scale=None):
+    gated = variant != "plain_nogain"
+    stored = pi.draw(dtype, M, K, N, gated, seed)
+    if x_scale is not None:  # SwiGLU has no normalisation: keep the products O(1)
+        x = pi.to_f64(stored["X"], dtype).astype(np.float32) * np.float32(x_scale)
+        stored["X"] = pi.f32_to_bf16_bits(x) if dtype == pi.BF16 else x
+    P.prism_set_override(path, split, tile)
+    try:
+        plan = P.prism_plan(int(gated), M, K, N, 1 if dtype == pi.BF16 else 0)
+        print(f"variant={variant} dtype={dtype} M={M} K={K} N={N} seed={seed} plan={plan}", flush=True)
+        y = run_gpu_variant(stored, dtype, variant, 1e-6)
+    finally:
+        P.prism_set_override(0, 0, 0)
+    yhat = run_oracle_variant(stored, dtype, variant, 1e-6)
+    return assert_parity(y, yhat, dtype, f"{variant} M={M} K={K} N={N} plan={plan}")
+
+
+@pytest.mark.parametrize("variant", ["plain_nogain", "glu", "glu_nogain", "swiglu"])
+@pytest.mark.parametrize("dtype,M,K,N", [(pi.F32, 8, 256, 512), (pi.F32, 5, 100, 36), (pi.BF16, 8, 1024, 1024),
+                                         (pi.BF16, 16, 1024, 4096), (pi.BF16, 8, 4096, 4096),
+                                         (pi.BF16, 7, 1000, 264), (pi.BF16, 3, 77, 130),
+                                         (pi.BF16, 300, 712, 648), (pi.BF16, 1024, 1024, 512)])
+def test_paper_variants(P, variant, dtype, M, K, N):
+    # SwiGLU: X of unit scale times W of variance 1/K already gives products of unit scale
+    _variant_case(P, dtype, M, K, N, variant, seed=800 + M + K)
+
+
+@pytest.mark.parametrize("variant", ["glu", "swiglu"])
+@pytest.mark.parametrize("split", [1, 3, 8])
+def test_paper_variants_every_split(P, variant, split):
+    _variant_case(P, pi.BF16, 16, 2056, 1160, variant, seed=810, path=P.PRISM_PATH_DECODE, split=split, tile=8)
+
+
+@pytest.mark.parametrize("variant", ["glu", "swiglu"])
+@pytest.mark.parametrize("tile", [256256, 128256, 128128])
+def test_paper_variants_every_gated_tile(P, variant, tile):
+    _variant_case(P, pi.BF16, 300, 712, 648, variant, seed=811, path=P.PRISM_PATH_PREFILL, tile=tile)
+
+
+def test_no_gain_equals_gain_of_ones_bit_for_bit(P):
+    """g = NULL is defined as g = 1: multiplying by one is exact, so the outputs are identical."""
+    import torch
+    from gpu_util import to_device
+    for M, K, N in [(16, 1024, 512), (200, 512, 384), (6, 100, 36)]:
+        stored = pi.draw(pi.BF16, M, K, N, False, 820)
+        X, W = to_device(stored["X"], pi.BF16), to_device(stored["W"], pi.BF16)
+        ones = torch.ones(K, dtype=torch.bfloat16, device="cuda")
+        Y0 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        Y1 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        P.prism_rmsnorm_matmul(X, None, W, Y0)
+        P.prism_rmsnorm_matmul(X, ones, W, Y1)
+        torch.cuda.synchronize()
+        assert torch.equal(Y0.view(torch.uint16), Y1.view(torch.uint16))
 
 
 # ---- degenerate inputs -------------------------------------------------------------------------

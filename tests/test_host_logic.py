@@ -43,7 +43,7 @@ def test_argument_validation_needs_no_device(P):
     ok = lambda **kw: None
     call = lambda X=a, g=a, W=a, Y=a, M=4, K=64, N=64, eps=1e-6, dt=1: L.prism_rmsnorm_matmul(
         X, g, W, Y, M, K, N, eps, dt, None)
-    assert call(X=None) == 1 and call(g=None) == 1 and call(W=None) == 1 and call(Y=None) == 1
+    assert call(X=None) == 1 and call(W=None) == 1 and call(Y=None) == 1   # g = None means: no gain tensor
     assert call(X=a + 2) == 1                       # misaligned
     assert call(M=-1) == 1 and call(N=-1) == 1 and call(K=0) == 1 and call(K=-8) == 1
     assert call(eps=-1.0) == 1 and call(eps=float("nan")) == 1 and call(eps=float("inf")) == 1
@@ -51,6 +51,9 @@ def test_argument_validation_needs_no_device(P):
     assert call(M=0) == 0 and call(N=0) == 0        # empty problem: success, no launch
     gcall = lambda W2=a, **kw: L.prism_rmsnorm_gated_mlp(a, a, a, W2, a, 4, 64, 64, 1e-6, 1, None)
     assert gcall(W2=None) == 1
+    assert L.prism_rmsnorm_glu(a, a, a, None, a, 4, 64, 64, 1e-6, 1, None) == 1
+    assert L.prism_swiglu(a, None, a, a, 4, 64, 64, 1, None) == 1 and L.prism_swiglu(a, a, a, a, 0, 64, 64, 1, None) == 0
+    assert L.prism_swiglu(a, a, a, a, 4, 0, 64, 1, None) == 1 and L.prism_swiglu(a, a, a, a, 4, 64, 64, 9, None) == 2
 
 
 def test_plan_picks_paths_by_shape(P):
