@@ -23,8 +23,9 @@
  *   - g may be NULL: the call then has no gain tensor (g = 1), as in the paper's
  *     own workloads, whose rms_norm takes X alone (Section 7.1, Section 7.6).
  *   - Layout: row-major, contiguous.  X[M,K], g[K], W[K,N], Y[M,N].
- *   - dtype names the storage type of X, g, W*, Y alike.  PRISM_BF16 multiplies
- *     on the bf16 matrix cores and accumulates in fp32; PRISM_F32 uses fp32 FMAs.
+ *   - dtype names the storage type of X, g, W*, Y alike.  PRISM_BF16 and PRISM_F16
+ *     multiply on the matrix cores in that format and accumulate in fp32 (X * g is
+ *     rounded to the format on its way in); PRISM_F32 uses fp32 FMAs.
  *   - Pointers must be 16-byte aligned.
  *   - Work is enqueued on `stream` and the call returns without waiting for it.
  *   - Errors are reported by return code only; nothing is printed or thrown.
@@ -51,7 +52,8 @@ typedef enum {
     PRISM_ERR_HIP = 4          /* the HIP runtime reported an error at launch */
 } prism_status_t;
 
-typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1 } prism_dtype_t;
+/* PRISM_F16 is the paper's own precision (Section 7.1: half precision). */
+typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1, PRISM_F16 = 2 } prism_dtype_t;
 
 typedef enum { PRISM_OP_RMSNORM_MATMUL = 0, PRISM_OP_RMSNORM_GATED_MLP = 1 } prism_op_t;
 
@@ -60,7 +62,7 @@ typedef enum {
     PRISM_PATH_AUTO = 0,
     PRISM_PATH_SIMPLE = 1,  /* plain FMA kernel: any M, K, N; the only path for PRISM_F32 */
     PRISM_PATH_DECODE = 2,  /* few rows: W streamed once, split-K over wavefronts and workgroups */
-    PRISM_PATH_PREFILL = 3  /* many rows: LDS-tiled bf16 MFMA GEMM */
+    PRISM_PATH_PREFILL = 3  /* many rows: LDS-tiled MFMA GEMM */
 } prism_path_t;
 
 /* What the dispatcher does for one call (filled by prism_plan). */

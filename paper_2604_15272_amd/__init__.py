@@ -7,6 +7,7 @@ PyTorch fallback; if the shared library is missing the import fails.
 from .binding import (  # noqa: F401
     PRISM_BF16,
     PRISM_F32,
+    PRISM_F16,
     PRISM_OP_RMSNORM_GATED_MLP,
     PRISM_OP_RMSNORM_MATMUL,
     PRISM_PATH_AUTO,

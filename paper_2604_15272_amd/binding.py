@@ -5,7 +5,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "libprism.so")
 
-PRISM_F32, PRISM_BF16 = 0, 1
+PRISM_F32, PRISM_BF16, PRISM_F16 = 0, 1, 2
 PRISM_OP_RMSNORM_MATMUL, PRISM_OP_RMSNORM_GATED_MLP = 0, 1
 PRISM_PATH_AUTO, PRISM_PATH_SIMPLE, PRISM_PATH_DECODE, PRISM_PATH_PREFILL = 0, 1, 2, 3
 WORKSPACE_HEADER_BYTES = 262144
@@ -39,6 +39,13 @@ def _load():
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2604_15272_amd.build` "
             "(there is no fallback implementation)")
+    # PyTorch ships its own copy of the HIP runtime, and the memory and streams the library is handed
+    # come from it: load torch first, so that the library's dependency on the runtime resolves to the
+    # copy that is already in the process and not to a second one.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(_LIB_PATH)
     vp, i64, f32, i32, u64 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_float, ctypes.c_int32, ctypes.c_uint64
     L.prism_rmsnorm_matmul.argtypes = [vp, vp, vp, vp, i64, i64, i64, f32, i32, vp]
@@ -108,6 +115,8 @@ def _dtype_of(t, dtype):
         return PRISM_F32
     if t.dtype == torch.bfloat16:
         return PRISM_BF16
+    if t.dtype == torch.float16:
+        return PRISM_F16
     raise TypeError(f"unsupported tensor dtype {t.dtype}")
 
 

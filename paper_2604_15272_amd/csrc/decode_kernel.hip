@@ -36,7 +36,7 @@ __device__ __forceinline__ void load_w_block(WRows& w, __amdgpu_buffer_rsrc_t rs
 
 // B operand j (j = 0..7) of a lane: column 8c + j of its 8 x 8 sub-block, eight K values.
 template <int J>
-__device__ __forceinline__ bf16x8 b_operand(const WRows& w) {
+__device__ __forceinline__ u32x4 b_operand(const WRows& w) {
     constexpr int d = J >> 1;
     constexpr u32 sel = (J & 1) ? 0x07060302u : 0x05040100u;
     u32x4 b;
@@ -44,37 +44,39 @@ __device__ __forceinline__ bf16x8 b_operand(const WRows& w) {
     b[1] = __builtin_amdgcn_perm(w.r[3][d], w.r[2][d], sel);
     b[2] = __builtin_amdgcn_perm(w.r[5][d], w.r[4][d], sel);
     b[3] = __builtin_amdgcn_perm(w.r[7][d], w.r[6][d], sel);
-    return __builtin_bit_cast(bf16x8, b);
+    return b;
 }
 
-__device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], bf16x8 a, const WRows& w) {
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<0>(w), acc[0], 0, 0, 0);
-    acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<1>(w), acc[1], 0, 0, 0);
-    acc[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<2>(w), acc[2], 0, 0, 0);
-    acc[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<3>(w), acc[3], 0, 0, 0);
-    acc[4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<4>(w), acc[4], 0, 0, 0);
-    acc[5] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<5>(w), acc[5], 0, 0, 0);
-    acc[6] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<6>(w), acc[6], 0, 0, 0);
-    acc[7] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_operand<7>(w), acc[7], 0, 0, 0);
+template <typename F>
+__device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], u32x4 a, const WRows& w) {
+    acc[0] = F::mfma_16x16x32(a, b_operand<0>(w), acc[0]);
+    acc[1] = F::mfma_16x16x32(a, b_operand<1>(w), acc[1]);
+    acc[2] = F::mfma_16x16x32(a, b_operand<2>(w), acc[2]);
+    acc[3] = F::mfma_16x16x32(a, b_operand<3>(w), acc[3]);
+    acc[4] = F::mfma_16x16x32(a, b_operand<4>(w), acc[4]);
+    acc[5] = F::mfma_16x16x32(a, b_operand<5>(w), acc[5]);
+    acc[6] = F::mfma_16x16x32(a, b_operand<6>(w), acc[6]);
+    acc[7] = F::mfma_16x16x32(a, b_operand<7>(w), acc[7]);
 }
 
-// A operand of a lane: X[m = c][8 K values] * g, rounded to bf16; adds the raw squares to ss.
-__device__ __forceinline__ bf16x8 a_operand(u32x4 x, u32x4 gg, float& ss) {
+// A operand of a lane: X[m = c][8 K values] * g, rounded to the storage format; adds the raw squares to ss.
+template <typename F>
+__device__ __forceinline__ u32x4 a_operand(u32x4 x, u32x4 gg, float& ss) {
     u32x4 a;
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-        const float x0 = bf16_lo(x[d]), x1 = bf16_hi(x[d]);
+        const float x0 = F::lo(x[d]), x1 = F::hi(x[d]);
         ss = fmaf(x0, x0, ss);
         ss = fmaf(x1, x1, ss);
-        a[d] = pack_bf16(x0 * bf16_lo(gg[d]), x1 * bf16_hi(gg[d]));
+        a[d] = F::pack(x0 * F::lo(gg[d]), x1 * F::hi(gg[d]));
     }
-    return __builtin_bit_cast(bf16x8, a);
+    return a;
 }
 
 }  // namespace
 
 // LDS: per wavefront a 16 x 128 fp32 tile, plus 16 sums of squares.
-template <int NW, bool GATED>
+template <typename F, int NW, bool GATED>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restrict__ X,
                                                          const uint16_t* __restrict__ g,
                                                          const uint16_t* __restrict__ W1,
@@ -142,15 +144,15 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
             const bool k_ok = has && k < K;
             // X and g first: they come from L2 and let the A operand be ready before W lands.
             xr[u] = load16(rx, (row_ok && k_ok) ? (u32)(((size_t)c * K + k) * 2) : kOutOfRange);
-            gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : bf16_ones();
+            gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
             load_w_block(w1[u], rw1, woff, row_bytes);
             if (GATED) load_w_block(w2[u], rw2, woff, row_bytes);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bf16x8 a = a_operand(xr[u], gr[u], ss);
-            mfma_block(acc1, a, w1[u]);
-            if (GATED) mfma_block(acc2, a, w2[u]);
+            const u32x4 a = a_operand<F>(xr[u], gr[u], ss);
+            mfma_block<F>(acc1, a, w1[u]);
+            if (GATED) mfma_block<F>(acc2, a, w2[u]);
         }
     }
 
@@ -286,18 +288,18 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     }
     uint16_t* out = Y + (size_t)m * N + n;
     if (CPT == 1) {
-        out[0] = (uint16_t)(pack_bf16(y[0], 0.f) & 0xFFFFu);
+        out[0] = (uint16_t)(F::pack(y[0], 0.f) & 0xFFFFu);
     } else {
         u32 packed[CPT / 2 > 0 ? CPT / 2 : 1];
 #pragma unroll
-        for (int e = 0; e < CPT / 2; ++e) packed[e] = pack_bf16(y[2 * e], y[2 * e + 1]);
+        for (int e = 0; e < CPT / 2; ++e) packed[e] = F::pack(y[2 * e], y[2 * e + 1]);
         if (CPT == 2) *(u32*)out = packed[0];
         if (CPT == 4) *(u32x2*)out = u32x2{packed[0], packed[1]};
         if (CPT == 8) *(u32x4*)out = u32x4{packed[0], packed[1], packed[2], packed[3]};
     }
 }
 
-template <int NW>
+template <typename F, int NW>
 static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& ws) {
     const int n_tiles = (c.N + TN - 1) / TN;
     dim3 grid(n_tiles, S), block(NW * 64);
@@ -308,13 +310,13 @@ static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& 
     auto* W2 = (const uint16_t*)c.W2;
     auto* Y = (uint16_t*)c.Y;
     if (c.gated) {
-        auto kern = decode_kernel<NW, true>;
+        auto kern = decode_kernel<F, NW, true>;
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W2, Y, ws.acc_part, ws.ss_part, ws.tickets,
                            c.M, c.K, c.N, c.eps, S, c.flags);
     } else {
-        auto kern = decode_kernel<NW, false>;
+        auto kern = decode_kernel<F, NW, false>;
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W1, Y, ws.acc_part, ws.ss_part, ws.tickets,
@@ -323,13 +325,18 @@ static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& 
     return hipGetLastError();
 }
 
-hipError_t launch_decode_bf16(const Call& c, int split_k, int waves, const DecodeWorkspace& ws) {
+template <typename F>
+static hipError_t launch_decode_fmt(const Call& c, int split_k, int waves, const DecodeWorkspace& ws) {
     switch (waves) {
-        case 4: return launch_decode_nw<4>(c, split_k, ws);
-        case 8: return launch_decode_nw<8>(c, split_k, ws);
-        case 16: return launch_decode_nw<16>(c, split_k, ws);
+        case 4: return launch_decode_nw<F, 4>(c, split_k, ws);
+        case 8: return launch_decode_nw<F, 8>(c, split_k, ws);
+        case 16: return launch_decode_nw<F, 16>(c, split_k, ws);
         default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, const DecodeWorkspace& ws) {
+    return f16 ? launch_decode_fmt<F16>(c, split_k, waves, ws) : launch_decode_fmt<Bf16>(c, split_k, waves, ws);
 }
 
 }  // namespace prism

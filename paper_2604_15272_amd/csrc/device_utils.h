@@ -21,14 +21,51 @@ constexpr u32 kOutOfRange = 0x80000000u;
 __device__ __forceinline__ float bf16_lo(u32 u) { return __builtin_bit_cast(float, u << 16); }
 __device__ __forceinline__ float bf16_hi(u32 u) { return __builtin_bit_cast(float, u & 0xFFFF0000u); }
 
-// Eight bf16 ones (the gain of a call without a gain tensor).
-__device__ __forceinline__ u32x4 bf16_ones() { return u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u}; }
-
 // Two floats -> two bf16 (round to nearest even) in one dword, a in the low half.
 __device__ __forceinline__ u32 pack_bf16(float a, float b) {
     f32x2 v = {a, b};
     return __builtin_bit_cast(u32, __builtin_convertvector(v, bf16x2));
 }
+
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+// The two 16-bit storage formats of the matrix-core kernels.  A dword holds two elements, the one at
+// the lower address in its low half.  lo/hi widen exactly to fp32; pack rounds two fp32 values to
+// nearest even; the MFMA wrappers take operands as raw dwords.
+struct Bf16 {
+    static constexpr u32 kOnePair = 0x3F803F80u;  // two elements of value 1
+    static __device__ __forceinline__ float lo(u32 u) { return bf16_lo(u); }
+    static __device__ __forceinline__ float hi(u32 u) { return bf16_hi(u); }
+    static __device__ __forceinline__ u32 pack(float a, float b) { return pack_bf16(a, b); }
+    static __device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                       0, 0);
+    }
+    static __device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                       0, 0);
+    }
+};
+struct F16 {
+    static constexpr u32 kOnePair = 0x3C003C00u;
+    static __device__ __forceinline__ float lo(u32 u) { return (float)__builtin_bit_cast(f16x2, u)[0]; }
+    static __device__ __forceinline__ float hi(u32 u) { return (float)__builtin_bit_cast(f16x2, u)[1]; }
+    static __device__ __forceinline__ u32 pack(float a, float b) {
+        const f16x2 v = {(_Float16)a, (_Float16)b};
+        return __builtin_bit_cast(u32, v);
+    }
+    static __device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
+                                                      0);
+    }
+    static __device__ __forceinline__ f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
+                                                      0);
+    }
+};
+// Eight elements of value 1 (the gain of a call without a gain tensor).
+template <typename F> __device__ __forceinline__ u32x4 ones8() { return u32x4{F::kOnePair, F::kOnePair, F::kOnePair, F::kOnePair}; }
 
 // Raw buffer descriptor over [p, p + bytes): accesses past the end read as zero.
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, u32 bytes) {

@@ -68,7 +68,7 @@ __device__ __forceinline__ int swz(int n) { return n ^ ((n >> 3) & 15); }
 
 }  // namespace
 
-template <int BM, int BN, bool GATED>
+template <typename F, int BM, int BN, bool GATED>
 __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ g,
                                                       const uint16_t* __restrict__ W1,
                                                       const uint16_t* __restrict__ W2, uint16_t* __restrict__ Y,
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
             // Without a gain tensor the load is still issued (out of range: it returns zero and touches
             // no memory): the wait counts of the pipeline below count instructions.
             const u32x4 v = load16(rg, has_gain ? (u32)(kt * BK + 8 * wkb) * 2u : kOutOfRange);
-            const u32x4 one = bf16_ones();
+            const u32x4 one = ones8<F>();
             s.g = u32x4{has_gain ? v[0] : one[0], has_gain ? v[1] : one[1], has_gain ? v[2] : one[2],
                         has_gain ? v[3] : one[3]};
         }
@@ -183,9 +183,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     auto stage_w_piece = [&](const WSet& s, u32x4* b_stage, int j, int t) {
         const int d = j >> 1;
         const u32 w0 = s.w[2 * t][d], w1 = s.w[2 * t + 1][d], gg = s.g[t];
-        const float e0 = (j & 1) ? bf16_hi(w0) : bf16_lo(w0);
-        const float e1 = (j & 1) ? bf16_hi(w1) : bf16_lo(w1);
-        wb[t] = pack_bf16(e0 * bf16_lo(gg), e1 * bf16_hi(gg));
+        const float e0 = (j & 1) ? F::hi(w0) : F::lo(w0);
+        const float e1 = (j & 1) ? F::hi(w1) : F::lo(w1);
+        wb[t] = F::pack(e0 * F::lo(gg), e1 * F::hi(gg));
         if (t == 3) b_stage[w_dst[j]] = wb;
     };
 
@@ -275,17 +275,22 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #pragma unroll
                 for (int ib = 0; ib < TM32; ++ib) {
                     const u32x2 v = {xf[ib][2 * h], xf[ib][2 * h + 1]};
-                    if constexpr (TM32 >= 4)  // three other MFMAs separate the two uses of an accumulator
-                        asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %1, %0" : "+v"(gram[ib]) : "v"(v));
-                    else
-                        asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %1, %0\n\ts_nop 4" : "+v"(gram[ib]) : "v"(v));
+                    constexpr bool kBf16 = std::is_same<F, Bf16>::value;
+                    if constexpr (TM32 >= 4) {  // three other MFMAs separate the two uses of an accumulator
+                        if constexpr (kBf16) asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %1, %0" : "+v"(gram[ib]) : "v"(v));
+                        else asm volatile("v_mfma_f32_4x4x4_16b_f16 %0, %1, %1, %0" : "+v"(gram[ib]) : "v"(v));
+                    } else {
+                        if constexpr (kBf16)
+                            asm volatile("v_mfma_f32_4x4x4_16b_bf16 %0, %1, %1, %0\n\ts_nop 4" : "+v"(gram[ib]) : "v"(v));
+                        else
+                            asm volatile("v_mfma_f32_4x4x4_16b_f16 %0, %1, %1, %0\n\ts_nop 4" : "+v"(gram[ib]) : "v"(v));
+                    }
                 }
         }
 #pragma unroll
         for (int q = 0; q < MF; ++q) {
             const int jb = q / TM32, ib = q % TM32;
-            acc[jb][ib] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wf[jb]),
-                                                                  __builtin_bit_cast(bf16x8, xf[ib]), acc[jb][ib], 0, 0, 0);
+            acc[jb][ib] = F::mfma_32x32x16(wf[jb], xf[ib], acc[jb][ib]);
 #pragma unroll
             for (int r = q * RPS; r < (q + 1) * RPS && r < RD; ++r) {
                 if (r < TM32) xf_n[r] = a_rd[a_slot[kk_rd] + 4 * XGS * r];
@@ -410,18 +415,18 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
                     y[e] = acc[jb][ib][4 * vg + e] * r;
                     if (GATED) y[e] = (act_silu ? silu_f32(y[e]) : y[e]) * (acc[jb + OB][ib][4 * vg + e] * r);
                 }
-                *(u32x2*)(Y + (size_t)m * N + n) = u32x2{pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3])};
+                *(u32x2*)(Y + (size_t)m * N + n) = u32x2{F::pack(y[0], y[1]), F::pack(y[2], y[3])};
             }
         }
     }
 }
 
-template <int BM, int BN, bool GATED>
+template <typename F, int BM, int BN, bool GATED>
 static hipError_t launch_tile(const Call& c) {
     constexpr int CW = GATED ? BN / 2 : BN;
     const int tiles_m = (c.M + BM - 1) / BM, tiles_n = (c.N + CW - 1) / CW;
     const size_t lds = (size_t)(2 * (BM / 8) * XGS + 2 * KCH * (BN + PAD)) * 16 + (size_t)BM * 4;
-    auto kern = prefill_kernel<BM, BN, GATED>;
+    auto kern = prefill_kernel<F, BM, BN, GATED>;
     static std::atomic<uint64_t> opted{0};
     if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds, c.stream, (const uint16_t*)c.X,
@@ -430,18 +435,23 @@ static hipError_t launch_tile(const Call& c) {
     return hipGetLastError();
 }
 
-hipError_t launch_prefill_bf16(const Call& c, int tile_m, int tile_n) {
+template <typename F>
+static hipError_t launch_prefill_fmt(const Call& c, int tile_m, int tile_n) {
     if (c.gated) {
-        if (tile_m == 256 && tile_n == 256) return launch_tile<256, 256, true>(c);
-        if (tile_m == 128 && tile_n == 256) return launch_tile<128, 256, true>(c);
-        if (tile_m == 128 && tile_n == 128) return launch_tile<128, 128, true>(c);
+        if (tile_m == 256 && tile_n == 256) return launch_tile<F, 256, 256, true>(c);
+        if (tile_m == 128 && tile_n == 256) return launch_tile<F, 128, 256, true>(c);
+        if (tile_m == 128 && tile_n == 128) return launch_tile<F, 128, 128, true>(c);
     } else {
-        if (tile_m == 256 && tile_n == 256) return launch_tile<256, 256, false>(c);
-        if (tile_m == 256 && tile_n == 192) return launch_tile<256, 192, false>(c);
-        if (tile_m == 128 && tile_n == 128) return launch_tile<128, 128, false>(c);
-        if (tile_m == 64 && tile_n == 64) return launch_tile<64, 64, false>(c);
+        if (tile_m == 256 && tile_n == 256) return launch_tile<F, 256, 256, false>(c);
+        if (tile_m == 256 && tile_n == 192) return launch_tile<F, 256, 192, false>(c);
+        if (tile_m == 128 && tile_n == 128) return launch_tile<F, 128, 128, false>(c);
+        if (tile_m == 64 && tile_n == 64) return launch_tile<F, 64, 64, false>(c);
     }
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n) {
+    return f16 ? launch_prefill_fmt<F16>(c, tile_m, tile_n) : launch_prefill_fmt<Bf16>(c, tile_m, tile_n);
 }
 
 }  // namespace prism

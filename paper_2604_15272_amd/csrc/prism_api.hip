@@ -30,7 +30,8 @@ struct Plan {
     uint64_t ss_bytes;  // decode: bytes of the partial sums of squares (rounded)
 };
 
-bool bf16_vector_ok(int64_t K, int64_t N) { return K % 8 == 0 && N % 8 == 0; }
+bool vector16_ok(int64_t K, int64_t N) { return K % 8 == 0 && N % 8 == 0; }
+bool dtype_known(prism_dtype_t d) { return d == PRISM_F32 || d == PRISM_BF16 || d == PRISM_F16; }
 
 // Prefill tile choice: fewest "rounds" of 256 workgroups, weighted by how well a tile shape feeds
 // the matrix cores (bigger tiles re-read less from LDS per MFMA).
@@ -70,7 +71,7 @@ bool prefill_tile_known(bool gated, int bm, int bn) {
 
 prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Plan* out) {
     if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP) return PRISM_ERR_UNSUPPORTED;
-    if (dtype != PRISM_F32 && dtype != PRISM_BF16) return PRISM_ERR_UNSUPPORTED;
+    if (!dtype_known(dtype)) return PRISM_ERR_UNSUPPORTED;
     if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return PRISM_ERR_UNSUPPORTED;
     const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
@@ -84,7 +85,7 @@ prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_d
     int path = forced;
     if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL) return PRISM_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return PRISM_OK;  // empty problem: nothing is launched
-    const bool fast_ok = dtype == PRISM_BF16 && bf16_vector_ok(K, N);
+    const bool fast_ok = dtype != PRISM_F32 && vector16_ok(K, N);
     if (path == PRISM_PATH_AUTO) {
         if (!fast_ok) path = PRISM_PATH_SIMPLE;
         else path = (M <= kDecodeMaxRows) ? PRISM_PATH_DECODE : PRISM_PATH_PREFILL;
@@ -167,7 +168,7 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                    int flags = kFlagGain | kFlagNorm | kFlagSilu) {
     const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
     if (!g) flags &= ~kFlagGain;
-    if (dtype != PRISM_F32 && dtype != PRISM_BF16) return PRISM_ERR_UNSUPPORTED;
+    if (!dtype_known(dtype)) return PRISM_ERR_UNSUPPORTED;
     if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
     if (!(eps >= 0.0f) || !std::isfinite(eps)) return PRISM_ERR_INVALID_ARG;
     if (M == 0 || N == 0) return PRISM_OK;  // empty problem: pointers are not looked at
@@ -182,7 +183,8 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
     hipError_t err = hipSuccess;
     switch (plan.pub.path) {
         case PRISM_PATH_SIMPLE:
-            err = (dtype == PRISM_F32) ? launch_simple_f32(c) : launch_simple_bf16(c);
+            err = (dtype == PRISM_F32) ? launch_simple_f32(c)
+                  : (dtype == PRISM_F16) ? launch_simple_f16(c) : launch_simple_bf16(c);
             break;
         case PRISM_PATH_DECODE: {
             DecodeWorkspace ws{nullptr, nullptr, nullptr};
@@ -197,11 +199,11 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                 ws.ss_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES);
                 ws.acc_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES + plan.ss_bytes);
             }
-            err = launch_decode_bf16(c, plan.pub.split_k, plan.waves, ws);
+            err = launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.waves, ws);
             break;
         }
         case PRISM_PATH_PREFILL:
-            err = launch_prefill_bf16(c, plan.pub.tile_m, plan.pub.tile_n);
+            err = launch_prefill_16bit(c, dtype == PRISM_F16, plan.pub.tile_m, plan.pub.tile_n);
             break;
         default:
             return PRISM_ERR_UNSUPPORTED;

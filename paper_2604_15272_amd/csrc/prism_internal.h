@@ -56,7 +56,9 @@ inline hipError_t allow_large_lds(const void* kernel, size_t bytes, std::atomic<
 
 hipError_t launch_simple_f32(const Call& c);
 hipError_t launch_simple_bf16(const Call& c);
-hipError_t launch_decode_bf16(const Call& c, int split_k, int waves, const DecodeWorkspace& ws);
-hipError_t launch_prefill_bf16(const Call& c, int tile_m, int tile_n);
+hipError_t launch_simple_f16(const Call& c);
+// The matrix-core kernels, for either 16-bit storage format (f16 = false: bf16).
+hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, const DecodeWorkspace& ws);
+hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);
 
 }  // namespace prism

@@ -1,4 +1,4 @@
-// Plain FMA kernel for any M, K, N and both storage types.
+// Plain FMA kernel for any M, K, N and every storage type.
 //
 // One workgroup owns an 8-row by 256-column output tile.  It walks K in chunks: each chunk of X is
 // staged in LDS already multiplied by the gain, while the raw squares are summed on the side
@@ -19,7 +19,9 @@ template <> __device__ __forceinline__ float load_elem<float>(const float* p, si
 template <> __device__ __forceinline__ float load_elem<uint16_t>(const uint16_t* p, size_t i) {
     return __builtin_bit_cast(float, (u32)p[i] << 16);
 }
+template <> __device__ __forceinline__ float load_elem<_Float16>(const _Float16* p, size_t i) { return (float)p[i]; }
 template <typename T> __device__ __forceinline__ void store_elem(T* p, size_t i, float v);
+template <> __device__ __forceinline__ void store_elem<_Float16>(_Float16* p, size_t i, float v) { p[i] = (_Float16)v; }
 template <> __device__ __forceinline__ void store_elem<float>(float* p, size_t i, float v) { p[i] = v; }
 template <> __device__ __forceinline__ void store_elem<uint16_t>(uint16_t* p, size_t i, float v) {
     p[i] = (uint16_t)(pack_bf16(v, 0.0f) & 0xFFFFu);
@@ -115,5 +117,6 @@ static hipError_t launch_simple(const Call& c) {
 
 hipError_t launch_simple_f32(const Call& c) { return launch_simple<float>(c); }
 hipError_t launch_simple_bf16(const Call& c) { return launch_simple<uint16_t>(c); }
+hipError_t launch_simple_f16(const Call& c) { return launch_simple<_Float16>(c); }
 
 }  // namespace prism

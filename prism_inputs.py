@@ -6,9 +6,9 @@ the HIP path's callers may use it; neither of those two imports the other.
 
 The paper measures on tensor shapes taken from LLM layers, not on a dataset
 (Section 7.1), so every input is dense i.i.d. noise of the workload's shape:
-X ~ N(0,1), g ~ U(0.5,1.5), W ~ N(0, variance 1/K).  bf16 workloads round the
-fp32 draw once, to nearest even, and that stored value is the input for both
-sides.
+X ~ N(0,1), g ~ U(0.5,1.5), W ~ N(0, variance 1/K).  bf16 and fp16 workloads round
+the fp32 draw once, to nearest even, and that stored value is the input for
+both sides.
 """
 from dataclasses import dataclass
 
@@ -16,6 +16,7 @@ import numpy as np
 
 F32 = "f32"
 BF16 = "bf16"
+F16 = "f16"   # the paper's own precision (Section 7.1); stored as numpy float16
 
 
 @dataclass(frozen=True)
@@ -60,11 +61,17 @@ def to_f64(stored, dtype):
     """Exact float64 value of a stored array (fp32 array, or uint16 bf16 bit patterns)."""
     if dtype == BF16:
         return bf16_bits_to_f32(stored).astype(np.float64)
+    if dtype == F16:
+        return np.asarray(stored, dtype=np.float16).astype(np.float64)
     return np.asarray(stored, dtype=np.float32).astype(np.float64)
 
 
 def _store(a32, dtype):
-    return f32_to_bf16_bits(a32) if dtype == BF16 else np.ascontiguousarray(a32, dtype=np.float32)
+    if dtype == BF16:
+        return f32_to_bf16_bits(a32)
+    if dtype == F16:
+        return np.ascontiguousarray(a32, dtype=np.float32).astype(np.float16)  # nearest even
+    return np.ascontiguousarray(a32, dtype=np.float32)
 
 
 def _stream(seed, tensor_id):
@@ -75,7 +82,7 @@ def draw(dtype, M, K, N, gated, seed, w_scale=None):
     """Draw X[M,K], g[K] and W[K,N] (or W1, W2) in storage format.
 
     Returns a dict of stored arrays: float32 arrays for F32, uint16 bit
-    patterns for BF16.  Each tensor has its own counter-based stream, so a
+    patterns for BF16, float16 arrays for F16.  Each tensor has its own counter-based stream, so a
     tensor's values do not depend on which others were drawn.
     """
     std = (1.0 / np.sqrt(K)) if w_scale is None else float(w_scale)

@@ -4,6 +4,14 @@ import numpy as np
 import prism_inputs as pi
 
 
+DTYPE_CODE = {pi.F32: 0, pi.BF16: 1, pi.F16: 2}   # prism_dtype_t
+
+
+def torch_dtype(dtype):
+    import torch
+    return {pi.F32: torch.float32, pi.BF16: torch.bfloat16, pi.F16: torch.float16}[dtype]
+
+
 def to_device(stored, dtype):
     import torch
     t = torch.from_numpy(np.ascontiguousarray(stored)).cuda()
@@ -14,7 +22,7 @@ def from_device(t, dtype):
     import torch
     if dtype == pi.BF16:
         return pi.to_f64(t.view(torch.uint16).cpu().numpy(), pi.BF16)
-    return t.cpu().numpy().astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)   # fp32 and fp16 widen exactly
 
 
 def run_gpu(stored, dtype, gated, eps, poison=True):
@@ -24,7 +32,7 @@ def run_gpu(stored, dtype, gated, eps, poison=True):
     X = to_device(stored["X"], dtype)
     g = to_device(stored["g"], dtype)
     M = X.shape[0]
-    tdt = torch.bfloat16 if dtype == pi.BF16 else torch.float32
+    tdt = torch_dtype(dtype)
     if gated:
         W1, W2 = to_device(stored["W1"], dtype), to_device(stored["W2"], dtype)
         N = W1.shape[1]
@@ -52,7 +60,7 @@ def run_gpu_variant(stored, dtype, variant, eps):
     X = to_device(stored["X"], dtype)
     g = to_device(stored["g"], dtype)
     M = X.shape[0]
-    tdt = torch.bfloat16 if dtype == pi.BF16 else torch.float32
+    tdt = torch_dtype(dtype)
     names = ("W",) if variant == "plain_nogain" else ("W1", "W2")
     Ws = [to_device(stored[n], dtype) for n in names]
     N = Ws[0].shape[1]
@@ -101,11 +109,14 @@ def run_oracle(stored, dtype, gated, eps, rows=None):
     return oracle.rmsnorm_matmul(X, g, pi.to_f64(stored["W"], dtype), eps)
 
 
-TOL = {pi.F32: 1e-5, pi.BF16: 2e-2}
+# fp32 and bf16: stated by the benchmark spec.  fp16: the bf16 bar scaled by the three extra significand bits
+# (both error sources, the rounding of x * g on its way into the matrix core and the rounding of y,
+# are 2^-11 instead of 2^-8 relative).
+TOL = {pi.F32: 1e-5, pi.BF16: 2e-2, pi.F16: 2.5e-3}
 
 
 def worst_error(y, yhat):
-    """max |y - yhat| / (|yhat| + 1): the parity bar is this <= 1e-5 (fp32) or 2e-2 (bf16)."""
+    """max |y - yhat| / (|yhat| + 1): the parity bar is this <= 1e-5 (fp32), 2e-2 (bf16), 2.5e-3 (fp16)."""
     y = np.asarray(y, dtype=np.float64)
     yhat = np.asarray(yhat, dtype=np.float64)
     assert y.shape == yhat.shape

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import prism_inputs as pi
-from gpu_util import assert_parity, run_gpu, run_gpu_variant, run_oracle, run_oracle_variant, worst_error
+from gpu_util import DTYPE_CODE, assert_parity, run_gpu, run_gpu_variant, run_oracle, run_oracle_variant, worst_error
 
 pytestmark = pytest.mark.gpu
 
@@ -25,7 +25,7 @@ def _case(P, dtype, M, K, N, gated, seed, eps=1e-6, path=0, split=0, variant=0, 
     stored = pi.draw(dtype, M, K, N, gated, seed)
     P.prism_set_override(path, split, variant)
     try:
-        plan = P.prism_plan(int(gated), M, K, N, 1 if dtype == pi.BF16 else 0)
+        plan = P.prism_plan(int(gated), M, K, N, DTYPE_CODE[dtype])
         if expect_path is not None:
             assert plan["path"] == expect_path, plan
         print(f"case dtype={dtype} M={M} K={K} N={N} gated={gated} seed={seed} plan={plan}", flush=True)
@@ -154,7 +154,7 @@ def _variant_case(P, dtype, M, K, N, variant, seed, path=0, split=0, tile=0, x_s
         stored["X"] = pi.f32_to_bf16_bits(x) if dtype == pi.BF16 else x
     P.prism_set_override(path, split, tile)
     try:
-        plan = P.prism_plan(int(gated), M, K, N, 1 if dtype == pi.BF16 else 0)
+        plan = P.prism_plan(int(gated), M, K, N, DTYPE_CODE[dtype])
         print(f"variant={variant} dtype={dtype} M={M} K={K} N={N} seed={seed} plan={plan}", flush=True)
         y = run_gpu_variant(stored, dtype, variant, 1e-6)
     finally:
@@ -199,6 +199,34 @@ def test_no_gain_equals_gain_of_ones_bit_for_bit(P):
         P.prism_rmsnorm_matmul(X, ones, W, Y1)
         torch.cuda.synchronize()
         assert torch.equal(Y0.view(torch.uint16), Y1.view(torch.uint16))
+
+
+# ---- fp16, the paper's precision (Section 7.1) -------------------------------------------------------
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("M,K,N,path", [(3, 77, 130, 1), (8, 256, 512, 2), (8, 1024, 1024, 2), (16, 4096, 4096, 2),
+                                        (13, 2056, 1160, 2), (33, 200, 264, 3), (300, 712, 648, 3),
+                                        (1024, 1024, 768, 3)])
+def test_f16_shapes(P, M, K, N, path, gated):
+    _case(P, pi.F16, M, K, N, gated, seed=900 + M, expect_path=path)
+
+
+@pytest.mark.parametrize("variant", ["plain_nogain", "glu_nogain", "swiglu"])
+@pytest.mark.parametrize("M,K,N", [(8, 1024, 1024), (16, 1024, 4096), (8, 4096, 4096), (16, 4096, 14336), (512, 1024, 512)])
+def test_f16_paper_variants_at_paper_shapes(P, variant, M, K, N):
+    """What the paper measures: n in {8, 16}, d in {1024, 4096}, half precision, no gain (Section 7.1)."""
+    _variant_case(P, pi.F16, M, K, N, variant, seed=910 + M + K)
+
+
+@pytest.mark.parametrize("gated,tile", [(False, 256256), (False, 256192), (False, 128128), (False, 64064),
+                                        (True, 256256), (True, 128256), (True, 128128)])
+def test_f16_prefill_every_tile(P, gated, tile):
+    _case(P, pi.F16, 300, 712, 648, gated, seed=920, path=P.PRISM_PATH_PREFILL, variant=tile)
+
+
+@pytest.mark.parametrize("split,waves", [(1, 8), (3, 4), (7, 8), (4, 16)])
+def test_f16_decode_splits(P, split, waves):
+    _case(P, pi.F16, 16, 2056, 1160, True, seed=921, path=P.PRISM_PATH_DECODE, split=split, variant=waves)
 
 
 # ---- degenerate inputs -------------------------------------------------------------------------

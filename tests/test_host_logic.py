@@ -68,6 +68,9 @@ def test_plan_picks_paths_by_shape(P):
     pg = P.prism_plan(1, 4096, 4096, 14336, bf16)
     assert pg["path"] == P.PRISM_PATH_PREFILL
     assert pg["grid_x"] == -(-4096 // pg["tile_m"]) * -(-14336 // (pg["tile_n"] // 2))
+    assert P.prism_plan(0, 16, 4096, 4096, P.PRISM_F16) == d
+    assert P.prism_plan(1, 4096, 4096, 14336, P.PRISM_F16) == pg
+    assert P.prism_plan(0, 16, 4100, 4096, P.PRISM_F16)["path"] == P.PRISM_PATH_SIMPLE
     # unaligned bf16 shapes go to the plain kernel
     assert P.prism_plan(0, 16, 4100, 4096, bf16)["path"] == P.PRISM_PATH_SIMPLE
     assert P.prism_plan(0, 16, 4096, 4100, bf16)["path"] == P.PRISM_PATH_SIMPLE
@@ -111,4 +114,9 @@ def test_inputs_are_deterministic_and_bf16_exact():
     assert np.array_equal(pi.f32_to_bf16_bits(x), a["X"])
     g = pi.to_f64(a["g"], pi.BF16)
     assert g.min() >= 0.5 and g.max() <= 1.5
+    h = pi.draw(pi.F16, 4, 64, 32, False, 5)
+    assert h["X"].dtype == np.float16 and np.array_equal(pi.to_f64(h["X"], pi.F16), h["X"].astype(np.float64))
+    # the fp16 draw is the fp32 draw of the same seed, rounded once
+    f = pi.draw(pi.F32, 4, 64, 32, False, 5)
+    assert np.array_equal(h["W"], f["W"].astype(np.float16))
     assert len(pi.WORKLOADS) == 5 and pi.WORKLOADS[1].N == 4096 and pi.WORKLOADS[3].gated
