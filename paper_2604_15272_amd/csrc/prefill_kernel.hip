@@ -57,6 +57,16 @@ namespace prism {
 
 namespace {
 
+// One row of a thread's block of W: 8 columns (16 bytes) or 6 (12 bytes; the fourth dword is unused).
+template <int CB> __device__ __forceinline__ u32x4 load_cols(__amdgpu_buffer_rsrc_t r, u32 voff) {
+    if constexpr (CB == 8) {
+        return load16(r, voff);
+    } else {
+        const u32x3 v = __builtin_amdgcn_raw_buffer_load_b96(r, (int)voff, 0, 0);
+        return u32x4{v[0], v[1], v[2], 0u};
+    }
+}
+
 constexpr int BK = 64;       // K depth of one LDS stage
 constexpr int KCH = BK / 8;  // 16-byte K chunks per row of a stage
 constexpr int PAD = 1;       // 16-byte slots of padding per K-chunk plane of the W stage
@@ -122,25 +132,35 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     const size_t x_left = ((size_t)M * K - x_first) * 2;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + x_first, (u32)(x_left < 0x7FFFFFFFull ? x_left : 0x7FFFFFFFull));
     const __amdgpu_buffer_rsrc_t rg = make_rsrc(g, (u32)K * 2u);
-    // W: thread t owns one 8 (k) x 8 (n) block of the stage.  Which matrix a wavefront reads is the
-    // same for all its lanes (CW is a multiple of 64); say so, to keep the descriptor in SGPRs.
-    constexpr int NB8 = CW / 8;  // 8-column groups per weight matrix
-    const int wmat = GATED ? __builtin_amdgcn_readfirstlane((tid / CW) & 1) : 0;
-    const int wt = GATED ? tid % CW : tid;
-    const bool w_active = tid < BN;
-    const int wkb = wt / NB8, wnb = wt % NB8;
-    const bool w_col_ok = w_active && (n0 + 8 * wnb) < N;
+    // W: thread t owns one 8 (k) x CB (n) block of the stage, CB = 8 columns (one 16-byte load per
+    // row).  A 192-column tile would leave a quarter of the threads without a block while the others
+    // carry the whole transposition, which is more vector work than fits under their 48 MFMAs per K
+    // step; there a block is 6 columns wide (12-byte loads), so that all 256 threads share the work.
+    // Which matrix a wavefront reads is the same for all its lanes (a matrix's threads are a multiple of 64);
+    // say so, to keep the descriptor in SGPRs.
+    constexpr int CB = (BN == 192) ? 6 : 8;
+    constexpr int NBG = CW / CB;     // column groups per weight matrix
+    constexpr int TPM = KCH * NBG;   // threads per weight matrix
+    constexpr int NP = 4 * CB;       // staging pieces per thread and tile (4 per column)
+    static_assert(CW % CB == 0 && TPM % 64 == 0 && (GATED ? 2 : 1) * TPM <= 256, "W staging map");
+    const int wmat = GATED ? __builtin_amdgcn_readfirstlane((tid / TPM) & 1) : 0;
+    const int wt = GATED ? tid % TPM : tid;
+    const bool w_active = tid < (GATED ? 2 : 1) * TPM;
+    const int wkb = wt / NBG, wnb = wt % NBG;
+    // (A 6-column group that straddles N reads columns that belong to the next row of W: they only
+    // reach accumulators of columns >= N, which are never stored.)
+    const bool w_col_ok = w_active && (n0 + CB * wnb) < N;
     const size_t w_left = ((size_t)K * N - n0) * 2;
     const u32 w_bytes = (u32)(w_left < 0x7FFFFFFFull ? w_left : 0x7FFFFFFFull);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc((wmat ? W2 : W1) + n0, w_bytes);
     const u32 row_bytes = (u32)N * 2u;
-    const u32 w_lane = w_col_ok ? ((u32)(8 * wkb) * row_bytes + (u32)(16 * wnb)) : kOutOfRange;
-    const int w_lds_col = wmat * (BN / 2) + 8 * wnb;  // first LDS column of the block
+    const u32 w_lane = w_col_ok ? ((u32)(8 * wkb) * row_bytes + (u32)(2 * CB * wnb)) : kOutOfRange;
+    const int w_lds_col = wmat * (BN / 2) + CB * wnb;  // first LDS column of the block
     // LDS slot of column j of the block, within a stage.  Threads without a block (tiles narrower than
     // 256) store to a padding slot instead of branching, which keeps the K loop one basic block.
-    int w_dst[8];
+    int w_dst[CB];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) w_dst[j] = w_active ? wkb * B_PLANE + swz(w_lds_col + j) : BN;
+    for (int j = 0; j < CB; ++j) w_dst[j] = w_active ? wkb * B_PLANE + swz(w_lds_col + j) : BN;
 
     // Two register sets for W: while one is being staged into LDS, the other already holds the tile
     // after it, so a tile's loads have more than a whole K step to arrive.
@@ -162,7 +182,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
             s.g = u32x4{has_gain ? v[0] : one[0], has_gain ? v[1] : one[1], has_gain ? v[2] : one[2],
                         has_gain ? v[3] : one[3]};
         }
-        else s.w[i - 1] = load16(rw, w_lane + (u32)kt * BK * row_bytes + (u32)(i - 1) * row_bytes);
+        else s.w[i - 1] = load_cols<CB>(rw, w_lane + (u32)kt * BK * row_bytes + (u32)(i - 1) * row_bytes);
     };
     constexpr int NWL = 9;  // loads per set
     // X, request i of K step kt: this wavefront moves rows 8 * wave + 32 i .. + 7 (64 K values each)
@@ -315,11 +335,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         asm volatile("" ::: "memory");
     };
 
-    // W pieces (4 per column, 32 per tile): the first P3 could be staged a step early, in phase 3 (after
+    // W pieces (4 per column, NP per tile): the first P3 could be staged a step early, in phase 3 (after
     // the barrier, into the stage just vacated), the rest in phases 0, 1, 2.  Measured best with none
     // in phase 3: the set's last loads are issued only two phases before it.
     constexpr int P3 = 0;
-    constexpr int wp1 = P3 + (32 - P3) / 3, wp2 = P3 + 2 * (32 - P3) / 3;
+    constexpr int wp1 = P3 + (NP - P3) / 3, wp2 = P3 + 2 * (NP - P3) / 3;
     const int KT = (K + BK - 1) / BK;
     const int KT2 = (KT + 1) & ~1;  // the loop body holds two steps (one per register set); an odd
                                     // count is padded with a step whose X and W read as zero
@@ -340,7 +360,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #define IC(v) integral_constant<int, (v)> {}
         phase(IC(0), IC(1), IC(P3), IC(wp1 - P3), a_cur, b_cur, 1, xfA, wfA, xfB, wfB, a_nxt, kt + 1, wo, ws, b_nxt);
         phase(IC(1), IC(2), IC(wp1), IC(wp2 - wp1), a_cur, b_cur, 2, xfB, wfB, xfA, wfA, a_nxt, kt + 1, wo, ws, b_nxt);
-        phase(IC(2), IC(-1), IC(wp2), IC(32 - wp2), a_cur, b_cur, 3, xfA, wfA, xfB, wfB, a_nxt, kt + 1, wo, ws, b_nxt);
+        phase(IC(2), IC(-1), IC(wp2), IC(NP - wp2), a_cur, b_cur, 3, xfA, wfA, xfB, wfB, a_nxt, kt + 1, wo, ws, b_nxt);
         // The next tile is complete in LDS (the requests of its X part are followed by NWL younger
         // instructions only); nobody reads the current stage any more.
         stage_barrier(IC(NWL));
@@ -359,7 +379,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
 #pragma unroll
     for (int i = 0; i < NWL; ++i) load_w(ws_a, 1, i);
 #pragma unroll
-    for (int p = 0; p < 32; ++p) stage_w_piece(ws_b, Bs, p / 4, p % 4);
+    for (int p = 0; p < NP; ++p) stage_w_piece(ws_b, Bs, p / 4, p % 4);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int q = 0; q < MF; ++q) refill_slot(integral_constant<int, 0>{}, q, As + A_SLOTS, 1, ws_b);
