@@ -73,8 +73,15 @@ constexpr int PAD = 1;       // 16-byte slots of padding per K-chunk plane of th
 constexpr int XGS = 72;      // 16-byte slots per group of 8 rows of the X stage: 64 of data, 8 of padding
 
 // Column swizzle of the W tile: a bijection on every aligned group of 16 columns (given the
-// higher bits), chosen so that the permuted 8 x 8 blocks store without bank conflicts.
-__device__ __forceinline__ int swz(int n) { return n ^ ((n >> 3) & 15); }
+// higher bits), so that operand reads of consecutive columns stay conflict-free, chosen so that
+// the stores of the transposed blocks are conflict-free too.  With 8-column blocks sixteen lanes
+// store columns 8 i + j: an XOR with the group number separates them.  With 6-column blocks
+// (192-wide tile) they store columns 6 i + j, whose positions within a group of 16 repeat after
+// 48 columns: every other run of three groups is rotated by one.
+template <int CB> __device__ __forceinline__ int swz(int n) {
+    if constexpr (CB == 8) return n ^ ((n >> 3) & 15);
+    else return (n & ~15) | ((n + (((n >> 4) / 3) & 1)) & 15);
+}
 
 }  // namespace
 
@@ -160,7 +167,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     // 256) store to a padding slot instead of branching, which keeps the K loop one basic block.
     int w_dst[CB];
 #pragma unroll
-    for (int j = 0; j < CB; ++j) w_dst[j] = w_active ? wkb * B_PLANE + swz(w_lds_col + j) : BN;
+    for (int j = 0; j < CB; ++j) w_dst[j] = w_active ? wkb * B_PLANE + swz<CB>(w_lds_col + j) : BN;
 
     // Two register sets for W: while one is being staged into LDS, the other already holds the tile
     // after it, so a tile's loads have more than a whole K step to arrive.
@@ -226,7 +233,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         } else {
             col = wn * WTN + 32 * jb;
         }
-        b_slot[jb] = lh * B_PLANE + swz(col + l32);
+        b_slot[jb] = lh * B_PLANE + swz<CB>(col + l32);
     }
     // Operands of 16-deep phase kk of a stage: chunk plane 2 kk + lh.
     auto read_frags = [&](const u32x4* a_stage, const u32x4* b_stage, int kk, u32x4 (&xf)[TM32], u32x4 (&wf)[TN32]) {
