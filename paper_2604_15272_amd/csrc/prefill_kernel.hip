@@ -420,31 +420,51 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     }
     __syncthreads();
 
-    // ---- epilogue: register v of block (jb, ib) is row 32 ib + l32, column 32 jb + 8 (v / 4) + 4 lh + v % 4
+    // ---- epilogue: register v of block (jb, ib) is row 32 ib + l32, column 32 jb + 8 (v / 4) + 4 lh + v % 4.
+    // A lane's 8 bytes of a row, stored from the registers, would be one cache request each (a quarter
+    // of a million per tile, a tenth of everything the L2 sees, and the L2 is what this kernel keeps
+    // busy).  So the finished tile goes through LDS, which is free now: every wavefront writes its own
+    // part in the storage format and reads it back row by row, and a store instruction then covers
+    // whole 64- to 256-byte runs of a row.  The staged row pitch is 8 bytes more than the row, which
+    // spreads the 32 rows a store instruction touches over all banks.
     constexpr int OB = GATED ? TN32 / 2 : TN32;  // output 32-column blocks per wavefront
+    constexpr int WOC = 32 * OB;                 // output columns per wavefront
+    constexpr int PB = CW * 2 + 8;               // bytes per staged row
+    constexpr int CPR = WOC / 8;                 // 16-byte pieces per row of a wavefront's part
+    static_assert(BM * PB <= (2 * A_SLOTS + 2 * B_SLOTS) * 16, "the staged tile fits in the operand stages");
+    static_assert((WTM * CPR) % 64 == 0, "whole store instructions");
     const bool act_silu = (flags & kFlagSilu) != 0;
+    char* ostage = (char*)lds;
 #pragma unroll
     for (int ib = 0; ib < TM32; ++ib) {
         const int ml = wm * WTM + 32 * ib + l32;
-        const int m = m0 + ml;
         const float r = rscale[ml];
-        if (m >= M) continue;
 #pragma unroll
         for (int jb = 0; jb < OB; ++jb) {
-            const int cbase = n0 + wn * (GATED ? WTN / 2 : WTN) + 32 * jb + 4 * lh;
 #pragma unroll
             for (int vg = 0; vg < 4; ++vg) {
-                const int n = cbase + 8 * vg;
-                if (n >= N) continue;
+                const int col = wn * WOC + 32 * jb + 4 * lh + 8 * vg;
                 float y[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     y[e] = acc[jb][ib][4 * vg + e] * r;
                     if (GATED) y[e] = (act_silu ? silu_f32(y[e]) : y[e]) * (acc[jb + OB][ib][4 * vg + e] * r);
                 }
-                *(u32x2*)(Y + (size_t)m * N + n) = u32x2{F::pack(y[0], y[1]), F::pack(y[2], y[3])};
+                *(u32x2*)(ostage + ml * PB + col * 2) = u32x2{F::pack(y[0], y[1]), F::pack(y[2], y[3])};
             }
         }
+    }
+    // The same wavefront reads what it wrote (LDS accesses of a wavefront complete in order).
+#pragma unroll
+    for (int i = 0; i < WTM * CPR / 64; ++i) {
+        const int idx = i * 64 + lane;
+        const int row = idx / CPR, piece = idx % CPR;
+        const int ml = wm * WTM + row;
+        const int col = wn * WOC + 8 * piece;
+        const u32x2 lo = *(const u32x2*)(ostage + ml * PB + col * 2);
+        const u32x2 hi = *(const u32x2*)(ostage + ml * PB + col * 2 + 8);
+        const int m = m0 + ml, n = n0 + col;
+        if (m < M && n < N) *(u32x4*)(Y + (size_t)m * N + n) = u32x4{lo[0], lo[1], hi[0], hi[1]};
     }
 }
 
