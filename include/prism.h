@@ -154,6 +154,22 @@ prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_
  */
 prism_status_t prism_set_override(int32_t path, int32_t split_k, int32_t variant);
 
+/*
+ * Plan table: per-shape parameter assignments that take precedence over the built-in heuristic (but
+ * not over prism_set_override).  This is where a tuner puts what it found: the paper instantiates
+ * the parameters of a program by sampling valid assignments and profiling them (Section 5,
+ * "parameter instantiation"); the kernels here are correct for every admissible assignment, so the
+ * same can be done at run time (see the tune module of the Python package).
+ * prism_plan_table_set: (path, split_k, variant) as in prism_set_override, for calls of exactly this
+ *   (op, M, K, N, dtype); the three gated operations share PRISM_OP_RMSNORM_GATED_MLP.  Replaces an
+ *   existing entry for the same key.  PRISM_ERR_UNSUPPORTED if the assignment cannot run the shape
+ *   or the table (256 entries) is full.  Host-side only, thread-safe, touches no device.
+ */
+prism_status_t prism_plan_table_set(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype,
+                                    int32_t path, int32_t split_k, int32_t variant);
+prism_status_t prism_plan_table_clear(void);
+int32_t prism_plan_table_size(void);
+
 const char* prism_status_string(prism_status_t status);
 int32_t prism_version(void);
 

@@ -20,6 +20,9 @@ from .binding import (  # noqa: F401
     lib,
     library_path,
     prism_plan,
+    prism_plan_table_clear,
+    prism_plan_table_set,
+    prism_plan_table_size,
     prism_rmsnorm_gated_mlp,
     prism_rmsnorm_glu,
     prism_swiglu,

@@ -67,6 +67,12 @@ def _load():
     L.prism_set_workspace.restype = i32
     L.prism_plan.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
     L.prism_plan.restype = i32
+    L.prism_plan_table_set.argtypes = [i32, i64, i64, i64, i32, i32, i32, i32]
+    L.prism_plan_table_set.restype = i32
+    L.prism_plan_table_clear.argtypes = []
+    L.prism_plan_table_clear.restype = i32
+    L.prism_plan_table_size.argtypes = []
+    L.prism_plan_table_size.restype = i32
     L.prism_set_override.argtypes = [i32, i32, i32]
     L.prism_set_override.restype = i32
     L.prism_status_string.argtypes = [i32]
@@ -142,6 +148,20 @@ def prism_set_override(path=0, split_k=0, variant=0):
     st = lib.prism_set_override(int(path), int(split_k), int(variant))
     if st != 0:
         raise PrismError(st, "prism_set_override")
+
+
+def prism_plan_table_set(op, M, K, N, dtype, path, split_k=0, variant=0):
+    st = lib.prism_plan_table_set(int(op), int(M), int(K), int(N), int(dtype), int(path), int(split_k), int(variant))
+    if st != 0:
+        raise PrismError(st, "prism_plan_table_set")
+
+
+def prism_plan_table_clear():
+    lib.prism_plan_table_clear()
+
+
+def prism_plan_table_size():
+    return int(lib.prism_plan_table_size())
 
 
 # Device memory for the split-K workspace comes from torch (one tensor per device, grown on demand).

@@ -2,6 +2,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "prism_internal.h"
 
@@ -69,15 +70,45 @@ bool prefill_tile_known(bool gated, int bm, int bn) {
     return (bm == 256 && bn == 256) || (bm == 256 && bn == 192) || (bm == 128 && bn == 128) || (bm == 64 && bn == 64);
 }
 
-prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Plan* out) {
+// A parameter assignment (paper Section 5, "parameter instantiation"): kernel family, split-K
+// factor and tile / wavefront variant; 0 = let the built-in heuristic choose.
+struct Choice {
+    int path, split_k, variant;
+};
+
+// Per-shape assignments installed by a tuner.  A fixed table, searched linearly: tuned shapes are few.
+struct TableEntry {
+    int32_t op, dtype;
+    int64_t M, K, N;
+    Choice c;
+};
+constexpr int kTableCapacity = 256;
+TableEntry g_table[kTableCapacity];
+int g_table_size = 0;
+std::mutex g_table_mutex;
+
+// The process-wide override wins; then an entry of the plan table for exactly this call; then the heuristic.
+Choice resolve_choice(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype) {
+    const Choice o{g_override.path.load(), g_override.split_k.load(), g_override.variant.load()};
+    if (o.path != 0 || o.split_k != 0 || o.variant != 0) return o;
+    std::lock_guard<std::mutex> lock(g_table_mutex);
+    for (int i = 0; i < g_table_size; ++i) {
+        const TableEntry& e = g_table[i];
+        if (e.op == (int32_t)op && e.dtype == (int32_t)dtype && e.M == M && e.K == K && e.N == N) return e.c;
+    }
+    return Choice{0, 0, 0};
+}
+
+prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Choice choice,
+                              Plan* out) {
     if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP) return PRISM_ERR_UNSUPPORTED;
     if (!dtype_known(dtype)) return PRISM_ERR_UNSUPPORTED;
     if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return PRISM_ERR_UNSUPPORTED;
     const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
-    const int forced = g_override.path.load();
-    const int forced_split = g_override.split_k.load();
-    const int variant = g_override.variant.load();
+    const int forced = choice.path;
+    const int forced_split = choice.split_k;
+    const int variant = choice.variant;
     std::memset(out, 0, sizeof(*out));
     prism_plan_t& p = out->pub;
     p.split_k = 1;
@@ -157,6 +188,11 @@ prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_d
     p.grid_y = 1;
     p.block = 256;
     return PRISM_OK;
+}
+
+prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Plan* out) {
+    if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP) return PRISM_ERR_UNSUPPORTED;
+    return make_plan_with(op, M, K, N, dtype, resolve_choice(op, M, K, N, dtype), out);
 }
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -296,6 +332,37 @@ prism_status_t prism_set_override(int32_t path, int32_t split_k, int32_t variant
     return PRISM_OK;
 }
 
+prism_status_t prism_plan_table_set(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, int32_t path,
+                                    int32_t split_k, int32_t variant) {
+    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL || split_k < 0 || variant < 0) return PRISM_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0) return PRISM_ERR_INVALID_ARG;
+    // An assignment that cannot run this shape is refused here, not at the call.
+    Plan probe;
+    const prism_status_t st = make_plan_with(op, M, K, N, dtype, Choice{path, split_k, variant}, &probe);
+    if (st != PRISM_OK) return st;
+    std::lock_guard<std::mutex> lock(g_table_mutex);
+    int slot = g_table_size;
+    for (int i = 0; i < g_table_size; ++i) {
+        const TableEntry& e = g_table[i];
+        if (e.op == (int32_t)op && e.dtype == (int32_t)dtype && e.M == M && e.K == K && e.N == N) slot = i;
+    }
+    if (slot == kTableCapacity) return PRISM_ERR_UNSUPPORTED;
+    g_table[slot] = TableEntry{(int32_t)op, (int32_t)dtype, M, K, N, Choice{path, split_k, variant}};
+    if (slot == g_table_size) ++g_table_size;
+    return PRISM_OK;
+}
+
+prism_status_t prism_plan_table_clear(void) {
+    std::lock_guard<std::mutex> lock(g_table_mutex);
+    g_table_size = 0;
+    return PRISM_OK;
+}
+
+int32_t prism_plan_table_size(void) {
+    std::lock_guard<std::mutex> lock(g_table_mutex);
+    return g_table_size;
+}
+
 const char* prism_status_string(prism_status_t status) {
     switch (status) {
         case PRISM_OK: return "ok";
@@ -307,6 +374,6 @@ const char* prism_status_string(prism_status_t status) {
     }
 }
 
-int32_t prism_version(void) { return 110; }
+int32_t prism_version(void) { return 120; }
 
 }  // extern "C"

@@ -229,6 +229,27 @@ def test_f16_decode_splits(P, split, waves):
     _case(P, pi.F16, 16, 2056, 1160, True, seed=921, path=P.PRISM_PATH_DECODE, split=split, variant=waves)
 
 
+# ---- parameter instantiation by sampling and timing (paper Section 5) -------------------------------
+
+def test_tuner_installs_a_plan_that_is_correct_and_not_slower(P):
+    from paper_2604_15272_amd import tune
+    M, K, N = 16, 2048, 2048
+    P.prism_plan_table_clear()
+    try:
+        r = tune.tune(P.PRISM_OP_RMSNORM_MATMUL, M, K, N, dtype=P.PRISM_BF16, samples=8, seed=3)
+        print("tuned:", r["best"], "default:", r["default"], flush=True)
+        assert P.prism_plan_table_size() == 1
+        assert r["default"] is not None and r["best"]["us"] <= r["default"]["us"]
+        plan = P.prism_plan(0, M, K, N, P.PRISM_BF16)
+        assert plan == r["best"]["plan"]
+        # parity with the installed plan (the table, not an override, selects it)
+        stored = pi.draw(pi.BF16, M, K, N, False, 950)
+        assert_parity(run_gpu(stored, pi.BF16, False, 1e-6), run_oracle(stored, pi.BF16, False, 1e-6), pi.BF16,
+                      f"tuned plan {plan}")
+    finally:
+        P.prism_plan_table_clear()
+
+
 # ---- degenerate inputs -------------------------------------------------------------------------
 
 def test_zero_rows_and_zero_input(P):

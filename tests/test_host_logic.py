@@ -100,6 +100,62 @@ def test_override_and_workspace_size(P):
         P.prism_set_override(9, 0, 0)
 
 
+def test_plan_table_precedence_and_validation(P):
+    """Heuristic < plan table < override; an assignment that cannot run the shape is refused when it is set."""
+    bf16 = P.PRISM_BF16
+    P.prism_plan_table_clear()
+    base = P.prism_plan(0, 16, 4096, 4096, bf16)
+    try:
+        P.prism_plan_table_set(0, 16, 4096, 4096, bf16, P.PRISM_PATH_DECODE, 4, 4)
+        assert P.prism_plan_table_size() == 1
+        t = P.prism_plan(0, 16, 4096, 4096, bf16)
+        assert t["split_k"] == 4 and t["block"] == 256 and t["grid_y"] == 4
+        assert P.prism_workspace_bytes(0, 16, 4096, 4096, bf16) == t["workspace_bytes"]
+        # exactly this key only: other shapes, the gated op and other storage types keep the heuristic
+        assert P.prism_plan(0, 8, 4096, 4096, bf16)["split_k"] == P.prism_plan(0, 8, 4096, 4096, P.PRISM_F16)["split_k"]
+        assert P.prism_plan(0, 16, 4096, 4096, P.PRISM_F16) == base
+        assert P.prism_plan(1, 16, 4096, 4096, bf16)["block"] == 512
+        # the override still wins
+        P.prism_set_override(P.PRISM_PATH_DECODE, 2, 8)
+        assert P.prism_plan(0, 16, 4096, 4096, bf16)["split_k"] == 2
+        P.prism_set_override(0, 0, 0)
+        # replacing an entry does not grow the table
+        P.prism_plan_table_set(0, 16, 4096, 4096, bf16, P.PRISM_PATH_PREFILL, 0, 128128)
+        assert P.prism_plan_table_size() == 1 and P.prism_plan(0, 16, 4096, 4096, bf16)["tile_m"] == 128
+        # refused: decode for 64 rows, an unknown tile, a negative split
+        for bad in ((0, 64, 4096, 4096, bf16, P.PRISM_PATH_DECODE, 0, 0), (0, 64, 4096, 4096, bf16, P.PRISM_PATH_PREFILL, 0, 999),
+                    (0, 16, 4096, 4096, bf16, P.PRISM_PATH_DECODE, -1, 0), (0, 0, 4096, 4096, bf16, P.PRISM_PATH_DECODE, 1, 8)):
+            with pytest.raises(P.PrismError):
+                P.prism_plan_table_set(*bad)
+        assert P.prism_plan_table_size() == 1
+        # capacity: 256 entries, then refused
+        for i in range(255):
+            P.prism_plan_table_set(0, 16, 4096, 8 * (i + 1), bf16, P.PRISM_PATH_DECODE, 1, 8)
+        assert P.prism_plan_table_size() == 256
+        with pytest.raises(P.PrismError):
+            P.prism_plan_table_set(0, 16, 4096, 8 * 1000, bf16, P.PRISM_PATH_DECODE, 1, 8)
+    finally:
+        P.prism_plan_table_clear()
+        P.prism_set_override(0, 0, 0)
+    assert P.prism_plan_table_size() == 0 and P.prism_plan(0, 16, 4096, 4096, bf16) == base
+
+
+def test_tuner_enumerates_admissible_assignments(P):
+    """The candidate list comes from the library's own planner: every entry is a plan it accepts."""
+    from paper_2604_15272_amd import tune
+    c = tune.candidates(0, 16, 2048, 1024, P.PRISM_BF16, max_split=16)
+    paths = {x["path"] for x in c}
+    assert paths == {P.PRISM_PATH_SIMPLE, P.PRISM_PATH_DECODE, P.PRISM_PATH_PREFILL}
+    dec = [x for x in c if x["path"] == P.PRISM_PATH_DECODE]
+    assert {x["plan"]["block"] for x in dec} == {256, 512, 1024}
+    assert len({(x["plan"]["split_k"], x["plan"]["block"]) for x in dec}) == len(dec)  # distinct plans only
+    assert all(1 <= x["split_k"] <= 16 for x in dec)
+    # many rows: no decode candidates; fp32: the plain kernel only
+    assert all(x["path"] != P.PRISM_PATH_DECODE for x in tune.candidates(1, 512, 1024, 1024, P.PRISM_BF16))
+    assert [x["path"] for x in tune.candidates(0, 8, 256, 512, P.PRISM_F32)] == [P.PRISM_PATH_SIMPLE]
+    assert P.prism_plan(0, 16, 2048, 1024, P.PRISM_BF16)["path"] == P.PRISM_PATH_DECODE  # override is reset
+
+
 def test_inputs_are_deterministic_and_bf16_exact():
     import numpy as np
     import prism_inputs as pi
