@@ -11,5 +11,6 @@ from .rmsnorm_family import (  # noqa: F401
     rmsnorm_gated_mlp,
     rmsnorm_glu,
     swiglu,
+    softmax_matmul,
     silu,
 )

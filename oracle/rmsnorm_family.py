@@ -128,3 +128,22 @@ def swiglu(X, W_gate, W_up):
     if W_gate.shape != W_up.shape or W_gate.shape[0] != X.shape[1]:
         raise ValueError("W_gate and W_up must both be [K,N]")
     return silu(np.matmul(X, W_gate)) * np.matmul(X, W_up)
+
+
+def softmax_matmul(X, W):
+    """Y[M,N] = softmax(X, over k) @ W: the paper's running example (Figure 1(a): Softmax, then Matmul).
+
+    softmax(x)[k] = exp(x[k]) / sum_j exp(x[j]), written out as the definition; the fused program of
+    Figure 1(b) (exp and the row sum in the loop, the division after it) reaches the same result.
+    In float64 exp overflows only above 709: callers keep |x| far below that (subtracting a constant
+    from a row does not change its softmax, which one of the pins checks).
+    """
+    X = _f64(X, 2, "X")
+    W = _f64(W, 2, "W")
+    if W.shape[0] != X.shape[1]:
+        raise ValueError("W must be [K,N]")
+    P = np.empty_like(X)
+    for m in range(X.shape[0]):
+        e = np.exp(X[m])
+        P[m] = e / np.sum(e)
+    return np.matmul(P, W)

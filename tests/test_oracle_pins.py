@@ -263,7 +263,55 @@ def pin_paper_variants(o):
                                rtol=1e-12, atol=1e-15)
 
 
-PINS = [pin_paper_variants, pin_hand_worked, pin_scale_invariance, pin_unit_rms, pin_identity_weight, pin_brute_force,
+def pin_softmax_matmul(o):
+    """The running example (Figure 1): hand-worked values, closed forms, invariances, brute force."""
+    gv = _golden()
+    # case G (tests/golden): X = [[0, ln 3]] -> softmax = [1/4, 3/4]; W = [[1, 2], [3, 4]] -> Y = [2.5, 3.5]
+    X = np.array([[0.0, gv["ln3"]]])
+    W = np.array([[1.0, 2.0], [3.0, 4.0]])
+    np.testing.assert_allclose(o.softmax_matmul(X, W), [[2.5, 3.5]], rtol=1e-15)
+    Xr, _, W1r, _ = _rand(50, 5, 24, 7)
+    Y = o.softmax_matmul(Xr, W1r)
+    # W = ones: every row of softmax sums to one; W = I: the softmax itself, positive, ordered like X
+    np.testing.assert_allclose(o.softmax_matmul(Xr, np.ones((24, 3))), np.ones((5, 3)), rtol=1e-14)
+    Pm = o.softmax_matmul(Xr, np.eye(24))
+    assert np.all(Pm > 0) and np.array_equal(np.argsort(Pm, axis=1), np.argsort(Xr, axis=1))
+    np.testing.assert_allclose(Pm[:, 3] / Pm[:, 9], np.exp(Xr[:, 3] - Xr[:, 9]), rtol=1e-13)
+    # shift invariance per row, and no scale invariance (unlike rms_norm)
+    shift = np.array([[3.0], [-7.5], [0.25], [100.0], [-200.0]])
+    np.testing.assert_allclose(o.softmax_matmul(Xr + shift, W1r), Y, rtol=1e-11, atol=1e-14)
+    assert not np.allclose(o.softmax_matmul(2.0 * Xr, W1r), Y)
+    # constant row: the plain mean of the rows of W; one entry far above the rest: that row of W
+    np.testing.assert_allclose(o.softmax_matmul(np.full((1, 24), -1.75), W1r), [W1r.mean(axis=0)], rtol=1e-13)
+    Xd = np.zeros((1, 24))
+    Xd[0, 11] = 60.0
+    np.testing.assert_allclose(o.softmax_matmul(Xd, W1r), [W1r[11]], rtol=1e-12, atol=1e-15)
+    # column partition exact, split-K of numerator and denominator (the fused program's two accumulators)
+    np.testing.assert_allclose(o.softmax_matmul(Xr, W1r[:, 2:5]), Y[:, 2:5], rtol=1e-14)
+    E = np.exp(Xr)
+    num = sum(E[:, s:s + 8] @ W1r[s:s + 8] for s in range(0, 24, 8))
+    den = sum(E[:, s:s + 8].sum(axis=1, keepdims=True) for s in range(0, 24, 8))
+    np.testing.assert_allclose(num / den, Y, rtol=1e-13)
+    # brute force, scalar loops
+    for seed, (M, K, N) in enumerate([(1, 1, 1), (3, 5, 2), (2, 9, 4)]):
+        Xb, _, Wb, _ = _rand(60 + seed, M, K, N)
+        ref = np.zeros((M, N))
+        for m in range(M):
+            den = 0.0
+            for k in range(K):
+                den += math.exp(Xb[m, k])
+            for j in range(N):
+                acc = 0.0
+                for k in range(K):
+                    acc += math.exp(Xb[m, k]) / den * Wb[k, j]
+                ref[m, j] = acc
+        np.testing.assert_allclose(o.softmax_matmul(Xb, Wb), ref, rtol=1e-12, atol=1e-15)
+    torch = pytest.importorskip("torch")
+    np.testing.assert_allclose(Y, (torch.softmax(torch.from_numpy(Xr), dim=1) @ torch.from_numpy(W1r)).numpy(),
+                               rtol=1e-12, atol=1e-15)
+
+
+PINS = [pin_softmax_matmul, pin_paper_variants, pin_hand_worked, pin_scale_invariance, pin_unit_rms, pin_identity_weight, pin_brute_force,
         pin_fused_order, pin_closed_form_rows, pin_partitions, pin_gated_identities,
         pin_torch_second_opinion, pin_output_variance]
 
@@ -278,7 +326,7 @@ def test_pin(pin):
 def _mutant(**over):
     ns = types.SimpleNamespace(rms_norm=O.rms_norm, rmsnorm_matmul=O.rmsnorm_matmul,
                                rmsnorm_gated_mlp=O.rmsnorm_gated_mlp, silu=O.silu,
-                               rmsnorm_glu=O.rmsnorm_glu, swiglu=O.swiglu)
+                               rmsnorm_glu=O.rmsnorm_glu, swiglu=O.swiglu, softmax_matmul=O.softmax_matmul)
     for k, v in over.items():
         setattr(ns, k, v)
     # rebuild the composite functions on top of the (possibly replaced) pieces
@@ -331,6 +379,12 @@ MUTANTS = {
     "swiglu_normalised": _mutant(swiglu=lambda X, Wg, Wu: O.rmsnorm_gated_mlp(X, np.ones(X.shape[1]), Wg, Wu, 0.0)),
     "swiglu_silu_on_up": _mutant(swiglu=lambda X, Wg, Wu: O.swiglu(X, Wu, Wg)),
     "swiglu_no_activation": _mutant(swiglu=lambda X, Wg, Wu: (X @ Wg) * (X @ Wu)),
+    "softmax_no_denominator": _mutant(softmax_matmul=lambda X, W: np.exp(X) @ W),
+    "softmax_over_rows_of_X": _mutant(softmax_matmul=lambda X, W: (np.exp(X) / np.exp(X).sum(axis=0, keepdims=True)) @ W),
+    "softmax_base_2": _mutant(softmax_matmul=lambda X, W: (np.exp2(X) / np.exp2(X).sum(axis=1, keepdims=True)) @ W),
+    "softmax_divides_by_K": _mutant(softmax_matmul=lambda X, W: (np.exp(X) / X.shape[1]) @ W),
+    "softmax_of_abs": _mutant(softmax_matmul=lambda X, W: (np.exp(np.abs(X)) / np.exp(np.abs(X)).sum(axis=1, keepdims=True)) @ W),
+    "softmax_W_transposed": _mutant(softmax_matmul=lambda X, W: O.softmax_matmul(X, W.T if W.shape[0] == W.shape[1] else W)),
     "scale_after_silu": _mutant(rmsnorm_gated_mlp=lambda X, g, W1, W2, eps: (
         O.silu((X * g) @ W1) * ((X * g) @ W2) / (np.mean(X * X, axis=1, keepdims=True) + eps))),
 }
