@@ -8,7 +8,8 @@ GEMM, split-K reduction, 1/rms, and the SiLU gate for the gated workloads) over 
 synthetic input that is already resident in HBM.  The headline workload is benchmark configuration
 index 1 (decode RMSNorm -> MatMul, bf16, X[16,4096], W[4096,4096]); the other three bf16
 configurations are timed too and reported under "other_workloads", and the paper's own workloads at its
-shapes and in its precision (fp16, 8 or 16 rows, hidden size 1024 or 4096) under "paper_shapes".
+shapes and in its precision (fp16, 8 or 16 rows, hidden size 1024 or 4096) under "paper_shapes", its
+running example (softmax, then a matrix product, Figure 1) under "running_example".
 
 Decode workloads rotate over enough distinct weight buffers (>= 1 GiB in total) that W is streamed
 from HBM and not from the 256 MB last-level cache; the cache-hot single-buffer time is reported
@@ -250,6 +251,50 @@ def measure_paper_shape(name, M, K, N, steps=1000, warmup=50):
     return res
 
 
+def measure_running_example(steps=500, warmup=30):
+    """The paper's running example (Figure 1): softmax(X[4096,4096]) @ W[4096,128] in fp16.  X is the large
+    operand: it rotates over 17 buffers (544 MiB) so that it is streamed from HBM.  Bound: HBM."""
+    import torch
+    import paper_2604_15272_amd as P
+    M, K, N, sets = 4096, 4096, 128, 17
+    gen = torch.Generator(device="cuda").manual_seed(0x5EED2000)
+    Xs = [(torch.randn((M, K), generator=gen, device="cuda") * 3.0).to(torch.float16) for _ in range(sets)]
+    W = torch.randn((K, N), generator=gen, device="cuda").to(torch.float16)
+    Ys = [torch.empty((M, N), dtype=torch.float16, device="cuda") for _ in range(sets)]
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    args = [(vp(Xs[s].data_ptr()), vp(W.data_ptr()), vp(Ys[s].data_ptr()), i64(M), i64(K), i64(N),
+             ctypes.c_int32(P.PRISM_F16), stream) for s in range(sets)]
+    fn = P.lib.prism_softmax_matmul
+
+    def run(n, first=0, used=sets):
+        for i in range(n):
+            st = fn(*args[(first + i) % used])
+            if st != 0:
+                raise RuntimeError(f"library call failed: {P.prism_status_string(st)}")
+
+    def timed(used):
+        run(warmup, used=used)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run(steps, first=warmup, used=used)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    ms, hot_ms = timed(sets), timed(1)
+    nbytes = 2 * (M * K + K * N + M * N)
+    res = {"workload": "softmax_matmul_running_example", "dtype": "f16", "M": M, "K": K, "N": N, "x_buffers": sets,
+           "steps": steps, "us_per_call": ms * 1e3, "bound": "hbm", "bytes_per_launch": nbytes,
+           "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "cache_hot_us_per_call": hot_ms * 1e3,
+           "plan": P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, M, K, N, P.PRISM_F16)}
+    log(f"[bench]   running example softmax(X[4096,4096]) W[4096,128] fp16: {ms * 1e3:.2f} us/call, "
+        f"{res['achieved']:.0f} GB/s = {100 * res['frac']:.1f}% of hbm peak (cache-hot {hot_ms * 1e3:.2f} us)")
+    return res
+
+
 COPY_CALIBRATION_BYTES = 256 << 20
 
 
@@ -278,6 +323,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", type=int, default=1, help="benchmark configuration index (1..4)")
     ap.add_argument("--no-extra", action="store_true", help="time only the headline workload")
+    ap.add_argument("--only-running-example", action="store_true",
+                    help="time only the softmax -> matmul running example (for profiling that kernel)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one device-to-device copy of 256 MiB (outside the timed region): under "
@@ -302,6 +349,9 @@ def main():
         log(f"[bench] calibration copy: {COPY_CALIBRATION_BYTES} bytes read and as many written")
         del src, dst
 
+    if a.only_running_example:
+        print(json.dumps({"running_example": measure_running_example()}), flush=True)
+        return
     head, runner = measure(a.workload, a.steps, a.warmup)
     traffic = measured_traffic(head["workload"])
     out = {
@@ -344,6 +394,8 @@ def main():
         for name, M, K, N in PAPER_SHAPES:
             out["paper_shapes"].append(measure_paper_shape(name, M, K, N))
             torch.cuda.empty_cache()
+        out["running_example"] = measure_running_example()
+        torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
 
 

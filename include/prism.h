@@ -55,14 +55,19 @@ typedef enum {
 /* PRISM_F16 is the paper's own precision (Section 7.1: half precision). */
 typedef enum { PRISM_F32 = 0, PRISM_BF16 = 1, PRISM_F16 = 2 } prism_dtype_t;
 
-typedef enum { PRISM_OP_RMSNORM_MATMUL = 0, PRISM_OP_RMSNORM_GATED_MLP = 1 } prism_op_t;
+typedef enum {
+    PRISM_OP_RMSNORM_MATMUL = 0,
+    PRISM_OP_RMSNORM_GATED_MLP = 1, /* also prism_rmsnorm_glu and prism_swiglu */
+    PRISM_OP_SOFTMAX_MATMUL = 2
+} prism_op_t;
 
 /* Kernel families.  AUTO picks by shape; the others are for tests and tuning sweeps. */
 typedef enum {
     PRISM_PATH_AUTO = 0,
     PRISM_PATH_SIMPLE = 1,  /* plain FMA kernel: any M, K, N; the only path for PRISM_F32 */
     PRISM_PATH_DECODE = 2,  /* few rows: W streamed once, split-K over wavefronts and workgroups */
-    PRISM_PATH_PREFILL = 3  /* many rows: LDS-tiled MFMA GEMM */
+    PRISM_PATH_PREFILL = 3, /* many rows: LDS-tiled MFMA GEMM */
+    PRISM_PATH_ROWS = 4     /* prism_softmax_matmul only: a workgroup owns 32 rows of X over the whole of K */
 } prism_path_t;
 
 /* What the dispatcher does for one call (filled by prism_plan). */
@@ -110,6 +115,16 @@ prism_status_t prism_rmsnorm_glu(const void* X, const void* g, const void* W1, c
  */
 prism_status_t prism_swiglu(const void* X, const void* W_gate, const void* W_up, void* Y,
                             int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, hipStream_t stream);
+
+/*
+ * The paper's running example (Figure 1): Y[M,N] = softmax(X[M,K]) . W[K,N], the softmax taken
+ * over k.  As in the fused program of Figure 1(b), exp and its row sum are accumulated in the loop
+ * over k beside the product and the division follows the loop; softmax(X) is never written to
+ * memory.  The row maximum is subtracted before the exponential (it cancels in exact arithmetic),
+ * so any finite X is safe.  dtype as above; no workspace is needed.
+ */
+prism_status_t prism_softmax_matmul(const void* X, const void* W, void* Y, int64_t M, int64_t K,
+                                    int64_t N, prism_dtype_t dtype, hipStream_t stream);
 
 /* The first two operations with the storage type in the name instead of an argument. */
 prism_status_t prism_rmsnorm_matmul_bf16(const void* X, const void* g, const void* W, void* Y,

@@ -10,9 +10,11 @@ from .binding import (  # noqa: F401
     PRISM_F16,
     PRISM_OP_RMSNORM_GATED_MLP,
     PRISM_OP_RMSNORM_MATMUL,
+    PRISM_OP_SOFTMAX_MATMUL,
     PRISM_PATH_AUTO,
     PRISM_PATH_DECODE,
     PRISM_PATH_PREFILL,
+    PRISM_PATH_ROWS,
     PRISM_PATH_SIMPLE,
     PrismError,
     Plan,
@@ -26,6 +28,7 @@ from .binding import (  # noqa: F401
     prism_rmsnorm_gated_mlp,
     prism_rmsnorm_glu,
     prism_swiglu,
+    prism_softmax_matmul,
     prism_rmsnorm_matmul,
     prism_set_override,
     prism_set_workspace,

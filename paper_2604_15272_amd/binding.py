@@ -6,8 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(HERE, "libprism.so")
 
 PRISM_F32, PRISM_BF16, PRISM_F16 = 0, 1, 2
-PRISM_OP_RMSNORM_MATMUL, PRISM_OP_RMSNORM_GATED_MLP = 0, 1
-PRISM_PATH_AUTO, PRISM_PATH_SIMPLE, PRISM_PATH_DECODE, PRISM_PATH_PREFILL = 0, 1, 2, 3
+PRISM_OP_RMSNORM_MATMUL, PRISM_OP_RMSNORM_GATED_MLP, PRISM_OP_SOFTMAX_MATMUL = 0, 1, 2
+PRISM_PATH_AUTO, PRISM_PATH_SIMPLE, PRISM_PATH_DECODE, PRISM_PATH_PREFILL, PRISM_PATH_ROWS = 0, 1, 2, 3, 4
 WORKSPACE_HEADER_BYTES = 262144
 
 
@@ -61,6 +61,8 @@ def _load():
     L.prism_rmsnorm_glu.restype = i32
     L.prism_swiglu.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp]
     L.prism_swiglu.restype = i32
+    L.prism_softmax_matmul.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
+    L.prism_softmax_matmul.restype = i32
     L.prism_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
     L.prism_workspace_bytes.restype = u64
     L.prism_set_workspace.argtypes = [vp, u64]
@@ -240,4 +242,16 @@ def prism_swiglu(X, W_gate, W_up, Y, M=None, K=None, N=None, dtype=None, stream=
                           _stream_handle(stream))
     if st != 0:
         raise PrismError(st, "prism_swiglu")
+    return Y
+
+
+def prism_softmax_matmul(X, W, Y, M=None, K=None, N=None, dtype=None, stream=None):
+    """Y[M,N] = softmax(X, over k) @ W: the paper's running example (Figure 1)."""
+    if M is None:
+        M, K = X.shape
+        N = W.shape[1]
+    dt = _dtype_of(X, dtype)
+    st = lib.prism_softmax_matmul(_ptr(X), _ptr(W), _ptr(Y), int(M), int(K), int(N), dt, _stream_handle(stream))
+    if st != 0:
+        raise PrismError(st, "prism_softmax_matmul")
     return Y

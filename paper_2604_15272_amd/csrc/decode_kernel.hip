@@ -17,6 +17,7 @@
 // stores Y.  The normalised X never exists in memory.
 #include "device_utils.h"
 #include "prism_internal.h"
+#include "w_block.h"
 
 namespace prism {
 
@@ -24,28 +25,6 @@ namespace {
 
 constexpr int TN = kDecodeTileN;   // 128
 constexpr int KB = kDecodeKBlock;  // 32
-
-struct WRows {
-    u32x4 r[8];
-};
-
-__device__ __forceinline__ void load_w_block(WRows& w, __amdgpu_buffer_rsrc_t rs, u32 voff, u32 row_bytes) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) w.r[i] = load16(rs, voff + (u32)i * row_bytes);
-}
-
-// B operand j (j = 0..7) of a lane: column 8c + j of its 8 x 8 sub-block, eight K values.
-template <int J>
-__device__ __forceinline__ u32x4 b_operand(const WRows& w) {
-    constexpr int d = J >> 1;
-    constexpr u32 sel = (J & 1) ? 0x07060302u : 0x05040100u;
-    u32x4 b;
-    b[0] = __builtin_amdgcn_perm(w.r[1][d], w.r[0][d], sel);
-    b[1] = __builtin_amdgcn_perm(w.r[3][d], w.r[2][d], sel);
-    b[2] = __builtin_amdgcn_perm(w.r[5][d], w.r[4][d], sel);
-    b[3] = __builtin_amdgcn_perm(w.r[7][d], w.r[6][d], sel);
-    return b;
-}
 
 template <typename F>
 __device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], u32x4 a, const WRows& w) {

@@ -99,12 +99,40 @@ Choice resolve_choice(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtyp
     return Choice{0, 0, 0};
 }
 
+// Softmax -> MatMul: the matrix-core kernel for 16-bit storage with K and N multiples of 8, else the plain one.
+prism_status_t make_softmax_plan(int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Choice choice, Plan* out) {
+    std::memset(out, 0, sizeof(*out));
+    prism_plan_t& p = out->pub;
+    p.split_k = 1;
+    if (choice.path != PRISM_PATH_AUTO && choice.path != PRISM_PATH_SIMPLE && choice.path != PRISM_PATH_ROWS)
+        return PRISM_ERR_UNSUPPORTED;
+    if (choice.split_k > 1 || choice.variant != 0) return PRISM_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0) return PRISM_OK;
+    const int64_t row_blocks = (M + kSoftmaxRows - 1) / kSoftmaxRows;
+    const bool fast_ok = dtype != PRISM_F32 && vector16_ok(K, N) && (uint64_t)K * N * 2 < kTwoGiB &&
+                         K <= (1 << 24) && row_blocks <= 65535;
+    int path = choice.path;
+    if (path == PRISM_PATH_AUTO) path = fast_ok ? PRISM_PATH_ROWS : PRISM_PATH_SIMPLE;
+    if (path == PRISM_PATH_ROWS && !fast_ok) return PRISM_ERR_UNSUPPORTED;
+    p.path = path;
+    p.block = path == PRISM_PATH_ROWS ? 512 : 256;
+    p.tile_m = path == PRISM_PATH_ROWS ? kSoftmaxRows : 8;
+    p.tile_n = path == PRISM_PATH_ROWS ? kSoftmaxTileN : 256;
+    p.grid_x = (int32_t)((N + p.tile_n - 1) / p.tile_n);
+    const int64_t gy = (M + p.tile_m - 1) / p.tile_m;
+    if (gy > 65535) return PRISM_ERR_UNSUPPORTED;
+    p.grid_y = (int32_t)gy;
+    return PRISM_OK;
+}
+
 prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Choice choice,
                               Plan* out) {
-    if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP) return PRISM_ERR_UNSUPPORTED;
+    if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP && op != PRISM_OP_SOFTMAX_MATMUL)
+        return PRISM_ERR_UNSUPPORTED;
     if (!dtype_known(dtype)) return PRISM_ERR_UNSUPPORTED;
     if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
     if (M > 0x7FFFFFFF || N > 0x7FFFFFFF || K > 0x7FFFFFFF) return PRISM_ERR_UNSUPPORTED;
+    if (op == PRISM_OP_SOFTMAX_MATMUL) return make_softmax_plan(M, K, N, dtype, choice, out);
     const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
     const int forced = choice.path;
     const int forced_split = choice.split_k;
@@ -114,7 +142,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
     p.split_k = 1;
 
     int path = forced;
-    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL) return PRISM_ERR_UNSUPPORTED;
+    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL) return PRISM_ERR_UNSUPPORTED;  // PRISM_PATH_ROWS is softmax only
     if (M == 0 || N == 0) return PRISM_OK;  // empty problem: nothing is launched
     const bool fast_ok = dtype != PRISM_F32 && vector16_ok(K, N);
     if (path == PRISM_PATH_AUTO) {
@@ -191,7 +219,8 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
 }
 
 prism_status_t make_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Plan* out) {
-    if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP) return PRISM_ERR_UNSUPPORTED;
+    if (op != PRISM_OP_RMSNORM_MATMUL && op != PRISM_OP_RMSNORM_GATED_MLP && op != PRISM_OP_SOFTMAX_MATMUL)
+        return PRISM_ERR_UNSUPPORTED;
     return make_plan_with(op, M, K, N, dtype, resolve_choice(op, M, K, N, dtype), out);
 }
 
@@ -275,6 +304,22 @@ prism_status_t prism_swiglu(const void* X, const void* W_gate, const void* W_up,
     return run(PRISM_OP_RMSNORM_GATED_MLP, X, nullptr, W_gate, W_up, Y, M, K, N, 0.0f, dtype, stream, kFlagSilu);
 }
 
+prism_status_t prism_softmax_matmul(const void* X, const void* W, void* Y, int64_t M, int64_t K, int64_t N,
+                                    prism_dtype_t dtype, hipStream_t stream) {
+    if (!dtype_known(dtype)) return PRISM_ERR_UNSUPPORTED;
+    if (M < 0 || N < 0 || K <= 0) return PRISM_ERR_INVALID_ARG;
+    if (M == 0 || N == 0) return PRISM_OK;
+    if (!X || !W || !Y) return PRISM_ERR_INVALID_ARG;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return PRISM_ERR_INVALID_ARG;
+    Plan plan;
+    const prism_status_t st = make_plan(PRISM_OP_SOFTMAX_MATMUL, M, K, N, dtype, &plan);
+    if (st != PRISM_OK) return st;
+    const SoftmaxCall c{X, W, Y, (int)M, (int)K, (int)N, stream};
+    const hipError_t err = plan.pub.path == PRISM_PATH_ROWS ? launch_softmax_rows_16bit(c, dtype == PRISM_F16)
+                                                            : launch_softmax_simple(c, (int)dtype);
+    return err == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
+}
+
 prism_status_t prism_rmsnorm_matmul_bf16(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K,
                                          int64_t N, float eps, hipStream_t stream) {
     return run(PRISM_OP_RMSNORM_MATMUL, X, g, W, nullptr, Y, M, K, N, eps, PRISM_BF16, stream);
@@ -325,7 +370,7 @@ prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_
 }
 
 prism_status_t prism_set_override(int32_t path, int32_t split_k, int32_t variant) {
-    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL || split_k < 0 || variant < 0) return PRISM_ERR_INVALID_ARG;
+    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_ROWS || split_k < 0 || variant < 0) return PRISM_ERR_INVALID_ARG;
     g_override.path.store(path);
     g_override.split_k.store(split_k);
     g_override.variant.store(variant);
@@ -334,7 +379,7 @@ prism_status_t prism_set_override(int32_t path, int32_t split_k, int32_t variant
 
 prism_status_t prism_plan_table_set(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, int32_t path,
                                     int32_t split_k, int32_t variant) {
-    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_PREFILL || split_k < 0 || variant < 0) return PRISM_ERR_INVALID_ARG;
+    if (path < PRISM_PATH_AUTO || path > PRISM_PATH_ROWS || split_k < 0 || variant < 0) return PRISM_ERR_INVALID_ARG;
     if (M <= 0 || N <= 0) return PRISM_ERR_INVALID_ARG;
     // An assignment that cannot run this shape is refused here, not at the call.
     Plan probe;
@@ -374,6 +419,6 @@ const char* prism_status_string(prism_status_t status) {
     }
 }
 
-int32_t prism_version(void) { return 120; }
+int32_t prism_version(void) { return 130; }
 
 }  // extern "C"

@@ -27,6 +27,18 @@ constexpr int kFlagGain = 1;  // multiply the row by g[K] (off: g is not read)
 constexpr int kFlagNorm = 2;  // scale by 1/rms (off: the sums of squares are ignored)
 constexpr int kFlagSilu = 4;  // gated calls: SiLU on the W1 branch (off: plain product of the branches)
 
+struct SoftmaxCall {
+    const void* X;
+    const void* W;
+    void* Y;
+    int M, K, N;
+    hipStream_t stream;
+};
+
+// Geometry of the softmax kernel: rows of X and columns of W per workgroup.
+constexpr int kSoftmaxRows = 16;
+constexpr int kSoftmaxTileN = 128;
+
 // Geometry of the decode (few-row) path.
 constexpr int kDecodeMaxRows = 16;     // one 16-row MFMA block
 constexpr int kDecodeTileN = 128;      // columns of W per workgroup
@@ -60,5 +72,7 @@ hipError_t launch_simple_f16(const Call& c);
 // The matrix-core kernels, for either 16-bit storage format (f16 = false: bf16).
 hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, const DecodeWorkspace& ws);
 hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);
+hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16);
+hipError_t launch_softmax_simple(const SoftmaxCall& c, int dtype);
 
 }  // namespace prism

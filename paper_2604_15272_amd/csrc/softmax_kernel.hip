@@ -1,0 +1,379 @@
+// Softmax followed by a matrix product, Y = softmax(X over k) . W: the paper's running example
+// (Figure 1).  The fused program of Figure 1(b) keeps two accumulators in its loop over k, the row
+// sum of exp(X) and the product exp(X) . W, and divides after the loop; softmax(X) is never written
+// to memory.  Both kernels here have that structure.  What the figure leaves out and a library
+// needs is the row maximum: exp(x - max) instead of exp(x), which changes nothing in exact
+// arithmetic and keeps every term in (0, 1].  A workgroup owns its rows over the whole of K, so the
+// maximum is a first pass over the same rows (the second pass finds them in the caches).
+//
+// Matrix-core kernel (16-bit storage): a workgroup owns 16 rows (one MFMA row group) and 128 columns
+// of W; its wavefronts take the 32-deep K-blocks round-robin.  X is K-contiguous, which is the
+// layout of an MFMA A operand, so a lane loads its 8 K values of a row straight from memory,
+// applies exp and rounds to the storage format; the row sums are a ninth MFMA against ones, so
+// numerator and denominator weigh the same rounded values.  W is handled as in the decode kernel (8 x 8 sub-blocks per lane,
+// permuted into B operands).  The partial products and sums of the wavefronts meet in LDS.
+// X is the large operand here and the roofline is streaming it from HBM once; what the kernel is
+// actually bound by at the paper's shape is W, which every workgroup re-reads from the L2 for its
+// 16 rows (1 MiB per workgroup), and the exponentials on the vector pipe.
+//
+// Plain kernel: any shape and storage type, 8 rows x 256 columns per workgroup, fp32 arithmetic.
+#include <type_traits>
+
+#include "device_utils.h"
+#include "prism_internal.h"
+#include "w_block.h"
+
+namespace prism {
+
+namespace {
+
+constexpr int TN = 128;  // columns of W per workgroup (matrix-core kernel)
+constexpr int KB = 32;   // K depth of one MFMA
+constexpr int RG = 1;    // 16-row groups per workgroup (2 halves the W traffic but fills only 128 CUs at 4096 rows: slower)
+
+template <typename T> __device__ __forceinline__ float ld_elem(const T* p, size_t i);
+template <> __device__ __forceinline__ float ld_elem<float>(const float* p, size_t i) { return p[i]; }
+template <> __device__ __forceinline__ float ld_elem<uint16_t>(const uint16_t* p, size_t i) {
+    return __builtin_bit_cast(float, (u32)p[i] << 16);
+}
+template <> __device__ __forceinline__ float ld_elem<_Float16>(const _Float16* p, size_t i) { return (float)p[i]; }
+template <typename T> __device__ __forceinline__ void st_elem(T* p, size_t i, float v);
+template <> __device__ __forceinline__ void st_elem<float>(float* p, size_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void st_elem<uint16_t>(uint16_t* p, size_t i, float v) {
+    p[i] = (uint16_t)(pack_bf16(v, 0.0f) & 0xFFFFu);
+}
+template <> __device__ __forceinline__ void st_elem<_Float16>(_Float16* p, size_t i, float v) { p[i] = (_Float16)v; }
+
+}  // namespace
+
+// ---- matrix-core kernel --------------------------------------------------------------------------
+template <typename F, int NW>
+__global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* __restrict__ X,
+                                                               const uint16_t* __restrict__ W,
+                                                               uint16_t* __restrict__ Y, int M, int K, int N) {
+    constexpr int NT = NW * 64;
+    constexpr int CPT = 16 * TN / NT;  // columns per thread in the epilogue
+    constexpr int TPR = TN / CPT;      // threads per output row
+    static_assert(CPT == 2 || CPT == 4 || CPT == 8, "epilogue mapping");
+    constexpr float kLog2e = 1.4426950408889634f;
+
+    extern __shared__ float lds[];
+    float* red = lds;                       // [NW][16][TN], used once per row group
+    float* wave_max = lds + NW * 16 * TN;   // [NW][32]
+    float* wave_sum = wave_max + NW * 32;   // [NW][32]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = lane >> 4, c = lane & 15;
+    const int n0 = blockIdx.x * TN, m0 = blockIdx.y * (16 * RG);
+    const int kblocks = (K + KB - 1) / KB;
+
+    // Descriptors: X from this workgroup's first row to the end of the matrix (rows past M read as
+    // zero and are masked anyway), W from its first column to the end.
+    const size_t x_left = ((size_t)(M - m0) * K) * 2;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (size_t)m0 * K, (u32)(x_left < 0x7FFFFFFFull ? x_left : 0x7FFFFFFFull));
+    const size_t w_left = ((size_t)K * N - n0) * 2;
+    const __amdgpu_buffer_rsrc_t rw = make_rsrc(W + n0, (u32)(w_left < 0x7FFFFFFFull ? w_left : 0x7FFFFFFFull));
+    const u32 row_bytes = (u32)N * 2u;
+    const bool col_ok = (n0 + 8 * c) < N;
+    const u32 w_lane = col_ok ? ((u32)(8 * q) * row_bytes + (u32)(16 * c)) : kOutOfRange;
+    bool row_ok[RG];
+    u32 x_row[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        row_ok[r] = (m0 + 16 * r + c) < M;
+        x_row[r] = (u32)(16 * r + c) * (u32)K * 2u;
+    }
+
+    // ---- pass 1: row maxima.  Sixteen K-blocks of loads (32 per lane, all of a 4096-deep row share)
+    // are issued before the first is looked at: this pass is the one that pulls X from HBM.
+    float mx[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) mx[r] = -__builtin_inff();
+    constexpr int U = 16;
+    for (int i = wave; i < kblocks; i += U * NW) {
+        u32x4 xr[U][RG];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int k = (i + u * NW) * KB + 8 * q;
+            ok[u] = (i + u * NW) < kblocks && k < K;
+#pragma unroll
+            for (int r = 0; r < RG; ++r)
+                xr[u][r] = load16(rx, (ok[u] && row_ok[r]) ? x_row[r] + (u32)k * 2u : kOutOfRange);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                float v = F::lo(xr[u][r][0]);
+#pragma unroll
+                for (int d = 0; d < 4; ++d) v = fmaxf(v, fmaxf(F::lo(xr[u][r][d]), F::hi(xr[u][r][d])));
+                mx[r] = fmaxf(mx[r], (ok[u] && row_ok[r]) ? v : -__builtin_inff());
+            }
+    }
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 16, 64));
+        mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 32, 64));
+        if (q == 0) wave_max[wave * 32 + 16 * r + c] = mx[r];
+    }
+    __syncthreads();
+    float shift[RG];  // -max * log2(e), so that exp(x - max) = exp2(x * log2(e) + shift)
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        float m = -__builtin_inff();
+#pragma unroll
+        for (int w = 0; w < NW; ++w) m = fmaxf(m, wave_max[w * 32 + 16 * r + c]);
+        shift[r] = row_ok[r] ? -m * kLog2e : 0.f;  // a row past M has no maximum: keep the arithmetic finite
+    }
+
+    // ---- pass 2: exp, row sums and the product
+    f32x4 acc[RG][8], sum_acc[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        sum_acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    // Two register sets alternate: the loads of the next K-block (X from the caches now, W from the L2)
+    // are issued before the arithmetic of the current one.
+    struct Trip {
+        WRows w;
+        u32x4 xr[RG];
+        int i;
+    };
+    auto issue = [&](Trip& t, int i) {
+        t.i = i;
+        const int k = i * KB + 8 * q;
+        const bool k_ok = i < kblocks && k < K;  // past the end: out-of-range offsets, zeros, no memory traffic
+#pragma unroll
+        for (int r = 0; r < RG; ++r) t.xr[r] = load16(rx, (k_ok && row_ok[r]) ? x_row[r] + (u32)k * 2u : kOutOfRange);
+        load_w_block(t.w, rw, (i < kblocks) ? w_lane + (u32)i * KB * row_bytes : kOutOfRange, row_bytes);
+    };
+    auto consume = [&](const Trip& t) {
+        const bool k_ok = t.i * KB + 8 * q < K;
+        u32x4 a[RG];
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const bool v = k_ok && row_ok[r];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const float e0 = __builtin_amdgcn_exp2f(fmaf(F::lo(t.xr[r][d]), kLog2e, shift[r]));
+                const float e1 = __builtin_amdgcn_exp2f(fmaf(F::hi(t.xr[r][d]), kLog2e, shift[r]));
+                a[r][d] = v ? F::pack(e0, e1) : 0u;
+            }
+        }
+        // One set of B operands serves both row groups.
+        auto step = [&](auto jc) {
+            constexpr int J = decltype(jc)::value;
+            const u32x4 b = b_operand<J>(t.w);
+#pragma unroll
+            for (int r = 0; r < RG; ++r) acc[r][J] = F::mfma_16x16x32(a[r], b, acc[r][J]);
+        };
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
+        step(std::integral_constant<int, 2>{});
+        step(std::integral_constant<int, 3>{});
+        step(std::integral_constant<int, 4>{});
+        step(std::integral_constant<int, 5>{});
+        step(std::integral_constant<int, 6>{});
+        step(std::integral_constant<int, 7>{});
+        // The row sums ride on the matrix cores too: a ninth product against a block of ones adds up
+        // exactly the rounded values the other eight use (every column of the result is the row sum).
+        // The vector pipe, which the exponentials keep busy, is spared two instructions per element.
+#pragma unroll
+        for (int r = 0; r < RG; ++r) sum_acc[r] = F::mfma_16x16x32(a[r], ones8<F>(), sum_acc[r]);
+    };
+    {
+        Trip ta, tb;
+        int i = wave;
+        if (i < kblocks) {
+            issue(ta, i);
+            for (;;) {
+                issue(tb, i + NW);
+                consume(ta);
+                i += NW;
+                if (i >= kblocks) break;
+                issue(ta, i + NW);
+                consume(tb);
+                i += NW;
+                if (i >= kblocks) break;
+            }
+        }
+    }
+    // Element i of the sum block in lane (q, c) is row 4q + i (any column c: they are all equal).
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        if (c == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) wave_sum[wave * 32 + 16 * r + 4 * q + i] = sum_acc[r][i];
+        }
+    }
+
+    // ---- across wavefronts through LDS, one row group at a time, then the division (Figure 1(b): Div
+    // after the loop).  Accumulator j, element i of lane (q, c) is row 4q + i, column 8c + j.
+    const int m = tid / TPR;
+    const int col = (tid % TPR) * CPT;
+    const int n = n0 + col;
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        if (r > 0) __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            // As in the decode kernel: the upper eight column groups write their second half first, so
+            // that one store instruction covers 16 different 16-byte bank groups.
+            float* dst = red + (wave * 16 + (4 * q + i)) * TN + 8 * c;
+            const f32x4 lo = f32x4{acc[r][0][i], acc[r][1][i], acc[r][2][i], acc[r][3][i]};
+            const f32x4 hi = f32x4{acc[r][4][i], acc[r][5][i], acc[r][6][i], acc[r][7][i]};
+            const bool upper = (c & 8) != 0;
+            *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
+            *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
+        }
+        __syncthreads();
+        float v[CPT], den = 0.f;
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) v[e] = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float* src = red + (w * 16 + m) * TN + col;
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) v[e] += src[e];
+            den += wave_sum[w * 32 + 16 * r + m];
+        }
+        const int row = m0 + 16 * r + m;
+        if (row < M && n < N) {  // N % 8 == 0 and CPT | 8: all CPT columns valid together
+            const float inv = 1.0f / den;
+            u32 packed[CPT / 2];
+#pragma unroll
+            for (int e = 0; e < CPT / 2; ++e) packed[e] = F::pack(v[2 * e] * inv, v[2 * e + 1] * inv);
+            uint16_t* out = Y + (size_t)row * N + n;
+            if (CPT == 2) *(u32*)out = packed[0];
+            if (CPT == 4) *(u32x2*)out = u32x2{packed[0], packed[1]};
+            if (CPT == 8) *(u32x4*)out = u32x4{packed[0], packed[1], packed[2 % (CPT / 2)], packed[3 % (CPT / 2)]};
+        }
+    }
+}
+
+template <typename F>
+static hipError_t launch_softmax_rows_fmt(const SoftmaxCall& c) {
+    constexpr int NW = 8;
+    dim3 grid((c.N + TN - 1) / TN, (c.M + 16 * RG - 1) / (16 * RG)), block(NW * 64);
+    const size_t lds = (size_t)(NW * 16 * TN + 2 * NW * 32) * sizeof(float);
+    auto kern = softmax_rows_kernel<F, NW>;
+    static std::atomic<uint64_t> opted{0};
+    if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, block, lds, c.stream, (const uint16_t*)c.X, (const uint16_t*)c.W, (uint16_t*)c.Y,
+                       c.M, c.K, c.N);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16) {
+    return f16 ? launch_softmax_rows_fmt<F16>(c) : launch_softmax_rows_fmt<Bf16>(c);
+}
+
+// ---- plain kernel -----------------------------------------------------------------------------------
+constexpr int kSmRows = 8;
+constexpr int kSmCols = 256;
+
+template <typename T>
+__global__ __launch_bounds__(kSmCols) void softmax_simple_kernel(const T* __restrict__ X, const T* __restrict__ W,
+                                                               T* __restrict__ Y, int M, int K, int N) {
+    __shared__ float es[kSmRows][kSmCols];
+    __shared__ float part[kSmCols / 64][kSmRows];
+    __shared__ float row_max[kSmRows];
+    const int t = threadIdx.x;
+    const int n = blockIdx.x * kSmCols + t;
+    const int m0 = blockIdx.y * kSmRows;
+    const bool col_ok = n < N;
+
+    // pass 1: row maxima (threads stride over k; lanes, then wavefronts)
+    float mx[kSmRows];
+#pragma unroll
+    for (int r = 0; r < kSmRows; ++r) mx[r] = -__builtin_inff();
+    for (int k = t; k < K; k += kSmCols) {
+#pragma unroll
+        for (int r = 0; r < kSmRows; ++r)
+            if (m0 + r < M) mx[r] = fmaxf(mx[r], ld_elem<T>(X, (size_t)(m0 + r) * K + k));
+    }
+#pragma unroll
+    for (int r = 0; r < kSmRows; ++r) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], off, 64));
+    }
+    if ((t & 63) == 0) {
+#pragma unroll
+        for (int r = 0; r < kSmRows; ++r) part[t >> 6][r] = mx[r];
+    }
+    __syncthreads();
+    if (t < kSmRows) {
+        float m = part[0][t];
+#pragma unroll
+        for (int w = 1; w < kSmCols / 64; ++w) m = fmaxf(m, part[w][t]);
+        row_max[t] = (m0 + t < M) ? m : 0.f;
+    }
+    __syncthreads();
+
+    // pass 2: exp and its row sum in the loop over k beside the product; the division after it
+    float acc[kSmRows], sum[kSmRows];
+#pragma unroll
+    for (int r = 0; r < kSmRows; ++r) { acc[r] = 0.f; sum[r] = 0.f; }
+    for (int kc = 0; kc < K; kc += kSmCols) {
+        __syncthreads();
+        const int k = kc + t;
+#pragma unroll
+        for (int r = 0; r < kSmRows; ++r) {
+            const int m = m0 + r;
+            const float e = (k < K && m < M) ? expf(ld_elem<T>(X, (size_t)m * K + k) - row_max[r]) : 0.f;
+            sum[r] += e;
+            es[r][t] = e;
+        }
+        __syncthreads();
+        const int kend = min(kSmCols, K - kc);
+        if (col_ok) {
+            for (int kk = 0; kk < kend; ++kk) {
+                const float w = ld_elem<T>(W, (size_t)(kc + kk) * N + n);
+#pragma unroll
+                for (int r = 0; r < kSmRows; ++r) acc[r] = fmaf(es[r][kk], w, acc[r]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kSmRows; ++r) {
+        float v = sum[r];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+        sum[r] = v;
+    }
+    __syncthreads();
+    if ((t & 63) == 0) {
+#pragma unroll
+        for (int r = 0; r < kSmRows; ++r) part[t >> 6][r] = sum[r];
+    }
+    __syncthreads();
+    if (!col_ok) return;
+#pragma unroll
+    for (int r = 0; r < kSmRows; ++r) {
+        const int m = m0 + r;
+        if (m >= M) break;
+        float den = 0.f;
+#pragma unroll
+        for (int w = 0; w < kSmCols / 64; ++w) den += part[w][r];
+        st_elem<T>(Y, (size_t)m * N + n, acc[r] / den);
+    }
+}
+
+template <typename T>
+static hipError_t launch_softmax_simple_t(const SoftmaxCall& c) {
+    dim3 grid((c.N + kSmCols - 1) / kSmCols, (c.M + kSmRows - 1) / kSmRows), block(kSmCols);
+    hipLaunchKernelGGL((softmax_simple_kernel<T>), grid, block, 0, c.stream, (const T*)c.X, (const T*)c.W, (T*)c.Y, c.M,
+                       c.K, c.N);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_simple(const SoftmaxCall& c, int dtype) {
+    if (dtype == PRISM_F32) return launch_softmax_simple_t<float>(c);
+    if (dtype == PRISM_F16) return launch_softmax_simple_t<_Float16>(c);
+    return launch_softmax_simple_t<uint16_t>(c);
+}
+
+}  // namespace prism

@@ -97,6 +97,15 @@ def draw(dtype, M, K, N, gated, seed, w_scale=None):
     return out
 
 
+def draw_softmax(dtype, M, K, N, seed, x_std=3.0):
+    """Inputs of the softmax -> matmul operator (the paper's running example): X[M,K] ~ N(0, x_std^2),
+    W[K,N] ~ N(0, 1).  With x_std = 3 a row's softmax is carried by a handful of entries, so the outputs
+    are of order one and a tolerance of the form tol * (|y| + 1) is a real constraint."""
+    x = _stream(seed, 0).standard_normal((M, K), dtype=np.float32) * np.float32(x_std)
+    w = _stream(seed, 2).standard_normal((K, N), dtype=np.float32)
+    return {"X": _store(x, dtype), "W": _store(w, dtype)}
+
+
 def draw_workload(wl, M=None):
     """Inputs of a benchmark configuration; ``M`` keeps only the first M rows of X."""
     d = draw(wl.dtype, wl.M, wl.K, wl.N, wl.gated, wl.seed)

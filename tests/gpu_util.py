@@ -98,6 +98,24 @@ def run_oracle_variant(stored, dtype, variant, eps, rows=None):
     raise ValueError(variant)
 
 
+def run_gpu_softmax(stored, dtype):
+    import torch
+    import paper_2604_15272_amd as P
+    X, W = to_device(stored["X"], dtype), to_device(stored["W"], dtype)
+    Y = torch.full((X.shape[0], W.shape[1]), float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    P.prism_softmax_matmul(X, W, Y)
+    torch.cuda.synchronize()
+    return from_device(Y, dtype)
+
+
+def run_oracle_softmax(stored, dtype, rows=None):
+    import oracle
+    X = pi.to_f64(stored["X"], dtype)
+    if rows is not None:
+        X = X[rows]
+    return oracle.softmax_matmul(X, pi.to_f64(stored["W"], dtype))
+
+
 def run_oracle(stored, dtype, gated, eps, rows=None):
     import oracle
     X = pi.to_f64(stored["X"], dtype)

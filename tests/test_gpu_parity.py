@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import prism_inputs as pi
-from gpu_util import DTYPE_CODE, assert_parity, run_gpu, run_gpu_variant, run_oracle, run_oracle_variant, worst_error
+from gpu_util import DTYPE_CODE, assert_parity, run_gpu, run_gpu_softmax, run_oracle_softmax, run_gpu_variant, run_oracle, run_oracle_variant, worst_error
 
 pytestmark = pytest.mark.gpu
 
@@ -227,6 +227,73 @@ def test_f16_prefill_every_tile(P, gated, tile):
 @pytest.mark.parametrize("split,waves", [(1, 8), (3, 4), (7, 8), (4, 16)])
 def test_f16_decode_splits(P, split, waves):
     _case(P, pi.F16, 16, 2056, 1160, True, seed=921, path=P.PRISM_PATH_DECODE, split=split, variant=waves)
+
+
+# ---- softmax -> matmul, the paper's running example (Figure 1) ------------------------------------------
+
+def _softmax_case(P, dtype, M, K, N, seed, path=0, x_std=3.0, expect_path=None):
+    stored = pi.draw_softmax(dtype, M, K, N, seed, x_std)
+    P.prism_set_override(path, 0, 0)
+    try:
+        plan = P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, M, K, N, DTYPE_CODE[dtype])
+        if expect_path is not None:
+            assert plan["path"] == expect_path, plan
+        print(f"softmax dtype={dtype} M={M} K={K} N={N} seed={seed} plan={plan}", flush=True)
+        y = run_gpu_softmax(stored, dtype)
+    finally:
+        P.prism_set_override(0, 0, 0)
+    yhat = run_oracle_softmax(stored, dtype)
+    assert np.sqrt(np.mean(yhat * yhat)) > 0.2   # outputs of order one: the "+ 1" of the bar is not what passes the test
+    return assert_parity(y, yhat, dtype, f"softmax M={M} K={K} N={N} plan={plan}")
+
+
+@pytest.mark.parametrize("dtype", [pi.BF16, pi.F16])
+@pytest.mark.parametrize("M,K,N", [(1, 8, 8), (16, 512, 128), (33, 1000, 264), (100, 4096, 128), (7, 72, 16),
+                                   (257, 2056, 136), (64, 8200, 128)])
+def test_softmax_matmul_rows_kernel(P, dtype, M, K, N):
+    _softmax_case(P, dtype, M, K, N, seed=1000 + M + K, expect_path=P.PRISM_PATH_ROWS)
+
+
+@pytest.mark.parametrize("dtype,M,K,N", [(pi.F32, 8, 256, 512), (pi.F32, 5, 100, 36), (pi.F32, 20, 1000, 513),
+                                         (pi.BF16, 5, 257, 300), (pi.F16, 17, 100, 36), (pi.BF16, 9, 64, 20)])
+def test_softmax_matmul_plain_kernel(P, dtype, M, K, N):
+    _softmax_case(P, dtype, M, K, N, seed=1100 + M, expect_path=P.PRISM_PATH_SIMPLE)
+
+
+def test_softmax_matmul_plain_kernel_forced_on_aligned_shape(P):
+    _softmax_case(P, pi.BF16, 40, 512, 128, seed=1200, path=P.PRISM_PATH_SIMPLE, expect_path=P.PRISM_PATH_SIMPLE)
+
+
+@pytest.mark.parametrize("dtype", [pi.F32, pi.BF16])
+def test_softmax_matmul_is_safe_for_large_inputs_and_shift_invariant(P, dtype):
+    """exp(x) alone would overflow at x = 200; the kernels subtract the row maximum, which cancels."""
+    stored = pi.draw_softmax(dtype, 24, 512, 128, 1300, x_std=3.0)
+    base = run_gpu_softmax(stored, dtype)
+    x = pi.to_f64(stored["X"], dtype)
+    shifted = dict(stored)
+    xs = (x + 200.0).astype(np.float32)
+    shifted["X"] = pi.f32_to_bf16_bits(xs) if dtype == pi.BF16 else xs
+    y = run_gpu_softmax(shifted, dtype)
+    assert np.isfinite(y).all()
+    # the oracle sees the stored (re-rounded) shifted values, minus a constant per row, which is an identity
+    xs64 = pi.to_f64(shifted["X"], dtype)
+    import oracle
+    ref = oracle.softmax_matmul(xs64 - xs64.max(axis=1, keepdims=True), pi.to_f64(stored["W"], dtype))
+    assert_parity(y, ref, dtype, "shifted by 200")
+    if dtype == pi.F32:   # fp32 storage keeps x + 200 to 1.5e-5: the outputs barely move
+        assert worst_error(y, base) < 1e-3
+
+
+def test_softmax_matmul_running_example_full_size_sampled_rows(P):
+    """The paper's shapes, X[4096,4096] W[4096,128] (Figure 1), in its precision; the oracle recomputes 64 rows."""
+    stored = pi.draw_softmax(pi.F16, 4096, 4096, 128, 0x5EED0010)
+    y = run_gpu_softmax(stored, pi.F16)
+    assert np.isfinite(y).all()
+    rows = np.unique(np.concatenate([[0, 31, 32, 4095], np.random.Generator(np.random.Philox(7)).choice(4096, 60, replace=False)]))
+    assert_parity(y[rows], run_oracle_softmax(stored, pi.F16, rows=rows), pi.F16, "running example")
+    # a property that holds at any size: every output lies between the column's extreme weights
+    W = pi.to_f64(stored["W"], pi.F16)
+    assert (y <= W.max(axis=0) + 1e-2).all() and (y >= W.min(axis=0) - 1e-2).all()
 
 
 # ---- parameter instantiation by sampling and timing (paper Section 5) -------------------------------

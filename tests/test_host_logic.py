@@ -100,6 +100,30 @@ def test_override_and_workspace_size(P):
         P.prism_set_override(9, 0, 0)
 
 
+def test_softmax_matmul_arguments_and_plan(P):
+    L = P.lib
+    a = 0x1000
+    sm = lambda X=a, W=a, Y=a, M=4, K=64, N=64, dt=1: L.prism_softmax_matmul(X, W, Y, M, K, N, dt, None)
+    assert sm(X=None) == 1 and sm(W=None) == 1 and sm(Y=None) == 1 and sm(X=a + 4) == 1
+    assert sm(M=-1) == 1 and sm(K=0) == 1 and sm(dt=9) == 2 and sm(M=0) == 0 and sm(N=0) == 0
+    op = P.PRISM_OP_SOFTMAX_MATMUL
+    p = P.prism_plan(op, 4096, 4096, 128, P.PRISM_F16)
+    assert p["path"] == P.PRISM_PATH_ROWS and p["grid_x"] == 1 and p["grid_y"] == 4096 // p["tile_m"] and p["workspace_bytes"] == 0
+    assert P.prism_plan(op, 8, 256, 512, P.PRISM_F32)["path"] == P.PRISM_PATH_SIMPLE
+    assert P.prism_plan(op, 8, 100, 36, P.PRISM_BF16)["path"] == P.PRISM_PATH_SIMPLE
+    # the kernel families of the other operators do not apply, and the softmax kernel applies to nothing else
+    for path in (P.PRISM_PATH_DECODE, P.PRISM_PATH_PREFILL):
+        P.prism_set_override(path, 0, 0)
+        with pytest.raises(P.PrismError):
+            P.prism_plan(op, 16, 512, 128, P.PRISM_BF16)
+    P.prism_set_override(P.PRISM_PATH_ROWS, 0, 0)
+    with pytest.raises(P.PrismError):
+        P.prism_plan(0, 16, 512, 128, P.PRISM_BF16)
+    with pytest.raises(P.PrismError):
+        P.prism_plan(op, 8, 256, 512, P.PRISM_F32)
+    P.prism_set_override(0, 0, 0)
+
+
 def test_plan_table_precedence_and_validation(P):
     """Heuristic < plan table < override; an assignment that cannot run the shape is refused when it is set."""
     bf16 = P.PRISM_BF16
