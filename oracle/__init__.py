@@ -12,5 +12,6 @@ from .rmsnorm_family import (  # noqa: F401
     rmsnorm_glu,
     swiglu,
     softmax_matmul,
+    gqa_decode_attention,
     silu,
 )

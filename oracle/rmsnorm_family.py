@@ -147,3 +147,27 @@ def softmax_matmul(X, W):
         e = np.exp(X[m])
         P[m] = e / np.sum(e)
     return np.matmul(P, W)
+
+
+def gqa_decode_attention(Q, K, V, scale=1.0, qk_norm=False, eps=0.0):
+    """O[b,g,:] = softmax(scale * Qn[b,g,:] . K[b]^T) . V[b], one query position, g query heads per KV head.
+
+    Q is [B,G,D], K and V are [B,H,D] (H keys and values of D numbers each), O is [B,G,D].
+    Paper Section 7.1, workloads "Attention" (qk_norm off: Qn = Q) and "QK-Attention" (qk_norm on:
+    Qn = rms_norm(Q) over D, without gain, with the eps-inside-the-root reading used throughout).  The
+    paper's formulas carry no 1/sqrt(D): scale = 1 is the paper's operator.  Plain loops over batch and
+    head; the softmax is the definition, as in softmax_matmul.
+    """
+    Q = _f64(Q, 3, "Q")
+    K = _f64(K, 3, "K")
+    V = _f64(V, 3, "V")
+    B, G, D = Q.shape
+    if K.shape != V.shape or K.shape[0] != B or K.shape[2] != D:
+        raise ValueError("K and V must both be [B,H,D]")
+    one = np.ones(D)
+    O = np.empty_like(Q)
+    for b in range(B):
+        Qn = rms_norm(Q[b], one, eps) if qk_norm else Q[b]
+        S = float(scale) * np.matmul(Qn, K[b].T)          # [G,H]
+        O[b] = softmax_matmul(S, V[b])
+    return O

@@ -311,7 +311,66 @@ def pin_softmax_matmul(o):
                                rtol=1e-12, atol=1e-15)
 
 
-PINS = [pin_softmax_matmul, pin_paper_variants, pin_hand_worked, pin_scale_invariance, pin_unit_rms, pin_identity_weight, pin_brute_force,
+def pin_gqa_decode_attention(o):
+    """Section 7.1, Attention and QK-Attention: hand-worked case, closed forms, brute force, invariances."""
+    gv = _golden()
+    ln3 = gv["ln3"]
+    # case H (tests/golden): one batch, one head, D = 2, two keys.  Q = [ln 3, 0], K = [[0, 5], [1, 7]]
+    #   scores = [0, ln 3] -> softmax = [1/4, 3/4];  V = [[1, 2], [3, 4]] -> O = [2.5, 3.5]
+    Q = np.array([[[ln3, 0.0]]])
+    K = np.array([[[0.0, 5.0], [1.0, 7.0]]])
+    V = np.array([[[1.0, 2.0], [3.0, 4.0]]])
+    np.testing.assert_allclose(o.gqa_decode_attention(Q, K, V), [[[2.5, 3.5]]], rtol=1e-15)
+    # case I: qk_norm at eps = 0 turns Q = [3, 4] into [0.6, 0.8] sqrt 2; with K = [[0, 0], [ln3/(0.6 sqrt2), 0]] the
+    #   scores are again [0, ln 3]
+    Q2 = np.array([[[3.0, 4.0]]])
+    K2 = np.array([[[0.0, 0.0], [ln3 / (0.6 * gv["sqrt2"]), 0.0]]])
+    np.testing.assert_allclose(o.gqa_decode_attention(Q2, K2, V, qk_norm=True, eps=0.0), [[[2.5, 3.5]]], rtol=1e-14)
+    r = _rng(70)
+    B, G, H, D = 2, 3, 9, 4
+    Qr, Kr, Vr = r.standard_normal((B, G, D)), r.standard_normal((B, H, D)), r.standard_normal((B, H, D))
+    for scale, qkn, eps in ((1.0, False, 0.0), (0.5, False, 0.0), (1.0, True, 1e-6), (0.37, True, 0.2)):
+        ref = np.zeros((B, G, D))
+        for b in range(B):
+            for g in range(G):
+                q = Qr[b, g].tolist()
+                if qkn:
+                    ms = sum(x * x for x in q) / D
+                    q = [x / math.sqrt(ms + eps) for x in q]
+                sc = [scale * sum(q[d] * Kr[b, hh, d] for d in range(D)) for hh in range(H)]
+                den = sum(math.exp(v) for v in sc)
+                for d in range(D):
+                    ref[b, g, d] = sum(math.exp(sc[hh]) / den * Vr[b, hh, d] for hh in range(H))
+        np.testing.assert_allclose(o.gqa_decode_attention(Qr, Kr, Vr, scale, qkn, eps), ref, rtol=1e-12, atol=1e-15)
+    base = o.gqa_decode_attention(Qr, Kr, Vr)
+    # heads are independent and share K, V of their batch; batches are independent
+    np.testing.assert_allclose(o.gqa_decode_attention(Qr[:, 1:2], Kr, Vr), base[:, 1:2], rtol=1e-14)
+    np.testing.assert_allclose(o.gqa_decode_attention(Qr[1:], Kr[1:], Vr[1:]), base[1:], rtol=1e-14)
+    assert not np.allclose(o.gqa_decode_attention(Qr, Kr[::-1], Vr[::-1]), base)
+    # the order of the keys does not matter as long as values move with them; a constant added to all scores cancels
+    perm = r.permutation(H)
+    np.testing.assert_allclose(o.gqa_decode_attention(Qr, Kr[:, perm], Vr[:, perm]), base, rtol=1e-13)
+    # Q = 0: uniform weights, the mean of V; one key: that value; all values equal: that value
+    np.testing.assert_allclose(o.gqa_decode_attention(np.zeros((B, G, D)), Kr, Vr),
+                               np.repeat(Vr.mean(axis=1, keepdims=True), G, axis=1), rtol=1e-13)
+    np.testing.assert_allclose(o.gqa_decode_attention(Qr, Kr[:, :1], Vr[:, :1]), np.repeat(Vr[:, :1], G, axis=1), rtol=1e-14)
+    np.testing.assert_allclose(o.gqa_decode_attention(Qr, Kr, np.ones((B, H, D)) * 2.5), np.full((B, G, D), 2.5), rtol=1e-14)
+    # scale multiplies the scores: scale s on Q equals Q * s; qk_norm makes the result independent of |Q| at eps = 0
+    np.testing.assert_allclose(o.gqa_decode_attention(Qr, Kr, Vr, scale=0.25), o.gqa_decode_attention(0.25 * Qr, Kr, Vr), rtol=1e-13)
+    np.testing.assert_allclose(o.gqa_decode_attention(7.0 * Qr, Kr, Vr, qk_norm=True), o.gqa_decode_attention(Qr, Kr, Vr, qk_norm=True), rtol=1e-12)
+    assert not np.allclose(o.gqa_decode_attention(Qr, Kr, Vr, qk_norm=True), base)
+    # reduction to the two operators it is made of
+    one = np.ones(D)
+    for b in range(B):
+        np.testing.assert_allclose(o.gqa_decode_attention(Qr, Kr, Vr, 1.0, True, 1e-6)[b],
+                                   o.softmax_matmul(o.rmsnorm_matmul(Qr[b], one, Kr[b].T.copy(), 1e-6), Vr[b]), rtol=1e-13)
+    torch = pytest.importorskip("torch")
+    tq, tk, tv = (torch.from_numpy(a) for a in (Qr, Kr, Vr))
+    ref = torch.softmax(0.5 * tq @ tk.transpose(1, 2), dim=-1) @ tv
+    np.testing.assert_allclose(o.gqa_decode_attention(Qr, Kr, Vr, scale=0.5), ref.numpy(), rtol=1e-12, atol=1e-15)
+
+
+PINS = [pin_gqa_decode_attention, pin_softmax_matmul, pin_paper_variants, pin_hand_worked, pin_scale_invariance, pin_unit_rms, pin_identity_weight, pin_brute_force,
         pin_fused_order, pin_closed_form_rows, pin_partitions, pin_gated_identities,
         pin_torch_second_opinion, pin_output_variance]
 
@@ -326,7 +385,8 @@ def test_pin(pin):
 def _mutant(**over):
     ns = types.SimpleNamespace(rms_norm=O.rms_norm, rmsnorm_matmul=O.rmsnorm_matmul,
                                rmsnorm_gated_mlp=O.rmsnorm_gated_mlp, silu=O.silu,
-                               rmsnorm_glu=O.rmsnorm_glu, swiglu=O.swiglu, softmax_matmul=O.softmax_matmul)
+                               rmsnorm_glu=O.rmsnorm_glu, swiglu=O.swiglu, softmax_matmul=O.softmax_matmul,
+                               gqa_decode_attention=O.gqa_decode_attention)
     for k, v in over.items():
         setattr(ns, k, v)
     # rebuild the composite functions on top of the (possibly replaced) pieces
@@ -385,6 +445,20 @@ MUTANTS = {
     "softmax_divides_by_K": _mutant(softmax_matmul=lambda X, W: (np.exp(X) / X.shape[1]) @ W),
     "softmax_of_abs": _mutant(softmax_matmul=lambda X, W: (np.exp(np.abs(X)) / np.exp(np.abs(X)).sum(axis=1, keepdims=True)) @ W),
     "softmax_W_transposed": _mutant(softmax_matmul=lambda X, W: O.softmax_matmul(X, W.T if W.shape[0] == W.shape[1] else W)),
+    "attn_scores_not_scaled": _mutant(gqa_decode_attention=lambda Q, K, V, scale=1.0, qk_norm=False, eps=0.0: (
+        O.gqa_decode_attention(Q, K, V, 1.0, qk_norm, eps))),
+    "attn_norm_on_keys_too": _mutant(gqa_decode_attention=lambda Q, K, V, scale=1.0, qk_norm=False, eps=0.0: (
+        O.gqa_decode_attention(Q, np.stack([O.rms_norm(k, np.ones(k.shape[1]), eps) for k in K]) if qk_norm else K, V,
+                               scale, qk_norm, eps))),
+    "attn_norm_ignored": _mutant(gqa_decode_attention=lambda Q, K, V, scale=1.0, qk_norm=False, eps=0.0: (
+        O.gqa_decode_attention(Q, K, V, scale, False, eps))),
+    "attn_softmax_over_heads": _mutant(gqa_decode_attention=lambda Q, K, V, scale=1.0, qk_norm=False, eps=0.0: np.stack([
+        (lambda S: (np.exp(S) / np.exp(S).sum(axis=0, keepdims=True)) @ V[b])(
+            scale * (O.rms_norm(Q[b], np.ones(Q.shape[2]), eps) if qk_norm else Q[b]) @ K[b].T) for b in range(Q.shape[0])])),
+    "attn_values_of_other_batch": _mutant(gqa_decode_attention=lambda Q, K, V, scale=1.0, qk_norm=False, eps=0.0: (
+        O.gqa_decode_attention(Q, K, V[::-1] if V.shape[0] > 1 else V, scale, qk_norm, eps))),
+    "attn_inverse_sqrt_d_added": _mutant(gqa_decode_attention=lambda Q, K, V, scale=1.0, qk_norm=False, eps=0.0: (
+        O.gqa_decode_attention(Q, K, V, scale / math.sqrt(Q.shape[2]), qk_norm, eps))),
     "scale_after_silu": _mutant(rmsnorm_gated_mlp=lambda X, g, W1, W2, eps: (
         O.silu((X * g) @ W1) * ((X * g) @ W2) / (np.mean(X * X, axis=1, keepdims=True) + eps))),
 }
