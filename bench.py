@@ -9,7 +9,8 @@ synthetic input that is already resident in HBM.  The headline workload is bench
 index 1 (decode RMSNorm -> MatMul, bf16, X[16,4096], W[4096,4096]); the other three bf16
 configurations are timed too and reported under "other_workloads", and the paper's own workloads at its
 shapes and in its precision (fp16, 8 or 16 rows, hidden size 1024 or 4096) under "paper_shapes", its
-running example (softmax, then a matrix product, Figure 1) under "running_example".
+running example (softmax, then a matrix product, Figure 1) under "running_example", its two attention
+workloads under "attention".
 
 Decode workloads rotate over enough distinct weight buffers (>= 1 GiB in total) that W is streamed
 from HBM and not from the 256 MB last-level cache; the cache-hot single-buffer time is reported
@@ -295,6 +296,45 @@ def measure_running_example(steps=500, warmup=30):
     return res
 
 
+def measure_attention(h, qk_norm, steps=1000, warmup=50):
+    """The paper's attention workloads (Section 7.1): b = 2, g = 8 query heads per batch entry, one query position,
+    head dimension 128, h keys, fp16; K and V rotate over enough buffers (>= 512 MiB) to come from HBM."""
+    import torch
+    import paper_2604_15272_amd as P
+    B, G, D = 2, 8, 128
+    kv_bytes = 2 * B * h * D * 2
+    sets = max(2, min(512, -(-(512 << 20) // kv_bytes)))
+    gen = torch.Generator(device="cuda").manual_seed(0x5EED3000 + h)
+    Q = torch.randn((B, G, D), generator=gen, device="cuda").to(torch.float16)
+    big = torch.randn((sets, 2, B, h, D), generator=gen, device="cuda").to(torch.float16)
+    Os = torch.empty((sets, B, G, D), dtype=torch.float16, device="cuda")
+    P.ensure_workspace(int(P.lib.prism_attention_workspace_bytes(B, G, h, D, P.PRISM_F16)))
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    args = [(vp(Q.data_ptr()), vp(big[s, 0].data_ptr()), vp(big[s, 1].data_ptr()), vp(Os[s].data_ptr()), i64(B), i64(G),
+             i64(h), i64(D), ctypes.c_float(1.0), ctypes.c_int32(int(qk_norm)), ctypes.c_float(1e-6),
+             ctypes.c_int32(P.PRISM_F16), stream) for s in range(sets)]
+    fn = P.lib.prism_gqa_decode_attention
+    for i in range(warmup):
+        if fn(*args[i % sets]) != 0:
+            raise RuntimeError("attention call failed")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fn(*args[(warmup + i) % sets])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    nbytes = 2 * (2 * B * G * D) + kv_bytes
+    res = {"workload": "qk_attention" if qk_norm else "attention", "dtype": "f16", "B": B, "G": G, "H": h, "D": D,
+           "kv_sets": sets, "steps": steps, "us_per_call": ms * 1e3, "bound": "hbm", "bytes_per_launch": nbytes,
+           "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "plan": P.prism_attention_plan(B, G, h, D, P.PRISM_F16)}
+    log(f"[bench]   paper {res['workload']} b=2 g=8 d=128 h={h} fp16: {ms * 1e3:.2f} us/call, {res['achieved']:.0f} GB/s")
+    return res
+
+
 COPY_CALIBRATION_BYTES = 256 << 20
 
 
@@ -323,6 +363,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", type=int, default=1, help="benchmark configuration index (1..4)")
     ap.add_argument("--no-extra", action="store_true", help="time only the headline workload")
+    ap.add_argument("--only-attention", action="store_true",
+                    help="time only the paper's attention workloads (for profiling that kernel)")
     ap.add_argument("--only-running-example", action="store_true",
                     help="time only the softmax -> matmul running example (for profiling that kernel)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
@@ -351,6 +393,10 @@ def main():
 
     if a.only_running_example:
         print(json.dumps({"running_example": measure_running_example()}), flush=True)
+        return
+    if a.only_attention:
+        print(json.dumps({"attention": [measure_attention(h, qk) for h in (1024, 2048) for qk in (False, True)]}),
+              flush=True)
         return
     head, runner = measure(a.workload, a.steps, a.warmup)
     traffic = measured_traffic(head["workload"])
@@ -395,6 +441,8 @@ def main():
             out["paper_shapes"].append(measure_paper_shape(name, M, K, N))
             torch.cuda.empty_cache()
         out["running_example"] = measure_running_example()
+        torch.cuda.empty_cache()
+        out["attention"] = [measure_attention(h, qk) for h in (1024, 2048) for qk in (False, True)]
         torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
 

@@ -67,7 +67,8 @@ typedef enum {
     PRISM_PATH_SIMPLE = 1,  /* plain FMA kernel: any M, K, N; the only path for PRISM_F32 */
     PRISM_PATH_DECODE = 2,  /* few rows: W streamed once, split-K over wavefronts and workgroups */
     PRISM_PATH_PREFILL = 3, /* many rows: LDS-tiled MFMA GEMM */
-    PRISM_PATH_ROWS = 4     /* prism_softmax_matmul only: a workgroup owns 32 rows of X over the whole of K */
+    PRISM_PATH_ROWS = 4,    /* prism_softmax_matmul only: a workgroup owns 16 rows of X over the whole of K */
+    PRISM_PATH_ATTENTION = 5 /* prism_gqa_decode_attention only: matrix-core kernel, keys split over workgroups */
 } prism_path_t;
 
 /* What the dispatcher does for one call (filled by prism_plan). */
@@ -125,6 +126,26 @@ prism_status_t prism_swiglu(const void* X, const void* W_gate, const void* W_up,
  */
 prism_status_t prism_softmax_matmul(const void* X, const void* W, void* Y, int64_t M, int64_t K,
                                     int64_t N, prism_dtype_t dtype, hipStream_t stream);
+
+/*
+ * The paper's "Attention" and "QK-Attention" workloads (Section 7.1): group-query attention at one
+ * query position,
+ *     O[b,g,:] = softmax(scale * Qn[b,g,:] . K[b]^T) . V[b],
+ * where the G query heads of batch entry b share its H keys and values, and Qn = rms_norm(Q) over
+ * the head dimension D (no gain, eps inside the root) when qk_norm != 0, else Qn = Q.
+ * Layouts (row-major, contiguous): Q[B,G,D], K[B,H,D], V[B,H,D], O[B,G,D].  The paper's formulas have
+ * no 1/sqrt(D): scale = 1 is the paper's operator.  The softmax over the keys is never written to
+ * memory.  When the keys are split over workgroups (prism_attention_workspace_bytes > 0) the call
+ * needs the registered workspace, under the same rules as the split-K calls above.
+ * prism_attention_plan reports path, slices (split_k), keys per slice (tile_n), grid and workspace.
+ */
+prism_status_t prism_gqa_decode_attention(const void* Q, const void* K, const void* V, void* O,
+                                          int64_t B, int64_t G, int64_t H, int64_t D, float scale,
+                                          int32_t qk_norm, float eps, prism_dtype_t dtype,
+                                          hipStream_t stream);
+uint64_t prism_attention_workspace_bytes(int64_t B, int64_t G, int64_t H, int64_t D, prism_dtype_t dtype);
+prism_status_t prism_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, prism_dtype_t dtype,
+                                    prism_plan_t* plan);
 
 /* The first two operations with the storage type in the name instead of an argument. */
 prism_status_t prism_rmsnorm_matmul_bf16(const void* X, const void* g, const void* W, void* Y,

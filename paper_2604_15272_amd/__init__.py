@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     PRISM_PATH_DECODE,
     PRISM_PATH_PREFILL,
     PRISM_PATH_ROWS,
+    PRISM_PATH_ATTENTION,
     PRISM_PATH_SIMPLE,
     PrismError,
     Plan,
@@ -29,6 +30,8 @@ from .binding import (  # noqa: F401
     prism_rmsnorm_glu,
     prism_swiglu,
     prism_softmax_matmul,
+    prism_gqa_decode_attention,
+    prism_attention_plan,
     prism_rmsnorm_matmul,
     prism_set_override,
     prism_set_workspace,

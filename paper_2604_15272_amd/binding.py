@@ -8,6 +8,7 @@ _LIB_PATH = os.path.join(HERE, "libprism.so")
 PRISM_F32, PRISM_BF16, PRISM_F16 = 0, 1, 2
 PRISM_OP_RMSNORM_MATMUL, PRISM_OP_RMSNORM_GATED_MLP, PRISM_OP_SOFTMAX_MATMUL = 0, 1, 2
 PRISM_PATH_AUTO, PRISM_PATH_SIMPLE, PRISM_PATH_DECODE, PRISM_PATH_PREFILL, PRISM_PATH_ROWS = 0, 1, 2, 3, 4
+PRISM_PATH_ATTENTION = 5
 WORKSPACE_HEADER_BYTES = 262144
 
 
@@ -63,6 +64,12 @@ def _load():
     L.prism_swiglu.restype = i32
     L.prism_softmax_matmul.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp]
     L.prism_softmax_matmul.restype = i32
+    L.prism_gqa_decode_attention.argtypes = [vp, vp, vp, vp, i64, i64, i64, i64, f32, i32, f32, i32, vp]
+    L.prism_gqa_decode_attention.restype = i32
+    L.prism_attention_workspace_bytes.argtypes = [i64, i64, i64, i64, i32]
+    L.prism_attention_workspace_bytes.restype = u64
+    L.prism_attention_plan.argtypes = [i64, i64, i64, i64, i32, ctypes.POINTER(Plan)]
+    L.prism_attention_plan.restype = i32
     L.prism_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
     L.prism_workspace_bytes.restype = u64
     L.prism_set_workspace.argtypes = [vp, u64]
@@ -255,3 +262,24 @@ def prism_softmax_matmul(X, W, Y, M=None, K=None, N=None, dtype=None, stream=Non
     if st != 0:
         raise PrismError(st, "prism_softmax_matmul")
     return Y
+
+
+def prism_attention_plan(B, G, H, D, dtype):
+    p = Plan()
+    st = lib.prism_attention_plan(int(B), int(G), int(H), int(D), int(dtype), ctypes.byref(p))
+    if st != 0:
+        raise PrismError(st, "prism_attention_plan")
+    return p.as_dict()
+
+
+def prism_gqa_decode_attention(Q, K, V, O, scale=1.0, qk_norm=False, eps=1e-6, dtype=None, stream=None):
+    """O[B,G,D] = softmax(scale * Qn @ K^T) @ V per batch entry (Q [B,G,D]; K, V [B,H,D]); Qn = rms_norm(Q) if qk_norm."""
+    B, G, D = Q.shape
+    H = K.shape[1]
+    dt = _dtype_of(Q, dtype)
+    ensure_workspace(int(lib.prism_attention_workspace_bytes(B, G, H, D, dt)))
+    st = lib.prism_gqa_decode_attention(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), B, G, H, D, float(scale), int(bool(qk_norm)),
+                                        float(eps), dt, _stream_handle(stream))
+    if st != 0:
+        raise PrismError(st, "prism_gqa_decode_attention")
+    return O

@@ -35,6 +35,39 @@ struct SoftmaxCall {
     hipStream_t stream;
 };
 
+struct AttentionCall {
+    const void* Q;
+    const void* K;
+    const void* V;
+    void* O;
+    int B, G, H, D;
+    float scale;
+    int qk_norm;
+    float eps;
+    hipStream_t stream;
+};
+
+// The matrix-core attention kernel: head dimension, rows (query heads) per batch entry, key slices.
+constexpr int kAttnHeadDim = 128;
+constexpr int kAttnMaxHeads = 16;
+constexpr int kAttnSliceKeys = 128;     // keys per workgroup while the slices number at most kAttnMaxSlices
+constexpr int kAttnMaxSlices = 64;
+constexpr int kAttnMaxSliceKeys = 1024;  // LDS holds a slice's scores
+
+struct AttentionPlan {
+    int path;        // PRISM_PATH_SIMPLE or PRISM_PATH_ATTENTION
+    int splits;      // key slices per batch entry
+    int slice_keys;  // keys per slice (a multiple of 32)
+    uint64_t workspace_bytes;
+};
+
+struct AttentionWorkspace {
+    unsigned* tickets;  // [B], in the workspace header, zero between calls
+    float* m_part;      // [B][S][16]
+    float* l_part;      // [B][S][16]
+    float* acc_part;    // [B][S][16][128]
+};
+
 // Geometry of the softmax kernel: rows of X and columns of W per workgroup.
 constexpr int kSoftmaxRows = 16;
 constexpr int kSoftmaxTileN = 128;
@@ -74,5 +107,7 @@ hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, 
 hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);
 hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16);
 hipError_t launch_softmax_simple(const SoftmaxCall& c, int dtype);
+hipError_t launch_gqa_16bit(const AttentionCall& c, bool f16, const AttentionPlan& p, const AttentionWorkspace& ws);
+hipError_t launch_gqa_simple(const AttentionCall& c, int dtype);
 
 }  // namespace prism

@@ -106,6 +106,16 @@ def draw_softmax(dtype, M, K, N, seed, x_std=3.0):
     return {"X": _store(x, dtype), "W": _store(w, dtype)}
 
 
+def draw_attention(dtype, B, G, H, D, seed, q_std=1.0):
+    """Inputs of group-query attention at one query position: Q[B,G,D] ~ N(0, q_std^2), K[B,H,D] and
+    V[B,H,D] ~ N(0,1).  With D = 128 the scores have a standard deviation of about 11 q_std, so a softmax
+    row is carried by few keys and the outputs are of order one."""
+    q = _stream(seed, 0).standard_normal((B, G, D), dtype=np.float32) * np.float32(q_std)
+    k = _stream(seed, 1).standard_normal((B, H, D), dtype=np.float32)
+    v = _stream(seed, 2).standard_normal((B, H, D), dtype=np.float32)
+    return {"Q": _store(q, dtype), "K": _store(k, dtype), "V": _store(v, dtype)}
+
+
 def draw_workload(wl, M=None):
     """Inputs of a benchmark configuration; ``M`` keeps only the first M rows of X."""
     d = draw(wl.dtype, wl.M, wl.K, wl.N, wl.gated, wl.seed)

@@ -116,6 +116,22 @@ def run_oracle_softmax(stored, dtype, rows=None):
     return oracle.softmax_matmul(X, pi.to_f64(stored["W"], dtype))
 
 
+def run_gpu_attention(stored, dtype, scale=1.0, qk_norm=False, eps=1e-6):
+    import torch
+    import paper_2604_15272_amd as P
+    Q, K, V = (to_device(stored[k], dtype) for k in ("Q", "K", "V"))
+    O = torch.full(Q.shape, float("nan"), dtype=torch_dtype(dtype), device="cuda")
+    P.prism_gqa_decode_attention(Q, K, V, O, scale=scale, qk_norm=qk_norm, eps=eps)
+    torch.cuda.synchronize()
+    return from_device(O, dtype)
+
+
+def run_oracle_attention(stored, dtype, scale=1.0, qk_norm=False, eps=1e-6):
+    import oracle
+    Q, K, V = (pi.to_f64(stored[k], dtype) for k in ("Q", "K", "V"))
+    return oracle.gqa_decode_attention(Q, K, V, scale, qk_norm, float(np.float32(eps)))
+
+
 def run_oracle(stored, dtype, gated, eps, rows=None):
     import oracle
     X = pi.to_f64(stored["X"], dtype)

@@ -7,7 +7,8 @@ import numpy as np
 import pytest
 
 import prism_inputs as pi
-from gpu_util import DTYPE_CODE, assert_parity, run_gpu, run_gpu_softmax, run_oracle_softmax, run_gpu_variant, run_oracle, run_oracle_variant, worst_error
+from gpu_util import (DTYPE_CODE, assert_parity, run_gpu, run_gpu_attention, run_gpu_softmax, run_oracle_attention,
+                      run_oracle_softmax, run_gpu_variant, run_oracle, run_oracle_variant, worst_error)
 
 pytestmark = pytest.mark.gpu
 
@@ -294,6 +295,75 @@ def test_softmax_matmul_running_example_full_size_sampled_rows(P):
     # a property that holds at any size: every output lies between the column's extreme weights
     W = pi.to_f64(stored["W"], pi.F16)
     assert (y <= W.max(axis=0) + 1e-2).all() and (y >= W.min(axis=0) - 1e-2).all()
+
+
+# ---- group-query attention at one query position (paper Section 7.1: Attention, QK-Attention) ---------------
+
+def _attention_case(P, dtype, B, G, H, D, seed, scale=1.0, qk_norm=False, eps=1e-6, path=0, split=0, expect_path=None):
+    stored = pi.draw_attention(dtype, B, G, H, D, seed)
+    P.prism_set_override(path, split, 0)
+    try:
+        plan = P.prism_attention_plan(B, G, H, D, DTYPE_CODE[dtype])
+        if expect_path is not None:
+            assert plan["path"] == expect_path, plan
+        print(f"attention dtype={dtype} B={B} G={G} H={H} D={D} scale={scale} qk_norm={qk_norm} plan={plan}", flush=True)
+        y = run_gpu_attention(stored, dtype, scale, qk_norm, eps)
+    finally:
+        P.prism_set_override(0, 0, 0)
+    yhat = run_oracle_attention(stored, dtype, scale, qk_norm, eps)
+    return assert_parity(y, yhat, dtype, f"attention B={B} G={G} H={H} D={D} qk_norm={qk_norm} plan={plan}")
+
+
+@pytest.mark.parametrize("qk_norm", [False, True])
+@pytest.mark.parametrize("dtype", [pi.F16, pi.BF16])
+@pytest.mark.parametrize("B,G,H", [(2, 8, 1024), (2, 8, 2048), (1, 1, 1), (3, 16, 100), (2, 5, 129), (1, 8, 8200),
+                                   (4, 7, 33)])
+def test_attention_matrix_core_kernel(P, B, G, H, dtype, qk_norm):
+    """The paper's sizes (b = 2, g = 8, d = 128, h in {1024, 2048}) and ragged ones around the slice boundaries."""
+    _attention_case(P, dtype, B, G, H, 128, seed=1400 + H, qk_norm=qk_norm, expect_path=P.PRISM_PATH_ATTENTION)
+
+
+@pytest.mark.parametrize("split", [2, 3, 7, 16, 64])
+def test_attention_every_split(P, split):
+    """The result may not depend on how the keys are split over workgroups (one slice holds at most 1024 keys)."""
+    _attention_case(P, pi.F16, 2, 8, 2048, 128, seed=1410, qk_norm=True, path=P.PRISM_PATH_ATTENTION, split=split)
+
+
+def test_attention_single_slice(P):
+    _attention_case(P, pi.F16, 2, 8, 1000, 128, seed=1411, qk_norm=True, path=P.PRISM_PATH_ATTENTION, split=1)
+
+
+@pytest.mark.parametrize("dtype,B,G,H,D", [(pi.F32, 2, 8, 300, 128), (pi.F32, 1, 3, 77, 20), (pi.BF16, 2, 8, 257, 64),
+                                           (pi.F16, 1, 20, 500, 128), (pi.F32, 2, 2, 1000, 520)])
+@pytest.mark.parametrize("qk_norm", [False, True])
+def test_attention_plain_kernel(P, dtype, B, G, H, D, qk_norm):
+    _attention_case(P, dtype, B, G, H, D, seed=1420 + H, scale=128.0 ** 0.5 / D ** 0.5, qk_norm=qk_norm,
+                    expect_path=P.PRISM_PATH_SIMPLE)
+
+
+def test_attention_scale_and_sign(P):
+    """scale multiplies the scores (1 is the paper's operator); a negative scale prefers the lowest scores."""
+    for scale in (0.25, -1.0, 0.0):
+        _attention_case(P, pi.F16, 2, 8, 300, 128, seed=1430, scale=scale, qk_norm=False)
+        _attention_case(P, pi.F32, 2, 8, 300, 128, seed=1431, scale=scale, qk_norm=True)
+
+
+def test_attention_is_bit_reproducible_and_leaves_tickets_clean(P):
+    import torch
+    from gpu_util import to_device
+    stored = pi.draw_attention(pi.BF16, 2, 8, 2048, 128, 1440)
+    Q, K, V = (to_device(stored[k], pi.BF16) for k in ("Q", "K", "V"))
+    outs = []
+    for _ in range(30):
+        O = torch.full(Q.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        P.prism_gqa_decode_attention(Q, K, V, O, qk_norm=True)
+        outs.append(O)
+    torch.cuda.synchronize()
+    assert P.prism_attention_plan(2, 8, 2048, 128, P.PRISM_BF16)["split_k"] > 1
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.uint16), outs[0].view(torch.uint16))
+    # the same workspace serves the split-K decode kernel right after
+    _case(P, pi.BF16, 16, 2056, 1160, False, seed=1441, expect_path=P.PRISM_PATH_DECODE)
 
 
 # ---- parameter instantiation by sampling and timing (paper Section 5) -------------------------------

@@ -124,6 +124,40 @@ def test_softmax_matmul_arguments_and_plan(P):
     P.prism_set_override(0, 0, 0)
 
 
+def test_attention_arguments_and_plan(P):
+    L = P.lib
+    a = 0x1000
+    at = lambda Q=a, K=a, V=a, O=a, B=2, G=8, H=64, D=128, scale=1.0, eps=1e-6, dt=1: L.prism_gqa_decode_attention(
+        Q, K, V, O, B, G, H, D, scale, 0, eps, dt, None)
+    assert at(Q=None) == 1 and at(K=None) == 1 and at(V=None) == 1 and at(O=None) == 1 and at(K=a + 8) == 1
+    assert at(H=0) == 1 and at(D=0) == 1 and at(B=-1) == 1 and at(eps=-1.0) == 1 and at(scale=float("nan")) == 1
+    assert at(dt=9) == 2 and at(D=2048) == 2 and at(B=0) == 0 and at(G=0) == 0
+    f16 = P.PRISM_F16
+    p = P.prism_attention_plan(2, 8, 2048, 128, f16)
+    assert p["path"] == P.PRISM_PATH_ATTENTION and p["split_k"] == 16 and p["tile_n"] == 128 and p["grid_y"] == 2
+    assert p["workspace_bytes"] == 262144 + 2 * 16 * 16 * (2 + 128) * 4
+    assert P.prism_attention_plan(2, 8, 100, 128, f16)["split_k"] == 1
+    assert P.prism_attention_plan(2, 8, 100, 128, f16)["workspace_bytes"] == 0
+    big = P.prism_attention_plan(1, 8, 65536, 128, f16)
+    assert big["split_k"] == 64 and big["tile_n"] == 1024
+    mid = P.prism_attention_plan(1, 8, 8192, 128, f16)
+    assert mid["split_k"] == 32 and mid["tile_n"] == 256
+    # what the matrix-core kernel does not cover goes to the plain kernel
+    for shape in ((2, 8, 2048, 64), (2, 17, 2048, 128), (1, 8, 65537, 128)):
+        assert P.prism_attention_plan(*shape, f16)["path"] == P.PRISM_PATH_SIMPLE
+    assert P.prism_attention_plan(2, 8, 2048, 128, P.PRISM_F32)["path"] == P.PRISM_PATH_SIMPLE
+    P.prism_set_override(P.PRISM_PATH_ATTENTION, 0, 0)
+    with pytest.raises(P.PrismError):
+        P.prism_attention_plan(2, 8, 2048, 64, f16)
+    P.prism_set_override(P.PRISM_PATH_ATTENTION, 3, 0)
+    s3 = P.prism_attention_plan(2, 8, 2048, 128, f16)
+    assert s3["split_k"] == 3 and s3["tile_n"] == 704
+    P.prism_set_override(P.PRISM_PATH_DECODE, 0, 0)
+    with pytest.raises(P.PrismError):
+        P.prism_attention_plan(2, 8, 2048, 128, f16)
+    P.prism_set_override(0, 0, 0)
+
+
 def test_plan_table_precedence_and_validation(P):
     """Heuristic < plan table < override; an assignment that cannot run the shape is refused when it is set."""
     bf16 = P.PRISM_BF16
