@@ -184,10 +184,15 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             if (S < 1) S = 1;
         }
         if (S > kblocks) S = kblocks;
-        if (S > 65535) return PRISM_ERR_UNSUPPORTED;
-        // Byte offsets inside one K-slice must fit in 31 bits.
-        const uint64_t slice_rows = (uint64_t)((kblocks + S - 1) / S) * kDecodeKBlock + 8;
-        if (slice_rows * (uint64_t)N * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
+        // Byte offsets inside one K-slice must fit in 31 bits: a weight matrix of 2 GiB or more is cut
+        // into more slices (unless the split was forced).
+        auto slice_fits = [&](int64_t s) {
+            const uint64_t slice_rows = (uint64_t)((kblocks + s - 1) / s) * kDecodeKBlock + 8;
+            return slice_rows * (uint64_t)N * 2 < kTwoGiB;
+        };
+        if (forced_split <= 0)
+            while (!slice_fits(S) && S < kblocks) S = std::min<int64_t>(kblocks, 2 * S);
+        if (S > 65535 || !slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
         out->waves = waves;
         p.split_k = (int32_t)S;
         p.tile_m = kDecodeMaxRows;

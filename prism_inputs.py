@@ -46,9 +46,13 @@ def f32_to_bf16_bits(a):
 
     Finite inputs only: NaN payloads are not preserved.
     """
-    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    u = u + (((u >> np.uint64(16)) & np.uint64(1)) + np.uint64(0x7FFF))
-    return (u >> np.uint64(16)).astype(np.uint16)
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    # 32-bit arithmetic suffices for finite values (the largest, 0x7F7FFFFF, plus 0x8000 does not wrap)
+    r = (u >> np.uint32(16)) & np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u
+    r >>= np.uint32(16)
+    return r.astype(np.uint16)
 
 
 def bf16_bits_to_f32(b):

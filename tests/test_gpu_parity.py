@@ -387,6 +387,36 @@ def test_tuner_installs_a_plan_that_is_correct_and_not_slower(P):
         P.prism_plan_table_clear()
 
 
+# ---- large shapes: the oracle recomputes a sample of the outputs ------------------------------------------
+
+def test_decode_vocabulary_sized_output_sampled_columns(P):
+    """X[8,1024] against W[1024,128256] (1002 column tiles, no split): 256 sampled columns."""
+    M, K, N = 8, 1024, 128256
+    stored = pi.draw(pi.BF16, M, K, N, False, 1500)
+    plan = P.prism_plan(0, M, K, N, P.PRISM_BF16)
+    assert plan["path"] == P.PRISM_PATH_DECODE and plan["split_k"] == 1 and plan["grid_x"] == 1002
+    y = run_gpu(stored, pi.BF16, False, 1e-6)
+    assert np.isfinite(y).all()
+    cols = np.unique(np.concatenate([[0, 127, 128, N - 1, N - 64],
+                                     np.random.Generator(np.random.Philox(15)).choice(N, 251, replace=False)]))
+    sub = dict(stored)
+    sub["W"] = np.ascontiguousarray(stored["W"][:, cols])
+    assert_parity(y[:, cols], run_oracle(sub, pi.BF16, False, 1e-6), pi.BF16, "vocabulary-sized decode")
+    assert abs(y.var() - 13.0 / 12.0) < 0.02
+
+
+def test_prefill_long_k_and_many_rows(P):
+    """K = 32768 (512 K steps per tile) and M = 20000 (ragged last row tile): sampled rows."""
+    for (M, K, N), seed in (((300, 32768, 256), 1510), ((20000, 512, 384), 1511)):
+        stored = pi.draw(pi.BF16, M, K, N, True, seed)
+        assert P.prism_plan(1, M, K, N, P.PRISM_BF16)["path"] == P.PRISM_PATH_PREFILL
+        y = run_gpu(stored, pi.BF16, True, 1e-6)
+        assert np.isfinite(y).all()
+        rows = np.unique(np.concatenate([[0, M - 1, min(255, M - 1), min(256, M - 1)],
+                                         np.random.Generator(np.random.Philox(seed)).choice(M, 60, replace=False)]))
+        assert_parity(y[rows], run_oracle(stored, pi.BF16, True, 1e-6, rows=rows), pi.BF16, f"prefill M={M} K={K} N={N}")
+
+
 # ---- degenerate inputs -------------------------------------------------------------------------
 
 def test_zero_rows_and_zero_input(P):

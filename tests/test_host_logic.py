@@ -158,6 +158,15 @@ def test_attention_arguments_and_plan(P):
     P.prism_set_override(0, 0, 0)
 
 
+def test_shapes_past_the_32_bit_offsets_take_the_plain_kernel(P):
+    """2 GiB of W is what the buffer addressing of the matrix-core kernels covers; beyond, the plan says so."""
+    bf16 = P.PRISM_BF16
+    assert P.prism_plan(0, 64, 16384, 65536, bf16)["path"] == P.PRISM_PATH_SIMPLE     # W = 2 GiB
+    assert P.prism_plan(0, 64, 16384, 65528, bf16)["path"] == P.PRISM_PATH_PREFILL    # just below
+    big = P.prism_plan(0, 16, 16384, 131072, bf16)                                    # W = 4 GiB: decode offsets are
+    assert big["path"] == P.PRISM_PATH_DECODE and big["split_k"] == 4                 # per slice, so it takes 4 slices
+
+
 def test_plan_table_precedence_and_validation(P):
     """Heuristic < plan table < override; an assignment that cannot run the shape is refused when it is set."""
     bf16 = P.PRISM_BF16
