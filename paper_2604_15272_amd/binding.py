@@ -23,12 +23,12 @@ class Plan(ctypes.Structure):
         ("path", ctypes.c_int32), ("split_k", ctypes.c_int32),
         ("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
         ("grid_x", ctypes.c_int32), ("grid_y", ctypes.c_int32),
-        ("block", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("block", ctypes.c_int32), ("grid_z", ctypes.c_int32),
         ("workspace_bytes", ctypes.c_uint64),
     ]
 
     def as_dict(self):
-        return {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "reserved"}
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
 
 def library_path():

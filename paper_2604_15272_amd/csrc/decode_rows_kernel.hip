@@ -1,0 +1,338 @@
+// Decode path for 17 to a few hundred rows of X: still bound by streaming W, so W is still read once
+// per row block and the MFMA work is hidden behind it.
+//
+// Same decomposition as the 16-row decode kernel (a workgroup owns 128 columns of W and one K-slice, its
+// eight wavefronts take the 32-deep K-blocks round-robin, W blocks are permuted into B operands in
+// registers), with one difference: a workgroup carries RG groups of 16 rows (32 or 64 rows of X),
+// and every B operand built from W is used for all of them.  More rows than that are further row
+// blocks (the grid's z): each re-reads W, which for a few hundred rows is still far cheaper than
+// walking K in 64-deep steps with the tiled prefill kernel.
+// The reduction across wavefronts (LDS) and across K-slices (workspace, ticket, slice order) is the
+// one of the 16-row kernel, run per row group.
+#include "device_utils.h"
+#include "prism_internal.h"
+#include "w_block.h"
+
+#include <type_traits>
+
+namespace prism {
+
+namespace {
+
+constexpr int TN = kDecodeTileN;   // 128
+constexpr int KB = kDecodeKBlock;  // 32
+constexpr int NW = 8;              // wavefronts per workgroup
+constexpr int NT = NW * 64;
+constexpr int CPT = 16 * TN / NT;  // 4 columns per thread in the epilogue
+constexpr int TPR = TN / CPT;      // 32 threads per output row
+constexpr int kRedFloats = NW * 16 * TN;  // one row group's partial tiles of all wavefronts
+
+template <typename F>
+__device__ __forceinline__ u32x4 scaled_operand(u32x4 x, u32x4 gg, float& ss) {
+    u32x4 a;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const float x0 = F::lo(x[d]), x1 = F::hi(x[d]);
+        ss = fmaf(x0, x0, ss);
+        ss = fmaf(x1, x1, ss);
+        a[d] = F::pack(x0 * F::lo(gg[d]), x1 * F::hi(gg[d]));
+    }
+    return a;
+}
+
+}  // namespace
+
+template <typename F, bool GATED, int RG>
+__global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ g,
+                                                         const uint16_t* __restrict__ W1,
+                                                         const uint16_t* __restrict__ W2, uint16_t* __restrict__ Y,
+                                                         float* __restrict__ acc_part, float* __restrict__ ss_part,
+                                                         unsigned* __restrict__ tickets, int M, int K, int N, float eps,
+                                                         int S, int flags) {
+    constexpr int G = GATED ? 2 : 1;
+    constexpr int RB = 16 * RG;  // rows per workgroup
+
+    extern __shared__ float lds[];
+    float* red = lds;                    // [2][NW][16][TN], reused for every (weight matrix, pair of row groups)
+    float* ss_red = lds + 2 * kRedFloats;  // [NW][RB]
+    __shared__ int is_last;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = lane >> 4, c = lane & 15;
+    const int ntile = blockIdx.x, split = blockIdx.y, rblock = blockIdx.z;
+    const int n_tiles = gridDim.x;
+    const int n0 = ntile * TN, m0 = rblock * RB;
+
+    const int kblocks = (K + KB - 1) / KB;
+    const int per = kblocks / S, rem = kblocks % S;
+    const int b_beg = split * per + min(split, rem);
+    const int b_cnt = per + (split < rem ? 1 : 0);
+
+    const u32 row_bytes = (u32)N * 2u;
+    const size_t w_first = (size_t)b_beg * KB * N + n0;
+    const size_t w_total = (size_t)K * N;
+    const size_t w_left = (w_first < w_total ? w_total - w_first : 0) * 2;
+    const u32 w_bytes = (u32)(w_left < 0x7FFFFFFFull ? w_left : 0x7FFFFFFFull);
+    const __amdgpu_buffer_rsrc_t rw1 = make_rsrc(W1 + w_first, w_bytes);
+    const __amdgpu_buffer_rsrc_t rw2 = make_rsrc((GATED ? W2 : W1) + w_first, w_bytes);
+    // X from this row block's first row: offsets inside the block stay small whatever M is.
+    const size_t x_left = ((size_t)(M - m0) * K) * 2;
+    const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (size_t)m0 * K, (u32)(x_left < 0x7FFFFFFFull ? x_left : 0x7FFFFFFFull));
+    const __amdgpu_buffer_rsrc_t rg = make_rsrc(g, (u32)K * 2u);
+
+    const bool col_ok = (n0 + 8 * c) < N;
+    const u32 w_lane = col_ok ? ((u32)(8 * q) * row_bytes + (u32)(16 * c)) : kOutOfRange;
+    bool row_ok[RG];
+    u32 x_row[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        row_ok[r] = (m0 + 16 * r + c) < M;
+        x_row[r] = (u32)(16 * r + c) * (u32)K * 2u;
+    }
+
+    f32x4 acc1[RG][8], acc2[GATED ? RG : 1][8];
+    float ss[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        ss[r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            acc1[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (GATED) acc2[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    // U K-blocks per trip: sixteen 16-byte row loads of W in flight per lane where the registers allow it.
+    constexpr int U = (!GATED && RG <= 2) ? 2 : 1;
+    for (int i = wave; i < b_cnt; i += U * NW) {
+        WRows w1[U], w2[GATED ? U : 1];
+        u32x4 xr[U][RG], gr[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int ib = i + u * NW;
+            const bool has = ib < b_cnt;
+            const u32 woff = has ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange;
+            const int k = (b_beg + ib) * KB + 8 * q;
+            const bool k_ok = has && k < K;
+#pragma unroll
+            for (int r = 0; r < RG; ++r)
+                xr[u][r] = load16(rx, (row_ok[r] && k_ok) ? x_row[r] + (u32)k * 2u : kOutOfRange);
+            gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
+            load_w_block(w1[u], rw1, woff, row_bytes);
+            if (GATED) load_w_block(w2[u], rw2, woff, row_bytes);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            u32x4 a[RG];
+#pragma unroll
+            for (int r = 0; r < RG; ++r) a[r] = scaled_operand<F>(xr[u][r], gr[u], ss[r]);
+            auto step = [&](auto jc) {
+                constexpr int J = decltype(jc)::value;
+                const u32x4 b1 = b_operand<J>(w1[u]);
+#pragma unroll
+                for (int r = 0; r < RG; ++r) acc1[r][J] = F::mfma_16x16x32(a[r], b1, acc1[r][J]);
+                if (GATED) {
+                    const u32x4 b2 = b_operand<J>(w2[GATED ? u : 0]);
+#pragma unroll
+                    for (int r = 0; r < RG; ++r) acc2[r][J] = F::mfma_16x16x32(a[r], b2, acc2[r][J]);
+                }
+            };
+            step(std::integral_constant<int, 0>{});
+            step(std::integral_constant<int, 1>{});
+            step(std::integral_constant<int, 2>{});
+            step(std::integral_constant<int, 3>{});
+            step(std::integral_constant<int, 4>{});
+            step(std::integral_constant<int, 5>{});
+            step(std::integral_constant<int, 6>{});
+            step(std::integral_constant<int, 7>{});
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        ss[r] += __shfl_xor(ss[r], 16, 64);
+        ss[r] += __shfl_xor(ss[r], 32, 64);
+        if (q == 0) ss_red[wave * RB + 16 * r + c] = ss[r];
+    }
+
+    // Epilogue mapping: thread -> (row m of a group, CPT consecutive columns).
+    const int m = tid / TPR;
+    const int col = (tid % TPR) * CPT;
+    const int n = n0 + col;
+    bool out_ok[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) out_ok[r] = (m0 + 16 * r + m < M) && (n < N);
+
+    // Across wavefronts through LDS, two row groups of one weight matrix at a time.  Accumulator j, element
+    // i of lane (q, c) is row 4q + i of the group, column 8c + j of the tile.
+    float v1[RG][CPT], v2[RG][CPT], ssum[RG];
+    auto put = [&](float* base, const f32x4 (&acc)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            // As in the 16-row kernel: the upper eight column groups write their second half first.
+            float* dst = base + (wave * 16 + (4 * q + i)) * TN + 8 * c;
+            const f32x4 lo = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+            const f32x4 hi = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+            const bool upper = (c & 8) != 0;
+            *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
+            *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
+        }
+    };
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+#pragma unroll
+        for (int r0 = 0; r0 < RG; r0 += 2) {
+            if (gi + r0 > 0) __syncthreads();
+#pragma unroll
+            for (int h = 0; h < 2; ++h) put(red + h * kRedFloats, gi == 0 ? acc1[r0 + h] : acc2[GATED ? r0 + h : 0]);
+            __syncthreads();  // also orders the ss_red stores before their first reader
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int r = r0 + h;
+                float v[CPT];
+#pragma unroll
+                for (int e = 0; e < CPT; ++e) v[e] = 0.f;
+                float sq = 0.f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) {
+                    const float* src = red + h * kRedFloats + (w * 16 + m) * TN + col;
+#pragma unroll
+                    for (int e = 0; e < CPT; ++e) v[e] += src[e];
+                    if (gi == 0) sq += ss_red[w * RB + 16 * r + m];
+                }
+                if (gi == 0) ssum[r] = sq;
+#pragma unroll
+                for (int e = 0; e < CPT; ++e) {
+                    if (gi == 0) v1[r][e] = v[e];
+                    else v2[r][e] = v[e];
+                }
+            }
+        }
+    }
+    if (!GATED) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) v2[r][e] = 0.f;
+    }
+
+    if (S > 1) {
+        // Exchange between the K-slices of this (column tile, row block): see the 16-row kernel.
+        const size_t tile_id = (size_t)rblock * n_tiles + ntile;
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const int row = m0 + 16 * r + m;
+            if (out_ok[r]) {
+                float* p = acc_part + (((size_t)split * G) * M + row) * N + n;
+#pragma unroll
+                for (int e = 0; e < CPT; e += 2) {
+                    store_coherent2(p + e, v1[r][e], v1[r][e + 1]);
+                    if (GATED) store_coherent2(p + (size_t)M * N + e, v2[r][e], v2[r][e + 1]);
+                }
+            }
+            if (col == 0) store_coherent(ss_part + (tile_id * S + split) * RB + 16 * r + m, ssum[r]);
+        }
+        wait_stores_acknowledged();
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned prev = __hip_atomic_fetch_add(&tickets[tile_id], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (prev == (unsigned)(S - 1));
+        }
+        __syncthreads();
+        if (!is_last) return;
+        if (tid == 0) tickets[tile_id] = 0u;
+
+        // A batch of slices at a time, every row group's loads issued before the first sum; summed in slice order.
+        constexpr int BATCH = (RG * G >= 4) ? 4 : 8;
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            ssum[r] = 0.f;
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) { v1[r][e] = 0.f; v2[r][e] = 0.f; }
+        }
+        for (int s0 = 0; s0 < S; s0 += BATCH) {
+            float sq[BATCH][RG];
+            f32x2 pa[BATCH][RG][CPT / 2], pb[BATCH][GATED ? RG : 1][CPT / 2];
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                const int s = min(s0 + j, S - 1);
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    sq[j][r] = load_coherent(ss_part + (tile_id * S + s) * RB + 16 * r + m);
+                    if (out_ok[r]) {
+                        const float* p = acc_part + (((size_t)s * G) * M + (m0 + 16 * r + m)) * N + n;
+#pragma unroll
+                        for (int e = 0; e < CPT / 2; ++e) {
+                            pa[j][r][e] = load_coherent2(p + 2 * e);
+                            if (GATED) pb[j][GATED ? r : 0][e] = load_coherent2(p + (size_t)M * N + 2 * e);
+                        }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j) {
+                if (s0 + j >= S) break;
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    ssum[r] += sq[j][r];
+                    if (out_ok[r]) {
+#pragma unroll
+                        for (int e = 0; e < CPT / 2; ++e) {
+                            v1[r][2 * e] += pa[j][r][e][0];
+                            v1[r][2 * e + 1] += pa[j][r][e][1];
+                            if (GATED) {
+                                v2[r][2 * e] += pb[j][GATED ? r : 0][e][0];
+                                v2[r][2 * e + 1] += pb[j][GATED ? r : 0][e][1];
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        if (!out_ok[r]) continue;
+        const float rinv = (flags & kFlagNorm) ? __builtin_amdgcn_rsqf(ssum[r] / (float)K + eps) : 1.0f;
+        float y[CPT];
+#pragma unroll
+        for (int e = 0; e < CPT; ++e) {
+            y[e] = v1[r][e] * rinv;
+            if (GATED) y[e] = ((flags & kFlagSilu) ? silu_f32(y[e]) : y[e]) * (v2[r][e] * rinv);
+        }
+        *(u32x2*)(Y + (size_t)(m0 + 16 * r + m) * N + n) = u32x2{F::pack(y[0], y[1]), F::pack(y[2], y[3])};
+    }
+}
+
+template <typename F, bool GATED, int RG>
+static hipError_t launch_rows(const Call& c, int S, const DecodeWorkspace& ws) {
+    const int n_tiles = (c.N + TN - 1) / TN;
+    const int row_blocks = (c.M + 16 * RG - 1) / (16 * RG);
+    dim3 grid(n_tiles, S, row_blocks), block(NT);
+    const size_t lds = (size_t)(2 * kRedFloats + NW * 16 * RG) * sizeof(float);
+    auto kern = decode_rows_kernel<F, GATED, RG>;
+    static std::atomic<uint64_t> opted{0};
+    if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
+    hipLaunchKernelGGL(kern, grid, block, lds, c.stream, (const uint16_t*)c.X, (const uint16_t*)c.g,
+                       (const uint16_t*)c.W1, (const uint16_t*)(c.gated ? c.W2 : c.W1), (uint16_t*)c.Y, ws.acc_part,
+                       ws.ss_part, ws.tickets, c.M, c.K, c.N, c.eps, S, c.flags);
+    return hipGetLastError();
+}
+
+template <typename F>
+static hipError_t launch_rows_fmt(const Call& c, int split_k, int row_groups, const DecodeWorkspace& ws) {
+    if (c.gated) {
+        if (row_groups == 2) return launch_rows<F, true, 2>(c, split_k, ws);
+    } else {
+        if (row_groups == 2) return launch_rows<F, false, 2>(c, split_k, ws);
+        if (row_groups == 4) return launch_rows<F, false, 4>(c, split_k, ws);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, const DecodeWorkspace& ws) {
+    return f16 ? launch_rows_fmt<F16>(c, split_k, row_groups, ws) : launch_rows_fmt<Bf16>(c, split_k, row_groups, ws);
+}
+
+}  // namespace prism

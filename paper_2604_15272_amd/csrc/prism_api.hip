@@ -29,6 +29,7 @@ uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 struct Plan {
     prism_plan_t pub;
     int waves;          // decode: wavefronts per workgroup
+    int row_groups;     // decode: 16-row groups per workgroup (1: the 16-row kernel)
     uint64_t ss_bytes;  // decode: bytes of the partial sums of squares (rounded)
 };
 
@@ -64,6 +65,21 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
             *bn = t[i].bn;
         }
     }
+}
+
+// More than 16 rows on the decode path: 16-row groups per workgroup (2 or 4), or 0 if the tiled prefill
+// kernel is the better choice.  Measured on MI355X (bf16, K x N from 1024 x 1024 to 14336 x 4096, 17 to 512
+// rows): the decode path wins while all its workgroups run at once (one per CU) and W is deep enough that
+// the prefill kernel's 64-deep K-steps over few tiles dominate; 32 rows per workgroup win over 64 while the
+// row blocks' re-reads of W stay within the 256 MiB last-level cache.
+int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
+    const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
+    const int64_t z32 = (M + 31) / 32, z64 = (M + 63) / 64;
+    if (M > kDecodeRowsMax || (M > 64 && K < 2048)) return 0;
+    if (gated) return (M <= 64 && n_tiles * z32 <= 256) ? 2 : 0;
+    const uint64_t w_bytes = (uint64_t)K * N * 2;
+    if ((M <= 32 || z32 * w_bytes <= (256ull << 20)) && n_tiles * z32 <= 256) return 2;
+    return n_tiles * z64 <= 256 ? 4 : 0;
 }
 
 bool prefill_tile_known(bool gated, int bm, int bn) {
@@ -148,7 +164,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
     const bool fast_ok = dtype != PRISM_F32 && vector16_ok(K, N);
     if (path == PRISM_PATH_AUTO) {
         if (!fast_ok) path = PRISM_PATH_SIMPLE;
-        else path = (M <= kDecodeMaxRows) ? PRISM_PATH_DECODE : PRISM_PATH_PREFILL;
+        else path = (M <= kDecodeMaxRows || decode_row_groups(gated, M, K, N) > 0) ? PRISM_PATH_DECODE : PRISM_PATH_PREFILL;
         // Shapes whose byte offsets do not fit the 32-bit buffer addressing fall back.
         if (path == PRISM_PATH_PREFILL && (uint64_t)K * N * 2 >= kTwoGiB) path = PRISM_PATH_SIMPLE;
         if (path == PRISM_PATH_DECODE && (uint64_t)M * K * 2 >= kTwoGiB) path = PRISM_PATH_SIMPLE;
@@ -167,18 +183,33 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
     if (!fast_ok) return PRISM_ERR_UNSUPPORTED;
 
     if (path == PRISM_PATH_DECODE) {
-        if (M > kDecodeMaxRows || (uint64_t)M * K * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
-        int waves = (variant > 0) ? variant : 8;
-        if (waves != 4 && waves != 8 && waves != 16) return PRISM_ERR_UNSUPPORTED;
+        if ((uint64_t)M * K * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
+        // Variant: 4, 8 or 16 wavefronts for at most 16 rows; 32 or 64 rows per workgroup for more.
+        int waves = 8, row_groups = 1;
+        if (M <= kDecodeMaxRows) {
+            if (variant > 0) waves = variant;
+            if (waves != 4 && waves != 8 && waves != 16) return PRISM_ERR_UNSUPPORTED;
+        } else {
+            // Every 16-row group reuses the B operands built from W: 64 rows per workgroup unless the
+            // registers (gated: two weight matrices) or the row count say 32.
+            row_groups = decode_row_groups(gated, M, K, N);
+            if (row_groups == 0) row_groups = gated ? 2 : 4;  // forced onto a shape the heuristic leaves to prefill
+            if (variant == 32 || variant == 64) row_groups = variant / 16;
+            else if (variant != 0 && variant != 8) return PRISM_ERR_UNSUPPORTED;
+            if (gated && row_groups != 2) return PRISM_ERR_UNSUPPORTED;
+        }
+        const int64_t row_blocks = (M + 16 * row_groups - 1) / (16 * row_groups);
         const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
         const int64_t kblocks = (K + kDecodeKBlock - 1) / kDecodeKBlock;
-        if (n_tiles > kMaxTickets) return PRISM_ERR_UNSUPPORTED;
+        if (row_blocks > 65535 || n_tiles * row_blocks > kMaxTickets) return PRISM_ERR_UNSUPPORTED;
         int64_t S = forced_split;
         if (S <= 0) {
             // About one workgroup per CU (measured best on MI355X: more slices only add partial-sum
             // traffic and tickets), each wavefront keeping at least one K-block.
             const int64_t target = 256;
-            S = (target + n_tiles / 2) / n_tiles;
+            const int64_t wgs = n_tiles * row_blocks;
+            // The multi-row kernel fits one workgroup per CU: never more workgroups than CUs if that can be helped.
+            S = (row_groups > 1) ? target / wgs : (target + wgs / 2) / wgs;
             const int64_t s_max = kblocks / waves;
             if (S > s_max) S = s_max;
             if (S < 1) S = 1;
@@ -194,14 +225,16 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             while (!slice_fits(S) && S < kblocks) S = std::min<int64_t>(kblocks, 2 * S);
         if (S > 65535 || !slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
         out->waves = waves;
+        out->row_groups = row_groups;
         p.split_k = (int32_t)S;
-        p.tile_m = kDecodeMaxRows;
+        p.tile_m = 16 * row_groups;
         p.tile_n = kDecodeTileN;
         p.grid_x = (int32_t)n_tiles;
         p.grid_y = (int32_t)S;
+        p.grid_z = (int32_t)row_blocks;
         p.block = waves * 64;
         if (S > 1) {
-            out->ss_bytes = round_up((uint64_t)n_tiles * S * 16 * 4, 256);
+            out->ss_bytes = round_up((uint64_t)n_tiles * row_blocks * S * 16 * row_groups * 4, 256);
             p.workspace_bytes = PRISM_WORKSPACE_HEADER_BYTES + out->ss_bytes +
                                 (uint64_t)S * (gated ? 2 : 1) * M * N * 4;
         }
@@ -306,7 +339,9 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                 ws.ss_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES);
                 ws.acc_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES + plan.ss_bytes);
             }
-            err = launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.waves, ws);
+            err = plan.row_groups > 1
+                      ? launch_decode_rows_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.row_groups, ws)
+                      : launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.waves, ws);
             break;
         }
         case PRISM_PATH_PREFILL:

@@ -73,15 +73,18 @@ constexpr int kSoftmaxRows = 16;
 constexpr int kSoftmaxTileN = 128;
 
 // Geometry of the decode (few-row) path.
-constexpr int kDecodeMaxRows = 16;     // one 16-row MFMA block
+constexpr int kDecodeMaxRows = 16;     // one 16-row MFMA block (the 16-row kernel)
+// More rows than that still take the decode path (its multi-row-group kernel) up to this count, shape
+// permitting; beyond it re-reading W per row block costs more than the tiled prefill kernel.
+constexpr int kDecodeRowsMax = 512;
 constexpr int kDecodeTileN = 128;      // columns of W per workgroup
 constexpr int kDecodeKBlock = 32;      // K depth of one MFMA
 constexpr int kDecodeWaves = 8;        // wavefronts per workgroup (default variant)
 constexpr int kMaxTickets = PRISM_WORKSPACE_HEADER_BYTES / 4;
 
 struct DecodeWorkspace {
-    unsigned* tickets;  // [n_tiles] arrival counters, zero between calls
-    float* ss_part;     // [n_tiles][S][16] partial sums of squares
+    unsigned* tickets;  // [row_blocks][n_tiles] arrival counters, zero between calls
+    float* ss_part;     // [row_blocks][n_tiles][S][rows per workgroup] partial sums of squares
     float* acc_part;    // [S][G][M][N] partial products (G = 2 if gated)
 };
 
@@ -104,6 +107,7 @@ hipError_t launch_simple_bf16(const Call& c);
 hipError_t launch_simple_f16(const Call& c);
 // The matrix-core kernels, for either 16-bit storage format (f16 = false: bf16).
 hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, const DecodeWorkspace& ws);
+hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, const DecodeWorkspace& ws);
 hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);
 hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16);
 hipError_t launch_softmax_simple(const SoftmaxCall& c, int dtype);

@@ -16,7 +16,8 @@ import random
 
 from . import binding as B
 
-_DECODE_WAVES = (4, 8, 16)
+_DECODE_VARIANTS = (4, 8, 16, 32, 64)   # wavefronts (at most 16 rows) or rows per workgroup (more)
+_DECODE_MAX_ROWS = 512                  # the decode path re-reads W per row block: not worth timing beyond
 _PLAIN_TILES = (256256, 256192, 128128, 64064)
 _GATED_TILES = (256256, 128256, 128128)
 _TORCH_DTYPE = {B.PRISM_F32: "float32", B.PRISM_BF16: "bfloat16", B.PRISM_F16: "float16"}
@@ -30,7 +31,9 @@ def candidates(op, M, K, N, dtype, max_split=64):
             if path == B.PRISM_PATH_SIMPLE:
                 grid = [(0, 0)]
             elif path == B.PRISM_PATH_DECODE:
-                grid = [(s, w) for w in _DECODE_WAVES for s in range(1, max_split + 1)]
+                if M > _DECODE_MAX_ROWS:
+                    continue
+                grid = [(s, v) for v in _DECODE_VARIANTS for s in range(1, max_split + 1)]
             else:
                 grid = [(0, t) for t in (_GATED_TILES if op == B.PRISM_OP_RMSNORM_GATED_MLP else _PLAIN_TILES)]
             seen = set()

@@ -96,13 +96,62 @@ def test_decode_is_bit_reproducible_and_leaves_tickets_clean(P):
         assert torch.equal(o.view(torch.uint16), ref)
 
 
+# ---- decode path, more than 16 rows (several 16-row groups per workgroup, row blocks in the grid) --------
+
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("M,K,N", [(17, 512, 128), (32, 4096, 1024), (33, 1000, 264), (48, 4104, 4104), (64, 64, 8),
+                                   (65, 2048, 520), (100, 8, 16), (128, 4096, 2048)])
+def test_decode_rows_shapes(P, M, K, N, gated):
+    _case(P, pi.BF16, M, K, N, gated, seed=450 + M + N, path=P.PRISM_PATH_DECODE)
+
+
+@pytest.mark.parametrize("M,K,N", [(17, 4096, 4096), (200, 2048, 520), (256, 4096, 4096), (100, 14336, 4096)])
+def test_decode_rows_chosen_by_the_dispatcher(P, M, K, N):
+    _case(P, pi.BF16, M, K, N, False, seed=460 + M, expect_path=P.PRISM_PATH_DECODE)
+
+
+def test_decode_rows_gated_chosen_by_the_dispatcher(P):
+    _case(P, pi.BF16, 40, 4096, 14336, True, seed=465, expect_path=P.PRISM_PATH_DECODE)
+
+
+@pytest.mark.parametrize("gated,rows", [(False, 32), (False, 64), (True, 32)])
+@pytest.mark.parametrize("split", [1, 2, 3, 7, 16, 33])
+def test_decode_rows_every_split_and_row_count(P, split, rows, gated):
+    """Table 1, parallelized matmul (reduction; row partition): neither the split factor nor the rows per
+    workgroup may change the result."""
+    _case(P, pi.BF16, 75, 2056, 1160, gated, seed=470, path=P.PRISM_PATH_DECODE, split=split, variant=rows)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_decode_rows_f16_and_forced_beyond_the_automatic_range(P, gated):
+    _case(P, pi.F16, 300, 1024, 264, gated, seed=480, path=P.PRISM_PATH_DECODE)
+
+
+def test_decode_rows_is_bit_reproducible_and_leaves_tickets_clean(P):
+    import torch
+    from gpu_util import to_device
+    stored = pi.draw(pi.BF16, 80, 4096, 4096, False, 481)
+    X, g, W = (to_device(stored[k], pi.BF16) for k in ("X", "g", "W"))
+    assert P.prism_plan(0, 80, 4096, 4096, 1)["split_k"] > 1
+    outs = []
+    for _ in range(30):
+        Y = torch.empty((80, 4096), dtype=torch.bfloat16, device="cuda")
+        P.prism_rmsnorm_matmul(X, g, W, Y)
+        outs.append(Y)
+    torch.cuda.synchronize()
+    ref = outs[0].view(torch.uint16)
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.uint16), ref)
+
+
 # ---- prefill path -----------------------------------------------------------------------------
 
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("M,K,N", [(17, 64, 64), (33, 200, 264), (100, 1024, 520), (256, 512, 384), (300, 4096, 256),
                                    (513, 72, 1032)])
 def test_prefill_shapes(P, M, K, N, gated):
-    _case(P, pi.BF16, M, K, N, gated, seed=500 + M, expect_path=P.PRISM_PATH_PREFILL)
+    # forced: up to a few hundred rows the dispatcher prefers the decode path's multi-row kernel
+    _case(P, pi.BF16, M, K, N, gated, seed=500 + M, path=P.PRISM_PATH_PREFILL, expect_path=P.PRISM_PATH_PREFILL)
 
 
 @pytest.mark.parametrize("gated,variant", [(False, 256256), (False, 256192), (False, 128128), (False, 64064),
@@ -206,8 +255,8 @@ def test_no_gain_equals_gain_of_ones_bit_for_bit(P):
 
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("M,K,N,path", [(3, 77, 130, 1), (8, 256, 512, 2), (8, 1024, 1024, 2), (16, 4096, 4096, 2),
-                                        (13, 2056, 1160, 2), (33, 200, 264, 3), (300, 712, 648, 3),
-                                        (1024, 1024, 768, 3)])
+                                        (13, 2056, 1160, 2), (33, 200, 264, 2), (300, 712, 648, 3),
+                                        (1024, 1024, 768, 3), (600, 200, 264, 3)])
 def test_f16_shapes(P, M, K, N, path, gated):
     _case(P, pi.F16, M, K, N, gated, seed=900 + M, expect_path=path)
 

@@ -89,9 +89,9 @@ def test_override_and_workspace_size(P):
     # a forced path that cannot run the shape is refused, not silently replaced
     P.prism_set_override(P.PRISM_PATH_DECODE, 0, 0)
     with pytest.raises(P.PrismError):
-        P.prism_plan(0, 64, 4096, 4096, bf16)
-    with pytest.raises(P.PrismError):
         P.prism_plan(0, 8, 256, 512, P.PRISM_F32)
+    with pytest.raises(P.PrismError):
+        P.prism_plan(0, 64, 4100, 4096, bf16)
     P.prism_set_override(P.PRISM_PATH_PREFILL, 0, 999999)
     with pytest.raises(P.PrismError):
         P.prism_plan(0, 64, 4096, 4096, bf16)
@@ -158,11 +158,56 @@ def test_attention_arguments_and_plan(P):
     P.prism_set_override(0, 0, 0)
 
 
+def test_decode_plan_for_more_than_sixteen_rows(P):
+    """Several 16-row groups per workgroup, further rows as row blocks in the grid's z."""
+    bf16 = P.PRISM_BF16
+    d = P.prism_plan(0, 17, 4096, 4096, bf16)
+    assert (d["path"], d["tile_m"], d["grid_x"], d["grid_z"], d["block"]) == (P.PRISM_PATH_DECODE, 32, 32, 1, 512)
+    assert d["grid_y"] == d["split_k"] == 8
+    d = P.prism_plan(0, 100, 4096, 4096, bf16)    # four passes over 32 MiB of W stay in the last-level cache
+    assert (d["path"], d["tile_m"], d["grid_z"], d["split_k"]) == (P.PRISM_PATH_DECODE, 32, 4, 2)
+    n_tiles, rb, S = 32, 4, 2
+    assert d["workspace_bytes"] == 262144 + n_tiles * rb * S * 32 * 4 + S * 100 * 4096 * 4
+    d = P.prism_plan(0, 100, 14336, 4096, bf16)   # 112 MiB of W: 64 rows per workgroup, two passes
+    assert (d["path"], d["tile_m"], d["grid_z"], d["split_k"]) == (P.PRISM_PATH_DECODE, 64, 2, 4)
+    assert P.prism_plan(0, 512, 4096, 4096, bf16)["path"] == P.PRISM_PATH_DECODE
+    assert P.prism_plan(0, 512, 4096, 6144, bf16)["path"] == P.PRISM_PATH_PREFILL   # 384 workgroups: not at once
+    assert P.prism_plan(0, 100, 1024, 1024, bf16)["path"] == P.PRISM_PATH_PREFILL   # shallow K
+    g = P.prism_plan(1, 64, 4096, 14336, bf16)
+    assert (g["path"], g["tile_m"], g["grid_z"]) == (P.PRISM_PATH_DECODE, 32, 2)
+    assert P.prism_plan(1, 100, 4096, 14336, bf16)["path"] == P.PRISM_PATH_PREFILL
+    # the variant picks the rows per workgroup; wavefront counts belong to the 16-row kernel
+    try:
+        P.prism_set_override(P.PRISM_PATH_DECODE, 3, 32)
+        d = P.prism_plan(0, 100, 4096, 4096, bf16)
+        assert (d["tile_m"], d["grid_z"], d["split_k"]) == (32, 4, 3)
+        with pytest.raises(P.PrismError):
+            P.prism_plan(0, 16, 4096, 4096, bf16)
+        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 0)
+        assert P.prism_plan(1, 100, 4096, 14336, bf16)["grid_z"] == 4
+        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 64)
+        with pytest.raises(P.PrismError):
+            P.prism_plan(1, 100, 4096, 14336, bf16)
+        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 4)
+        with pytest.raises(P.PrismError):
+            P.prism_plan(0, 100, 4096, 4096, bf16)
+        # forced, the decode path takes any row count whose counters fit the workspace header
+        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 0)
+        assert P.prism_plan(0, 5000, 4096, 4096, bf16)["grid_z"] == -(-5000 // 64)
+        with pytest.raises(P.PrismError):
+            P.prism_plan(0, 200000, 1024, 8192, bf16)   # 3125 row blocks x 64 column tiles of counters
+    finally:
+        P.prism_set_override(0, 0, 0)
+    # beyond a few hundred rows the tiled kernel takes over
+    assert P.prism_plan(0, 2048, 4096, 4096, bf16)["path"] == P.PRISM_PATH_PREFILL
+    assert P.prism_plan(1, 2048, 4096, 14336, bf16)["path"] == P.PRISM_PATH_PREFILL
+
+
 def test_shapes_past_the_32_bit_offsets_take_the_plain_kernel(P):
     """2 GiB of W is what the buffer addressing of the matrix-core kernels covers; beyond, the plan says so."""
     bf16 = P.PRISM_BF16
-    assert P.prism_plan(0, 64, 16384, 65536, bf16)["path"] == P.PRISM_PATH_SIMPLE     # W = 2 GiB
-    assert P.prism_plan(0, 64, 16384, 65528, bf16)["path"] == P.PRISM_PATH_PREFILL    # just below
+    assert P.prism_plan(0, 1024, 16384, 65536, bf16)["path"] == P.PRISM_PATH_SIMPLE     # W = 2 GiB
+    assert P.prism_plan(0, 1024, 16384, 65528, bf16)["path"] == P.PRISM_PATH_PREFILL    # just below
     big = P.prism_plan(0, 16, 16384, 131072, bf16)                                    # W = 4 GiB: decode offsets are
     assert big["path"] == P.PRISM_PATH_DECODE and big["split_k"] == 4                 # per slice, so it takes 4 slices
 
@@ -189,8 +234,8 @@ def test_plan_table_precedence_and_validation(P):
         # replacing an entry does not grow the table
         P.prism_plan_table_set(0, 16, 4096, 4096, bf16, P.PRISM_PATH_PREFILL, 0, 128128)
         assert P.prism_plan_table_size() == 1 and P.prism_plan(0, 16, 4096, 4096, bf16)["tile_m"] == 128
-        # refused: decode for 64 rows, an unknown tile, a negative split
-        for bad in ((0, 64, 4096, 4096, bf16, P.PRISM_PATH_DECODE, 0, 0), (0, 64, 4096, 4096, bf16, P.PRISM_PATH_PREFILL, 0, 999),
+        # refused: four wavefronts for 64 rows, an unknown tile, a negative split
+        for bad in ((0, 64, 4096, 4096, bf16, P.PRISM_PATH_DECODE, 0, 4), (0, 64, 4096, 4096, bf16, P.PRISM_PATH_PREFILL, 0, 999),
                     (0, 16, 4096, 4096, bf16, P.PRISM_PATH_DECODE, -1, 0), (0, 0, 4096, 4096, bf16, P.PRISM_PATH_DECODE, 1, 8)):
             with pytest.raises(P.PrismError):
                 P.prism_plan_table_set(*bad)
@@ -217,8 +262,13 @@ def test_tuner_enumerates_admissible_assignments(P):
     assert {x["plan"]["block"] for x in dec} == {256, 512, 1024}
     assert len({(x["plan"]["split_k"], x["plan"]["block"]) for x in dec}) == len(dec)  # distinct plans only
     assert all(1 <= x["split_k"] <= 16 for x in dec)
+    # more than 16 rows: the variant is the rows per workgroup
+    mid = [x for x in tune.candidates(0, 100, 2048, 1024, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
+    assert {x["plan"]["tile_m"] for x in mid} == {32, 64} and all(x["plan"]["block"] == 512 for x in mid)
+    gmid = [x for x in tune.candidates(1, 100, 2048, 1024, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
+    assert {x["plan"]["tile_m"] for x in gmid} == {32}
     # many rows: no decode candidates; fp32: the plain kernel only
-    assert all(x["path"] != P.PRISM_PATH_DECODE for x in tune.candidates(1, 512, 1024, 1024, P.PRISM_BF16))
+    assert all(x["path"] != P.PRISM_PATH_DECODE for x in tune.candidates(1, 2048, 1024, 1024, P.PRISM_BF16))
     assert [x["path"] for x in tune.candidates(0, 8, 256, 512, P.PRISM_F32)] == [P.PRISM_PATH_SIMPLE]
     assert P.prism_plan(0, 16, 2048, 1024, P.PRISM_BF16)["path"] == P.PRISM_PATH_DECODE  # override is reset
 
