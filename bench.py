@@ -267,6 +267,7 @@ def measure_running_example(steps=500, warmup=30):
     args = [(vp(Xs[s].data_ptr()), vp(W.data_ptr()), vp(Ys[s].data_ptr()), i64(M), i64(K), i64(N),
              ctypes.c_int32(P.PRISM_F16), stream) for s in range(sets)]
     fn = P.lib.prism_softmax_matmul
+    P.ensure_workspace(P.prism_workspace_bytes(P.PRISM_OP_SOFTMAX_MATMUL, M, K, N, P.PRISM_F16))
 
     def run(n, first=0, used=sets):
         for i in range(n):

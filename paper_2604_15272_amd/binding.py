@@ -258,6 +258,8 @@ def prism_softmax_matmul(X, W, Y, M=None, K=None, N=None, dtype=None, stream=Non
         M, K = X.shape
         N = W.shape[1]
     dt = _dtype_of(X, dtype)
+    if not isinstance(X, int):
+        ensure_workspace(prism_workspace_bytes(PRISM_OP_SOFTMAX_MATMUL, M, K, N, dt))
     st = lib.prism_softmax_matmul(_ptr(X), _ptr(W), _ptr(Y), int(M), int(K), int(N), dt, _stream_handle(stream))
     if st != 0:
         raise PrismError(st, "prism_softmax_matmul")

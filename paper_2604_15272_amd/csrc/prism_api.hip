@@ -116,29 +116,76 @@ Choice resolve_choice(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtyp
     return Choice{0, 0, 0};
 }
 
-// Softmax -> MatMul: the matrix-core kernel for 16-bit storage with K and N multiples of 8, else the plain one.
+// Softmax -> MatMul: the matrix-core kernels for 16-bit storage with K and N multiples of 8 (variant 16: 16 rows
+// per workgroup over the whole of K; variant 32: 32 rows and one of split_k K-slices), else the plain one.
 prism_status_t make_softmax_plan(int64_t M, int64_t K, int64_t N, prism_dtype_t dtype, Choice choice, Plan* out) {
     std::memset(out, 0, sizeof(*out));
     prism_plan_t& p = out->pub;
     p.split_k = 1;
     if (choice.path != PRISM_PATH_AUTO && choice.path != PRISM_PATH_SIMPLE && choice.path != PRISM_PATH_ROWS)
         return PRISM_ERR_UNSUPPORTED;
-    if (choice.split_k > 1 || choice.variant != 0) return PRISM_ERR_UNSUPPORTED;
+    if (choice.variant != 0 && choice.variant != 16 && choice.variant != 32) return PRISM_ERR_UNSUPPORTED;
     if (M == 0 || N == 0) return PRISM_OK;
-    const int64_t row_blocks = (M + kSoftmaxRows - 1) / kSoftmaxRows;
     const bool fast_ok = dtype != PRISM_F32 && vector16_ok(K, N) && (uint64_t)K * N * 2 < kTwoGiB &&
-                         K <= (1 << 24) && row_blocks <= 65535;
+                         K <= (1 << 24) && (M + kSoftmaxRows - 1) / kSoftmaxRows <= 65535;
     int path = choice.path;
     if (path == PRISM_PATH_AUTO) path = fast_ok ? PRISM_PATH_ROWS : PRISM_PATH_SIMPLE;
     if (path == PRISM_PATH_ROWS && !fast_ok) return PRISM_ERR_UNSUPPORTED;
     p.path = path;
-    p.block = path == PRISM_PATH_ROWS ? 512 : 256;
-    p.tile_m = path == PRISM_PATH_ROWS ? kSoftmaxRows : 8;
-    p.tile_n = path == PRISM_PATH_ROWS ? kSoftmaxTileN : 256;
-    p.grid_x = (int32_t)((N + p.tile_n - 1) / p.tile_n);
-    const int64_t gy = (M + p.tile_m - 1) / p.tile_m;
-    if (gy > 65535) return PRISM_ERR_UNSUPPORTED;
-    p.grid_y = (int32_t)gy;
+    if (path == PRISM_PATH_SIMPLE) {
+        if (choice.split_k > 1 || choice.variant != 0) return PRISM_ERR_UNSUPPORTED;
+        p.block = 256;
+        p.tile_m = 8;
+        p.tile_n = 256;
+        p.grid_x = (int32_t)((N + 255) / 256);
+        const int64_t gy = (M + 7) / 8;
+        if (gy > 65535) return PRISM_ERR_UNSUPPORTED;
+        p.grid_y = (int32_t)gy;
+        return PRISM_OK;
+    }
+    const int64_t n_tiles = (N + kSoftmaxTileN - 1) / kSoftmaxTileN;
+    const int64_t kblocks = (K + 31) / 32;
+    const int64_t rb32 = (M + kSoftmaxSplitRows - 1) / kSoftmaxSplitRows;
+    const int64_t rb16 = (M + kSoftmaxRows - 1) / kSoftmaxRows;
+    int64_t S = choice.split_k;
+    int variant = choice.variant;
+    if (S <= 0 && variant == 16) S = 1;
+    if (S <= 0) {
+        // All workgroups at once (the split kernel fits one per CU) and at least four K-blocks per wavefront.
+        S = std::min<int64_t>(256 / std::max<int64_t>(1, n_tiles * rb32), kblocks / 32);
+        S = std::max<int64_t>(1, std::min<int64_t>(S, kSoftmaxMaxSplits));
+        if (variant == 0 && n_tiles * rb16 <= 256) {
+            // Both kernels run in one round.  Measured on MI355X: a wavefront's K-block costs about 75 ns of the
+            // call with 16 rows per workgroup and 156 ns with 32, and handing partials across slices a few
+            // microseconds: the 16-row kernel keeps the call unless the slices shorten the loop by 3 us.
+            const double saved_ns = (double)kblocks * (75.0 - 156.0 / (double)S);
+            if (S < 2 || saved_ns < 3000.0) {
+                variant = 16;
+                S = 1;
+            }
+        }
+    }
+    if (S > kblocks) S = kblocks;
+    if (variant == 0) variant = 32;
+    if (variant == 16 && S != 1) return PRISM_ERR_UNSUPPORTED;
+    if (S > kSoftmaxMaxSplits) return PRISM_ERR_UNSUPPORTED;
+    p.block = 512;
+    p.tile_n = kSoftmaxTileN;
+    p.grid_x = (int32_t)n_tiles;
+    p.split_k = (int32_t)S;
+    if (variant == 16) {
+        p.tile_m = kSoftmaxRows;
+        p.grid_y = (int32_t)((M + kSoftmaxRows - 1) / kSoftmaxRows);
+        return PRISM_OK;
+    }
+    if (rb32 > 65535 || (S > 1 && n_tiles * rb32 > kMaxTickets)) return PRISM_ERR_UNSUPPORTED;
+    p.tile_m = kSoftmaxSplitRows;
+    p.grid_y = (int32_t)S;
+    p.grid_z = (int32_t)rb32;
+    if (S > 1) {
+        out->ss_bytes = round_up((uint64_t)n_tiles * rb32 * S * kSoftmaxSplitRows * 2 * 4, 256);
+        p.workspace_bytes = PRISM_WORKSPACE_HEADER_BYTES + out->ss_bytes + (uint64_t)S * M * N * 4;
+    }
     return PRISM_OK;
 }
 
@@ -392,8 +439,26 @@ prism_status_t prism_softmax_matmul(const void* X, const void* W, void* Y, int64
     const prism_status_t st = make_plan(PRISM_OP_SOFTMAX_MATMUL, M, K, N, dtype, &plan);
     if (st != PRISM_OK) return st;
     const SoftmaxCall c{X, W, Y, (int)M, (int)K, (int)N, stream};
-    const hipError_t err = plan.pub.path == PRISM_PATH_ROWS ? launch_softmax_rows_16bit(c, dtype == PRISM_F16)
-                                                            : launch_softmax_simple(c, (int)dtype);
+    hipError_t err;
+    if (plan.pub.path != PRISM_PATH_ROWS) {
+        err = launch_softmax_simple(c, (int)dtype);
+    } else if (plan.pub.tile_m == kSoftmaxRows) {
+        err = launch_softmax_rows_16bit(c, dtype == PRISM_F16);
+    } else {
+        SoftmaxWorkspace ws{nullptr, nullptr, nullptr};
+        if (plan.pub.split_k > 1) {
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+            if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
+            const Workspace w = g_workspace[dev];
+            if (!w.ptr || w.bytes < plan.pub.workspace_bytes) return PRISM_ERR_WORKSPACE;
+            char* base = (char*)w.ptr;
+            ws.tickets = (unsigned*)base;
+            ws.ml_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES);
+            ws.acc_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES + plan.ss_bytes);
+        }
+        err = launch_softmax_split_16bit(c, dtype == PRISM_F16, plan.pub.split_k, ws);
+    }
     return err == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
 }
 

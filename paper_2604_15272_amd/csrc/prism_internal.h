@@ -71,6 +71,17 @@ struct AttentionWorkspace {
 // Geometry of the softmax kernel: rows of X and columns of W per workgroup.
 constexpr int kSoftmaxRows = 16;
 constexpr int kSoftmaxTileN = 128;
+// The K-split softmax kernel: rows per workgroup, most K-slices, and the 32-deep K-blocks of X a wavefront
+// keeps in registers between its two passes.
+constexpr int kSoftmaxSplitRows = 32;
+constexpr int kSoftmaxMaxSplits = 16;
+constexpr int kSoftmaxKeepBlocks = 8;
+
+struct SoftmaxWorkspace {
+    unsigned* tickets;  // [row_blocks][n_tiles], in the workspace header, zero between calls
+    float* ml_part;     // [row_blocks][n_tiles][S][32 rows][2]: slice maximum and sum of exponentials
+    float* acc_part;    // [S][M][N] partial products
+};
 
 // Geometry of the decode (few-row) path.
 constexpr int kDecodeMaxRows = 16;     // one 16-row MFMA block (the 16-row kernel)
@@ -110,6 +121,7 @@ hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, 
 hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, const DecodeWorkspace& ws);
 hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);
 hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16);
+hipError_t launch_softmax_split_16bit(const SoftmaxCall& c, bool f16, int split_k, const SoftmaxWorkspace& ws);
 hipError_t launch_softmax_simple(const SoftmaxCall& c, int dtype);
 hipError_t launch_gqa_16bit(const AttentionCall& c, bool f16, const AttentionPlan& p, const AttentionWorkspace& ws);
 hipError_t launch_gqa_simple(const AttentionCall& c, int dtype);

@@ -281,9 +281,9 @@ def test_f16_decode_splits(P, split, waves):
 
 # ---- softmax -> matmul, the paper's running example (Figure 1) ------------------------------------------
 
-def _softmax_case(P, dtype, M, K, N, seed, path=0, x_std=3.0, expect_path=None):
+def _softmax_case(P, dtype, M, K, N, seed, path=0, x_std=3.0, expect_path=None, split=0, variant=0):
     stored = pi.draw_softmax(dtype, M, K, N, seed, x_std)
-    P.prism_set_override(path, 0, 0)
+    P.prism_set_override(path, split, variant)
     try:
         plan = P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, M, K, N, DTYPE_CODE[dtype])
         if expect_path is not None:
@@ -302,6 +302,57 @@ def _softmax_case(P, dtype, M, K, N, seed, path=0, x_std=3.0, expect_path=None):
                                    (257, 2056, 136), (64, 8200, 128)])
 def test_softmax_matmul_rows_kernel(P, dtype, M, K, N):
     _softmax_case(P, dtype, M, K, N, seed=1000 + M + K, expect_path=P.PRISM_PATH_ROWS)
+
+
+@pytest.mark.parametrize("rows", [16, 32])
+@pytest.mark.parametrize("M,K,N", [(16, 512, 128), (33, 1000, 264), (100, 4096, 128), (40, 20000, 136)])
+def test_softmax_matmul_either_rows_kernel_forced(P, rows, M, K, N):
+    """Table 1, parallelized matmul (row partition): 16 or 32 rows per workgroup, one K-slice."""
+    _softmax_case(P, pi.BF16, M, K, N, seed=1050 + M, path=P.PRISM_PATH_ROWS, split=1, variant=rows,
+                  x_std=4.0 if K > 8192 else 3.0)   # long rows: keep the softmax carried by few entries
+
+
+@pytest.mark.parametrize("dtype", [pi.BF16, pi.F16])
+@pytest.mark.parametrize("split", [2, 3, 7, 16])
+@pytest.mark.parametrize("M,K,N", [(75, 2056, 264), (20, 16384, 128)])
+def test_softmax_matmul_every_split(P, split, M, K, N, dtype):
+    """Table 1, parallelized matmul (reduction): slices carry (maximum, sum, partial product); the result may not
+    depend on their number.  The second shape has slices too long for the registers (X is read again)."""
+    _softmax_case(P, dtype, M, K, N, seed=1060 + M, path=P.PRISM_PATH_ROWS, split=split, variant=32,
+                  x_std=4.0 if K > 8192 else 3.0)
+
+
+def test_softmax_matmul_split_with_rows_of_very_different_maxima(P):
+    """Slices whose maxima differ by hundreds: the rescaling factors underflow to zero, never overflow."""
+    M, K, N = 48, 4096, 128
+    stored = pi.draw_softmax(pi.F32, M, K, N, 1070, 3.0)
+    x = stored["X"].astype(np.float32)
+    x[:, : K // 4] += 300.0          # the first slice (of 4) dominates every row
+    x[::2, -K // 4:] += 600.0        # in every other row, the last one does
+    st = {"X": pi.f32_to_bf16_bits(x), "W": pi.f32_to_bf16_bits(stored["W"].astype(np.float32))}
+    P.prism_set_override(P.PRISM_PATH_ROWS, 4, 32)
+    try:
+        y = run_gpu_softmax(st, pi.BF16)
+    finally:
+        P.prism_set_override(0, 0, 0)
+    assert np.isfinite(y).all()
+    assert_parity(y, run_oracle_softmax(st, pi.BF16), pi.BF16, "maxima 300 and 600 apart")
+
+
+def test_softmax_matmul_split_is_bit_reproducible_and_leaves_tickets_clean(P):
+    import torch
+    from gpu_util import to_device
+    stored = pi.draw_softmax(pi.F16, 512, 4096, 128, 1080)
+    X, W = to_device(stored["X"], pi.F16), to_device(stored["W"], pi.F16)
+    assert P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, 512, 4096, 128, P.PRISM_F16)["split_k"] == 4
+    outs = []
+    for _ in range(30):
+        Y = torch.empty((512, 128), dtype=torch.float16, device="cuda")
+        P.prism_softmax_matmul(X, W, Y)
+        outs.append(Y)
+    torch.cuda.synchronize()
+    for o in outs[1:]:
+        assert torch.equal(o.view(torch.uint16), outs[0].view(torch.uint16))
 
 
 @pytest.mark.parametrize("dtype,M,K,N", [(pi.F32, 8, 256, 512), (pi.F32, 5, 100, 36), (pi.F32, 20, 1000, 513),

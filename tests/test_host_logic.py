@@ -107,8 +107,31 @@ def test_softmax_matmul_arguments_and_plan(P):
     assert sm(X=None) == 1 and sm(W=None) == 1 and sm(Y=None) == 1 and sm(X=a + 4) == 1
     assert sm(M=-1) == 1 and sm(K=0) == 1 and sm(dt=9) == 2 and sm(M=0) == 0 and sm(N=0) == 0
     op = P.PRISM_OP_SOFTMAX_MATMUL
-    p = P.prism_plan(op, 4096, 4096, 128, P.PRISM_F16)
-    assert p["path"] == P.PRISM_PATH_ROWS and p["grid_x"] == 1 and p["grid_y"] == 4096 // p["tile_m"] and p["workspace_bytes"] == 0
+    p = P.prism_plan(op, 4096, 4096, 128, P.PRISM_F16)   # the paper's shape: 256 workgroups of 16 rows, no slices
+    assert (p["path"], p["tile_m"], p["grid_x"], p["grid_y"], p["split_k"], p["workspace_bytes"]) == (P.PRISM_PATH_ROWS, 16, 1, 256, 1, 0)
+    p = P.prism_plan(op, 512, 4096, 128, P.PRISM_F16)    # fewer rows: 16 row blocks x 4 K-slices
+    assert (p["path"], p["tile_m"], p["grid_x"], p["grid_y"], p["grid_z"], p["split_k"]) == (P.PRISM_PATH_ROWS, 32, 1, 4, 16, 4)
+    assert p["workspace_bytes"] == 262144 + 16 * 4 * 32 * 2 * 4 + 4 * 512 * 128 * 4
+    assert p["workspace_bytes"] == P.prism_workspace_bytes(op, 512, 4096, 128, P.PRISM_F16)
+    p = P.prism_plan(op, 16, 256, 4096, P.PRISM_BF16)    # 16 rows, nothing to split: the 16-row kernel
+    assert (p["tile_m"], p["grid_x"], p["grid_y"], p["split_k"], p["workspace_bytes"]) == (16, 32, 1, 1, 0)
+    p = P.prism_plan(op, 16, 32768, 128, P.PRISM_BF16)   # 16 rows, deep K: slices
+    assert (p["tile_m"], p["split_k"]) == (32, 16)
+    p = P.prism_plan(op, 4096, 4096, 4096, P.PRISM_BF16)
+    assert (p["tile_m"], p["split_k"], p["grid_z"], p["workspace_bytes"]) == (32, 1, 128, 0)
+    try:
+        P.prism_set_override(P.PRISM_PATH_ROWS, 0, 16)
+        p = P.prism_plan(op, 4096, 4096, 128, P.PRISM_F16)
+        assert (p["tile_m"], p["grid_y"], p["split_k"], p["workspace_bytes"]) == (16, 256, 1, 0)
+        P.prism_set_override(P.PRISM_PATH_ROWS, 5, 32)
+        assert P.prism_plan(op, 4096, 4096, 128, P.PRISM_F16)["split_k"] == 5
+        for bad in ((P.PRISM_PATH_ROWS, 2, 16), (P.PRISM_PATH_ROWS, 17, 32), (P.PRISM_PATH_ROWS, 0, 64),
+                    (P.PRISM_PATH_SIMPLE, 2, 0)):
+            P.prism_set_override(*bad)
+            with pytest.raises(P.PrismError):
+                P.prism_plan(op, 4096, 4096, 128, P.PRISM_F16)
+    finally:
+        P.prism_set_override(0, 0, 0)
     assert P.prism_plan(op, 8, 256, 512, P.PRISM_F32)["path"] == P.PRISM_PATH_SIMPLE
     assert P.prism_plan(op, 8, 100, 36, P.PRISM_BF16)["path"] == P.PRISM_PATH_SIMPLE
     # the kernel families of the other operators do not apply, and the softmax kernel applies to nothing else
