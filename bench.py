@@ -10,7 +10,7 @@ index 1 (decode RMSNorm -> MatMul, bf16, X[16,4096], W[4096,4096]); the other th
 configurations are timed too and reported under "other_workloads", and the paper's own workloads at its
 shapes and in its precision (fp16, 8 or 16 rows, hidden size 1024 or 4096) under "paper_shapes", its
 running example (softmax, then a matrix product, Figure 1) under "running_example", its two attention
-workloads under "attention".
+workloads under "attention", and 32 / 128 / 512 rows against the decode-sized weights under "mid_rows".
 
 Decode workloads rotate over enough distinct weight buffers (>= 1 GiB in total) that W is streamed
 from HBM and not from the 256 MB last-level cache; the cache-hot single-buffer time is reported
@@ -339,6 +339,28 @@ def measure_attention(h, qk_norm, steps=1000, warmup=50):
 COPY_CALIBRATION_BYTES = 256 << 20
 
 
+def measure_mid_rows(M, K, N, gated, steps=300, warmup=20):
+    """Between decode and prefill: 17 to 512 rows on the decode path's multi-row kernel (W is still what is
+    streamed; buffer sets rotate so that it comes from HBM).  Bound: HBM, algorithmic bytes X + g + W (+W2) + Y."""
+    import torch
+    wl = pi.Workload(f"mid_rows_M{M}_{'gated' if gated else 'plain'}", pi.BF16, M, K, N, gated, 1e-6, 0x5EED3000 + M)
+    wbytes = 2 * K * N * (2 if gated else 1)
+    r = Runner(wl, max(2, -(-(1 << 30) // wbytes)))
+    _, ev_ms = r.timed(steps, warmup)
+    nbytes = counted_bytes(wl)
+    res = {"workload": wl.name, "dtype": "bf16", "M": M, "K": K, "N": N, "gated": gated, "plan": r.plan, "steps": steps,
+           "us_per_call": ev_ms * 1e3, "bound": "hbm", "bytes_per_launch": nbytes,
+           "achieved": nbytes / (ev_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": nbytes / (ev_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "TFLOPs": counted_flops(wl) / (ev_ms * 1e-3) / 1e12}
+    log(f"[bench]   {wl.name} K={K} N={N}: {ev_ms * 1e3:.2f} us/call, {res['achieved']:.0f} GB/s = "
+        f"{100 * res['frac']:.1f}% of hbm peak, {res['TFLOPs']:.0f} TFLOP/s, path {r.plan['path']} "
+        f"tile_m {r.plan['tile_m']} split {r.plan['split_k']} row blocks {r.plan['grid_z']}")
+    del r
+    torch.cuda.empty_cache()
+    return res
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the workload's kernel, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     and recorded in profiles/hbm_traffic.md (one line per workload: `traffic <workload> fetch_bytes=...
@@ -366,6 +388,8 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="time only the headline workload")
     ap.add_argument("--only-attention", action="store_true",
                     help="time only the paper's attention workloads (for profiling that kernel)")
+    ap.add_argument("--only-mid-rows", action="store_true",
+                    help="time only the 17-to-512-row shapes (for profiling the multi-row decode kernel)")
     ap.add_argument("--only-running-example", action="store_true",
                     help="time only the softmax -> matmul running example (for profiling that kernel)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
@@ -394,6 +418,11 @@ def main():
 
     if a.only_running_example:
         print(json.dumps({"running_example": measure_running_example()}), flush=True)
+        return
+    if a.only_mid_rows:
+        print(json.dumps({"mid_rows": [measure_mid_rows(M, K, N, g) for M, K, N, g in
+                                       ((32, 4096, 4096, False), (128, 4096, 4096, False), (512, 4096, 4096, False),
+                                        (32, 4096, 14336, True))]}), flush=True)
         return
     if a.only_attention:
         print(json.dumps({"attention": [measure_attention(h, qk) for h in (1024, 2048) for qk in (False, True)]}),
@@ -443,6 +472,10 @@ def main():
             torch.cuda.empty_cache()
         out["running_example"] = measure_running_example()
         torch.cuda.empty_cache()
+        log("[bench] 17 to 512 rows (the decode path's multi-row kernel)")
+        out["mid_rows"] = [measure_mid_rows(M, K, N, g) for M, K, N, g in
+                           ((32, 4096, 4096, False), (128, 4096, 4096, False), (512, 4096, 4096, False),
+                            (32, 4096, 14336, True))]
         out["attention"] = [measure_attention(h, qk) for h in (1024, 2048) for qk in (False, True)]
         torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
