@@ -185,7 +185,7 @@ prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_
 /*
  * Process-wide override for tests and tuning: force a kernel family and/or a split-K factor and
  * a tile variant (0 = automatic for each).  Variants: PRISM_PATH_DECODE with at most 16 rows: 4, 8 or 16
- * wavefronts per workgroup; with more rows: 32 or 64 rows per workgroup (64: not for gated calls);
+ * wavefronts per workgroup; with more rows: 32 or 64 rows per workgroup;
  * PRISM_PATH_PREFILL: 1000 * tile_m + tile_n.  A forced path that cannot run a shape makes the call
  * return PRISM_ERR_UNSUPPORTED.  The kernels are correct for every admissible value (the paper's
  * notion of a mapping that is correct for all parameter values, Section 2).

@@ -9,6 +9,9 @@
 // walking K in 64-deep steps with the tiled prefill kernel.
 // The reduction across wavefronts (LDS) and across K-slices (workspace, ticket, slice order) is the
 // one of the 16-row kernel, run per row group.
+// Gated calls with 64 rows per workgroup: the accumulators of four row groups and two weight matrices do
+// not fit a wavefront's registers, so the wavefronts split the matrices instead (0-3: W1, 4-7: W2, each
+// half taking the K-blocks round-robin); the halves meet in the LDS reduction.  W1 and W2 are still read once.
 #include "device_utils.h"
 #include "prism_internal.h"
 #include "w_block.h"
@@ -51,6 +54,9 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
                                                          int S, int flags) {
     constexpr int G = GATED ? 2 : 1;
     constexpr int RB = 16 * RG;  // rows per workgroup
+    constexpr bool HALVES = GATED && RG == 4;  // wavefronts 0-3 take W1, 4-7 take W2
+    constexpr bool BOTH = GATED && !HALVES;    // every wavefront takes both matrices
+    constexpr int LNW = HALVES ? NW / 2 : NW;  // wavefronts that share one matrix's K-blocks
 
     extern __shared__ float lds[];
     float* red = lds;                    // [2][NW][16][TN], reused for every (weight matrix, pair of row groups)
@@ -63,6 +69,9 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
     const int n_tiles = gridDim.x;
     const int n0 = ntile * TN, m0 = rblock * RB;
 
+    const int half = HALVES ? __builtin_amdgcn_readfirstlane(wave / LNW) : 0;
+    const int lwave = HALVES ? wave % LNW : wave;
+
     const int kblocks = (K + KB - 1) / KB;
     const int per = kblocks / S, rem = kblocks % S;
     const int b_beg = split * per + min(split, rem);
@@ -73,7 +82,7 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
     const size_t w_total = (size_t)K * N;
     const size_t w_left = (w_first < w_total ? w_total - w_first : 0) * 2;
     const u32 w_bytes = (u32)(w_left < 0x7FFFFFFFull ? w_left : 0x7FFFFFFFull);
-    const __amdgpu_buffer_rsrc_t rw1 = make_rsrc(W1 + w_first, w_bytes);
+    const __amdgpu_buffer_rsrc_t rw1 = make_rsrc(((HALVES && half) ? W2 : W1) + w_first, w_bytes);
     const __amdgpu_buffer_rsrc_t rw2 = make_rsrc((GATED ? W2 : W1) + w_first, w_bytes);
     // X from this row block's first row: offsets inside the block stay small whatever M is.
     const size_t x_left = ((size_t)(M - m0) * K) * 2;
@@ -90,7 +99,7 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
         x_row[r] = (u32)(16 * r + c) * (u32)K * 2u;
     }
 
-    f32x4 acc1[RG][8], acc2[GATED ? RG : 1][8];
+    f32x4 acc1[RG][8], acc2[BOTH ? RG : 1][8];
     float ss[RG];
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
@@ -98,18 +107,18 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             acc1[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if (GATED) acc2[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (BOTH) acc2[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
     }
 
     // U K-blocks per trip: sixteen 16-byte row loads of W in flight per lane where the registers allow it.
     constexpr int U = (!GATED && RG <= 2) ? 2 : 1;
-    for (int i = wave; i < b_cnt; i += U * NW) {
-        WRows w1[U], w2[GATED ? U : 1];
+    for (int i = lwave; i < b_cnt; i += U * LNW) {
+        WRows w1[U], w2[BOTH ? U : 1];
         u32x4 xr[U][RG], gr[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int ib = i + u * NW;
+            const int ib = i + u * LNW;
             const bool has = ib < b_cnt;
             const u32 woff = has ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange;
             const int k = (b_beg + ib) * KB + 8 * q;
@@ -119,7 +128,7 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
                 xr[u][r] = load16(rx, (row_ok[r] && k_ok) ? x_row[r] + (u32)k * 2u : kOutOfRange);
             gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
             load_w_block(w1[u], rw1, woff, row_bytes);
-            if (GATED) load_w_block(w2[u], rw2, woff, row_bytes);
+            if (BOTH) load_w_block(w2[u], rw2, woff, row_bytes);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -131,8 +140,8 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
                 const u32x4 b1 = b_operand<J>(w1[u]);
 #pragma unroll
                 for (int r = 0; r < RG; ++r) acc1[r][J] = F::mfma_16x16x32(a[r], b1, acc1[r][J]);
-                if (GATED) {
-                    const u32x4 b2 = b_operand<J>(w2[GATED ? u : 0]);
+                if (BOTH) {
+                    const u32x4 b2 = b_operand<J>(w2[BOTH ? u : 0]);
 #pragma unroll
                     for (int r = 0; r < RG; ++r) acc2[r][J] = F::mfma_16x16x32(a[r], b2, acc2[r][J]);
                 }
@@ -178,33 +187,38 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
             *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
         }
     };
+    constexpr int GL = BOTH ? 2 : 1;  // passes over the row groups: one per matrix a wavefront holds
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
+    for (int gi = 0; gi < GL; ++gi) {
 #pragma unroll
         for (int r0 = 0; r0 < RG; r0 += 2) {
             if (gi + r0 > 0) __syncthreads();
 #pragma unroll
-            for (int h = 0; h < 2; ++h) put(red + h * kRedFloats, gi == 0 ? acc1[r0 + h] : acc2[GATED ? r0 + h : 0]);
+            for (int h = 0; h < 2; ++h) put(red + h * kRedFloats, gi == 0 ? acc1[r0 + h] : acc2[BOTH ? r0 + h : 0]);
             __syncthreads();  // also orders the ss_red stores before their first reader
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const int r = r0 + h;
-                float v[CPT];
+                float va[CPT], vb[CPT];
 #pragma unroll
-                for (int e = 0; e < CPT; ++e) v[e] = 0.f;
+                for (int e = 0; e < CPT; ++e) { va[e] = 0.f; vb[e] = 0.f; }
                 float sq = 0.f;
 #pragma unroll
                 for (int w = 0; w < NW; ++w) {
                     const float* src = red + h * kRedFloats + (w * 16 + m) * TN + col;
 #pragma unroll
-                    for (int e = 0; e < CPT; ++e) v[e] += src[e];
-                    if (gi == 0) sq += ss_red[w * RB + 16 * r + m];
+                    for (int e = 0; e < CPT; ++e) {
+                        if (HALVES && w >= LNW) vb[e] += src[e];
+                        else va[e] += src[e];
+                    }
+                    if (gi == 0 && w < LNW) sq += ss_red[w * RB + 16 * r + m];  // each half has seen all of X
                 }
                 if (gi == 0) ssum[r] = sq;
 #pragma unroll
                 for (int e = 0; e < CPT; ++e) {
-                    if (gi == 0) v1[r][e] = v[e];
-                    else v2[r][e] = v[e];
+                    if (gi == 0) v1[r][e] = va[e];
+                    else v2[r][e] = va[e];
+                    if (HALVES) v2[r][e] = vb[e];
                 }
             }
         }
@@ -324,6 +338,7 @@ template <typename F>
 static hipError_t launch_rows_fmt(const Call& c, int split_k, int row_groups, const DecodeWorkspace& ws) {
     if (c.gated) {
         if (row_groups == 2) return launch_rows<F, true, 2>(c, split_k, ws);
+        if (row_groups == 4) return launch_rows<F, true, 4>(c, split_k, ws);
     } else {
         if (row_groups == 2) return launch_rows<F, false, 2>(c, split_k, ws);
         if (row_groups == 4) return launch_rows<F, false, 4>(c, split_k, ws);

@@ -71,13 +71,21 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 // kernel is the better choice.  Measured on MI355X (bf16, K x N from 1024 x 1024 to 14336 x 4096, 17 to 512
 // rows): the decode path wins while all its workgroups run at once (one per CU) and W is deep enough that
 // the prefill kernel's 64-deep K-steps over few tiles dominate; 32 rows per workgroup win over 64 while the
-// row blocks' re-reads of W stay within the 256 MiB last-level cache.
+// row blocks' re-reads of W stay within the 256 MiB last-level cache (two row blocks that drift apart by more
+// than an L2's worth of W fetch it twice).
 int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
     const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
     const int64_t z32 = (M + 31) / 32, z64 = (M + 63) / 64;
     if (M > kDecodeRowsMax || (M > 64 && K < 2048)) return 0;
-    if (gated) return (M <= 64 && n_tiles * z32 <= 256) ? 2 : 0;
-    const uint64_t w_bytes = (uint64_t)K * N * 2;
+    const uint64_t w_bytes = (uint64_t)K * N * 2 * (gated ? 2 : 1);
+    if (gated) {
+        // Two weight matrices: the accumulators allow 32 rows per wavefront, or 64 with the matrices split
+        // across the wavefronts; beyond the last-level cache's worth of re-reads the prefill kernel wins.
+        if (M <= 32) return n_tiles <= 256 ? 2 : 0;
+        if (K < 2048) return 0;
+        if (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= 256) return 2;
+        return (z64 * w_bytes <= (256ull << 20) && n_tiles * z64 <= 256) ? 4 : 0;
+    }
     if ((M <= 32 || z32 * w_bytes <= (256ull << 20)) && n_tiles * z32 <= 256) return 2;
     return n_tiles * z64 <= 256 ? 4 : 0;
 }
@@ -240,10 +248,9 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             // Every 16-row group reuses the B operands built from W: 64 rows per workgroup unless the
             // registers (gated: two weight matrices) or the row count say 32.
             row_groups = decode_row_groups(gated, M, K, N);
-            if (row_groups == 0) row_groups = gated ? 2 : 4;  // forced onto a shape the heuristic leaves to prefill
+            if (row_groups == 0) row_groups = 4;  // forced onto a shape the heuristic leaves to prefill
             if (variant == 32 || variant == 64) row_groups = variant / 16;
             else if (variant != 0 && variant != 8) return PRISM_ERR_UNSUPPORTED;
-            if (gated && row_groups != 2) return PRISM_ERR_UNSUPPORTED;
         }
         const int64_t row_blocks = (M + 16 * row_groups - 1) / (16 * row_groups);
         const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;

@@ -110,11 +110,17 @@ def test_decode_rows_chosen_by_the_dispatcher(P, M, K, N):
     _case(P, pi.BF16, M, K, N, False, seed=460 + M, expect_path=P.PRISM_PATH_DECODE)
 
 
-def test_decode_rows_gated_chosen_by_the_dispatcher(P):
-    _case(P, pi.BF16, 40, 4096, 14336, True, seed=465, expect_path=P.PRISM_PATH_DECODE)
+@pytest.mark.parametrize("M", [24, 40, 64])
+def test_decode_rows_gated_chosen_by_the_dispatcher(P, M):
+    _case(P, pi.BF16, M, 4096, 14336, True, seed=465 + M, expect_path=P.PRISM_PATH_DECODE)
 
 
-@pytest.mark.parametrize("gated,rows", [(False, 32), (False, 64), (True, 32)])
+@pytest.mark.parametrize("variant", ["glu", "glu_nogain", "swiglu"])
+def test_decode_rows_paper_variants_with_64_rows(P, variant):
+    _variant_case(P, pi.F16, 50, 1024, 1032, variant, seed=490, path=P.PRISM_PATH_DECODE, split=3, tile=64)
+
+
+@pytest.mark.parametrize("gated,rows", [(False, 32), (False, 64), (True, 32), (True, 64)])
 @pytest.mark.parametrize("split", [1, 2, 3, 7, 16, 33])
 def test_decode_rows_every_split_and_row_count(P, split, rows, gated):
     """Table 1, parallelized matmul (reduction; row partition): neither the split factor nor the rows per
@@ -255,7 +261,7 @@ def test_no_gain_equals_gain_of_ones_bit_for_bit(P):
 
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("M,K,N,path", [(3, 77, 130, 1), (8, 256, 512, 2), (8, 1024, 1024, 2), (16, 4096, 4096, 2),
-                                        (13, 2056, 1160, 2), (33, 200, 264, 2), (300, 712, 648, 3),
+                                        (13, 2056, 1160, 2), (30, 200, 264, 2), (300, 712, 648, 3),
                                         (1024, 1024, 768, 3), (600, 200, 264, 3)])
 def test_f16_shapes(P, M, K, N, path, gated):
     _case(P, pi.F16, M, K, N, gated, seed=900 + M, expect_path=path)
@@ -507,10 +513,16 @@ def test_decode_vocabulary_sized_output_sampled_columns(P):
 
 def test_prefill_long_k_and_many_rows(P):
     """K = 32768 (512 K steps per tile) and M = 20000 (ragged last row tile): sampled rows."""
-    for (M, K, N), seed in (((300, 32768, 256), 1510), ((20000, 512, 384), 1511)):
+    for (M, K, N), seed, path in (((300, 32768, 256), 1510, P.PRISM_PATH_PREFILL), ((20000, 512, 384), 1511, 0),
+                                  ((300, 32768, 256), 1510, 0)):   # the last: as dispatched (multi-row decode kernel)
         stored = pi.draw(pi.BF16, M, K, N, True, seed)
-        assert P.prism_plan(1, M, K, N, P.PRISM_BF16)["path"] == P.PRISM_PATH_PREFILL
-        y = run_gpu(stored, pi.BF16, True, 1e-6)
+        P.prism_set_override(path, 0, 0)
+        try:
+            plan = P.prism_plan(1, M, K, N, P.PRISM_BF16)
+            assert plan["path"] == (P.PRISM_PATH_DECODE if (path == 0 and M == 300) else P.PRISM_PATH_PREFILL), plan
+            y = run_gpu(stored, pi.BF16, True, 1e-6)
+        finally:
+            P.prism_set_override(0, 0, 0)
         assert np.isfinite(y).all()
         rows = np.unique(np.concatenate([[0, M - 1, min(255, M - 1), min(256, M - 1)],
                                          np.random.Generator(np.random.Philox(seed)).choice(M, 60, replace=False)]))

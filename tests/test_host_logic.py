@@ -196,8 +196,10 @@ def test_decode_plan_for_more_than_sixteen_rows(P):
     assert P.prism_plan(0, 512, 4096, 4096, bf16)["path"] == P.PRISM_PATH_DECODE
     assert P.prism_plan(0, 512, 4096, 6144, bf16)["path"] == P.PRISM_PATH_PREFILL   # 384 workgroups: not at once
     assert P.prism_plan(0, 100, 1024, 1024, bf16)["path"] == P.PRISM_PATH_PREFILL   # shallow K
-    g = P.prism_plan(1, 64, 4096, 14336, bf16)
-    assert (g["path"], g["tile_m"], g["grid_z"]) == (P.PRISM_PATH_DECODE, 32, 2)
+    g = P.prism_plan(1, 64, 4096, 14336, bf16)    # gated, 33 to 64 rows: one row block, matrices split across wavefronts
+    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 64, 1, 2)
+    g = P.prism_plan(1, 32, 4096, 14336, bf16)
+    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 32, 1, 2)
     assert P.prism_plan(1, 100, 4096, 14336, bf16)["path"] == P.PRISM_PATH_PREFILL
     # the variant picks the rows per workgroup; wavefront counts belong to the 16-row kernel
     try:
@@ -207,10 +209,9 @@ def test_decode_plan_for_more_than_sixteen_rows(P):
         with pytest.raises(P.PrismError):
             P.prism_plan(0, 16, 4096, 4096, bf16)
         P.prism_set_override(P.PRISM_PATH_DECODE, 0, 0)
+        assert P.prism_plan(1, 100, 4096, 14336, bf16)["grid_z"] == 2
+        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 32)
         assert P.prism_plan(1, 100, 4096, 14336, bf16)["grid_z"] == 4
-        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 64)
-        with pytest.raises(P.PrismError):
-            P.prism_plan(1, 100, 4096, 14336, bf16)
         P.prism_set_override(P.PRISM_PATH_DECODE, 0, 4)
         with pytest.raises(P.PrismError):
             P.prism_plan(0, 100, 4096, 4096, bf16)
@@ -289,7 +290,7 @@ def test_tuner_enumerates_admissible_assignments(P):
     mid = [x for x in tune.candidates(0, 100, 2048, 1024, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
     assert {x["plan"]["tile_m"] for x in mid} == {32, 64} and all(x["plan"]["block"] == 512 for x in mid)
     gmid = [x for x in tune.candidates(1, 100, 2048, 1024, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
-    assert {x["plan"]["tile_m"] for x in gmid} == {32}
+    assert {x["plan"]["tile_m"] for x in gmid} == {32, 64}
     # many rows: no decode candidates; fp32: the plain kernel only
     assert all(x["path"] != P.PRISM_PATH_DECODE for x in tune.candidates(1, 2048, 1024, 1024, P.PRISM_BF16))
     assert [x["path"] for x in tune.candidates(0, 8, 256, 512, P.PRISM_F32)] == [P.PRISM_PATH_SIMPLE]
