@@ -264,7 +264,15 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             const int64_t wgs = n_tiles * row_blocks;
             // The multi-row kernel fits one workgroup per CU: never more workgroups than CUs if that can be helped.
             S = (row_groups > 1) ? target / wgs : (target + wgs / 2) / wgs;
-            const int64_t s_max = kblocks / waves;
+            int64_t s_max = kblocks / waves;
+            if (row_groups == 1) {
+                // Measured over shapes from 2 to 235 MB of weights: the exchange between slices costs about
+                // 3.5 us, so a tile column of at most 256 KiB is not split at all, a slice keeps at least
+                // 128 KiB, and there are never more than eight (the last arrival reads eight slices'
+                // partials in one round trip).
+                const int64_t column_kib = K * (gated ? 2 : 1) * kDecodeTileN * 2 / 1024;
+                s_max = std::min<int64_t>(s_max, column_kib <= 256 ? 1 : std::min<int64_t>(8, column_kib / 128));
+            }
             if (S > s_max) S = s_max;
             if (S < 1) S = 1;
         }

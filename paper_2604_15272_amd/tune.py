@@ -17,6 +17,7 @@ import random
 from . import binding as B
 
 _DECODE_VARIANTS = (4, 8, 16, 32, 64)   # wavefronts (at most 16 rows) or rows per workgroup (more)
+_SOFTMAX_MAX_SPLIT = 16
 _DECODE_MAX_ROWS = 512                  # the decode path re-reads W per row block: not worth timing beyond
 _PLAIN_TILES = (256256, 256192, 128128, 64064)
 _GATED_TILES = (256256, 128256, 128128)
@@ -26,10 +27,14 @@ _TORCH_DTYPE = {B.PRISM_F32: "float32", B.PRISM_BF16: "bfloat16", B.PRISM_F16: "
 def candidates(op, M, K, N, dtype, max_split=64):
     """Every admissible (path, split_k, variant) for this call, as the library's planner sees it."""
     out = []
+    softmax = op == B.PRISM_OP_SOFTMAX_MATMUL
     try:
-        for path in (B.PRISM_PATH_SIMPLE, B.PRISM_PATH_DECODE, B.PRISM_PATH_PREFILL):
+        for path in ((B.PRISM_PATH_SIMPLE, B.PRISM_PATH_ROWS) if softmax else
+                     (B.PRISM_PATH_SIMPLE, B.PRISM_PATH_DECODE, B.PRISM_PATH_PREFILL)):
             if path == B.PRISM_PATH_SIMPLE:
                 grid = [(0, 0)]
+            elif path == B.PRISM_PATH_ROWS:   # softmax: 16 rows per workgroup, or 32 rows and K-slices
+                grid = [(1, 16)] + [(s, 32) for s in range(1, min(max_split, _SOFTMAX_MAX_SPLIT) + 1)]
             elif path == B.PRISM_PATH_DECODE:
                 if M > _DECODE_MAX_ROWS:
                     continue
@@ -48,7 +53,8 @@ def candidates(op, M, K, N, dtype, max_split=64):
                 if plan["path"] != path or key in seen:
                     continue
                 seen.add(key)
-                out.append({"path": path, "split_k": plan["split_k"] if path == B.PRISM_PATH_DECODE else 0,
+                out.append({"path": path,
+                            "split_k": plan["split_k"] if path in (B.PRISM_PATH_DECODE, B.PRISM_PATH_ROWS) else 0,
                             "variant": variant, "plan": plan})
     finally:
         B.prism_set_override(0, 0, 0)
@@ -83,23 +89,29 @@ def tune(op, M, K, N, dtype=B.PRISM_BF16, samples=12, seed=0, steps=None, instal
     import ctypes
     import torch
     gated = op == B.PRISM_OP_RMSNORM_GATED_MLP
+    softmax = op == B.PRISM_OP_SOFTMAX_MATMUL
     tdt = getattr(torch, _TORCH_DTYPE[dtype])
     esize = 4 if dtype == B.PRISM_F32 else 2
     nw = 2 if gated else 1
     wbytes = esize * K * N * nw
     sets = max(1, min(64, weight_bytes_total // max(wbytes, 1)))
     gen = torch.Generator(device="cuda").manual_seed(1234 + seed)
-    X = torch.randn((M, K), generator=gen, device="cuda").to(tdt)
+    X = (torch.randn((M, K), generator=gen, device="cuda") * (3.0 if softmax else 1.0)).to(tdt)
     g = (torch.rand((K,), generator=gen, device="cuda") + 0.5).to(tdt)
     Ws = [[(torch.randn((K, N), generator=gen, device="cuda") / K ** 0.5).to(tdt) for _ in range(nw)]
           for _ in range(sets)]
     Y = torch.empty((M, N), dtype=tdt, device="cuda")
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     vp, i64 = ctypes.c_void_p, ctypes.c_int64
-    tail = (vp(Y.data_ptr()), i64(M), i64(K), i64(N), ctypes.c_float(1e-6), ctypes.c_int32(dtype), stream)
-    fn = B.lib.prism_rmsnorm_gated_mlp if gated else B.lib.prism_rmsnorm_matmul
-    args_sets = [(vp(X.data_ptr()), vp(g.data_ptr()), *[vp(w.data_ptr()) for w in Ws[s]]) + tail
-                 for s in range(sets)]
+    if softmax:
+        tail = (vp(Y.data_ptr()), i64(M), i64(K), i64(N), ctypes.c_int32(dtype), stream)
+        fn = B.lib.prism_softmax_matmul
+        args_sets = [(vp(X.data_ptr()), vp(Ws[s][0].data_ptr())) + tail for s in range(sets)]
+    else:
+        tail = (vp(Y.data_ptr()), i64(M), i64(K), i64(N), ctypes.c_float(1e-6), ctypes.c_int32(dtype), stream)
+        fn = B.lib.prism_rmsnorm_gated_mlp if gated else B.lib.prism_rmsnorm_matmul
+        args_sets = [(vp(X.data_ptr()), vp(g.data_ptr()), *[vp(w.data_ptr()) for w in Ws[s]]) + tail
+                     for s in range(sets)]
 
     B.prism_set_override(0, 0, 0)
     saved_entry_plan = B.prism_plan(op, M, K, N, dtype)  # what the library does today (table or heuristic)
@@ -159,14 +171,15 @@ def load_table(path):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
-    ap.add_argument("--op", choices=("plain", "gated"), default="plain")
+    ap.add_argument("--op", choices=("plain", "gated", "softmax"), default="plain")
     ap.add_argument("--shape", type=int, nargs=3, metavar=("M", "K", "N"), required=True)
     ap.add_argument("--dtype", choices=("f32", "bf16", "f16"), default="bf16")
     ap.add_argument("--samples", type=int, default=12)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--save", help="write the winner to this JSON file")
     a = ap.parse_args()
-    op = B.PRISM_OP_RMSNORM_GATED_MLP if a.op == "gated" else B.PRISM_OP_RMSNORM_MATMUL
+    op = {"plain": B.PRISM_OP_RMSNORM_MATMUL, "gated": B.PRISM_OP_RMSNORM_GATED_MLP,
+          "softmax": B.PRISM_OP_SOFTMAX_MATMUL}[a.op]
     dt = {"f32": B.PRISM_F32, "bf16": B.PRISM_BF16, "f16": B.PRISM_F16}[a.dtype]
     r = tune(op, *a.shape, dtype=dt, samples=a.samples, seed=a.seed, verbose=True)
     d = r["default"]

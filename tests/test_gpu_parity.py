@@ -493,6 +493,21 @@ def test_tuner_installs_a_plan_that_is_correct_and_not_slower(P):
         P.prism_plan_table_clear()
 
 
+def test_tuner_on_the_softmax_operator(P):
+    from paper_2604_15272_amd import tune
+    op, M, K, N = P.PRISM_OP_SOFTMAX_MATMUL, 48, 8192, 128
+    P.prism_plan_table_clear()
+    try:
+        r = tune.tune(op, M, K, N, dtype=P.PRISM_F16, samples=6, seed=5)
+        print("tuned:", r["best"], "default:", r["default"], flush=True)
+        assert r["default"] is not None and r["best"]["us"] <= r["default"]["us"]
+        assert P.prism_plan(op, M, K, N, P.PRISM_F16) == r["best"]["plan"]
+        stored = pi.draw_softmax(pi.F16, M, K, N, 951)
+        assert_parity(run_gpu_softmax(stored, pi.F16), run_oracle_softmax(stored, pi.F16), pi.F16, "tuned softmax plan")
+    finally:
+        P.prism_plan_table_clear()
+
+
 # ---- large shapes: the oracle recomputes a sample of the outputs ------------------------------------------
 
 def test_decode_vocabulary_sized_output_sampled_columns(P):

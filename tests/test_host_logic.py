@@ -291,6 +291,11 @@ def test_tuner_enumerates_admissible_assignments(P):
     assert {x["plan"]["tile_m"] for x in mid} == {32, 64} and all(x["plan"]["block"] == 512 for x in mid)
     gmid = [x for x in tune.candidates(1, 100, 2048, 1024, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
     assert {x["plan"]["tile_m"] for x in gmid} == {32, 64}
+    # the softmax operator: the plain kernel, 16 rows per workgroup, 32 rows with 1..16 K-slices
+    sm = tune.candidates(P.PRISM_OP_SOFTMAX_MATMUL, 64, 16384, 128, P.PRISM_F16)
+    assert {x["path"] for x in sm} == {P.PRISM_PATH_SIMPLE, P.PRISM_PATH_ROWS}
+    assert sorted((x["plan"]["tile_m"], x["plan"]["split_k"]) for x in sm if x["path"] == P.PRISM_PATH_ROWS) == \
+        [(16, 1)] + [(32, s) for s in range(1, 17)]
     # many rows: no decode candidates; fp32: the plain kernel only
     assert all(x["path"] != P.PRISM_PATH_DECODE for x in tune.candidates(1, 2048, 1024, 1024, P.PRISM_BF16))
     assert [x["path"] for x in tune.candidates(0, 8, 256, 512, P.PRISM_F32)] == [P.PRISM_PATH_SIMPLE]
