@@ -162,16 +162,20 @@ prism_status_t make_softmax_plan(int64_t M, int64_t K, int64_t N, prism_dtype_t 
         // All workgroups at once (the split kernel fits one per CU) and at least four K-blocks per wavefront.
         S = std::min<int64_t>(256 / std::max<int64_t>(1, n_tiles * rb32), kblocks / 32);
         S = std::max<int64_t>(1, std::min<int64_t>(S, kSoftmaxMaxSplits));
-        if (variant == 0 && n_tiles * rb16 <= 256) {
-            // Both kernels run in one round.  Measured on MI355X: a wavefront's K-block costs about 75 ns of the
+        if (variant == 0 && rb16 == 1) {
+            // At most 16 rows: every workgroup streams its own columns of W, as in the decode kernel, and the
+            // same split rule applies (no split for a tile column up to 256 KiB, slices of at least 128 KiB).
+            const int64_t column_kib = K * kSoftmaxTileN * 2 / 1024;
+            S = column_kib <= 256 ? 1 : std::min<int64_t>(S, std::max<int64_t>(1, column_kib / 128));
+        } else if (variant == 0 && n_tiles * rb16 <= 256) {
+            // Both kernels run in one round.  Measured on MI355X: a wavefront's K-block costs about 57 ns of the
             // call with 16 rows per workgroup and 156 ns with 32, and handing partials across slices a few
             // microseconds: the 16-row kernel keeps the call unless the slices shorten the loop by 3 us.
-            const double saved_ns = (double)kblocks * (75.0 - 156.0 / (double)S);
-            if (S < 2 || saved_ns < 3000.0) {
-                variant = 16;
-                S = 1;
-            }
+            const double saved_ns = (double)kblocks * (57.0 - 156.0 / (double)S);
+            if (saved_ns < 3000.0) S = 1;
         }
+        // Without slices the 16-row kernel is the faster one (measured, also over several rounds of workgroups).
+        if (variant == 0 && S < 2) variant = 16;
     }
     if (S > kblocks) S = kblocks;
     if (variant == 0) variant = 32;

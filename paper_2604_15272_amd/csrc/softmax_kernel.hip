@@ -3,18 +3,19 @@
 // sum of exp(X) and the product exp(X) . W, and divides after the loop; softmax(X) is never written
 // to memory.  Both kernels here have that structure.  What the figure leaves out and a library
 // needs is the row maximum: exp(x - max) instead of exp(x), which changes nothing in exact
-// arithmetic and keeps every term in (0, 1].  A workgroup owns its rows over the whole of K, so the
-// maximum is a first pass over the same rows (the second pass finds them in the caches).
+// arithmetic and keeps every term in (0, 1].  The matrix-core kernel keeps a running maximum per wavefront
+// and rescales its accumulators when it moves (so X is read once, streaming under the arithmetic); the plain
+// kernel finds the maximum in a first pass over the same rows.
 //
 // Matrix-core kernel (16-bit storage): a workgroup owns 16 rows (one MFMA row group) and 128 columns
 // of W; its wavefronts take the 32-deep K-blocks round-robin.  X is K-contiguous, which is the
 // layout of an MFMA A operand, so a lane loads its 8 K values of a row straight from memory,
 // applies exp and rounds to the storage format; the row sums are a ninth MFMA against ones, so
 // numerator and denominator weigh the same rounded values.  W is handled as in the decode kernel (8 x 8 sub-blocks per lane,
-// permuted into B operands).  The partial products and sums of the wavefronts meet in LDS.
+// permuted into B operands).  The partial products, sums and maxima of the wavefronts meet in LDS.
 // X is the large operand here and the roofline is streaming it from HBM once; what the kernel is
-// actually bound by at the paper's shape is W, which every workgroup re-reads from the L2 for its
-// 16 rows (1 MiB per workgroup), and the exponentials on the vector pipe.
+// actually bound by at the paper's shape is the vector pipe (exponentials, conversions, the permutes
+// of W, which every workgroup re-reads from the L2 for its 16 rows).
 //
 // Plain kernel: any shape and storage type, 8 rows x 256 columns per workgroup, fp32 arithmetic.
 #include <type_traits>
@@ -29,7 +30,6 @@ namespace {
 
 constexpr int TN = 128;  // columns of W per workgroup (matrix-core kernel)
 constexpr int KB = 32;   // K depth of one MFMA
-constexpr int RG = 1;    // 16-row groups per workgroup (2 halves the W traffic but fills only 128 CUs at 4096 rows: slower)
 
 template <typename T> __device__ __forceinline__ float ld_elem(const T* p, size_t i);
 template <> __device__ __forceinline__ float ld_elem<float>(const float* p, size_t i) { return p[i]; }
@@ -47,6 +47,10 @@ template <> __device__ __forceinline__ void st_elem<_Float16>(_Float16* p, size_
 }  // namespace
 
 // ---- matrix-core kernel --------------------------------------------------------------------------
+// A wavefront walks its K-blocks in chunks of CH.  Per chunk: the chunk's row maxima (from the registers
+// the loads landed in), the running maximum, a rescale of the accumulators by 2^((old - new) log2 e) if
+// it moved, then exp, row sums and products of the chunk's K-blocks.  The next chunk's X is requested
+// before the current one is worked on, so the stream from HBM runs under the arithmetic.
 template <typename F, int NW>
 __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* __restrict__ X,
                                                                const uint16_t* __restrict__ W,
@@ -56,19 +60,20 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
     constexpr int TPR = TN / CPT;      // threads per output row
     static_assert(CPT == 2 || CPT == 4 || CPT == 8, "epilogue mapping");
     constexpr float kLog2e = 1.4426950408889634f;
+    constexpr int CH = 4;  // K-blocks per wavefront and chunk (even: the W register sets alternate per block)
 
     extern __shared__ float lds[];
-    float* red = lds;                       // [NW][16][TN], used once per row group
-    float* wave_max = lds + NW * 16 * TN;   // [NW][32]
-    float* wave_sum = wave_max + NW * 32;   // [NW][32]
+    float* red = lds;                       // [NW][16][TN]
+    float* wave_max = lds + NW * 16 * TN;   // [NW][16]
+    float* wave_sum = wave_max + NW * 16;   // [NW][16]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = lane >> 4, c = lane & 15;
-    const int n0 = blockIdx.x * TN, m0 = blockIdx.y * (16 * RG);
+    const int n0 = blockIdx.x * TN, m0 = blockIdx.y * 16;
     const int kblocks = (K + KB - 1) / KB;
 
-    // Descriptors: X from this workgroup's first row to the end of the matrix (rows past M read as
-    // zero and are masked anyway), W from its first column to the end.
+    // Descriptors: X from this workgroup's first row to the end of the matrix (rows past M are masked),
+    // W from its first column to the end.
     const size_t x_left = ((size_t)(M - m0) * K) * 2;
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(X + (size_t)m0 * K, (u32)(x_left < 0x7FFFFFFFull ? x_left : 0x7FFFFFFFull));
     const size_t w_left = ((size_t)K * N - n0) * 2;
@@ -76,189 +81,152 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
     const u32 row_bytes = (u32)N * 2u;
     const bool col_ok = (n0 + 8 * c) < N;
     const u32 w_lane = col_ok ? ((u32)(8 * q) * row_bytes + (u32)(16 * c)) : kOutOfRange;
-    bool row_ok[RG];
-    u32 x_row[RG];
-#pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        row_ok[r] = (m0 + 16 * r + c) < M;
-        x_row[r] = (u32)(16 * r + c) * (u32)K * 2u;
-    }
+    const bool row_ok = (m0 + c) < M;
+    const u32 x_row = (u32)c * (u32)K * 2u;
+    auto k_valid = [&](int ib) { return ib < kblocks && ib * KB + 8 * q < K; };
 
-    // ---- pass 1: row maxima.  Sixteen K-blocks of loads (32 per lane, all of a 4096-deep row share)
-    // are issued before the first is looked at: this pass is the one that pulls X from HBM.
-    float mx[RG];
+    f32x4 acc[8], sum_acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < RG; ++r) mx[r] = -__builtin_inff();
-    constexpr int U = 16;
-    for (int i = wave; i < kblocks; i += U * NW) {
-        u32x4 xr[U][RG];
-        bool ok[U];
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -__builtin_inff();  // running maximum of row c over this wavefront's K-blocks so far
+
+    auto load_chunk = [&](u32x4 (&xs)[CH], int i0) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int k = (i + u * NW) * KB + 8 * q;
-            ok[u] = (i + u * NW) < kblocks && k < K;
-#pragma unroll
-            for (int r = 0; r < RG; ++r)
-                xr[u][r] = load16(rx, (ok[u] && row_ok[r]) ? x_row[r] + (u32)k * 2u : kOutOfRange);
+        for (int u = 0; u < CH; ++u) {
+            const int ib = i0 + u * NW;
+            xs[u] = load16(rx, (k_valid(ib) && row_ok) ? x_row + (u32)(ib * KB + 8 * q) * 2u : kOutOfRange);
         }
+    };
+    auto load_w = [&](WRows& w, int ib) {
+        load_w_block(w, rw, (ib < kblocks) ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange, row_bytes);
+    };
+    WRows w[2];
+    auto chunk = [&](const u32x4 (&xs)[CH], int i0) {
+        float cm = -__builtin_inff();
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < CH; ++u) {
+            float v = F::lo(xs[u][0]);
 #pragma unroll
-            for (int r = 0; r < RG; ++r) {
-                float v = F::lo(xr[u][r][0]);
+            for (int d = 0; d < 4; ++d) v = fmaxf(v, fmaxf(F::lo(xs[u][d]), F::hi(xs[u][d])));
+            cm = fmaxf(cm, (k_valid(i0 + u * NW) && row_ok) ? v : -__builtin_inff());
+        }
+        cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
+        cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
+        const float m_new = fmaxf(m_run, cm);
+        if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+            // Accumulator element i of lane (q, c) belongs to row 4q + i; its factor lives in the lanes of row
+            // 4q + i.  Rows that have seen nothing yet keep the factor 1 (their accumulators are zero).
+            const float f = (m_run == -__builtin_inff()) ? 1.0f : __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e);
 #pragma unroll
-                for (int d = 0; d < 4; ++d) v = fmaxf(v, fmaxf(F::lo(xr[u][r][d]), F::hi(xr[u][r][d])));
-                mx[r] = fmaxf(mx[r], (ok[u] && row_ok[r]) ? v : -__builtin_inff());
+            for (int i = 0; i < 4; ++i) {
+                const float fi = __shfl(f, 4 * q + i, 64);
+                sum_acc[i] *= fi;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[j][i] *= fi;
             }
-    }
+            m_run = m_new;
+        }
+        const float shift = row_ok ? -m_run * kLog2e : 0.f;  // a row past M has no maximum: keep the arithmetic finite
 #pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 16, 64));
-        mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 32, 64));
-        if (q == 0) wave_max[wave * 32 + 16 * r + c] = mx[r];
-    }
-    __syncthreads();
-    float shift[RG];  // -max * log2(e), so that exp(x - max) = exp2(x * log2(e) + shift)
-#pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        float m = -__builtin_inff();
-#pragma unroll
-        for (int w = 0; w < NW; ++w) m = fmaxf(m, wave_max[w * 32 + 16 * r + c]);
-        shift[r] = row_ok[r] ? -m * kLog2e : 0.f;  // a row past M has no maximum: keep the arithmetic finite
-    }
-
-    // ---- pass 2: exp, row sums and the product
-    f32x4 acc[RG][8], sum_acc[RG];
-#pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        sum_acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-    // Two register sets alternate: the loads of the next K-block (X from the caches now, W from the L2)
-    // are issued before the arithmetic of the current one.
-    struct Trip {
-        WRows w;
-        u32x4 xr[RG];
-        int i;
-    };
-    auto issue = [&](Trip& t, int i) {
-        t.i = i;
-        const int k = i * KB + 8 * q;
-        const bool k_ok = i < kblocks && k < K;  // past the end: out-of-range offsets, zeros, no memory traffic
-#pragma unroll
-        for (int r = 0; r < RG; ++r) t.xr[r] = load16(rx, (k_ok && row_ok[r]) ? x_row[r] + (u32)k * 2u : kOutOfRange);
-        load_w_block(t.w, rw, (i < kblocks) ? w_lane + (u32)i * KB * row_bytes : kOutOfRange, row_bytes);
-    };
-    auto consume = [&](const Trip& t) {
-        const bool k_ok = t.i * KB + 8 * q < K;
-        u32x4 a[RG];
-#pragma unroll
-        for (int r = 0; r < RG; ++r) {
-            const bool v = k_ok && row_ok[r];
+        for (int u = 0; u < CH; ++u) {
+            const int ib = i0 + u * NW;
+            if (ib >= kblocks) break;                  // uniform over the wavefront
+            load_w(w[(u + 1) & 1], ib + NW);           // the next block's W, into the other register set
+            const bool v = k_valid(ib) && row_ok;
+            u32x4 a;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                const float e0 = __builtin_amdgcn_exp2f(fmaf(F::lo(t.xr[r][d]), kLog2e, shift[r]));
-                const float e1 = __builtin_amdgcn_exp2f(fmaf(F::hi(t.xr[r][d]), kLog2e, shift[r]));
-                a[r][d] = v ? F::pack(e0, e1) : 0u;
+                const float e0 = __builtin_amdgcn_exp2f(fmaf(F::lo(xs[u][d]), kLog2e, shift));
+                const float e1 = __builtin_amdgcn_exp2f(fmaf(F::hi(xs[u][d]), kLog2e, shift));
+                a[d] = v ? F::pack(e0, e1) : 0u;
             }
+            const WRows& wb = w[u & 1];
+            acc[0] = F::mfma_16x16x32(a, b_operand<0>(wb), acc[0]);
+            acc[1] = F::mfma_16x16x32(a, b_operand<1>(wb), acc[1]);
+            acc[2] = F::mfma_16x16x32(a, b_operand<2>(wb), acc[2]);
+            acc[3] = F::mfma_16x16x32(a, b_operand<3>(wb), acc[3]);
+            acc[4] = F::mfma_16x16x32(a, b_operand<4>(wb), acc[4]);
+            acc[5] = F::mfma_16x16x32(a, b_operand<5>(wb), acc[5]);
+            acc[6] = F::mfma_16x16x32(a, b_operand<6>(wb), acc[6]);
+            acc[7] = F::mfma_16x16x32(a, b_operand<7>(wb), acc[7]);
+            // The row sums ride on the matrix cores too: a ninth product against a block of ones adds up
+            // exactly the rounded values the other eight use (every column of the result is the row sum).
+            sum_acc = F::mfma_16x16x32(a, ones8<F>(), sum_acc);
         }
-        // One set of B operands serves both row groups.
-        auto step = [&](auto jc) {
-            constexpr int J = decltype(jc)::value;
-            const u32x4 b = b_operand<J>(t.w);
-#pragma unroll
-            for (int r = 0; r < RG; ++r) acc[r][J] = F::mfma_16x16x32(a[r], b, acc[r][J]);
-        };
-        step(std::integral_constant<int, 0>{});
-        step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 3>{});
-        step(std::integral_constant<int, 4>{});
-        step(std::integral_constant<int, 5>{});
-        step(std::integral_constant<int, 6>{});
-        step(std::integral_constant<int, 7>{});
-        // The row sums ride on the matrix cores too: a ninth product against a block of ones adds up
-        // exactly the rounded values the other eight use (every column of the result is the row sum).
-        // The vector pipe, which the exponentials keep busy, is spared two instructions per element.
-#pragma unroll
-        for (int r = 0; r < RG; ++r) sum_acc[r] = F::mfma_16x16x32(a[r], ones8<F>(), sum_acc[r]);
     };
     {
-        Trip ta, tb;
-        int i = wave;
-        if (i < kblocks) {
-            issue(ta, i);
-            for (;;) {
-                issue(tb, i + NW);
-                consume(ta);
-                i += NW;
-                if (i >= kblocks) break;
-                issue(ta, i + NW);
-                consume(tb);
-                i += NW;
-                if (i >= kblocks) break;
-            }
+        u32x4 xa[CH], xb[CH];
+        load_chunk(xa, wave);
+        load_w(w[0], wave);
+        for (int i0 = wave; i0 < kblocks;) {
+            load_chunk(xb, i0 + CH * NW);
+            chunk(xa, i0);
+            i0 += CH * NW;
+            if (i0 >= kblocks) break;
+            load_chunk(xa, i0 + CH * NW);
+            chunk(xb, i0);
+            i0 += CH * NW;
         }
     }
     // Element i of the sum block in lane (q, c) is row 4q + i (any column c: they are all equal).
+    if (c == 0) {
 #pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        if (c == 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) wave_sum[wave * 32 + 16 * r + 4 * q + i] = sum_acc[r][i];
-        }
+        for (int i = 0; i < 4; ++i) wave_sum[wave * 16 + 4 * q + i] = sum_acc[i];
     }
+    if (q == 0) wave_max[wave * 16 + c] = m_run;
 
-    // ---- across wavefronts through LDS, one row group at a time, then the division (Figure 1(b): Div
-    // after the loop).  Accumulator j, element i of lane (q, c) is row 4q + i, column 8c + j.
+    // ---- across wavefronts through LDS: every wavefront's partials are relative to its own maximum, so they
+    // are rescaled to the common one; then the division (Figure 1(b): Div after the loop).
+    // Accumulator j, element i of lane (q, c) is row 4q + i, column 8c + j.
     const int m = tid / TPR;
     const int col = (tid % TPR) * CPT;
     const int n = n0 + col;
 #pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        if (r > 0) __syncthreads();
+    for (int i = 0; i < 4; ++i) {
+        // As in the decode kernel: the upper eight column groups write their second half first, so
+        // that one store instruction covers 16 different 16-byte bank groups.
+        float* dst = red + (wave * 16 + (4 * q + i)) * TN + 8 * c;
+        const f32x4 lo = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+        const f32x4 hi = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+        const bool upper = (c & 8) != 0;
+        *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
+        *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
+    }
+    __syncthreads();
+    float gmax = -__builtin_inff();
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // As in the decode kernel: the upper eight column groups write their second half first, so
-            // that one store instruction covers 16 different 16-byte bank groups.
-            float* dst = red + (wave * 16 + (4 * q + i)) * TN + 8 * c;
-            const f32x4 lo = f32x4{acc[r][0][i], acc[r][1][i], acc[r][2][i], acc[r][3][i]};
-            const f32x4 hi = f32x4{acc[r][4][i], acc[r][5][i], acc[r][6][i], acc[r][7][i]};
-            const bool upper = (c & 8) != 0;
-            *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
-            *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
-        }
-        __syncthreads();
-        float v[CPT], den = 0.f;
+    for (int w8 = 0; w8 < NW; ++w8) gmax = fmaxf(gmax, wave_max[w8 * 16 + m]);
+    float v[CPT], den = 0.f;
 #pragma unroll
-        for (int e = 0; e < CPT; ++e) v[e] = 0.f;
+    for (int e = 0; e < CPT; ++e) v[e] = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float* src = red + (w * 16 + m) * TN + col;
+    for (int w8 = 0; w8 < NW; ++w8) {
+        const float mw = wave_max[w8 * 16 + m];
+        // a wavefront without K-blocks (or a row past M) has maximum -inf and zero partials
+        const float f = (mw == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((mw - gmax) * kLog2e);
+        const float* src = red + (w8 * 16 + m) * TN + col;
 #pragma unroll
-            for (int e = 0; e < CPT; ++e) v[e] += src[e];
-            den += wave_sum[w * 32 + 16 * r + m];
-        }
-        const int row = m0 + 16 * r + m;
-        if (row < M && n < N) {  // N % 8 == 0 and CPT | 8: all CPT columns valid together
-            const float inv = 1.0f / den;
-            u32 packed[CPT / 2];
+        for (int e = 0; e < CPT; ++e) v[e] = fmaf(f, src[e], v[e]);
+        den = fmaf(f, wave_sum[w8 * 16 + m], den);
+    }
+    const int row = m0 + m;
+    if (row < M && n < N) {  // N % 8 == 0 and CPT | 8: all CPT columns valid together
+        const float inv = 1.0f / den;
+        u32 packed[CPT / 2];
 #pragma unroll
-            for (int e = 0; e < CPT / 2; ++e) packed[e] = F::pack(v[2 * e] * inv, v[2 * e + 1] * inv);
-            uint16_t* out = Y + (size_t)row * N + n;
-            if (CPT == 2) *(u32*)out = packed[0];
-            if (CPT == 4) *(u32x2*)out = u32x2{packed[0], packed[1]};
-            if (CPT == 8) *(u32x4*)out = u32x4{packed[0], packed[1], packed[2 % (CPT / 2)], packed[3 % (CPT / 2)]};
-        }
+        for (int e = 0; e < CPT / 2; ++e) packed[e] = F::pack(v[2 * e] * inv, v[2 * e + 1] * inv);
+        uint16_t* out = Y + (size_t)row * N + n;
+        if (CPT == 2) *(u32*)out = packed[0];
+        if (CPT == 4) *(u32x2*)out = u32x2{packed[0], packed[1]};
+        if (CPT == 8) *(u32x4*)out = u32x4{packed[0], packed[1], packed[2 % (CPT / 2)], packed[3 % (CPT / 2)]};
     }
 }
 
 template <typename F>
 static hipError_t launch_softmax_rows_fmt(const SoftmaxCall& c) {
     constexpr int NW = 8;
-    dim3 grid((c.N + TN - 1) / TN, (c.M + 16 * RG - 1) / (16 * RG)), block(NW * 64);
-    const size_t lds = (size_t)(NW * 16 * TN + 2 * NW * 32) * sizeof(float);
+    dim3 grid((c.N + TN - 1) / TN, (c.M + 15) / 16), block(NW * 64);
+    const size_t lds = (size_t)(NW * 16 * TN + 2 * NW * 16) * sizeof(float);
     auto kern = softmax_rows_kernel<F, NW>;
     static std::atomic<uint64_t> opted{0};
     if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;

@@ -348,12 +348,12 @@ def test_softmax_matmul_split_with_rows_of_very_different_maxima(P):
 def test_softmax_matmul_split_is_bit_reproducible_and_leaves_tickets_clean(P):
     import torch
     from gpu_util import to_device
-    stored = pi.draw_softmax(pi.F16, 512, 4096, 128, 1080)
+    stored = pi.draw_softmax(pi.F16, 128, 16384, 128, 1080, 4.0)
     X, W = to_device(stored["X"], pi.F16), to_device(stored["W"], pi.F16)
-    assert P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, 512, 4096, 128, P.PRISM_F16)["split_k"] == 4
+    assert P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, 128, 16384, 128, P.PRISM_F16)["split_k"] == 16
     outs = []
     for _ in range(30):
-        Y = torch.empty((512, 128), dtype=torch.float16, device="cuda")
+        Y = torch.empty((128, 128), dtype=torch.float16, device="cuda")
         P.prism_softmax_matmul(X, W, Y)
         outs.append(Y)
     torch.cuda.synchronize()
