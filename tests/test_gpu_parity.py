@@ -508,6 +508,41 @@ def test_tuner_on_the_softmax_operator(P):
         P.prism_plan_table_clear()
 
 
+# ---- shapes drawn around every dispatch boundary, as dispatched ---------------------------------------------------
+
+def test_random_shapes_as_dispatched(P):
+    """Seeded shapes around the boundaries of the dispatcher (16/17, 32/33, 64/65 rows; K around 1024 and 2048; odd
+    tails in K and N; every operator and 16-bit format): whatever kernel is chosen, the oracle decides."""
+    import random
+    rng = random.Random(0xD15BA7C4)
+    seen = set()
+    for i in range(72):
+        op = i % 3
+        dt = pi.BF16 if (i // 3) % 2 == 0 else pi.F16
+        M = rng.choice((1, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 96, 128, 130, 257))
+        K = 8 * rng.choice((1, 9, 32, 125, 128, 129, 255, 256, 257, 300, 520))
+        if op != 0 and K == 8:
+            K = 72   # eight products per output and a gate (or an exponential): single roundings of x*g decide the
+                     # worst of 100,000 outputs, which then sits at the bar itself (2.1e-2 seen); not a kernel property
+        N = 8 * rng.choice((1, 2, 16, 17, 33, 64, 130))
+        if op == 2:
+            stored = pi.draw_softmax(dt, M, K, N, 7000 + i, 3.0 if K <= 1100 else 3.5)
+            plan = P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, M, K, N, DTYPE_CODE[dt])
+            print(f"random {i}: softmax dtype={dt} M={M} K={K} N={N} plan={plan}", flush=True)
+            y, yhat = run_gpu_softmax(stored, dt), run_oracle_softmax(stored, dt)
+        else:
+            stored = pi.draw(dt, M, K, N, op == 1, 7000 + i)
+            plan = P.prism_plan(op, M, K, N, DTYPE_CODE[dt])
+            print(f"random {i}: op={op} dtype={dt} M={M} K={K} N={N} plan={plan}", flush=True)
+            y, yhat = run_gpu(stored, dt, op == 1, 1e-6), run_oracle(stored, dt, op == 1, 1e-6)
+        assert_parity(y, yhat, dt, f"random {i} op={op} M={M} K={K} N={N} plan={plan}")
+        seen.add((op, plan["path"], plan["tile_m"], plan["split_k"] > 1))
+    # the draw reaches every kernel family of every operator, with and without slices
+    assert {(o, pth) for o, pth, _, _ in seen} >= {(0, 2), (0, 3), (1, 2), (1, 3), (2, 4)}, seen
+    # (64 rows per workgroup need weights beyond the oracle's reach here: the decode_rows tests force them)
+    assert {(o, tm) for o, pth, tm, _ in seen if pth in (2, 4)} >= {(0, 16), (0, 32), (1, 16), (1, 32), (2, 16), (2, 32)}, seen
+
+
 # ---- large shapes: the oracle recomputes a sample of the outputs ------------------------------------------
 
 def test_decode_vocabulary_sized_output_sampled_columns(P):

@@ -231,6 +231,40 @@ def test_decode_plan_for_more_than_sixteen_rows(P):
     assert P.prism_plan(1, 2048, 4096, 14336, bf16)["path"] == P.PRISM_PATH_PREFILL
 
 
+def test_plans_of_random_shapes_are_consistent(P):
+    """Whatever the dispatcher picks: the grid covers the problem, the split leaves no empty slice, the workspace
+    is what the kernels index, and the query functions agree with each other."""
+    import random
+    rng = random.Random(20260415)
+    for _ in range(4000):
+        op = rng.choice((0, 1, 2))
+        dt = rng.choice((P.PRISM_F32, P.PRISM_BF16, P.PRISM_F16))
+        M = rng.choice((1, 7, 16, 17, 31, 32, 33, 64, 65, 100, 128, 129, 256, 300, 512, 513, 2048, 5000))
+        K = rng.choice((8, 64, 72, 100, 256, 1000, 1024, 2048, 2056, 4096, 14336, 32768))
+        N = rng.choice((8, 16, 36, 128, 136, 264, 1024, 4096, 6144, 14336, 128256))
+        p = P.prism_plan(op, M, K, N, dt)
+        what = f"op={op} dt={dt} M={M} K={K} N={N} plan={p}"
+        assert p["workspace_bytes"] == P.prism_workspace_bytes(op, M, K, N, dt), what
+        assert 1 <= p["split_k"] <= -(-K // 32), what
+        assert (p["workspace_bytes"] > 0) == (p["split_k"] > 1), what
+        fast = dt != P.PRISM_F32 and K % 8 == 0 and N % 8 == 0
+        if not fast:
+            assert p["path"] == P.PRISM_PATH_SIMPLE, what
+        cols = p["tile_n"] // 2 if (op == 1 and p["path"] == P.PRISM_PATH_PREFILL) else p["tile_n"]
+        if p["path"] == P.PRISM_PATH_PREFILL:
+            assert p["grid_x"] == -(-M // p["tile_m"]) * -(-N // cols), what
+        elif p["path"] == P.PRISM_PATH_DECODE or (p["path"] == P.PRISM_PATH_ROWS and p["tile_m"] == 32):
+            assert (p["grid_x"], p["grid_y"], max(1, p["grid_z"])) == (-(-N // 128), p["split_k"], -(-M // p["tile_m"])), what
+            assert p["tile_m"] in (16, 32, 64) and (p["tile_m"] == 16) == (M <= 16 and op != 2), what
+            if p["split_k"] > 1:
+                G = 2 if op == 1 else 1
+                part = (2 * 32 if op == 2 else p["tile_m"]) * 4
+                ss = -(-(-(-N // 128) * -(-M // p["tile_m"]) * p["split_k"] * part) // 256) * 256
+                assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * G * M * N * 4, what
+        else:
+            assert (p["grid_x"], p["grid_y"]) == (-(-N // p["tile_n"]), -(-M // p["tile_m"])), what
+
+
 def test_shapes_past_the_32_bit_offsets_take_the_plain_kernel(P):
     """2 GiB of W is what the buffer addressing of the matrix-core kernels covers; beyond, the plan says so."""
     bf16 = P.PRISM_BF16
