@@ -129,7 +129,7 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
     // The V block of this wavefront's first key block is requested now, two barriers before it is used.
     WRows w_first;
     const u32 v_lane = (u32)(((size_t)(key0 + 8 * q) * AD) * 2 + 16 * c);
-    load_w_block(w_first, rv, wave < nblk ? v_lane + (u32)(32 * wave * AD * 2) : kOutOfRange, (u32)(AD * 2));
+    load_w_block<true>(w_first, rv, wave < nblk ? v_lane + (u32)(32 * wave * AD * 2) : kOutOfRange, (u32)(AD * 2));
 
     // ---- 1. scores of this slice's keys -> LDS.  Element i of the block in lane (q, c): head 4q + i, key c.
     for (int jb = wave; jb < nblk; jb += ANW) {
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
             const int key = key0 + 32 * jb + 16 * half + c;
 #pragma unroll
             for (int kb = 0; kb < 4; ++kb)
-                kf[half][kb] = load16(rk, key < H ? (u32)(((size_t)key * AD + 32 * kb + 8 * q) * 2) : kOutOfRange);
+                kf[half][kb] = load16_stream(rk, key < H ? (u32)(((size_t)key * AD + 32 * kb + 8 * q) * 2) : kOutOfRange);
         }
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
     for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int jb = wave; jb < nblk; jb += ANW) {
         WRows w = w_first;
-        if (jb != wave) load_w_block(w, rv, v_lane + (u32)(32 * jb * AD * 2), (u32)(AD * 2));
+        if (jb != wave) load_w_block<true>(w, rv, v_lane + (u32)(32 * jb * AD * 2), (u32)(AD * 2));
         const u32x4 a = *(const u32x4*)(pr + c * PP + 32 * jb + 8 * q);
         acc[0] = F::mfma_16x16x32(a, b_operand<0>(w), acc[0]);
         acc[1] = F::mfma_16x16x32(a, b_operand<1>(w), acc[1]);

@@ -124,8 +124,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
             // X and g first: they come from L2 and let the A operand be ready before W lands.
             xr[u] = load16(rx, (row_ok && k_ok) ? (u32)(((size_t)c * K + k) * 2) : kOutOfRange);
             gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
-            load_w_block(w1[u], rw1, woff, row_bytes);
-            if (GATED) load_w_block(w2[u], rw2, woff, row_bytes);
+            load_w_block<true>(w1[u], rw1, woff, row_bytes);
+            if (GATED) load_w_block<true>(w2[u], rw2, woff, row_bytes);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {

@@ -111,6 +111,8 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
         }
     }
 
+    // With one row block W is read once and streamed past the caches; several row blocks share it through the L2.
+    const bool stream_w = gridDim.z == 1;
     // U K-blocks per trip: sixteen 16-byte row loads of W in flight per lane where the registers allow it.
     constexpr int U = (!GATED && RG <= 2) ? 2 : 1;
     for (int i = lwave; i < b_cnt; i += U * LNW) {
@@ -127,8 +129,13 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
             for (int r = 0; r < RG; ++r)
                 xr[u][r] = load16(rx, (row_ok[r] && k_ok) ? x_row[r] + (u32)k * 2u : kOutOfRange);
             gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
-            load_w_block(w1[u], rw1, woff, row_bytes);
-            if (BOTH) load_w_block(w2[u], rw2, woff, row_bytes);
+            if (stream_w) {
+                load_w_block<true>(w1[u], rw1, woff, row_bytes);
+                if (BOTH) load_w_block<true>(w2[u], rw2, woff, row_bytes);
+            } else {
+                load_w_block<false>(w1[u], rw1, woff, row_bytes);
+                if (BOTH) load_w_block<false>(w2[u], rw2, woff, row_bytes);
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {

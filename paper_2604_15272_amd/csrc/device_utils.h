@@ -78,6 +78,12 @@ __device__ __forceinline__ u32x4 load16(__amdgpu_buffer_rsrc_t r, u32 voff) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
 }
 
+// The same for data that is read once per call (a streamed weight matrix): the non-temporal hint keeps it from
+// displacing what the caches should hold (measured on the decode kernel: 3.5 % / 6 % faster on 32 / 235 MB of W).
+__device__ __forceinline__ u32x4 load16_stream(__amdgpu_buffer_rsrc_t r, u32 voff) {
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 2);
+}
+
 // Device-coherent accesses for data handed from one workgroup to another inside a kernel.  On a
 // multi-XCD part every XCD has its own L2: these accesses go through to the memory side instead
 // of living in (or being served from) the issuing XCD's L2.

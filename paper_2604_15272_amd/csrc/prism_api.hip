@@ -270,12 +270,11 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             S = (row_groups > 1) ? target / wgs : (target + wgs / 2) / wgs;
             int64_t s_max = kblocks / waves;
             if (row_groups == 1) {
-                // Measured over shapes from 2 to 235 MB of weights: the exchange between slices costs about
-                // 3.5 us, so a tile column of at most 256 KiB is not split at all, a slice keeps at least
-                // 128 KiB, and there are never more than eight (the last arrival reads eight slices'
-                // partials in one round trip).
-                const int64_t column_kib = K * (gated ? 2 : 1) * kDecodeTileN * 2 / 1024;
-                s_max = std::min<int64_t>(s_max, column_kib <= 256 ? 1 : std::min<int64_t>(8, column_kib / 128));
+                // Measured over shapes from 2 to 235 MB of weights streamed from HBM (an exhaustive run of the
+                // tuner): never more than eight slices (the last arrival reads eight slices' partials in one
+                // round trip), and a slice keeps at least four K-blocks (eight when gated: two matrices), even
+                // if that leaves wavefronts idle.
+                s_max = std::min<int64_t>(8, std::max<int64_t>(1, kblocks / (gated ? 8 : 4)));
             }
             if (S > s_max) S = s_max;
             if (S < 1) S = 1;

@@ -11,9 +11,12 @@ struct WRows {
     u32x4 r[8];
 };
 
+// STREAM: the block is read by this workgroup only (non-temporal loads).
+template <bool STREAM = false>
 __device__ __forceinline__ void load_w_block(WRows& w, __amdgpu_buffer_rsrc_t rs, u32 voff, u32 row_bytes) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) w.r[i] = load16(rs, voff + (u32)i * row_bytes);
+    for (int i = 0; i < 8; ++i)
+        w.r[i] = STREAM ? load16_stream(rs, voff + (u32)i * row_bytes) : load16(rs, voff + (u32)i * row_bytes);
 }
 
 // B operand j (j = 0..7) of a lane: column 8c + j of its 8 x 8 sub-block, eight K values.

@@ -78,7 +78,7 @@ def _time_choice(fn, args_sets, steps, warmup):
     return e0.elapsed_time(e1) / steps * 1e3  # microseconds
 
 
-def tune(op, M, K, N, dtype=B.PRISM_BF16, samples=12, seed=0, steps=None, install=True, weight_bytes_total=1 << 29,
+def tune(op, M, K, N, dtype=B.PRISM_BF16, samples=12, seed=0, steps=None, install=True, weight_bytes_total=1 << 30,
          verbose=False):
     """Sample up to `samples` admissible assignments (the heuristic's own choice is always one of them),
     time each on random inputs of this shape, and install the fastest in the plan table.
@@ -94,7 +94,7 @@ def tune(op, M, K, N, dtype=B.PRISM_BF16, samples=12, seed=0, steps=None, instal
     esize = 4 if dtype == B.PRISM_F32 else 2
     nw = 2 if gated else 1
     wbytes = esize * K * N * nw
-    sets = max(1, min(64, weight_bytes_total // max(wbytes, 1)))
+    sets = max(1, min(1024, weight_bytes_total // max(wbytes, 1)))   # well past the 256 MB last-level cache
     gen = torch.Generator(device="cuda").manual_seed(1234 + seed)
     X = (torch.randn((M, K), generator=gen, device="cuda") * (3.0 if softmax else 1.0)).to(tdt)
     g = (torch.rand((K,), generator=gen, device="cuda") + 0.5).to(tdt)
