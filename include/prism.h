@@ -67,7 +67,8 @@ typedef enum {
     PRISM_PATH_SIMPLE = 1,  /* plain FMA kernel: any M, K, N; the only path for PRISM_F32 */
     PRISM_PATH_DECODE = 2,  /* few rows: W streamed once, split-K over wavefronts and workgroups */
     PRISM_PATH_PREFILL = 3, /* many rows: LDS-tiled MFMA GEMM */
-    PRISM_PATH_ROWS = 4,    /* prism_softmax_matmul only: a workgroup owns 16 rows of X over the whole of K */
+    PRISM_PATH_ROWS = 4,    /* prism_softmax_matmul only: the matrix-core kernels (variant 16: 16 rows of X over the
+                               whole of K per workgroup; variant 32: 32 rows and one of up to 16 K-slices) */
     PRISM_PATH_ATTENTION = 5 /* prism_gqa_decode_attention only: matrix-core kernel, keys split over workgroups */
 } prism_path_t;
 
@@ -122,7 +123,9 @@ prism_status_t prism_swiglu(const void* X, const void* W_gate, const void* W_up,
  * over k.  As in the fused program of Figure 1(b), exp and its row sum are accumulated in the loop
  * over k beside the product and the division follows the loop; softmax(X) is never written to
  * memory.  The row maximum is subtracted before the exponential (it cancels in exact arithmetic),
- * so any finite X is safe.  dtype as above; no workspace is needed.
+ * so any finite X is safe.  dtype as above.  Shapes whose plan splits K (prism_plan reports split_k > 1:
+ * few rows against a deep K) hand partial results across workgroups through the workspace, like the
+ * decode kernels: PRISM_ERR_WORKSPACE if prism_workspace_bytes(PRISM_OP_SOFTMAX_MATMUL, ...) is not met.
  */
 prism_status_t prism_softmax_matmul(const void* X, const void* W, void* Y, int64_t M, int64_t K,
                                     int64_t N, prism_dtype_t dtype, hipStream_t stream);
@@ -186,7 +189,8 @@ prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_
  * Process-wide override for tests and tuning: force a kernel family and/or a split-K factor and
  * a tile variant (0 = automatic for each).  Variants: PRISM_PATH_DECODE with at most 16 rows: 4, 8 or 16
  * wavefronts per workgroup; with more rows: 32 or 64 rows per workgroup;
- * PRISM_PATH_PREFILL: 1000 * tile_m + tile_n.  A forced path that cannot run a shape makes the call
+ * PRISM_PATH_PREFILL: 1000 * tile_m + tile_n; PRISM_PATH_ROWS: 16 or 32 rows per workgroup (a split applies
+ * to 32 only, at most 16 slices).  A forced path that cannot run a shape makes the call
  * return PRISM_ERR_UNSUPPORTED.  The kernels are correct for every admissible value (the paper's
  * notion of a mapping that is correct for all parameter values, Section 2).
  */

@@ -636,6 +636,6 @@ const char* prism_status_string(prism_status_t status) {
     }
 }
 
-int32_t prism_version(void) { return 140; }
+int32_t prism_version(void) { return 150; }
 
 }  // extern "C"

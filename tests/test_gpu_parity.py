@@ -472,6 +472,56 @@ def test_attention_is_bit_reproducible_and_leaves_tickets_clean(P):
     _case(P, pi.BF16, 16, 2056, 1160, False, seed=1441, expect_path=P.PRISM_PATH_DECODE)
 
 
+def test_calls_that_need_a_workspace_fail_loudly_without_one(P):
+    """No workspace (or too small a one) registered: the call returns PRISM_ERR_WORKSPACE, launches nothing and
+    leaves Y alone; with the workspace back the same call succeeds."""
+    import ctypes
+    import torch
+    from paper_2604_15272_amd import binding
+    vp = ctypes.c_void_p
+    X = torch.randn(16, 4096, device="cuda").bfloat16()
+    g = torch.ones(4096, device="cuda").bfloat16()
+    W = torch.randn(4096, 4096, device="cuda").bfloat16()
+    Xs = torch.randn(16, 16384, device="cuda").half()
+    Ws = torch.randn(16384, 128, device="cuda").half()
+    Q = torch.randn(2, 8, 128, device="cuda").half()
+    KV = torch.randn(2, 2048, 128, device="cuda").half()
+    P.ensure_workspace(64 << 20)
+    dev = torch.cuda.current_device()
+    buf = binding._workspaces[dev]
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+
+    def calls(Y, Ys, O):
+        return (P.lib.prism_rmsnorm_matmul(vp(X.data_ptr()), vp(g.data_ptr()), vp(W.data_ptr()), vp(Y.data_ptr()), 16, 4096, 4096,
+                                           1e-6, P.PRISM_BF16, stream),
+                P.lib.prism_softmax_matmul(vp(Xs.data_ptr()), vp(Ws.data_ptr()), vp(Ys.data_ptr()), 16, 16384, 128, P.PRISM_F16,
+                                           stream),
+                P.lib.prism_gqa_decode_attention(vp(Q.data_ptr()), vp(KV.data_ptr()), vp(KV.data_ptr()), vp(O.data_ptr()), 2, 8,
+                                                 2048, 128, 0.1, 0, 1e-6, P.PRISM_F16, stream))
+
+    assert P.prism_plan(0, 16, 4096, 4096, P.PRISM_BF16)["workspace_bytes"] > 0
+    assert P.prism_plan(P.PRISM_OP_SOFTMAX_MATMUL, 16, 16384, 128, P.PRISM_F16)["workspace_bytes"] > 0
+    assert P.prism_attention_plan(2, 8, 2048, 128, P.PRISM_F16)["workspace_bytes"] > 0
+    try:
+        for ptr, size in ((0, 0), (buf.data_ptr(), 262144 + 256)):   # none, then one that holds the counters only
+            P.prism_set_workspace(ptr, size)
+            Y = torch.full((16, 4096), 7.0, device="cuda", dtype=torch.bfloat16)
+            Ys = torch.full((16, 128), 7.0, device="cuda", dtype=torch.float16)
+            O = torch.full((2, 8, 128), 7.0, device="cuda", dtype=torch.float16)
+            assert calls(Y, Ys, O) == (3, 3, 3)
+            torch.cuda.synchronize()
+            assert bool((Y == 7).all()) and bool((Ys == 7).all()) and bool((O == 7).all())
+            assert "workspace" in P.prism_status_string(3)
+    finally:
+        P.prism_set_workspace(buf.data_ptr(), buf.numel())
+    Y = torch.full((16, 4096), float("nan"), device="cuda", dtype=torch.bfloat16)
+    Ys = torch.full((16, 128), float("nan"), device="cuda", dtype=torch.float16)
+    O = torch.full((2, 8, 128), float("nan"), device="cuda", dtype=torch.float16)
+    assert calls(Y, Ys, O) == (0, 0, 0)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Y.float()).all()) and bool(torch.isfinite(Ys.float()).all()) and bool(torch.isfinite(O.float()).all())
+
+
 # ---- parameter instantiation by sampling and timing (paper Section 5) -------------------------------
 
 def test_tuner_installs_a_plan_that_is_correct_and_not_slower(P):
