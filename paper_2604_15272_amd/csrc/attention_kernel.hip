@@ -28,6 +28,7 @@
 #include <type_traits>
 
 #include "device_utils.h"
+#include "exchange.h"
 #include "prism_internal.h"
 #include "w_block.h"
 
@@ -228,9 +229,8 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
 
     // ---- 4. across the slices of this batch entry
     if (S > 1) {
-        float* ap = acc_part + (((size_t)bi * S + s) * 16 + m) * AD + col;
-#pragma unroll
-        for (int e = 0; e < CPT; e += 2) store_coherent2(ap + e, v[e], v[e + 1]);
+        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)gridDim.y * S * 16 * AD);
+        store_partial<CPT>(racc, acc_part, (((size_t)bi * S + s) * 16 + m) * AD + col, v);
         if (col == 0) {
             store_coherent(m_part + ((size_t)bi * S + s) * 16 + m, m_row[m]);
             store_coherent(l_part + ((size_t)bi * S + s) * 16 + m, den);
@@ -261,14 +261,13 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
         den = 0.f;
         for (int t0 = 0; t0 < S; t0 += BATCH) {
             float mm[BATCH], ll[BATCH];
-            f32x2 x[BATCH][CPT / 2];
+            float x[BATCH][CPT];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
                 const size_t row = ((size_t)bi * S + min(t0 + j, S - 1)) * 16 + m;  // slots past the last slice re-read it
                 mm[j] = load_coherent(m_part + row);
                 ll[j] = load_coherent(l_part + row);
-#pragma unroll
-                for (int e = 0; e < CPT / 2; ++e) x[j][e] = load_coherent2(acc_part + row * AD + col + 2 * e);
+                load_partial<CPT>(racc, acc_part, row * AD + col, x[j]);
             }
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
@@ -276,10 +275,7 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
                 const float w = __builtin_amdgcn_exp2f((mm[j] - gmax) * kLog2e);
                 den = fmaf(ll[j], w, den);
 #pragma unroll
-                for (int e = 0; e < CPT / 2; ++e) {
-                    v[2 * e] = fmaf(x[j][e][0], w, v[2 * e]);
-                    v[2 * e + 1] = fmaf(x[j][e][1], w, v[2 * e + 1]);
-                }
+                for (int e = 0; e < CPT; ++e) v[e] = fmaf(x[j][e], w, v[e]);
             }
         }
     }

@@ -16,6 +16,7 @@
 // order (so the result does not depend on arrival order), applies 1/rms (and the SiLU gate) and
 // stores Y.  The normalised X never exists in memory.
 #include "device_utils.h"
+#include "exchange.h"
 #include "prism_internal.h"
 #include "w_block.h"
 
@@ -196,13 +197,11 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         // stores write through, loads do not hit a stale L2 line), so that no whole-cache
         // write-back or invalidate is needed: a workgroup waits until its stores are acknowledged,
         // then takes its ticket; whoever draws the last ticket reads after that.
+        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)S * G * M * N);
         if (out_ok) {
-            float* p = acc_part + (((size_t)split * G) * M + m) * N + n;
-#pragma unroll
-            for (int e = 0; e < CPT; e += 2) {
-                store_coherent2(p + e, v1[e], v1[e + 1]);
-                if (GATED) store_coherent2(p + (size_t)M * N + e, v2[e], v2[e + 1]);
-            }
+            const size_t idx = (((size_t)split * G) * M + m) * N + n;
+            store_partial<CPT>(racc, acc_part, idx, v1);
+            if (GATED) store_partial<CPT>(racc, acc_part, idx + (size_t)M * N, v2);
         }
         if (col == 0) store_coherent(ss_part + ((size_t)ntile * S + split) * 16 + m, ssum);
         wait_stores_acknowledged();
@@ -224,18 +223,15 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         constexpr int BATCH = 8;
         for (int s0 = 0; s0 < S; s0 += BATCH) {
             float sq[BATCH];
-            f32x2 pa[BATCH][CPT / 2], pb[BATCH][CPT / 2];
+            float pa[BATCH][CPT], pb[GATED ? BATCH : 1][CPT];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
                 const int s = min(s0 + j, S - 1);
                 sq[j] = load_coherent(ss_part + ((size_t)ntile * S + s) * 16 + m);
                 if (out_ok) {
-                    const float* p = acc_part + (((size_t)s * G) * M + m) * N + n;
-#pragma unroll
-                    for (int e = 0; e < CPT / 2; ++e) {
-                        pa[j][e] = load_coherent2(p + 2 * e);
-                        if (GATED) pb[j][e] = load_coherent2(p + (size_t)M * N + 2 * e);
-                    }
+                    const size_t idx = (((size_t)s * G) * M + m) * N + n;
+                    load_partial<CPT>(racc, acc_part, idx, pa[j]);
+                    if (GATED) load_partial<CPT>(racc, acc_part, idx + (size_t)M * N, pb[GATED ? j : 0]);
                 }
             }
 #pragma unroll
@@ -244,13 +240,9 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
                 ssum += sq[j];
                 if (out_ok) {
 #pragma unroll
-                    for (int e = 0; e < CPT / 2; ++e) {
-                        v1[2 * e] += pa[j][e][0];
-                        v1[2 * e + 1] += pa[j][e][1];
-                        if (GATED) {
-                            v2[2 * e] += pb[j][e][0];
-                            v2[2 * e + 1] += pb[j][e][1];
-                        }
+                    for (int e = 0; e < CPT; ++e) {
+                        v1[e] += pa[j][e];
+                        if (GATED) v2[e] += pb[GATED ? j : 0][e];
                     }
                 }
             }

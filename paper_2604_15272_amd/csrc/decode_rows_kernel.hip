@@ -13,6 +13,7 @@
 // not fit a wavefront's registers, so the wavefronts split the matrices instead (0-3: W1, 4-7: W2, each
 // half taking the K-blocks round-robin); the halves meet in the LDS reduction.  W1 and W2 are still read once.
 #include "device_utils.h"
+#include "exchange.h"
 #include "prism_internal.h"
 #include "w_block.h"
 
@@ -240,16 +241,14 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
     if (S > 1) {
         // Exchange between the K-slices of this (column tile, row block): see the 16-row kernel.
         const size_t tile_id = (size_t)rblock * n_tiles + ntile;
+        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)S * G * M * N);
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
             const int row = m0 + 16 * r + m;
             if (out_ok[r]) {
-                float* p = acc_part + (((size_t)split * G) * M + row) * N + n;
-#pragma unroll
-                for (int e = 0; e < CPT; e += 2) {
-                    store_coherent2(p + e, v1[r][e], v1[r][e + 1]);
-                    if (GATED) store_coherent2(p + (size_t)M * N + e, v2[r][e], v2[r][e + 1]);
-                }
+                const size_t idx = (((size_t)split * G) * M + row) * N + n;
+                store_partial<CPT>(racc, acc_part, idx, v1[r]);
+                if (GATED) store_partial<CPT>(racc, acc_part, idx + (size_t)M * N, v2[r]);
             }
             if (col == 0) store_coherent(ss_part + (tile_id * S + split) * RB + 16 * r + m, ssum[r]);
         }
@@ -273,7 +272,7 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
         }
         for (int s0 = 0; s0 < S; s0 += BATCH) {
             float sq[BATCH][RG];
-            f32x2 pa[BATCH][RG][CPT / 2], pb[BATCH][GATED ? RG : 1][CPT / 2];
+            float pa[BATCH][RG][CPT], pb[BATCH][GATED ? RG : 1][CPT];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
                 const int s = min(s0 + j, S - 1);
@@ -281,12 +280,9 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
                 for (int r = 0; r < RG; ++r) {
                     sq[j][r] = load_coherent(ss_part + (tile_id * S + s) * RB + 16 * r + m);
                     if (out_ok[r]) {
-                        const float* p = acc_part + (((size_t)s * G) * M + (m0 + 16 * r + m)) * N + n;
-#pragma unroll
-                        for (int e = 0; e < CPT / 2; ++e) {
-                            pa[j][r][e] = load_coherent2(p + 2 * e);
-                            if (GATED) pb[j][GATED ? r : 0][e] = load_coherent2(p + (size_t)M * N + 2 * e);
-                        }
+                        const size_t idx = (((size_t)s * G) * M + (m0 + 16 * r + m)) * N + n;
+                        load_partial<CPT>(racc, acc_part, idx, pa[j][r]);
+                        if (GATED) load_partial<CPT>(racc, acc_part, idx + (size_t)M * N, pb[j][GATED ? r : 0]);
                     }
                 }
             }
@@ -298,13 +294,9 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
                     ssum[r] += sq[j][r];
                     if (out_ok[r]) {
 #pragma unroll
-                        for (int e = 0; e < CPT / 2; ++e) {
-                            v1[r][2 * e] += pa[j][r][e][0];
-                            v1[r][2 * e + 1] += pa[j][r][e][1];
-                            if (GATED) {
-                                v2[r][2 * e] += pb[j][GATED ? r : 0][e][0];
-                                v2[r][2 * e + 1] += pb[j][GATED ? r : 0][e][1];
-                            }
+                        for (int e = 0; e < CPT; ++e) {
+                            v1[r][e] += pa[j][r][e];
+                            if (GATED) v2[r][e] += pb[j][GATED ? r : 0][e];
                         }
                     }
                 }

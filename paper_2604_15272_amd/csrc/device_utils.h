@@ -78,10 +78,14 @@ __device__ __forceinline__ u32x4 load16(__amdgpu_buffer_rsrc_t r, u32 voff) {
     return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0);
 }
 
+// Cache-policy operand of the buffer builtins on this target: bit 0 = sc0, bit 1 = nt, bit 4 = sc1.
+constexpr int kCachePolicyNt = 2;
+constexpr int kCachePolicySc1 = 16;
+
 // The same for data that is read once per call (a streamed weight matrix): the non-temporal hint keeps it from
 // displacing what the caches should hold (measured on the decode kernel: 3.5 % / 6 % faster on 32 / 235 MB of W).
 __device__ __forceinline__ u32x4 load16_stream(__amdgpu_buffer_rsrc_t r, u32 voff) {
-    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 2);
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, kCachePolicyNt);
 }
 
 // Device-coherent accesses for data handed from one workgroup to another inside a kernel.  On a
@@ -102,6 +106,15 @@ __device__ __forceinline__ f32x2 load_coherent2(const float* p) {
     const unsigned long long v =
         __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return __builtin_bit_cast(f32x2, v);
+}
+// 16-byte versions, through a buffer descriptor over the exchanged array (the same for all lanes) and a byte
+// offset per lane: the exchange of partial sums moves 16 bytes per lane and instruction instead of 8
+// (measured on the decode kernel: 12.0 -> 11.4 us at 16 x 4096 x 4096, 9.5 -> 8.7 us at 16 x 1024 x 4096).
+__device__ __forceinline__ void store_coherent4(__amdgpu_buffer_rsrc_t r, u32 byte_off, f32x4 v) {
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), r, (int)byte_off, 0, kCachePolicySc1);
+}
+__device__ __forceinline__ f32x4 load_coherent4(__amdgpu_buffer_rsrc_t r, u32 byte_off) {
+    return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kCachePolicySc1));
 }
 // Blocks until every store this wavefront issued has been acknowledged by the memory system.
 __device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }

@@ -191,6 +191,7 @@ prism_status_t make_softmax_plan(int64_t M, int64_t K, int64_t N, prism_dtype_t 
         return PRISM_OK;
     }
     if (rb32 > 65535 || (S > 1 && n_tiles * rb32 > kMaxTickets)) return PRISM_ERR_UNSUPPORTED;
+    if (S > 1 && (uint64_t)S * M * N * 4 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;  // 31-bit offsets into the partials
     p.tile_m = kSoftmaxSplitRows;
     p.grid_y = (int32_t)S;
     p.grid_z = (int32_t)rb32;
@@ -289,6 +290,12 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         if (forced_split <= 0)
             while (!slice_fits(S) && S < kblocks) S = std::min<int64_t>(kblocks, 2 * S);
         if (S > 65535 || !slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
+        // The partial sums are addressed with 31-bit byte offsets.
+        auto partials_fit = [&](int64_t s) { return (uint64_t)s * (gated ? 2 : 1) * M * N * 4 < kTwoGiB; };
+        if (forced_split <= 0)
+            while (S > 1 && !partials_fit(S)) --S;
+        if (S > 1 && !partials_fit(S)) return PRISM_ERR_UNSUPPORTED;
+        if (!slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
         out->waves = waves;
         out->row_groups = row_groups;
         p.split_k = (int32_t)S;
@@ -358,6 +365,12 @@ prism_status_t make_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, p
     keys = ((H + S - 1) / S + 31) / 32 * 32;
     if (keys > kAttnMaxSliceKeys) return PRISM_ERR_UNSUPPORTED;  // a forced split too coarse for the LDS
     S = (H + keys - 1) / keys;  // no empty slice
+    if (S > 1 && (uint64_t)B * S * 16 * kAttnHeadDim * 4 >= kTwoGiB) {
+        // 31-bit offsets into the partials: a batch this large is left to the plain kernel
+        if (forced == PRISM_PATH_ATTENTION) return PRISM_ERR_UNSUPPORTED;
+        *p = AttentionPlan{PRISM_PATH_SIMPLE, 1, 0, 0};
+        return PRISM_OK;
+    }
     p->splits = (int)S;
     p->slice_keys = (int)keys;
     if (S > 1) p->workspace_bytes = PRISM_WORKSPACE_HEADER_BYTES + (uint64_t)B * S * 16 * (2 + kAttnHeadDim) * 4;

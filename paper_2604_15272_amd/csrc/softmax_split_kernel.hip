@@ -14,6 +14,7 @@
 #include <type_traits>
 
 #include "device_utils.h"
+#include "exchange.h"
 #include "prism_internal.h"
 #include "w_block.h"
 
@@ -269,13 +270,10 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
         // Hand over (maximum, sum, partial product); the last arrival of the tile combines.
         const size_t tile_id = (size_t)rblock * n_tiles + ntile;
         float* ml = ml_part + (tile_id * S) * (2 * RB);
+        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)S * M * N);
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            if (out_ok[r]) {
-                float* p = acc_part + ((size_t)split * M + (m0 + 16 * r + m)) * N + n;
-#pragma unroll
-                for (int e = 0; e < CPT; e += 2) store_coherent2(p + e, v[r][e], v[r][e + 1]);
-            }
+            if (out_ok[r]) store_partial<CPT>(racc, acc_part, ((size_t)split * M + (m0 + 16 * r + m)) * N + n, v[r]);
             if (col == 0) store_coherent2(ml + (size_t)split * (2 * RB) + 2 * (16 * r + m), rmax[r], den[r]);
         }
         wait_stores_acknowledged();
@@ -317,16 +315,13 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
 #pragma unroll
         for (int s0 = 0; s0 < kSoftmaxMaxSplits; s0 += BATCH) {
             if (s0 >= S) break;
-            f32x2 pa[BATCH][RG][CPT / 2];
+            float pa[BATCH][RG][CPT];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j)
 #pragma unroll
                 for (int r = 0; r < RG; ++r)
-                    if (out_ok[r]) {
-                        const float* p = acc_part + ((size_t)min(s0 + j, S - 1) * M + (m0 + 16 * r + m)) * N + n;
-#pragma unroll
-                        for (int e = 0; e < CPT / 2; ++e) pa[j][r][e] = load_coherent2(p + 2 * e);
-                    }
+                    if (out_ok[r])
+                        load_partial<CPT>(racc, acc_part, ((size_t)min(s0 + j, S - 1) * M + (m0 + 16 * r + m)) * N + n, pa[j][r]);
 #pragma unroll
             for (int j = 0; j < BATCH; ++j)
 #pragma unroll
@@ -334,10 +329,7 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
                     if (out_ok[r]) {
                         const float f = fac[s0 + j][r];  // zero past the last slice
 #pragma unroll
-                        for (int e = 0; e < CPT / 2; ++e) {
-                            v[r][2 * e] = fmaf(f, pa[j][r][e][0], v[r][2 * e]);
-                            v[r][2 * e + 1] = fmaf(f, pa[j][r][e][1], v[r][2 * e + 1]);
-                        }
+                        for (int e = 0; e < CPT; ++e) v[r][e] = fmaf(f, pa[j][r][e], v[r][e]);
                     }
         }
     }
