@@ -204,15 +204,7 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
         acc[7] = F::mfma_16x16x32(a, b_operand<7>(w), acc[7]);
     }
     // Across wavefronts through LDS.  Accumulator j, element i of lane (q, c) is head 4q + i, column 8c + j.
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float* dst = red + (wave * 16 + (4 * q + i)) * AD + 8 * c;
-        const f32x4 lo = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-        const f32x4 hi = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
-        const bool upper = (c & 8) != 0;
-        *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
-        *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
-    }
+    store_acc_tile(red + wave * 16 * AD, AD, q, c, acc);
     __syncthreads();
     const int m = tid / TPR;           // head
     const int col = (tid % TPR) * CPT; // first of 8 output columns

@@ -39,20 +39,6 @@ __device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], u32x4 a, const WRows
     acc[7] = F::mfma_16x16x32(a, b_operand<7>(w), acc[7]);
 }
 
-// A operand of a lane: X[m = c][8 K values] * g, rounded to the storage format; adds the raw squares to ss.
-template <typename F>
-__device__ __forceinline__ u32x4 a_operand(u32x4 x, u32x4 gg, float& ss) {
-    u32x4 a;
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        const float x0 = F::lo(x[d]), x1 = F::hi(x[d]);
-        ss = fmaf(x0, x0, ss);
-        ss = fmaf(x1, x1, ss);
-        a[d] = F::pack(x0 * F::lo(gg[d]), x1 * F::hi(gg[d]));
-    }
-    return a;
-}
-
 }  // namespace
 
 // LDS: per wavefront a 16 x 128 fp32 tile, plus 16 sums of squares.
@@ -130,7 +116,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const u32x4 a = a_operand<F>(xr[u], gr[u], ss);
+            const u32x4 a = scaled_a_operand<F>(xr[u], gr[u], ss);
             mfma_block<F>(acc1, a, w1[u]);
             if (GATED) mfma_block<F>(acc2, a, w2[u]);
         }
@@ -153,20 +139,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 #pragma unroll
     for (int gi = 0; gi < G; ++gi) {
         if (gi == 1) __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // A lane owns 32 bytes of a row; lanes c and c + 8 are 256 bytes apart, the same banks.
-            // The upper eight write their second half first, so that one store instruction covers
-            // 16 different 16-byte bank groups.
-            float* dst = red + (wave * 16 + (4 * q + i)) * TN + 8 * c;
-            const f32x4 lo = (gi == 0) ? f32x4{acc1[0][i], acc1[1][i], acc1[2][i], acc1[3][i]}
-                                       : f32x4{acc2[0][i], acc2[1][i], acc2[2][i], acc2[3][i]};
-            const f32x4 hi = (gi == 0) ? f32x4{acc1[4][i], acc1[5][i], acc1[6][i], acc1[7][i]}
-                                       : f32x4{acc2[4][i], acc2[5][i], acc2[6][i], acc2[7][i]};
-            const bool upper = (c & 8) != 0;
-            *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
-            *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
-        }
+        store_acc_tile(red + wave * 16 * TN, TN, q, c, gi == 0 ? acc1 : acc2);
         if (gi == 0 && q == 0) ss_red[wave * 16 + c] = ss;
         __syncthreads();
         float v[CPT];

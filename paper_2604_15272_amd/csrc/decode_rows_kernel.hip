@@ -31,19 +31,6 @@ constexpr int CPT = 16 * TN / NT;  // 4 columns per thread in the epilogue
 constexpr int TPR = TN / CPT;      // 32 threads per output row
 constexpr int kRedFloats = NW * 16 * TN;  // one row group's partial tiles of all wavefronts
 
-template <typename F>
-__device__ __forceinline__ u32x4 scaled_operand(u32x4 x, u32x4 gg, float& ss) {
-    u32x4 a;
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        const float x0 = F::lo(x[d]), x1 = F::hi(x[d]);
-        ss = fmaf(x0, x0, ss);
-        ss = fmaf(x1, x1, ss);
-        a[d] = F::pack(x0 * F::lo(gg[d]), x1 * F::hi(gg[d]));
-    }
-    return a;
-}
-
 }  // namespace
 
 template <typename F, bool GATED, int RG>
@@ -142,7 +129,7 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
         for (int u = 0; u < U; ++u) {
             u32x4 a[RG];
 #pragma unroll
-            for (int r = 0; r < RG; ++r) a[r] = scaled_operand<F>(xr[u][r], gr[u], ss[r]);
+            for (int r = 0; r < RG; ++r) a[r] = scaled_a_operand<F>(xr[u][r], gr[u], ss[r]);
             auto step = [&](auto jc) {
                 constexpr int J = decltype(jc)::value;
                 const u32x4 b1 = b_operand<J>(w1[u]);
@@ -183,18 +170,6 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
     // Across wavefronts through LDS, two row groups of one weight matrix at a time.  Accumulator j, element
     // i of lane (q, c) is row 4q + i of the group, column 8c + j of the tile.
     float v1[RG][CPT], v2[RG][CPT], ssum[RG];
-    auto put = [&](float* base, const f32x4 (&acc)[8]) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // As in the 16-row kernel: the upper eight column groups write their second half first.
-            float* dst = base + (wave * 16 + (4 * q + i)) * TN + 8 * c;
-            const f32x4 lo = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-            const f32x4 hi = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
-            const bool upper = (c & 8) != 0;
-            *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
-            *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
-        }
-    };
     constexpr int GL = BOTH ? 2 : 1;  // passes over the row groups: one per matrix a wavefront holds
 #pragma unroll
     for (int gi = 0; gi < GL; ++gi) {
@@ -202,7 +177,8 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
         for (int r0 = 0; r0 < RG; r0 += 2) {
             if (gi + r0 > 0) __syncthreads();
 #pragma unroll
-            for (int h = 0; h < 2; ++h) put(red + h * kRedFloats, gi == 0 ? acc1[r0 + h] : acc2[BOTH ? r0 + h : 0]);
+            for (int h = 0; h < 2; ++h)
+                store_acc_tile(red + h * kRedFloats + wave * 16 * TN, TN, q, c, gi == 0 ? acc1[r0 + h] : acc2[BOTH ? r0 + h : 0]);
             __syncthreads();  // also orders the ss_red stores before their first reader
 #pragma unroll
             for (int h = 0; h < 2; ++h) {

@@ -181,17 +181,7 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
     const int m = tid / TPR;
     const int col = (tid % TPR) * CPT;
     const int n = n0 + col;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        // As in the decode kernel: the upper eight column groups write their second half first, so
-        // that one store instruction covers 16 different 16-byte bank groups.
-        float* dst = red + (wave * 16 + (4 * q + i)) * TN + 8 * c;
-        const f32x4 lo = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
-        const f32x4 hi = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
-        const bool upper = (c & 8) != 0;
-        *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
-        *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
-    }
+    store_acc_tile(red + wave * 16 * TN, TN, q, c, acc);
     __syncthreads();
     float gmax = -__builtin_inff();
 #pragma unroll

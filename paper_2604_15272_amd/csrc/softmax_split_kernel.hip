@@ -234,18 +234,7 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
     const int col = (tid % TPR) * CPT;
     const int n = n0 + col;
 #pragma unroll
-    for (int r = 0; r < RG; ++r) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // The upper eight column groups write their second half first: 16 different 16-byte bank groups per store.
-            float* dst = red + r * kRedFloats + (wave * 16 + (4 * q + i)) * TN + 8 * c;
-            const f32x4 lo = f32x4{acc[r][0][i], acc[r][1][i], acc[r][2][i], acc[r][3][i]};
-            const f32x4 hi = f32x4{acc[r][4][i], acc[r][5][i], acc[r][6][i], acc[r][7][i]};
-            const bool upper = (c & 8) != 0;
-            *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
-            *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
-        }
-    }
+    for (int r = 0; r < RG; ++r) store_acc_tile(red + r * kRedFloats + wave * 16 * TN, TN, q, c, acc[r]);
     __syncthreads();
     float v[RG][CPT], den[RG], rmax[RG];
     bool out_ok[RG];

@@ -1,6 +1,6 @@
 // A wavefront's 32 (k) x 128 (n) block of a row-major weight matrix, turned into MFMA B operands in
-// registers.  Shared by the kernels that stream W once and keep few rows of the other operand
-// (the decode kernel and the softmax kernel).
+// registers, and the other pieces the kernels built on it share (the decode kernels, the softmax kernels,
+// the attention kernel): they stream W once and keep few rows of the other operand.
 #pragma once
 #include "device_utils.h"
 
@@ -30,6 +30,37 @@ __device__ __forceinline__ u32x4 b_operand(const WRows& w) {
     b[2] = __builtin_amdgcn_perm(w.r[5][d], w.r[4][d], sel);
     b[3] = __builtin_amdgcn_perm(w.r[7][d], w.r[6][d], sel);
     return b;
+}
+
+// A operand of a lane for a row of X scaled by the gain: x[8 K values] * g, rounded to the storage format;
+// the raw squares are added to ss.
+template <typename F>
+__device__ __forceinline__ u32x4 scaled_a_operand(u32x4 x, u32x4 gg, float& ss) {
+    u32x4 a;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const float x0 = F::lo(x[d]), x1 = F::hi(x[d]);
+        ss = fmaf(x0, x0, ss);
+        ss = fmaf(x1, x1, ss);
+        a[d] = F::pack(x0 * F::lo(gg[d]), x1 * F::hi(gg[d]));
+    }
+    return a;
+}
+
+// A wavefront's 16 x 128 accumulator tile (eight 16x16 MFMA results: accumulator j, element i of lane
+// (q, c) is row 4q + i, column 8c + j) stored as rows of `pitch` floats at `tile`.  A lane owns 32 bytes
+// of a row; lanes c and c + 8 are 256 bytes apart, the same banks: the upper eight write their second
+// half first, so that one store instruction covers 16 different 16-byte bank groups.
+__device__ __forceinline__ void store_acc_tile(float* tile, int pitch, int q, int c, const f32x4 (&acc)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float* dst = tile + (4 * q + i) * pitch + 8 * c;
+        const f32x4 lo = f32x4{acc[0][i], acc[1][i], acc[2][i], acc[3][i]};
+        const f32x4 hi = f32x4{acc[4][i], acc[5][i], acc[6][i], acc[7][i]};
+        const bool upper = (c & 8) != 0;
+        *(f32x4*)(dst + (upper ? 4 : 0)) = upper ? hi : lo;
+        *(f32x4*)(dst + (upper ? 0 : 4)) = upper ? lo : hi;
+    }
 }
 
 }  // namespace prism
