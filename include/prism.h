@@ -173,6 +173,8 @@ prism_status_t prism_rmsnorm_gated_mlp_f32(const void* X, const void* g, const v
  *   place the library waits on the device) and every kernel leaves them zero again.  The
  *   memory must outlive all enqueued work.  Calls that use the workspace must not overlap in
  *   time on one device (use one stream, or order the streams).  Passing NULL/0 unregisters.
+ *   The calls themselves only enqueue kernels (no memset, no allocation, no synchronisation), so a
+ *   sequence of them may be recorded in a HIP graph and replayed (tested).
  */
 #define PRISM_WORKSPACE_HEADER_BYTES 262144u
 uint64_t prism_workspace_bytes(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype);

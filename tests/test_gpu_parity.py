@@ -522,6 +522,55 @@ def test_calls_that_need_a_workspace_fail_loudly_without_one(P):
     assert bool(torch.isfinite(Y.float()).all()) and bool(torch.isfinite(Ys.float()).all()) and bool(torch.isfinite(O.float()).all())
 
 
+def test_calls_can_be_captured_in_a_hip_graph_and_replayed(P):
+    """A serving loop records its launches once: four calls that use the workspace (decode, multi-row decode, sliced
+    softmax, attention) are captured on a side stream and replayed, with eager work between the replays; every replay
+    must equal the eager result bit for bit (the kernels leave their arrival counters at zero)."""
+    import torch
+    X16 = torch.randn(16, 4096, device="cuda").bfloat16()
+    X40 = torch.randn(40, 4096, device="cuda").bfloat16()
+    g = (torch.rand(4096, device="cuda") + 0.5).bfloat16()
+    W = (torch.randn(4096, 2048, device="cuda") / 64).bfloat16()
+    W2 = (torch.randn(4096, 2048, device="cuda") / 64).bfloat16()
+    Xs = (torch.randn(16, 16384, device="cuda") * 3).half()
+    Ws = torch.randn(16384, 128, device="cuda").half()
+    Q = torch.randn(2, 8, 128, device="cuda").half()
+    Kc = torch.randn(2, 2048, 128, device="cuda").half()
+    Vc = torch.randn(2, 2048, 128, device="cuda").half()
+    outs = [torch.empty(16, 2048, device="cuda", dtype=torch.bfloat16), torch.empty(40, 2048, device="cuda", dtype=torch.bfloat16),
+            torch.empty(16, 128, device="cuda", dtype=torch.float16), torch.empty(2, 8, 128, device="cuda", dtype=torch.float16)]
+
+    def calls(stream=None):
+        P.prism_rmsnorm_matmul(X16, g, W, outs[0], stream=stream)
+        P.prism_rmsnorm_gated_mlp(X40, g, W, W2, outs[1], stream=stream)
+        P.prism_softmax_matmul(Xs, Ws, outs[2], stream=stream)
+        P.prism_gqa_decode_attention(Q, Kc, Vc, outs[3], scale=0.09, qk_norm=True, stream=stream)
+
+    assert P.prism_plan(0, 16, 4096, 2048, P.PRISM_BF16)["split_k"] > 1
+    assert P.prism_plan(1, 40, 4096, 2048, P.PRISM_BF16)["split_k"] > 1
+    calls()                      # eager: sizes the workspace, opts the kernels into their LDS sizes
+    torch.cuda.synchronize()
+    ref = [o.clone() for o in outs]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            calls(stream=side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for o in outs:
+            o.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for o, r in zip(outs, ref):
+            assert torch.equal(o.view(torch.uint16), r.view(torch.uint16)), f"replay {rep}"
+        calls()                  # eager work between the replays
+        torch.cuda.synchronize()
+        for o, r in zip(outs, ref):
+            assert torch.equal(o.view(torch.uint16), r.view(torch.uint16)), f"eager after replay {rep}"
+
+
 # ---- parameter instantiation by sampling and timing (paper Section 5) -------------------------------
 
 def test_tuner_installs_a_plan_that_is_correct_and_not_slower(P):
