@@ -39,6 +39,13 @@ struct Bf16 {
     static __device__ __forceinline__ float lo(u32 u) { return bf16_lo(u); }
     static __device__ __forceinline__ float hi(u32 u) { return bf16_hi(u); }
     static __device__ __forceinline__ u32 pack(float a, float b) { return pack_bf16(a, b); }
+    // Largest of the eight elements of four dwords.
+    static __device__ __forceinline__ float max8(u32x4 x) {
+        float v = lo(x[0]);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) v = fmaxf(v, fmaxf(lo(x[d]), hi(x[d])));
+        return v;
+    }
     static __device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
                                                        0, 0);
@@ -55,6 +62,12 @@ struct F16 {
     static __device__ __forceinline__ u32 pack(float a, float b) {
         const f16x2 v = {(_Float16)a, (_Float16)b};
         return __builtin_bit_cast(u32, v);
+    }
+    // Largest of the eight elements of four dwords: pairwise in the storage format (packed maximum), widened once.
+    static __device__ __forceinline__ float max8(u32x4 x) {
+        f16x2 m = __builtin_elementwise_max(__builtin_bit_cast(f16x2, x[0]), __builtin_bit_cast(f16x2, x[1]));
+        m = __builtin_elementwise_max(m, __builtin_elementwise_max(__builtin_bit_cast(f16x2, x[2]), __builtin_bit_cast(f16x2, x[3])));
+        return fmaxf((float)m[0], (float)m[1]);
     }
     static __device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,

@@ -105,10 +105,7 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
         float cm = -__builtin_inff();
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
-            float v = F::lo(xs[u][0]);
-#pragma unroll
-            for (int d = 0; d < 4; ++d) v = fmaxf(v, fmaxf(F::lo(xs[u][d]), F::hi(xs[u][d])));
-            cm = fmaxf(cm, (k_valid(i0 + u * NW) && row_ok) ? v : -__builtin_inff());
+            cm = fmaxf(cm, (k_valid(i0 + u * NW) && row_ok) ? F::max8(xs[u]) : -__builtin_inff());
         }
         cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
         cm = fmaxf(cm, __shfl_xor(cm, 32, 64));

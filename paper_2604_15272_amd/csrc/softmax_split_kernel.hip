@@ -34,14 +34,6 @@ constexpr int TPR = TN / CPT;      // 32 threads per output row
 constexpr int kRedFloats = NW * 16 * TN;
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <typename F>
-__device__ __forceinline__ float max8(u32x4 x) {
-    float v = F::lo(x[0]);
-#pragma unroll
-    for (int d = 0; d < 4; ++d) v = fmaxf(v, fmaxf(F::lo(x[d]), F::hi(x[d])));
-    return v;
-}
-
 }  // namespace
 
 template <typename F, bool RESIDENT>
@@ -106,7 +98,7 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
 #pragma unroll
             for (int r = 0; r < RG; ++r) {
                 const bool v = k_valid(wave + u * NW) && row_ok[r];
-                mx[r] = fmaxf(mx[r], v ? max8<F>(xk[u][r]) : -__builtin_inff());
+                mx[r] = fmaxf(mx[r], v ? F::max8(xk[u][r]) : -__builtin_inff());
             }
     } else {
         constexpr int U = 8;
@@ -121,7 +113,7 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
 #pragma unroll
                 for (int r = 0; r < RG; ++r) {
                     const bool v = k_valid(i + u * NW) && row_ok[r];
-                    mx[r] = fmaxf(mx[r], v ? max8<F>(xr[u][r]) : -__builtin_inff());
+                    mx[r] = fmaxf(mx[r], v ? F::max8(xr[u][r]) : -__builtin_inff());
                 }
         }
     }
