@@ -115,6 +115,31 @@ class Runner:
             self.args, self.sets = saved
         return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
+    def probe(self, steps, warmup):
+        """The library's read-only probe over the same rotating weight sets, with this workload's split: what
+        streaming W alone costs (HIP-event ms per launch)."""
+        torch, P = self.torch, self.P
+        vp, i64 = ctypes.c_void_p, ctypes.c_int64
+        stream = vp(torch.cuda.current_stream().cuda_stream)
+        P.ensure_workspace(1 << 20)
+        args = [(vp(w[0].data_ptr()), vp(w[1].data_ptr()) if self.wl.gated else None, i64(self.wl.K), i64(self.wl.N),
+                 ctypes.c_int32(self.plan["split_k"]), stream) for w in self.W]
+
+        def run(n, first=0):
+            for i in range(n):
+                st = P.lib.prism_probe_stream(*args[(first + i) % self.sets])
+                if st != 0:
+                    raise RuntimeError(f"probe failed: {P.prism_status_string(st)}")
+
+        run(warmup)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run(steps, first=warmup)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
     def output(self, s=0):
         import torch
         y = self.Y[s]
@@ -147,10 +172,14 @@ def measure(idx, steps, warmup):
         _, hot_ms = r.timed(steps, warmup, sets_used=1)
         res["cache_hot_kernel_ms"] = hot_ms
         res["cache_hot_GBps"] = nbytes / (hot_ms * 1e-3) / 1e9
+        res["stream_probe_ms"] = r.probe(steps, warmup)
     else:
         res.update(value=flops / (wall_ms * 1e-3) / 1e12, unit="TFLOP/s", bound="mfma",
                    achieved=flops / (k_mean * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS)
     res["frac"] = res["achieved"] / res["peak"]
+    if "stream_probe_ms" in res:
+        log(f"[bench]   read-only probe, same access pattern and split: {res['stream_probe_ms'] * 1e3:.2f} us per launch "
+            f"({nbytes / (res['stream_probe_ms'] * 1e-3) / 1e9:.0f} GB/s)")
     log(f"[bench]   {res['value']:.1f} {res['unit']} back-to-back ({wall_ms * 1e3:.2f} us/step wall, "
         f"{ev_ms * 1e3:.2f} by events); kernel alone {k_mean * 1e3:.2f} us -> {res['achieved']:.1f} {res['unit']} "
         f"= {100 * res['frac']:.1f}% of {res['bound']} peak")
@@ -445,6 +474,11 @@ def main():
                      "kernel_ms_per_launch": head["kernel_ms"],
                      "timing": "HIP events around the timed region on the launch stream, divided by the launches"},
     }
+    if "stream_probe_ms" in head:
+        out["roofline"]["stream_probe"] = {
+            "ms_per_launch": head["stream_probe_ms"],
+            "GBps": head["bytes_per_launch"] / (head["stream_probe_ms"] * 1e-3) / 1e9,
+            "note": "prism_probe_stream: W read once with the kernel's access pattern and split, nothing computed"}
     if "cache_hot_GBps" in head:
         out["cache_hot"] = {"GBps": head["cache_hot_GBps"], "kernel_ms_per_launch": head["cache_hot_kernel_ms"],
                             "note": "single buffer set: W is served by the last-level cache, not HBM"}
@@ -462,7 +496,8 @@ def main():
             res, r = measure(idx, st, wu)
             del r
             others.append({k: res[k] for k in ("workload", "plan", "steps", "ms_per_step", "event_ms_per_step",
-                                               "kernel_ms", "value", "unit", "bound", "achieved", "peak", "frac")})
+                                               "kernel_ms", "value", "unit", "bound", "achieved", "peak", "frac",
+                                               "stream_probe_ms") if k in res})
         out["other_workloads"] = others
         torch.cuda.empty_cache()
         log("[bench] the paper's workloads at its shapes, fp16, no gain (output width assumed: see PAPER_SHAPES)")

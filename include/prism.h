@@ -214,6 +214,17 @@ prism_status_t prism_plan_table_set(prism_op_t op, int64_t M, int64_t K, int64_t
 prism_status_t prism_plan_table_clear(void);
 int32_t prism_plan_table_size(void);
 
+/*
+ * Diagnostic, for measurement: streams W[K,N] (16-bit elements, device memory, 16-byte aligned, N a multiple
+ * of 8; and W2 of the same shape unless NULL) once with the decode kernels' access pattern and split, and
+ * computes nothing.  Its duration is the
+ * floor that streaming W sets for a decode call on the machine at hand (bench.py reports it beside the
+ * kernels).  Needs a registered workspace of at least 2 * PRISM_WORKSPACE_HEADER_BYTES (one word past the
+ * counters may be written).
+ */
+prism_status_t prism_probe_stream(const void* W, const void* W2, int64_t K, int64_t N, int32_t split_k,
+                                  hipStream_t stream);
+
 const char* prism_status_string(prism_status_t status);
 int32_t prism_version(void);
 

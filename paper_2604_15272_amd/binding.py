@@ -86,6 +86,8 @@ def _load():
     L.prism_set_override.restype = i32
     L.prism_status_string.argtypes = [i32]
     L.prism_status_string.restype = ctypes.c_char_p
+    L.prism_probe_stream.argtypes = [vp, vp, i64, i64, i32, vp]
+    L.prism_probe_stream.restype = i32
     L.prism_version.argtypes = []
     L.prism_version.restype = i32
     return L

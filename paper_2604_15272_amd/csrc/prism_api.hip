@@ -638,6 +638,25 @@ int32_t prism_plan_table_size(void) {
     return g_table_size;
 }
 
+prism_status_t prism_probe_stream(const void* W, const void* W2, int64_t K, int64_t N, int32_t split_k,
+                                  hipStream_t stream) {
+    if (K <= 0 || N <= 0 || split_k < 1) return PRISM_ERR_INVALID_ARG;
+    if (!W || !aligned16(W) || !aligned16(W2)) return PRISM_ERR_INVALID_ARG;
+    const int64_t kblocks = (K + kDecodeKBlock - 1) / kDecodeKBlock;
+    const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
+    if (N % 8 != 0 || split_k > kblocks || split_k > 65535 || n_tiles > 0x7FFFFFFF) return PRISM_ERR_UNSUPPORTED;
+    // byte offsets inside a slice fit in 31 bits, as for the decode kernel
+    if ((uint64_t)((kblocks + split_k - 1) / split_k * kDecodeKBlock + 8) * (uint64_t)N * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
+    const Workspace w = g_workspace[dev];
+    if (!w.ptr || w.bytes < 2ull * PRISM_WORKSPACE_HEADER_BYTES) return PRISM_ERR_WORKSPACE;
+    // the probe's one possible store goes past the arrival counters
+    unsigned* sink = (unsigned*)((char*)w.ptr + PRISM_WORKSPACE_HEADER_BYTES);
+    return launch_probe_stream(W, W2, sink, (int)K, (int)N, split_k, stream) == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
+}
+
 const char* prism_status_string(prism_status_t status) {
     switch (status) {
         case PRISM_OK: return "ok";

@@ -522,6 +522,31 @@ def test_calls_that_need_a_workspace_fail_loudly_without_one(P):
     assert bool(torch.isfinite(Y.float()).all()) and bool(torch.isfinite(Ys.float()).all()) and bool(torch.isfinite(O.float()).all())
 
 
+def test_stream_probe_runs_and_writes_nothing(P):
+    """The read-only probe bench.py times beside the decode kernels: one and two matrices, ragged K and N, and the
+    workspace word it may write stays as it was."""
+    import ctypes
+    import torch
+    from paper_2604_15272_amd import binding
+    vp = ctypes.c_void_p
+    P.ensure_workspace(1 << 20)
+    buf = binding._workspaces[torch.cuda.current_device()]
+    buf[262144:262148] = 0x5A
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    for K, N, S, two in ((4096, 4096, 8, False), (4096, 14336, 2, True), (1000, 264, 3, False), (72, 8, 1, True)):
+        W = torch.randn(K, N, device="cuda").bfloat16()
+        W2 = torch.randn(K, N, device="cuda").bfloat16() if two else None
+        for _ in range(3):
+            assert P.lib.prism_probe_stream(vp(W.data_ptr()), vp(W2.data_ptr()) if two else None, K, N, S, stream) == 0
+        torch.cuda.synchronize()
+    assert bool((buf[262144:262148] == 0x5A).all())
+    P.prism_set_workspace(0, 0)
+    try:
+        assert P.lib.prism_probe_stream(vp(W.data_ptr()), None, 72, 8, 1, stream) == 3
+    finally:
+        P.prism_set_workspace(buf.data_ptr(), buf.numel())
+
+
 def test_calls_can_be_captured_in_a_hip_graph_and_replayed(P):
     """A serving loop records its launches once: four calls that use the workspace (decode, multi-row decode, sliced
     softmax, attention) are captured on a side stream and replayed, with eager work between the replays; every replay

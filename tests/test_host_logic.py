@@ -100,6 +100,13 @@ def test_override_and_workspace_size(P):
         P.prism_set_override(9, 0, 0)
 
 
+def test_probe_arguments_need_no_device(P):
+    L, a = P.lib, 0x1000
+    pr = lambda W=a, W2=None, K=4096, N=4096, S=8: L.prism_probe_stream(W, W2, K, N, S, None)
+    assert pr(W=None) == 1 and pr(W=a + 2) == 1 and pr(W2=a + 2) == 1 and pr(K=0) == 1 and pr(N=0) == 1 and pr(S=0) == 1
+    assert pr(N=4100) == 2 and pr(S=129) == 2 and pr(K=1 << 20, N=1 << 20, S=1) == 2
+
+
 def test_softmax_matmul_arguments_and_plan(P):
     L = P.lib
     a = 0x1000
