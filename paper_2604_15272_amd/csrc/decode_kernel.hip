@@ -41,7 +41,7 @@ __device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], u32x4 a, const WRows
 
 }  // namespace
 
-// LDS: per wavefront a 16 x 128 fp32 tile, plus 16 sums of squares.
+// LDS: per wavefront a 16 x 128 fp32 tile (two for gated calls with up to eight wavefronts), plus 16 sums of squares.
 template <typename F, int NW, bool GATED>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restrict__ X,
                                                          const uint16_t* __restrict__ g,
@@ -132,30 +132,41 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     const int n = n0 + col;
     const bool out_ok = (m < M) && (n < N);  // N % 8 == 0 and CPT | 8: all CPT columns valid together
 
-    // Reduce across wavefronts through LDS, one weight matrix at a time (the tile of W2 reuses the
-    // space).  Accumulator j, element i of lane (q, c) is row 4q + i, column 8c + j of the tile.
+    // Reduce across wavefronts through LDS.  Accumulator j, element i of lane (q, c) is row 4q + i, column
+    // 8c + j of the tile.  A gated call stores both matrices' tiles at once when LDS holds them (up to eight
+    // wavefronts): one barrier instead of three (measured: 44.5 -> 43.3 us on X[8,4096], 2 x W[4096,14336]);
+    // otherwise the tile of W2 reuses the space of W1's.
+    constexpr bool BOTH_TILES = GATED && NW <= 8;
+    float* red2 = red + NW * 16 * TN + NW * 16;  // behind ss_red
     float v1[CPT], v2[CPT];
     float ssum = 0.f;
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
+    for (int gi = 0; gi < (BOTH_TILES ? 1 : G); ++gi) {
         if (gi == 1) __syncthreads();
         store_acc_tile(red + wave * 16 * TN, TN, q, c, gi == 0 ? acc1 : acc2);
+        if (BOTH_TILES) store_acc_tile(red2 + wave * 16 * TN, TN, q, c, acc2);
         if (gi == 0 && q == 0) ss_red[wave * 16 + c] = ss;
         __syncthreads();
-        float v[CPT];
+        float v[CPT], vb[CPT];
 #pragma unroll
-        for (int e = 0; e < CPT; ++e) v[e] = 0.f;
+        for (int e = 0; e < CPT; ++e) { v[e] = 0.f; vb[e] = 0.f; }
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const float* src = red + (w * 16 + m) * TN + col;
 #pragma unroll
             for (int e = 0; e < CPT; ++e) v[e] += src[e];
+            if (BOTH_TILES) {
+                const float* src2 = red2 + (w * 16 + m) * TN + col;
+#pragma unroll
+                for (int e = 0; e < CPT; ++e) vb[e] += src2[e];
+            }
             if (gi == 0) ssum += ss_red[w * 16 + m];
         }
 #pragma unroll
         for (int e = 0; e < CPT; ++e) {
             if (gi == 0) v1[e] = v[e];
             else v2[e] = v[e];
+            if (BOTH_TILES) v2[e] = vb[e];
         }
     }
     if (!GATED) {
@@ -247,7 +258,7 @@ template <typename F, int NW>
 static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& ws) {
     const int n_tiles = (c.N + TN - 1) / TN;
     dim3 grid(n_tiles, S), block(NW * 64);
-    const size_t lds = (size_t)(NW * 16 * TN + NW * 16) * sizeof(float);
+    const size_t lds = (size_t)(((c.gated && NW <= 8) ? 2 : 1) * NW * 16 * TN + NW * 16) * sizeof(float);
     auto* X = (const uint16_t*)c.X;
     auto* g = (const uint16_t*)c.g;
     auto* W1 = (const uint16_t*)c.W1;
