@@ -8,15 +8,18 @@
 // with the partial product).
 //
 // Matrix-core kernel (16-bit storage, D = 128, G <= 16): a workgroup of four wavefronts owns one
-// batch entry and one slice of the keys.
+// batch entry and one slice of the keys; a wavefront takes the slice's 32-key blocks round-robin and
+// runs its own softmax over them, so nothing is synchronised until the partial outputs meet.
 //   1. scores: K is D-contiguous, which is the layout of an MFMA B operand (8 head-dimension
 //      values per lane), so a lane loads its operand of key c straight from memory; Q as stored is the
-//      A operand, rows padded to 16.  The 16 x 32 score blocks go to LDS.  The scale and, for
-//      QK-Attention, 1/rms of the head are applied to the scores, not to Q (the paper's rewrite:
-//      the division by the norm commutes with the matmul, Table 1).
-//   2. per row: maximum, exp, rounding to the storage format, sum of the rounded values (LDS).
-//   3. values: P from LDS is the A operand, a 32 x 128 block of V is turned into B operands as in the
-//      decode kernel (8 x 8 sub-blocks, byte permutes); partial outputs of the wavefronts meet in LDS.
+//      A operand, rows padded to 16.  The scale and, for QK-Attention, 1/rms of the head are applied
+//      to the scores, not to Q (the paper's rewrite: the division by the norm commutes with the
+//      matmul, Table 1).
+//   2. per head: running maximum over the wavefront's blocks (accumulators rescaled when it moves), exp,
+//      rounding to the storage format, sum of the rounded values; all in the registers the scores landed in.
+//   3. values: the rounded 16 x 32 tile of P goes through the wavefront's own piece of LDS into A-operand
+//      layout; a 32 x 128 block of V is turned into B operands as in the decode kernel (8 x 8 sub-blocks,
+//      byte permutes).  The wavefronts' partial outputs, each relative to its own maximum, meet in LDS.
 //   4. slices: each stores (partial output, maximum, sum) with device-coherent stores, waits for
 //      the acknowledgement and takes a ticket; the last arrival of a batch entry rescales and adds
 //      the partials in slice order, divides and stores O.  With one slice the division is direct.
@@ -80,15 +83,13 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
     constexpr int CPT = 16 * AD / NT;  // 8 output columns per thread
     constexpr int TPR = AD / CPT;      // 16 threads per output row
     const int KS = slice_keys;         // keys per slice, a multiple of 32
-    const int PP = KS + 8;             // row pitch of P in elements (keeps the operand reads off each other's banks)
+    constexpr int PW = 40;             // row pitch (elements) of a wavefront's 16 x 32 tile of P: rows 80 bytes apart
 
     extern __shared__ float lds[];
-    float* sc = lds;                                  // [16][KS] scores
-    uint16_t* pr = (uint16_t*)(lds + 16 * KS);        // [16][PP] exp(score - max), storage format
-    float* red = (float*)(pr + 16 * PP);              // [ANW][16][AD]
-    float* m_row = red + ANW * 16 * AD;               // [16]
-    float* l_row = m_row + 16;                        // [16]
-    float* f_row = l_row + 16;                        // [16] factor applied to the scores of a head
+    float* red = lds;                                   // [ANW][16][AD] partial outputs
+    float* wm = red + ANW * 16 * AD;                    // [ANW][16] running maxima of the wavefronts
+    float* wl = wm + ANW * 16;                          // [ANW][16] their sums of exponentials
+    uint16_t* pr = (uint16_t*)(wl + ANW * 16);          // [ANW][16][PW] exp(score - max), storage format
     __shared__ int is_last;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -104,15 +105,15 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
 
     // ---- Q as A operands of the four 32-deep blocks of the head dimension; lane (q, c): head c.
     u32x4 a_q[4];
+    float f4[4];  // factor applied to the scores of heads 4q .. 4q+3 (the rows this lane holds of a score block)
     {
-        u32x4 raw[4];
         float ss = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb) {
-            raw[kb] = load16(rq, c < G ? (u32)((c * AD + 32 * kb + 8 * q) * 2) : kOutOfRange);
+            a_q[kb] = load16(rq, c < G ? (u32)((c * AD + 32 * kb + 8 * q) * 2) : kOutOfRange);
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
-                const float x0 = F::lo(raw[kb][d]), x1 = F::hi(raw[kb][d]);
+                const float x0 = F::lo(a_q[kb][d]), x1 = F::hi(a_q[kb][d]);
                 ss = fmaf(x0, x0, ss);
                 ss = fmaf(x1, x1, ss);
             }
@@ -122,17 +123,28 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
         // The factor of a head (scale, times 1/rms when Q is normalised) goes on after the product with
         // K (paper Table 1, "matmul commutes with div denominator"): Q enters the matrix core as stored, with
         // no second rounding, and the sums of squares ride along the operand loads.
-        if (q == 0) f_row[c] = qk_norm ? scale * __builtin_amdgcn_rsqf(ss / (float)AD + eps) : scale;
+        const float f_c = qk_norm ? scale * __builtin_amdgcn_rsqf(ss / (float)AD + eps) : scale;  // head c
 #pragma unroll
-        for (int kb = 0; kb < 4; ++kb) a_q[kb] = raw[kb];
+        for (int i = 0; i < 4; ++i) f4[i] = __shfl(f_c, 4 * q + i, 64);
     }
 
-    // The V block of this wavefront's first key block is requested now, two barriers before it is used.
+    // The V block of this wavefront's first key block is requested now, before its scores are computed.
     WRows w_first;
     const u32 v_lane = (u32)(((size_t)(key0 + 8 * q) * AD) * 2 + 16 * c);
     load_w_block<true>(w_first, rv, wave < nblk ? v_lane + (u32)(32 * wave * AD * 2) : kOutOfRange, (u32)(AD * 2));
 
-    // ---- 1. scores of this slice's keys -> LDS.  Element i of the block in lane (q, c): head 4q + i, key c.
+    // ---- A wavefront takes the slice's 32-key blocks round-robin and runs its own softmax over them: scores on
+    // the matrix cores (element i of a block in lane (q, c): head 4q + i, key c), a running maximum per head
+    // with the accumulators rescaled when it moves, exp and rounding, the rounded tile through the wavefront's
+    // own piece of LDS into operand layout (head c, keys 8q .. 8q+7), then P . V.  No barrier until the
+    // wavefronts' partials meet.
+    float m_run[4], l_run[4];
+    f32x4 acc[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { m_run[i] = -__builtin_inff(); l_run[i] = 0.f; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    uint16_t* pw = pr + wave * 16 * PW;
     for (int jb = wave; jb < nblk; jb += ANW) {
         u32x4 kf[2][4];
 #pragma unroll
@@ -142,58 +154,41 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
             for (int kb = 0; kb < 4; ++kb)
                 kf[half][kb] = load16_stream(rk, key < H ? (u32)(((size_t)key * AD + 32 * kb + 8 * q) * 2) : kOutOfRange);
         }
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb) acc = F::mfma_16x16x32(a_q[kb], kf[half][kb], acc);
-            const int kl = 32 * jb + 16 * half + c;
-            const bool valid = key0 + kl < H;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) sc[(4 * q + i) * KS + kl] = valid ? acc[i] : -__builtin_inff();
-        }
-    }
-    __syncthreads();
-
-    // ---- 2. per row: maximum, exp, rounding, sum of what was rounded.  A wavefront takes four rows at
-    // once, sixteen lanes per row (lane (q, c): row 4 wave + q, keys c, c + 16, ...).
-    const int kpad = 32 * nblk;
-    {
-        const int r = 4 * wave + q;
-        const float f = f_row[r];
-        // A key past the end was stored as -inf and stays -inf whatever the sign of the factor.
-        auto scaled = [&](int k) {
-            const float x = sc[r * KS + k];
-            return x == -__builtin_inff() ? x : x * f;
-        };
-        float mx = -__builtin_inff();
-        for (int k = c; k < kpad; k += 16) mx = fmaxf(mx, scaled(k));
-#pragma unroll
-        for (int off = 8; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-        float sum = 0.f;
-        for (int k = c; k < kpad; k += 16) {
-            const float e = __builtin_amdgcn_exp2f((scaled(k) - mx) * kLog2e);
-            const u32 packed = F::pack(e, 0.f);
-            pr[r * PP + k] = (uint16_t)(packed & 0xFFFFu);
-            sum += F::lo(packed);
-        }
-#pragma unroll
-        for (int off = 8; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
-        if (c == 0) {
-            m_row[r] = mx;
-            l_row[r] = sum;
-        }
-    }
-    __syncthreads();
-
-    // ---- 3. P . V: lane (q, c) of the A operand is head c, keys 8q .. 8q+7 of the block.
-    f32x4 acc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int jb = wave; jb < nblk; jb += ANW) {
         WRows w = w_first;
         if (jb != wave) load_w_block<true>(w, rv, v_lane + (u32)(32 * jb * AD * 2), (u32)(AD * 2));
-        const u32x4 a = *(const u32x4*)(pr + c * PP + 32 * jb + 8 * q);
+        float sc[2][4];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            f32x4 t = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb) t = F::mfma_16x16x32(a_q[kb], kf[half][kb], t);
+            const bool valid = key0 + 32 * jb + 16 * half + c < H;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) sc[half][i] = valid ? t[i] * f4[i] : -__builtin_inff();
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float mb = fmaxf(sc[0][i], sc[1][i]);
+#pragma unroll
+            for (int off = 8; off > 0; off >>= 1) mb = fmaxf(mb, __shfl_xor(mb, off, 64));
+            const float m_new = fmaxf(m_run[i], mb);
+            // nothing accumulated yet: factor 1 (and no -inf minus -inf)
+            const float fac = (m_run[i] == -__builtin_inff()) ? 1.0f : __builtin_amdgcn_exp2f((m_run[i] - m_new) * kLog2e);
+            m_run[i] = m_new;
+            l_run[i] *= fac;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j][i] *= fac;
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const float x = sc[half][i];
+                const float e = (x == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((x - m_new) * kLog2e);
+                const u32 packed = F::pack(e, 0.f);
+                l_run[i] += F::lo(packed);  // the sum weighs what the product will see: the rounded value
+                pw[(4 * q + i) * PW + 16 * half + c] = (uint16_t)(packed & 0xFFFFu);
+            }
+        }
+        // The wavefront reads what it wrote (its LDS accesses complete in order).
+        const u32x4 a = *(const u32x4*)(pw + c * PW + 8 * q);
         acc[0] = F::mfma_16x16x32(a, b_operand<0>(w), acc[0]);
         acc[1] = F::mfma_16x16x32(a, b_operand<1>(w), acc[1]);
         acc[2] = F::mfma_16x16x32(a, b_operand<2>(w), acc[2]);
@@ -203,28 +198,44 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
         acc[6] = F::mfma_16x16x32(a, b_operand<6>(w), acc[6]);
         acc[7] = F::mfma_16x16x32(a, b_operand<7>(w), acc[7]);
     }
-    // Across wavefronts through LDS.  Accumulator j, element i of lane (q, c) is head 4q + i, column 8c + j.
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) l_run[i] += __shfl_xor(l_run[i], off, 64);
+        if (c == 0) {
+            wm[wave * 16 + 4 * q + i] = m_run[i];
+            wl[wave * 16 + 4 * q + i] = l_run[i];
+        }
+    }
+
+    // ---- across wavefronts through LDS: each partial is relative to its wavefront's maximum.  Accumulator j,
+    // element i of lane (q, c) is head 4q + i, column 8c + j.
     store_acc_tile(red + wave * 16 * AD, AD, q, c, acc);
     __syncthreads();
     const int m = tid / TPR;           // head
     const int col = (tid % TPR) * CPT; // first of 8 output columns
-    float v[CPT];
+    float row_max = -__builtin_inff();
+#pragma unroll
+    for (int w = 0; w < ANW; ++w) row_max = fmaxf(row_max, wm[w * 16 + m]);
+    float v[CPT], den = 0.f;
 #pragma unroll
     for (int e = 0; e < CPT; ++e) v[e] = 0.f;
 #pragma unroll
     for (int w = 0; w < ANW; ++w) {
+        const float mw = wm[w * 16 + m];
+        const float fw = (mw == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((mw - row_max) * kLog2e);  // a wavefront without keys
         const float* src = red + (w * 16 + m) * AD + col;
 #pragma unroll
-        for (int e = 0; e < CPT; ++e) v[e] += src[e];
+        for (int e = 0; e < CPT; ++e) v[e] = fmaf(fw, src[e], v[e]);
+        den = fmaf(fw, wl[w * 16 + m], den);
     }
-    float den = l_row[m];
 
     // ---- 4. across the slices of this batch entry
     if (S > 1) {
         const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)gridDim.y * S * 16 * AD);
         store_partial<CPT>(racc, acc_part, (((size_t)bi * S + s) * 16 + m) * AD + col, v);
         if (col == 0) {
-            store_coherent(m_part + ((size_t)bi * S + s) * 16 + m, m_row[m]);
+            store_coherent(m_part + ((size_t)bi * S + s) * 16 + m, row_max);
             store_coherent(l_part + ((size_t)bi * S + s) * 16 + m, den);
         }
         wait_stores_acknowledged();
@@ -278,14 +289,13 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
     *(u32x4*)(O + ((size_t)bi * G + m) * AD + col) = out;
 }
 
-size_t attention_lds_bytes(int slice_keys) {
-    return (size_t)(16 * slice_keys) * 4 + (size_t)16 * (slice_keys + 8) * 2 + (size_t)(ANW * 16 * AD + 48) * 4;
-}
+// Partial outputs, maxima and sums of the wavefronts, and their 16 x 32 tiles of P (row pitch 40 elements).
+constexpr size_t kAttentionLdsBytes = (size_t)(ANW * 16 * AD + 2 * ANW * 16) * 4 + (size_t)ANW * 16 * 40 * 2;
 
 template <typename F>
 static hipError_t launch_gqa_fmt(const AttentionCall& c, const AttentionPlan& p, const AttentionWorkspace& ws) {
     dim3 grid(p.splits, c.B), block(ANW * 64);
-    const size_t lds = attention_lds_bytes(p.slice_keys);
+    const size_t lds = kAttentionLdsBytes;
     auto kern = gqa_decode_kernel<F>;
     static std::atomic<uint64_t> opted{0};
     if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
