@@ -215,6 +215,21 @@ prism_status_t prism_plan_table_clear(void);
 int32_t prism_plan_table_size(void);
 
 /*
+ * Stream balancing of the 16-row decode kernel (the reduction partition of paper Table 1, "parallelized matmul
+ * (reduction)", with a partition that is not uniform over the column tiles).  When the row pitch of W is a multiple
+ * of 2 KiB, the 256-byte-wide stripe a workgroup streams keeps bits 8-10 of its byte addresses (its slot) for
+ * every row; on MI355X the stripes in slots 1 and 5 arrive 20 % slower than the rest.  Their column tiles are
+ * therefore cut into split_k + extra K-slices (prism_plan reports the base split_k, a one-dimensional grid, and
+ * the workspace for split_k + extra slices).  The slots are read off the address of W: the balanced launch needs W
+ * (and W2, in step with W1 modulo 2 KiB) on a 256-byte boundary and N a multiple of 1024; otherwise every tile gets
+ * split_k slices.  The number of slices decides the order of the fp32 sums, so results may differ in the last bit
+ * between buffers in different slots; for given addresses they are reproducible.
+ * slow_slots: bit s set = slot s is slow (0: no balancing, the default; 0x22 on the MI355X measured); extra_slices: -1 = the library's rule
+ * (about a quarter more slices, never more workgroups than CUs), 0..64 = that many.  Host-side, process-wide.
+ */
+prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t extra_slices);
+
+/*
  * Diagnostic, for measurement: streams W[K,N] (16-bit elements, device memory, 16-byte aligned, N a multiple
  * of 8; and W2 of the same shape unless NULL) once with the decode kernels' access pattern and split, and
  * computes nothing.  Its duration is the

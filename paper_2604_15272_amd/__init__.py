@@ -34,6 +34,7 @@ from .binding import (  # noqa: F401
     prism_attention_plan,
     prism_rmsnorm_matmul,
     prism_set_override,
+    prism_set_stream_balance,
     prism_set_workspace,
     prism_status_string,
     prism_version,

@@ -88,6 +88,8 @@ def _load():
     L.prism_status_string.restype = ctypes.c_char_p
     L.prism_probe_stream.argtypes = [vp, vp, i64, i64, i32, vp]
     L.prism_probe_stream.restype = i32
+    L.prism_set_stream_balance.argtypes = [i32, i32]
+    L.prism_set_stream_balance.restype = i32
     L.prism_version.argtypes = []
     L.prism_version.restype = i32
     return L
@@ -159,6 +161,12 @@ def prism_set_override(path=0, split_k=0, variant=0):
     st = lib.prism_set_override(int(path), int(split_k), int(variant))
     if st != 0:
         raise PrismError(st, "prism_set_override")
+
+
+def prism_set_stream_balance(slow_slots=0x22, extra_slices=-1):
+    st = lib.prism_set_stream_balance(int(slow_slots), int(extra_slices))
+    if st != 0:
+        raise PrismError(st, "prism_set_stream_balance")
 
 
 def prism_plan_table_set(op, M, K, N, dtype, path, split_k=0, variant=0):

@@ -49,7 +49,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
                                                          const uint16_t* __restrict__ W2,
                                                          uint16_t* __restrict__ Y, float* __restrict__ acc_part,
                                                          float* __restrict__ ss_part, unsigned* __restrict__ tickets,
-                                                         int M, int K, int N, float eps, int S, int flags) {
+                                                         int M, int K, int N, float eps, int S_base, int flags,
+                                                         int extra, int slow_slots) {
     constexpr int G = GATED ? 2 : 1;
     constexpr int NT = NW * 64;
     constexpr int CPT = 16 * TN / NT;  // columns per thread in the epilogue (4 for 8 wavefronts)
@@ -63,7 +64,35 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = lane >> 4, c = lane & 15;
-    const int ntile = blockIdx.x, split = blockIdx.y;
+    // Which column tile and K-slice.  Plain launch: grid (column tiles, S).  Balanced launch (extra > 0, one-
+    // dimensional grid): the row pitch is a multiple of 2 KiB, so a tile's 256-byte columns keep address bits 8-10
+    // (its "slot") for every row, and tiles in the slots named by slow_slots, which stream slower, are cut into
+    // S_base + extra slices instead of S_base.  Eight consecutive tiles hold each slot once; their work items are
+    // numbered together (the common S_base slices of the eight tiles, then the extra ones), so that consecutive
+    // workgroups, which the dispatcher deals out to the XCDs in turn, do not pile the extra ones on two XCDs.
+    int ntile = blockIdx.x, split = blockIdx.y, S = S_base;
+    const int S_pitch = S_base + extra;  // slices per tile in the workspace
+    if (extra > 0) {
+        const int P = __popc((unsigned)slow_slots);
+        const int per_group = 8 * S_base + P * extra;
+        const int group = blockIdx.x / per_group, idx = blockIdx.x % per_group;
+        const int slot0 = (int)(((size_t)W1 >> 8) & 7);  // slot of tiles 0, 8, 16, ...
+        int j = idx & 7;
+        split = idx >> 3;
+        if (idx >= 8 * S_base) {
+            const int e = idx - 8 * S_base;
+            int k = e % P, slot = 0;
+            split = S_base + e / P;
+            for (int b = 0; b < 8; ++b)  // the k-th slow slot
+                if ((slow_slots >> b) & 1) {
+                    if (k == 0) slot = b;
+                    --k;
+                }
+            j = (slot - slot0) & 7;
+        }
+        ntile = 8 * group + j;
+        if ((slow_slots >> ((slot0 + j) & 7)) & 1) S += extra;
+    }
     const int n0 = ntile * TN;
 
     // This workgroup's K-blocks: [b_beg, b_beg + b_cnt).
@@ -181,13 +210,13 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         // stores write through, loads do not hit a stale L2 line), so that no whole-cache
         // write-back or invalidate is needed: a workgroup waits until its stores are acknowledged,
         // then takes its ticket; whoever draws the last ticket reads after that.
-        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)S * G * M * N);
+        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)S_pitch * G * M * N);
         if (out_ok) {
             const size_t idx = (((size_t)split * G) * M + m) * N + n;
             store_partial<CPT>(racc, acc_part, idx, v1);
             if (GATED) store_partial<CPT>(racc, acc_part, idx + (size_t)M * N, v2);
         }
-        if (col == 0) store_coherent(ss_part + ((size_t)ntile * S + split) * 16 + m, ssum);
+        if (col == 0) store_coherent(ss_part + ((size_t)ntile * S_pitch + split) * 16 + m, ssum);
         wait_stores_acknowledged();
         __syncthreads();
         if (tid == 0) {
@@ -211,7 +240,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
                 const int s = min(s0 + j, S - 1);
-                sq[j] = load_coherent(ss_part + ((size_t)ntile * S + s) * 16 + m);
+                sq[j] = load_coherent(ss_part + ((size_t)ntile * S_pitch + s) * 16 + m);
                 if (out_ok) {
                     const size_t idx = (((size_t)s * G) * M + m) * N + n;
                     load_partial<CPT>(racc, acc_part, idx, pa[j]);
@@ -255,9 +284,10 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 }
 
 template <typename F, int NW>
-static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& ws) {
+static hipError_t launch_decode_nw(const Call& c, int S, int extra, int slow_slots, const DecodeWorkspace& ws) {
     const int n_tiles = (c.N + TN - 1) / TN;
     dim3 grid(n_tiles, S), block(NW * 64);
+    if (extra > 0) grid = dim3((n_tiles / 8) * (8 * S + __builtin_popcount((unsigned)slow_slots) * extra));
     const size_t lds = (size_t)(((c.gated && NW <= 8) ? 2 : 1) * NW * 16 * TN + NW * 16) * sizeof(float);
     auto* X = (const uint16_t*)c.X;
     auto* g = (const uint16_t*)c.g;
@@ -269,29 +299,32 @@ static hipError_t launch_decode_nw(const Call& c, int S, const DecodeWorkspace& 
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W2, Y, ws.acc_part, ws.ss_part, ws.tickets,
-                           c.M, c.K, c.N, c.eps, S, c.flags);
+                           c.M, c.K, c.N, c.eps, S, c.flags, extra, slow_slots);
     } else {
         auto kern = decode_kernel<F, NW, false>;
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W1, Y, ws.acc_part, ws.ss_part, ws.tickets,
-                           c.M, c.K, c.N, c.eps, S, c.flags);
+                           c.M, c.K, c.N, c.eps, S, c.flags, extra, slow_slots);
     }
     return hipGetLastError();
 }
 
 template <typename F>
-static hipError_t launch_decode_fmt(const Call& c, int split_k, int waves, const DecodeWorkspace& ws) {
+static hipError_t launch_decode_fmt(const Call& c, int split_k, int extra, int slow_slots, int waves,
+                                    const DecodeWorkspace& ws) {
     switch (waves) {
-        case 4: return launch_decode_nw<F, 4>(c, split_k, ws);
-        case 8: return launch_decode_nw<F, 8>(c, split_k, ws);
-        case 16: return launch_decode_nw<F, 16>(c, split_k, ws);
+        case 4: return launch_decode_nw<F, 4>(c, split_k, extra, slow_slots, ws);
+        case 8: return launch_decode_nw<F, 8>(c, split_k, extra, slow_slots, ws);
+        case 16: return launch_decode_nw<F, 16>(c, split_k, extra, slow_slots, ws);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, const DecodeWorkspace& ws) {
-    return f16 ? launch_decode_fmt<F16>(c, split_k, waves, ws) : launch_decode_fmt<Bf16>(c, split_k, waves, ws);
+hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int extra, int slow_slots, int waves,
+                               const DecodeWorkspace& ws) {
+    return f16 ? launch_decode_fmt<F16>(c, split_k, extra, slow_slots, waves, ws)
+               : launch_decode_fmt<Bf16>(c, split_k, extra, slow_slots, waves, ws);
 }
 
 }  // namespace prism

@@ -18,6 +18,14 @@ struct Override {
 };
 Override g_override;
 
+// Address slots (bits 8-10 of the byte address: which 256 bytes of every 2 KiB) whose columns stream slower from
+// HBM, and how many more K-slices their tiles get (-1: the rule in make_plan_with).  Measured on MI355X with
+// per-workgroup time stamps: with a row pitch that is a multiple of 2 KiB a workgroup's 256-byte-wide stripe of W
+// stays in one slot, and the stripes in slots 1 and 5 finish 20 % later than the others (37 us against 30 us on
+// X[8,4096], 2 x W[4096,14336]) whichever XCD reads them; a row pitch of 225 x 256 bytes, which takes every
+// workgroup through all slots, finishes all of them at 32 us.
+std::atomic<int32_t> g_slow_slots{0}, g_balance_extra{-1};
+
 struct Workspace {
     void* ptr;
     uint64_t bytes;
@@ -30,6 +38,7 @@ struct Plan {
     prism_plan_t pub;
     int waves;          // decode: wavefronts per workgroup
     int row_groups;     // decode: 16-row groups per workgroup (1: the 16-row kernel)
+    int extra;          // decode, 16-row kernel: additional K-slices for the tiles in slow address slots
     uint64_t ss_bytes;  // decode: bytes of the partial sums of squares (rounded)
 };
 
@@ -296,19 +305,49 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             while (S > 1 && !partials_fit(S)) --S;
         if (S > 1 && !partials_fit(S)) return PRISM_ERR_UNSUPPORTED;
         if (!slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
+        // More slices for the column tiles in slow address slots (16-row kernel, row pitch a multiple of 2 KiB,
+        // whole groups of eight tiles), as long as every workgroup still finds a CU of its own.
+        int64_t extra = 0;
+        const int slow = g_slow_slots.load() & 0xFF;
+        if (row_groups == 1 && slow != 0 && (N * 2) % 2048 == 0 && n_tiles % 8 == 0) {
+            const int64_t P = __builtin_popcount((unsigned)slow);
+            auto total = [&](int64_t s, int64_t e) { return n_tiles / 8 * (8 * s + P * e); };
+            const int forced_extra = g_balance_extra.load();
+            if (forced_extra >= 0) {
+                extra = forced_extra;
+            } else if (S >= 2) {
+                int64_t s = S, e = (s + 2) / 4;
+                if (total(s, e) > 256 && forced_split <= 0 && s > 2) {
+                    --s;
+                    e = (s + 2) / 4;
+                }
+                if (total(s, e) <= 256) {
+                    S = s;
+                    extra = e;
+                }
+            }
+            if (S + extra > kblocks || S + extra > 65535 || !partials_fit(S + extra) ||
+                total(S, extra) > 0x7FFFFFFF)
+                extra = 0;
+        }
         out->waves = waves;
         out->row_groups = row_groups;
+        out->extra = (int)extra;
         p.split_k = (int32_t)S;
         p.tile_m = 16 * row_groups;
         p.tile_n = kDecodeTileN;
         p.grid_x = (int32_t)n_tiles;
         p.grid_y = (int32_t)S;
+        if (extra > 0) {
+            p.grid_x = (int32_t)(n_tiles / 8 * (8 * S + __builtin_popcount((unsigned)slow) * extra));
+            p.grid_y = 1;
+        }
         p.grid_z = (int32_t)row_blocks;
         p.block = waves * 64;
-        if (S > 1) {
-            out->ss_bytes = round_up((uint64_t)n_tiles * row_blocks * S * 16 * row_groups * 4, 256);
+        if (S + extra > 1) {
+            out->ss_bytes = round_up((uint64_t)n_tiles * row_blocks * (S + extra) * 16 * row_groups * 4, 256);
             p.workspace_bytes = PRISM_WORKSPACE_HEADER_BYTES + out->ss_bytes +
-                                (uint64_t)S * (gated ? 2 : 1) * M * N * 4;
+                                (uint64_t)(S + extra) * (gated ? 2 : 1) * M * N * 4;
         }
         return PRISM_OK;
     }
@@ -345,8 +384,7 @@ prism_status_t make_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, p
     if (B > 65535 || G > 65535 || D > 1024 || H > 0x7FFFFFFF / 2048) return PRISM_ERR_UNSUPPORTED;
     const int forced = g_override.path.load();
     if (forced != PRISM_PATH_AUTO && forced != PRISM_PATH_SIMPLE && forced != PRISM_PATH_ATTENTION) return PRISM_ERR_UNSUPPORTED;
-    const bool fast_ok = dtype != PRISM_F32 && D == kAttnHeadDim && G <= kAttnMaxHeads &&
-                         H <= (int64_t)kAttnMaxSlices * kAttnMaxSliceKeys;
+    const bool fast_ok = dtype != PRISM_F32 && D == kAttnHeadDim && G <= kAttnMaxHeads;
     if (forced == PRISM_PATH_ATTENTION && !fast_ok) return PRISM_ERR_UNSUPPORTED;
     if (forced == PRISM_PATH_SIMPLE || !fast_ok) return PRISM_OK;
     p->path = PRISM_PATH_ATTENTION;
@@ -354,16 +392,15 @@ prism_status_t make_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, p
     const int forced_split = g_override.split_k.load();
     int64_t S = forced_split;
     if (S <= 0) {
-        // 128 keys per workgroup (one 32-key block per wavefront) while that gives at most 16 slices; the
-        // combining workgroup reads the slices' partials, so beyond that the slices grow instead (measured:
-        // 8192 keys take 31 us in 64 slices, 22.5 us in 32).
+        // 128 keys per workgroup (one 32-key block per wavefront) up to eight slices, which the combining
+        // workgroup reads in one round trip; longer contexts get longer slices first and more of them later
+        // (measured with two batch entries: 2048 keys 12.6 us in 8 slices, 13.3 in 16; 8192 keys 18.8 us in
+        // 16, 21.1 in 32, 30.6 in 64).
         S = (H + keys - 1) / keys;
-        if (S > 16) S = std::min<int64_t>(32, std::max<int64_t>(16, (H + 255) / 256));
-        if ((H + S - 1) / S > kAttnMaxSliceKeys) S = kAttnMaxSlices;
+        if (S > 8) S = H <= 2048 ? 8 : (H <= 16384 ? 16 : 32);
     }
     if (S > kAttnMaxSlices) S = kAttnMaxSlices;
     keys = ((H + S - 1) / S + 31) / 32 * 32;
-    if (keys > kAttnMaxSliceKeys) return PRISM_ERR_UNSUPPORTED;  // a forced split too coarse for the LDS
     S = (H + keys - 1) / keys;  // no empty slice
     if (S > 1 && (uint64_t)B * S * 16 * kAttnHeadDim * 4 >= kTwoGiB) {
         // 31-bit offsets into the partials: a batch this large is left to the plain kernel
@@ -406,7 +443,7 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
             break;
         case PRISM_PATH_DECODE: {
             DecodeWorkspace ws{nullptr, nullptr, nullptr};
-            if (plan.pub.split_k > 1) {
+            if (plan.pub.split_k + plan.extra > 1) {
                 int dev = 0;
                 if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
                 if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
@@ -417,9 +454,16 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                 ws.ss_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES);
                 ws.acc_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES + plan.ss_bytes);
             }
+            // The slots are read off the addresses: the balanced launch needs W on a slot boundary (and W2 in
+            // step with W1); any other alignment gets the same slices for every tile.
+            int extra = plan.extra;
+            if ((reinterpret_cast<uintptr_t>(W1) & 255u) != 0 ||
+                (gated && ((reinterpret_cast<uintptr_t>(W1) ^ reinterpret_cast<uintptr_t>(W2)) & 2047u) != 0))
+                extra = 0;
             err = plan.row_groups > 1
                       ? launch_decode_rows_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.row_groups, ws)
-                      : launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.waves, ws);
+                      : launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, extra,
+                                            g_slow_slots.load() & 0xFF, plan.waves, ws);
             break;
         }
         case PRISM_PATH_PREFILL:
@@ -636,6 +680,13 @@ prism_status_t prism_plan_table_clear(void) {
 int32_t prism_plan_table_size(void) {
     std::lock_guard<std::mutex> lock(g_table_mutex);
     return g_table_size;
+}
+
+prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t extra_slices) {
+    if (slow_slots < 0 || slow_slots > 0xFF || extra_slices < -1 || extra_slices > 64) return PRISM_ERR_INVALID_ARG;
+    g_slow_slots.store(slow_slots);
+    g_balance_extra.store(extra_slices);
+    return PRISM_OK;
 }
 
 prism_status_t prism_probe_stream(const void* W, const void* W2, int64_t K, int64_t N, int32_t split_k,

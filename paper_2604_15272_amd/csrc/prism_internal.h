@@ -50,9 +50,8 @@ struct AttentionCall {
 // The matrix-core attention kernel: head dimension, rows (query heads) per batch entry, key slices.
 constexpr int kAttnHeadDim = 128;
 constexpr int kAttnMaxHeads = 16;
-constexpr int kAttnSliceKeys = 128;     // keys per workgroup while the slices number at most kAttnMaxSlices
+constexpr int kAttnSliceKeys = 128;     // keys per workgroup for short contexts (one 32-key block per wavefront)
 constexpr int kAttnMaxSlices = 64;
-constexpr int kAttnMaxSliceKeys = 1024;  // LDS holds a slice's scores
 
 struct AttentionPlan {
     int path;        // PRISM_PATH_SIMPLE or PRISM_PATH_ATTENTION
@@ -117,7 +116,8 @@ hipError_t launch_simple_f32(const Call& c);
 hipError_t launch_simple_bf16(const Call& c);
 hipError_t launch_simple_f16(const Call& c);
 // The matrix-core kernels, for either 16-bit storage format (f16 = false: bf16).
-hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int waves, const DecodeWorkspace& ws);
+hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int extra, int slow_slots, int waves,
+                               const DecodeWorkspace& ws);
 hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, const DecodeWorkspace& ws);
 hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);
 hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16);
