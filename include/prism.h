@@ -215,19 +215,31 @@ prism_status_t prism_plan_table_clear(void);
 int32_t prism_plan_table_size(void);
 
 /*
- * Stream balancing of the 16-row decode kernel (the reduction partition of paper Table 1, "parallelized matmul
- * (reduction)", with a partition that is not uniform over the column tiles).  When the row pitch of W is a multiple
- * of 2 KiB, the 256-byte-wide stripe a workgroup streams keeps bits 8-10 of its byte addresses (its slot) for
- * every row; on MI355X the stripes in slots 1 and 5 arrive 20 % slower than the rest.  Their column tiles are
- * therefore cut into split_k + extra K-slices (prism_plan reports the base split_k, a one-dimensional grid, and
- * the workspace for split_k + extra slices).  The slots are read off the address of W: the balanced launch needs W
- * (and W2, in step with W1 modulo 2 KiB) on a 256-byte boundary and N a multiple of 1024; otherwise every tile gets
- * split_k slices.  The number of slices decides the order of the fp32 sums, so results may differ in the last bit
- * between buffers in different slots; for given addresses they are reproducible.
- * slow_slots: bit s set = slot s is slow (0: no balancing, the default; 0x22 on the MI355X measured); extra_slices: -1 = the library's rule
- * (about a quarter more slices, never more workgroups than CUs), 0..64 = that many.  Host-side, process-wide.
+ * Weighted partition of the 16-row decode kernel (the reduction partition of paper Table 1, "parallelized matmul
+ * (reduction)", with shares that are equal over the workgroups instead of over the column tiles).  When a grid of
+ * column tiles x equal K-slices would need more workgroups than the part has CUs, the library launches 256
+ * workgroups instead and gives each the same share of all K-blocks, tile after tile: a share may end one tile
+ * and begin the next.  prism_plan then reports a one-dimensional grid and, as split_k, the most workgroups
+ * that can share a tile (what the workspace is sized for).
+ * slow_slots: bit s set = column tiles whose first byte has s in bits 8-10 of its address weigh 5 : 4 in that
+ *   partition, because the 256-byte-wide stripes of W in some slots stream slower than others when the row
+ *   pitch of W is a multiple of 2 KiB (on the MI355X measured: slots 1 and 5, 0x22).  Applies when N is a
+ *   multiple of 1024, W is on a 256-byte boundary and W2 in step with W1 modulo 2 KiB.  The shares decide the
+ *   order of the fp32 sums, so with slots set, results may differ in the last bit between buffers at different
+ *   addresses; for given addresses they are reproducible.  Default 0: no slot weighs more.
+ * weighted_partition: 1 = use the partition where the rule above asks for it (default), 0 = never.
+ * Host-side, process-wide.
  */
-prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t extra_slices);
+prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t weighted_partition);
+
+/*
+ * Diagnostic, host-side: the K-blocks [*first, *first + *count) of column tile `tile` that workgroup `wg` works on
+ * in a weighted partition of n_tiles tiles of kblocks K-blocks over `workgroups` workgroups; slow_tiles: bit j set =
+ * tiles j, j + 8, ... weigh 5 : 4.  The same integer functions run in the kernel; this entry point lets a test check
+ * that they deal every K-block out exactly once.  PRISM_ERR_UNSUPPORTED if the total weight does not fit 31 bits.
+ */
+prism_status_t prism_stream_partition_blocks(int32_t workgroups, int32_t kblocks, int32_t n_tiles, int32_t slow_tiles,
+                                            int32_t wg, int32_t tile, int32_t* first, int32_t* count);
 
 /*
  * Diagnostic, for measurement: streams W[K,N] (16-bit elements, device memory, 16-byte aligned, N a multiple

@@ -35,6 +35,7 @@ from .binding import (  # noqa: F401
     prism_rmsnorm_matmul,
     prism_set_override,
     prism_set_stream_balance,
+    prism_stream_partition_blocks,
     prism_set_workspace,
     prism_status_string,
     prism_version,

@@ -15,9 +15,14 @@
 // stores its partial, takes a ticket, and the last arrival of a tile sums the partials in slice
 // order (so the result does not depend on arrival order), applies 1/rms (and the SiLU gate) and
 // stores Y.  The normalised X never exists in memory.
+//
+// Two ways to deal K out to workgroups: a plain grid (column tiles x S equal K-slices), or the weighted
+// partition of stream_partition.h, in which every workgroup of a one-dimensional grid gets the same share of
+// streaming time: a run of K-blocks that may end one tile and begin the next (then it makes two passes).
 #include "device_utils.h"
 #include "exchange.h"
 #include "prism_internal.h"
+#include "stream_partition.h"
 #include "w_block.h"
 
 namespace prism {
@@ -49,8 +54,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
                                                          const uint16_t* __restrict__ W2,
                                                          uint16_t* __restrict__ Y, float* __restrict__ acc_part,
                                                          float* __restrict__ ss_part, unsigned* __restrict__ tickets,
-                                                         int M, int K, int N, float eps, int S_base, int flags,
-                                                         int extra, int slow_slots) {
+                                                         int M, int K, int N, float eps, int S_grid, int flags,
+                                                         StreamPartition sp) {
     constexpr int G = GATED ? 2 : 1;
     constexpr int NT = NW * 64;
     constexpr int CPT = 16 * TN / NT;  // columns per thread in the epilogue (4 for 8 wavefronts)
@@ -64,42 +69,14 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = lane >> 4, c = lane & 15;
-    // Which column tile and K-slice.  Plain launch: grid (column tiles, S).  Balanced launch (extra > 0, one-
-    // dimensional grid): the row pitch is a multiple of 2 KiB, so a tile's 256-byte columns keep address bits 8-10
-    // (its "slot") for every row, and tiles in the slots named by slow_slots, which stream slower, are cut into
-    // S_base + extra slices instead of S_base.  Eight consecutive tiles hold each slot once; their work items are
-    // numbered together (the common S_base slices of the eight tiles, then the extra ones), so that consecutive
-    // workgroups, which the dispatcher deals out to the XCDs in turn, do not pile the extra ones on two XCDs.
-    int ntile = blockIdx.x, split = blockIdx.y, S = S_base;
-    const int S_pitch = S_base + extra;  // slices per tile in the workspace
-    if (extra > 0) {
-        const int P = __popc((unsigned)slow_slots);
-        const int per_group = 8 * S_base + P * extra;
-        const int group = blockIdx.x / per_group, idx = blockIdx.x % per_group;
-        const int slot0 = (int)(((size_t)W1 >> 8) & 7);  // slot of tiles 0, 8, 16, ...
-        int j = idx & 7;
-        split = idx >> 3;
-        if (idx >= 8 * S_base) {
-            const int e = idx - 8 * S_base;
-            int k = e % P, slot = 0;
-            split = S_base + e / P;
-            for (int b = 0; b < 8; ++b)  // the k-th slow slot
-                if ((slow_slots >> b) & 1) {
-                    if (k == 0) slot = b;
-                    --k;
-                }
-            j = (slot - slot0) & 7;
-        }
-        ntile = 8 * group + j;
-        if ((slow_slots >> ((slot0 + j) & 7)) & 1) S += extra;
-    }
-    const int n0 = ntile * TN;
-
-    // This workgroup's K-blocks: [b_beg, b_beg + b_cnt).
     const int kblocks = (K + KB - 1) / KB;
-    const int per = kblocks / S, rem = kblocks % S;
-    const int b_beg = split * per + min(split, rem);
-    const int b_cnt = per + (split < rem ? 1 : 0);
+    // One pass over a (column tile, run of K-blocks): the tile, the K-blocks [b_beg, b_beg + b_cnt) of it, and this
+    // workgroup's place among the S workgroups that share the tile (the order in which the partial sums are
+    // added).  Written once, expanded once per pass (a loop over passes would keep both passes' values in
+    // registers across its back edge: 256 instead of 168 registers, with spills).
+    auto pass = [&](const int ntile, const int split, const int S, const int b_beg, const int b_cnt)
+                    __attribute__((always_inline)) {
+    const int n0 = ntile * TN;
 
     // Buffer descriptors.  W starts at this workgroup's first row and first column; its end is the
     // end of the matrix, so rows past K read as zero.
@@ -210,13 +187,13 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         // stores write through, loads do not hit a stale L2 line), so that no whole-cache
         // write-back or invalidate is needed: a workgroup waits until its stores are acknowledged,
         // then takes its ticket; whoever draws the last ticket reads after that.
-        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)S_pitch * G * M * N);
+        const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)S_grid * G * M * N);
         if (out_ok) {
             const size_t idx = (((size_t)split * G) * M + m) * N + n;
             store_partial<CPT>(racc, acc_part, idx, v1);
             if (GATED) store_partial<CPT>(racc, acc_part, idx + (size_t)M * N, v2);
         }
-        if (col == 0) store_coherent(ss_part + ((size_t)ntile * S_pitch + split) * 16 + m, ssum);
+        if (col == 0) store_coherent(ss_part + ((size_t)ntile * S_grid + split) * 16 + m, ssum);
         wait_stores_acknowledged();
         __syncthreads();
         if (tid == 0) {
@@ -240,7 +217,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {
                 const int s = min(s0 + j, S - 1);
-                sq[j] = load_coherent(ss_part + ((size_t)ntile * S_pitch + s) * 16 + m);
+                sq[j] = load_coherent(ss_part + ((size_t)ntile * S_grid + s) * 16 + m);
                 if (out_ok) {
                     const size_t idx = (((size_t)s * G) * M + m) * N + n;
                     load_partial<CPT>(racc, acc_part, idx, pa[j]);
@@ -281,13 +258,46 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         if (CPT == 4) *(u32x2*)out = u32x2{packed[0], packed[1]};
         if (CPT == 8) *(u32x4*)out = u32x4{packed[0], packed[1], packed[2], packed[3]};
     }
+    };  // pass
+
+    if (sp.G == 0) {
+        // Plain grid: column tiles x S_grid equal K-slices.
+        const int split = blockIdx.y;
+        const int per = kblocks / S_grid, rem = kblocks % S_grid;
+        pass(blockIdx.x, split, S_grid, split * per + min(split, rem), per + (split < rem ? 1 : 0));
+        return;
+    }
+    // Weighted partition: this workgroup's range of weight units covers K-blocks of at most two tiles (the host
+    // keeps a workgroup's share below a tile's weight).
+    const uint32_t v_end = sp_boundary(sp, blockIdx.x + 1);
+    const uint32_t t0 = sp_tile_of(sp, sp_boundary(sp, blockIdx.x)), t1 = t0 + 1;
+    // A tile's sharers are neighbours in the grid: lane l looks at workgroup blockIdx.x - 32 + l (the host keeps
+    // the sharers of a tile at kStreamMaxSlices or fewer).
+    const int j = (int)blockIdx.x - 32 + lane;
+    const bool j_ok = j >= 0 && j < (int)sp.G;
+    uint32_t r0, r1, a0 = 0, a1 = 0;
+    sp_blocks(sp, blockIdx.x, t0, r0, r1);
+    const bool first = r1 > r0;
+    if (first) {
+        if (j_ok) sp_blocks(sp, (uint32_t)j, t0, a0, a1);
+        const unsigned long long sharers = __ballot(a1 > a0);
+        pass((int)t0, __popcll(sharers & 0xFFFFFFFFull), __popcll(sharers), (int)r0, (int)(r1 - r0));
+    }
+    if (t1 >= sp.n_tiles || sp_prefix(sp, t1) >= v_end) return;
+    sp_blocks(sp, blockIdx.x, t1, r0, r1);
+    if (r1 <= r0) return;
+    a0 = a1 = 0;
+    if (j_ok) sp_blocks(sp, (uint32_t)j, t1, a0, a1);
+    const unsigned long long sharers = __ballot(a1 > a0);
+    if (first) __syncthreads();  // the first pass has finished with LDS
+    pass((int)t1, __popcll(sharers & 0xFFFFFFFFull), __popcll(sharers), (int)r0, (int)(r1 - r0));
 }
 
 template <typename F, int NW>
-static hipError_t launch_decode_nw(const Call& c, int S, int extra, int slow_slots, const DecodeWorkspace& ws) {
+static hipError_t launch_decode_nw(const Call& c, int S, const StreamPartition& sp, const DecodeWorkspace& ws) {
     const int n_tiles = (c.N + TN - 1) / TN;
     dim3 grid(n_tiles, S), block(NW * 64);
-    if (extra > 0) grid = dim3((n_tiles / 8) * (8 * S + __builtin_popcount((unsigned)slow_slots) * extra));
+    if (sp.G != 0) grid = dim3(sp.G);  // S: the most workgroups that share a tile
     const size_t lds = (size_t)(((c.gated && NW <= 8) ? 2 : 1) * NW * 16 * TN + NW * 16) * sizeof(float);
     auto* X = (const uint16_t*)c.X;
     auto* g = (const uint16_t*)c.g;
@@ -299,32 +309,31 @@ static hipError_t launch_decode_nw(const Call& c, int S, int extra, int slow_slo
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W2, Y, ws.acc_part, ws.ss_part, ws.tickets,
-                           c.M, c.K, c.N, c.eps, S, c.flags, extra, slow_slots);
+                           c.M, c.K, c.N, c.eps, S, c.flags, sp);
     } else {
         auto kern = decode_kernel<F, NW, false>;
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W1, Y, ws.acc_part, ws.ss_part, ws.tickets,
-                           c.M, c.K, c.N, c.eps, S, c.flags, extra, slow_slots);
+                           c.M, c.K, c.N, c.eps, S, c.flags, sp);
     }
     return hipGetLastError();
 }
 
 template <typename F>
-static hipError_t launch_decode_fmt(const Call& c, int split_k, int extra, int slow_slots, int waves,
+static hipError_t launch_decode_fmt(const Call& c, int split_k, const StreamPartition& sp, int waves,
                                     const DecodeWorkspace& ws) {
     switch (waves) {
-        case 4: return launch_decode_nw<F, 4>(c, split_k, extra, slow_slots, ws);
-        case 8: return launch_decode_nw<F, 8>(c, split_k, extra, slow_slots, ws);
-        case 16: return launch_decode_nw<F, 16>(c, split_k, extra, slow_slots, ws);
+        case 4: return launch_decode_nw<F, 4>(c, split_k, sp, ws);
+        case 8: return launch_decode_nw<F, 8>(c, split_k, sp, ws);
+        case 16: return launch_decode_nw<F, 16>(c, split_k, sp, ws);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, int extra, int slow_slots, int waves,
+hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, const StreamPartition& sp, int waves,
                                const DecodeWorkspace& ws) {
-    return f16 ? launch_decode_fmt<F16>(c, split_k, extra, slow_slots, waves, ws)
-               : launch_decode_fmt<Bf16>(c, split_k, extra, slow_slots, waves, ws);
+    return f16 ? launch_decode_fmt<F16>(c, split_k, sp, waves, ws) : launch_decode_fmt<Bf16>(c, split_k, sp, waves, ws);
 }
 
 }  // namespace prism

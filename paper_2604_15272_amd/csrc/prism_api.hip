@@ -6,6 +6,7 @@
 #include <mutex>
 
 #include "prism_internal.h"
+#include "stream_partition.h"
 
 namespace prism {
 namespace {
@@ -18,13 +19,14 @@ struct Override {
 };
 Override g_override;
 
-// Address slots (bits 8-10 of the byte address: which 256 bytes of every 2 KiB) whose columns stream slower from
-// HBM, and how many more K-slices their tiles get (-1: the rule in make_plan_with).  Measured on MI355X with
-// per-workgroup time stamps: with a row pitch that is a multiple of 2 KiB a workgroup's 256-byte-wide stripe of W
-// stays in one slot, and the stripes in slots 1 and 5 finish 20 % later than the others (37 us against 30 us on
-// X[8,4096], 2 x W[4096,14336]) whichever XCD reads them; a row pitch of 225 x 256 bytes, which takes every
-// workgroup through all slots, finishes all of them at 32 us.
-std::atomic<int32_t> g_slow_slots{0}, g_balance_extra{-1};
+// The weighted partition of stream_partition.h (16-row decode kernel) and the address slots it may weigh.
+// Slots: bits 8-10 of the byte address, i.e. which 256 bytes of every 2 KiB.  Measured on MI355X with per-workgroup
+// time stamps: with a row pitch that is a multiple of 2 KiB a workgroup's 256-byte-wide stripe of W stays in one
+// slot, and the stripes in slots 1 and 5 finish 20 % later than the others (37 us against 30 us on X[8,4096],
+// 2 x W[4096,14336]) whichever XCD reads them; a row pitch of 225 x 256 bytes, which takes every workgroup
+// through all slots, finishes all of them at 32 us.  Weighing those tiles 5 : 4 takes 2 us off partitioned calls
+// with 112 or more tiles and adds 4 us with 32 tiles (more sharers per tile), so no slot is weighed by default.
+std::atomic<int32_t> g_slow_slots{0}, g_stream_partition{1};
 
 struct Workspace {
     void* ptr;
@@ -38,7 +40,8 @@ struct Plan {
     prism_plan_t pub;
     int waves;          // decode: wavefronts per workgroup
     int row_groups;     // decode: 16-row groups per workgroup (1: the 16-row kernel)
-    int extra;          // decode, 16-row kernel: additional K-slices for the tiles in slow address slots
+    StreamPartition sp; // decode, 16-row kernel: weighted partition (G = 0: plain grid); slow = the slots, not yet
+                        // rotated to the address of W
     uint64_t ss_bytes;  // decode: bytes of the partial sums of squares (rounded)
 };
 
@@ -305,49 +308,58 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             while (S > 1 && !partials_fit(S)) --S;
         if (S > 1 && !partials_fit(S)) return PRISM_ERR_UNSUPPORTED;
         if (!slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
-        // More slices for the column tiles in slow address slots (16-row kernel, row pitch a multiple of 2 KiB,
-        // whole groups of eight tiles), as long as every workgroup still finds a CU of its own.
-        int64_t extra = 0;
-        const int slow = g_slow_slots.load() & 0xFF;
-        if (row_groups == 1 && slow != 0 && (N * 2) % 2048 == 0 && n_tiles % 8 == 0) {
-            const int64_t P = __builtin_popcount((unsigned)slow);
-            auto total = [&](int64_t s, int64_t e) { return n_tiles / 8 * (8 * s + P * e); };
-            const int forced_extra = g_balance_extra.load();
-            if (forced_extra >= 0) {
-                extra = forced_extra;
-            } else if (S >= 2) {
-                int64_t s = S, e = (s + 2) / 4;
-                if (total(s, e) > 256 && forced_split <= 0 && s > 2) {
-                    --s;
-                    e = (s + 2) / 4;
-                }
-                if (total(s, e) <= 256) {
-                    S = s;
-                    extra = e;
+        // The weighted partition instead of a grid of equal K-slices when that grid would have more workgroups
+        // than CUs (a workgroup of this kernel fills a CU, so the surplus would wait for a second round): 256
+        // workgroups with equal shares, a share of at least four K-blocks (eight when gated).  Measured on
+        // X[16,4096] . W[4096,11008] (86 tiles x 3 slices): 27.8 -> 24.4 us.  Where the grid fits, it stays: a
+        // workgroup whose share spans two tiles makes two passes and pays the reduction twice (X[8,4096],
+        // 2 x W[4096,14336]: 42.9 us as 112 x 2, 49.4 us partitioned).  Tiles in the slots of g_slow_slots weigh
+        // 5 : 4 when the row pitch keeps a tile in its slot (whole groups of eight tiles).
+        StreamPartition sp{};
+        int64_t s_pitch = S;
+        if (row_groups == 1 && forced_split <= 0 && g_stream_partition.load() != 0 && n_tiles * S > 256 &&
+            n_tiles < 256) {
+            const int slow = ((N * 2) % 2048 == 0 && n_tiles % 8 == 0) ? (g_slow_slots.load() & 0xFF) : 0;
+            const uint64_t T = (uint64_t)(4 * n_tiles + n_tiles / 8 * __builtin_popcount((unsigned)slow)) * kblocks;
+            int64_t G = std::min<int64_t>(256, std::min<int64_t>(n_tiles * kblocks / (gated ? 8 : 4), 8 * n_tiles));
+            if (G < 1) G = 1;
+            if (T < (1ull << 31) && n_tiles < (1 << 24)) {
+                const uint64_t q = T / G;
+                // A tile's weight units meet at most this many workgroups' ranges.
+                int64_t most = (int64_t)(((slow ? 5u : 4u) * (uint64_t)kblocks + q - 1) / q) + 1;
+                if (!slow && T % G == 0 && (q % (4 * kblocks) == 0 || (4 * kblocks) % q == 0))
+                    most = std::max<int64_t>(1, 4 * kblocks / q);  // the ranges line up with the tiles
+                // Byte offsets inside one run of K-blocks must fit in 31 bits, as for a K-slice.
+                const uint64_t run_rows = std::min<uint64_t>(kblocks, q / 4 + 2) * kDecodeKBlock + 8;
+                // q < a tile's weight: a workgroup's range (q or q + 1 units) meets at most two tiles.
+                if (q < 4 * (uint64_t)kblocks && most <= kStreamMaxSlices && partials_fit(most) &&
+                    run_rows * (uint64_t)N * 2 < kTwoGiB) {
+                    sp = StreamPartition{(uint32_t)G, (uint32_t)kblocks, (uint32_t)n_tiles, (uint32_t)slow,
+                                         (uint32_t)q, (uint32_t)(T % G)};
+                    s_pitch = most;
                 }
             }
-            if (S + extra > kblocks || S + extra > 65535 || !partials_fit(S + extra) ||
-                total(S, extra) > 0x7FFFFFFF)
-                extra = 0;
         }
         out->waves = waves;
         out->row_groups = row_groups;
-        out->extra = (int)extra;
+        out->sp = sp;
         p.split_k = (int32_t)S;
         p.tile_m = 16 * row_groups;
         p.tile_n = kDecodeTileN;
         p.grid_x = (int32_t)n_tiles;
         p.grid_y = (int32_t)S;
-        if (extra > 0) {
-            p.grid_x = (int32_t)(n_tiles / 8 * (8 * S + __builtin_popcount((unsigned)slow) * extra));
+        if (sp.G != 0) {
+            S = s_pitch;  // the most workgroups that share a tile: the slices the workspace holds
+            p.split_k = (int32_t)S;
+            p.grid_x = (int32_t)sp.G;
             p.grid_y = 1;
         }
         p.grid_z = (int32_t)row_blocks;
         p.block = waves * 64;
-        if (S + extra > 1) {
-            out->ss_bytes = round_up((uint64_t)n_tiles * row_blocks * (S + extra) * 16 * row_groups * 4, 256);
+        if (S > 1) {
+            out->ss_bytes = round_up((uint64_t)n_tiles * row_blocks * S * 16 * row_groups * 4, 256);
             p.workspace_bytes = PRISM_WORKSPACE_HEADER_BYTES + out->ss_bytes +
-                                (uint64_t)(S + extra) * (gated ? 2 : 1) * M * N * 4;
+                                (uint64_t)S * (gated ? 2 : 1) * M * N * 4;
         }
         return PRISM_OK;
     }
@@ -443,7 +455,7 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
             break;
         case PRISM_PATH_DECODE: {
             DecodeWorkspace ws{nullptr, nullptr, nullptr};
-            if (plan.pub.split_k + plan.extra > 1) {
+            if (plan.pub.split_k > 1) {
                 int dev = 0;
                 if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
                 if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
@@ -454,16 +466,24 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                 ws.ss_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES);
                 ws.acc_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES + plan.ss_bytes);
             }
-            // The slots are read off the addresses: the balanced launch needs W on a slot boundary (and W2 in
-            // step with W1); any other alignment gets the same slices for every tile.
-            int extra = plan.extra;
-            if ((reinterpret_cast<uintptr_t>(W1) & 255u) != 0 ||
-                (gated && ((reinterpret_cast<uintptr_t>(W1) ^ reinterpret_cast<uintptr_t>(W2)) & 2047u) != 0))
-                extra = 0;
+            // The slots are read off the address of W: tile j's slot is that of tile 0 plus j.  W off a slot
+            // boundary, or W2 out of step with W1, gets equal weights.
+            StreamPartition sp = plan.sp;
+            if (sp.G != 0 && sp.slow != 0) {
+                const uintptr_t a1 = reinterpret_cast<uintptr_t>(W1), a2 = reinterpret_cast<uintptr_t>(W2);
+                if ((a1 & 255u) != 0 || (gated && ((a1 ^ a2) & 2047u) != 0)) {
+                    const uint64_t T = (uint64_t)4 * sp.n_tiles * sp.kblocks;
+                    sp.slow = 0;
+                    sp.q = (uint32_t)(T / sp.G);
+                    sp.r = (uint32_t)(T % sp.G);
+                } else {
+                    const unsigned slot0 = (unsigned)(a1 >> 8) & 7u;
+                    sp.slow = ((sp.slow >> slot0) | (sp.slow << (8 - slot0))) & 0xFFu;
+                }
+            }
             err = plan.row_groups > 1
                       ? launch_decode_rows_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.row_groups, ws)
-                      : launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, extra,
-                                            g_slow_slots.load() & 0xFF, plan.waves, ws);
+                      : launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, sp, plan.waves, ws);
             break;
         }
         case PRISM_PATH_PREFILL:
@@ -682,10 +702,29 @@ int32_t prism_plan_table_size(void) {
     return g_table_size;
 }
 
-prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t extra_slices) {
-    if (slow_slots < 0 || slow_slots > 0xFF || extra_slices < -1 || extra_slices > 64) return PRISM_ERR_INVALID_ARG;
+prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t weighted_partition) {
+    if (slow_slots < 0 || slow_slots > 0xFF || weighted_partition < 0 || weighted_partition > 1)
+        return PRISM_ERR_INVALID_ARG;
     g_slow_slots.store(slow_slots);
-    g_balance_extra.store(extra_slices);
+    g_stream_partition.store(weighted_partition);
+    return PRISM_OK;
+}
+
+prism_status_t prism_stream_partition_blocks(int32_t workgroups, int32_t kblocks, int32_t n_tiles, int32_t slow_tiles,
+                                            int32_t wg, int32_t tile, int32_t* first, int32_t* count) {
+    if (!first || !count || workgroups < 1 || workgroups > 65535 || kblocks < 1 || n_tiles < 1 || slow_tiles < 0 ||
+        slow_tiles > 0xFF || wg < 0 || wg >= workgroups || tile < 0 || tile >= n_tiles)
+        return PRISM_ERR_INVALID_ARG;
+    StreamPartition sp{(uint32_t)workgroups, (uint32_t)kblocks, (uint32_t)n_tiles, (uint32_t)slow_tiles, 0, 0};
+    const uint64_t T = (uint64_t)(4 * (uint64_t)n_tiles + (uint64_t)(n_tiles >> 3) * __builtin_popcount((unsigned)slow_tiles) +
+                                  __builtin_popcount((unsigned)slow_tiles & ((1u << (n_tiles & 7)) - 1u))) * (uint64_t)kblocks;
+    if (T >= (1ull << 31)) return PRISM_ERR_UNSUPPORTED;
+    sp.q = (uint32_t)(T / sp.G);
+    sp.r = (uint32_t)(T % sp.G);
+    uint32_t r0 = 0, r1 = 0;
+    sp_blocks(sp, (uint32_t)wg, (uint32_t)tile, r0, r1);
+    *first = (int32_t)r0;
+    *count = r1 > r0 ? (int32_t)(r1 - r0) : 0;
     return PRISM_OK;
 }
 

@@ -96,6 +96,67 @@ def test_decode_is_bit_reproducible_and_leaves_tickets_clean(P):
         assert torch.equal(o.view(torch.uint16), ref)
 
 
+# ---- decode path, weighted partition (256 workgroups with equal shares where tiles x slices would be more) -----
+
+@pytest.mark.parametrize("slow", [0, 0x22])
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("M,K,N", [(16, 4096, 11008), (8, 2048, 9216), (16, 1000, 5640), (3, 4096, 18432),
+                                   (16, 8192, 7168)])
+def test_decode_weighted_partition(P, M, K, N, gated, slow):
+    """Shares that end one tile and begin the next (two passes), with and without heavier slow-slot tiles."""
+    P.prism_set_stream_balance(slow, 1)
+    try:
+        plan = P.prism_plan(int(gated), M, K, N, P.PRISM_BF16)
+        if not gated:
+            assert (plan["path"], plan["grid_x"], plan["grid_y"]) == (P.PRISM_PATH_DECODE, 256, 1), plan
+        _case(P, pi.BF16, M, K, N, gated, seed=450 + N % 97, expect_path=P.PRISM_PATH_DECODE)
+    finally:
+        P.prism_set_stream_balance(0, 1)
+
+
+def test_decode_weighted_partition_f16_and_grid_agree(P):
+    """The partition changes who sums what, not the result beyond rounding: against the oracle, and against the
+    plain grid of the same call."""
+    e1 = _case(P, pi.F16, 16, 4096, 9216, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
+    P.prism_set_stream_balance(0, 0)
+    try:
+        assert P.prism_plan(0, 16, 4096, 9216, P.PRISM_F16)["grid_y"] > 1
+        e0 = _case(P, pi.F16, 16, 4096, 9216, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
+    finally:
+        P.prism_set_stream_balance(0, 1)
+    assert abs(e1 - e0) < 2.5e-3
+
+
+def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
+    """W that does not start on a 256-byte boundary gets equal weights; repeated calls agree bit for bit."""
+    import torch
+    from gpu_util import to_device, from_device
+    M, K, N = 16, 2048, 9216
+    stored = pi.draw(pi.BF16, M, K, N, False, 462)
+    X, g = (to_device(stored[k], pi.BF16) for k in ("X", "g"))
+    Wa = to_device(stored["W"], pi.BF16)
+    flat = torch.empty(K * N + 8, dtype=torch.bfloat16, device="cuda")
+    Wb = flat[8:].view(K, N)
+    Wb.copy_(Wa)
+    assert Wb.data_ptr() % 256 == 16
+    yhat = run_oracle(stored, pi.BF16, False, 1e-6)
+    P.prism_set_stream_balance(0x22, 1)
+    try:
+        assert P.prism_plan(0, M, K, N, P.PRISM_BF16)["grid_x"] == 256
+        for W in (Wa, Wb):
+            outs = []
+            for _ in range(20):
+                Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+                P.prism_rmsnorm_matmul(X, g, W, Y)
+                outs.append(Y)
+            torch.cuda.synchronize()
+            for o in outs[1:]:
+                assert torch.equal(o.view(torch.uint16), outs[0].view(torch.uint16))
+            assert_parity(from_device(outs[0], pi.BF16), yhat, pi.BF16, f"partition, W at {W.data_ptr() % 256} mod 256")
+    finally:
+        P.prism_set_stream_balance(0, 1)
+
+
 # ---- decode path, more than 16 rows (several 16-row groups per workgroup, row blocks in the grid) --------
 
 @pytest.mark.parametrize("gated", [False, True])

@@ -3,6 +3,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 
@@ -263,7 +264,11 @@ def test_plans_of_random_shapes_are_consistent(P):
         if p["path"] == P.PRISM_PATH_PREFILL:
             assert p["grid_x"] == -(-M // p["tile_m"]) * -(-N // cols), what
         elif p["path"] == P.PRISM_PATH_DECODE or (p["path"] == P.PRISM_PATH_ROWS and p["tile_m"] == 32):
-            assert (p["grid_x"], p["grid_y"], max(1, p["grid_z"])) == (-(-N // 128), p["split_k"], -(-M // p["tile_m"])), what
+            if p["path"] == P.PRISM_PATH_DECODE and p["tile_m"] == 16 and p["grid_y"] == 1 and p["grid_x"] != -(-N // 128):
+                # weighted partition: 256 workgroups where tiles x slices would have been more
+                assert p["grid_x"] == 256 and -(-N // 128) < 256 and 2 <= p["split_k"] <= 32, what
+            else:
+                assert (p["grid_x"], p["grid_y"], max(1, p["grid_z"])) == (-(-N // 128), p["split_k"], -(-M // p["tile_m"])), what
             assert p["tile_m"] in (16, 32, 64) and (p["tile_m"] == 16) == (M <= 16 and op != 2), what
             if p["split_k"] > 1:
                 G = 2 if op == 1 else 1
@@ -272,6 +277,90 @@ def test_plans_of_random_shapes_are_consistent(P):
                 assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * G * M * N * 4, what
         else:
             assert (p["grid_x"], p["grid_y"]) == (-(-N // p["tile_n"]), -(-M // p["tile_m"])), what
+
+
+def _partition(P, G, kblocks, n_tiles, slow):
+    """owner[tile] = list of (wg, first, count) with count > 0, in workgroup order."""
+    owner = [[] for _ in range(n_tiles)]
+    for wg in range(G):
+        for t in range(n_tiles):
+            first, count = P.prism_stream_partition_blocks(G, kblocks, n_tiles, slow, wg, t)
+            if count:
+                owner[t].append((wg, first, count))
+    return owner
+
+
+def test_weighted_partition_deals_every_k_block_out_once(P):
+    """The integer functions the decode kernel runs (through their host-side entry point): every K-block of every
+    tile belongs to exactly one workgroup, a tile's sharers are consecutive workgroups whose runs follow one another,
+    equal weights give shares that differ by at most one block, and slow tiles get 5/4 as many sharers."""
+    rng = np.random.Generator(np.random.Philox(77))
+    cases = [(256, 128, 86, 0), (256, 128, 112, 0x22), (64, 32, 8, 0x22), (1, 5, 3, 0), (7, 1, 7, 0x81)]
+    cases += [(int(rng.integers(1, 70)), int(rng.integers(1, 90)), int(rng.integers(1, 40)), int(rng.choice([0, 0x22, 0x44, 0xFF, 0x01])))
+              for _ in range(25)]
+    for G, kblocks, n_tiles, slow in cases:
+        # the dispatcher keeps a share at four K-blocks or more; five weight units already give every workgroup a block
+        G = max(1, min(G, sum(kblocks * (5 if (slow >> (t % 8)) & 1 else 4) for t in range(n_tiles)) // 5))
+        what = f"G={G} kblocks={kblocks} n_tiles={n_tiles} slow={slow:#x}"
+        owner = _partition(P, G, kblocks, n_tiles, slow)
+        per_wg = np.zeros(G, dtype=np.int64)
+        tiles_of_wg = [set() for _ in range(G)]
+        for t, runs in enumerate(owner):
+            assert runs, what
+            nxt = 0
+            for i, (wg, first, count) in enumerate(runs):
+                assert first == nxt, (what, t, runs)
+                nxt = first + count
+                if i:
+                    assert wg == runs[i - 1][0] + 1, (what, t, runs)   # neighbours in the grid
+                per_wg[wg] += count * (5 if (slow >> (t % 8)) & 1 else 4)
+                tiles_of_wg[wg].add(t)
+            assert nxt == kblocks, (what, t, runs)
+            assert len(runs) <= 32 or G > 32 * n_tiles, what
+        T = sum(kblocks * (5 if (slow >> (t % 8)) & 1 else 4) for t in range(n_tiles))
+        assert per_wg.sum() == T, what
+        # shares in weight units: equal up to one K-block either way
+        assert per_wg.max() - per_wg.min() <= 2 * 5 + 1, (what, per_wg)
+        if T // G < 4 * kblocks:
+            assert max(len(ts) for ts in tiles_of_wg) <= 2, what
+    # what the dispatcher relies on: a share below one tile's weight meets at most ceil(w * kblocks / q) + 1 workgroups
+    owner = _partition(P, 256, 128, 112, 0x22)
+    q = (112 * 4 + 28) * 128 // 256
+    assert max(len(r) for r in owner) <= -(-5 * 128 // q) + 1
+    slow_n = np.mean([len(owner[t]) for t in range(112) if t % 8 in (1, 5)])
+    fast_n = np.mean([len(owner[t]) for t in range(112) if t % 8 not in (1, 5)])
+    assert slow_n > fast_n
+
+
+def test_plan_uses_the_partition_when_the_grid_would_not_fit(P):
+    bf16 = P.PRISM_BF16
+    p = P.prism_plan(0, 16, 4096, 11008, bf16)            # 86 tiles x 3 slices = 258 workgroups
+    assert (p["path"], p["grid_x"], p["grid_y"], p["block"]) == (P.PRISM_PATH_DECODE, 256, 1, 512)
+    q = 86 * 4 * 128 // 256
+    assert p["split_k"] == -(-4 * 128 // q) + 1
+    ss = -(-(86 * p["split_k"] * 16 * 4) // 256) * 256
+    assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * 16 * 11008 * 4
+    P.prism_set_stream_balance(0, 0)
+    try:
+        c = P.prism_plan(0, 16, 4096, 11008, bf16)
+        assert (c["grid_x"], c["grid_y"], c["split_k"]) == (86, 3, 3)
+    finally:
+        P.prism_set_stream_balance(0, 1)
+    # the benchmark configurations fit a grid and keep it
+    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 4096, bf16)) == (32, 8)
+    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(1, 8, 4096, 14336, bf16)) == (112, 2)
+    # a forced split keeps the grid
+    P.prism_set_override(P.PRISM_PATH_DECODE, 3, 0)
+    try:
+        assert P.prism_plan(0, 16, 4096, 11008, bf16)["grid_y"] == 3
+    finally:
+        P.prism_set_override(0, 0, 0)
+    with pytest.raises(P.PrismError):
+        P.prism_set_stream_balance(0x100, 1)
+    with pytest.raises(P.PrismError):
+        P.prism_set_stream_balance(0, 2)
+    with pytest.raises(P.PrismError):
+        P.prism_stream_partition_blocks(4, 8, 8, 0, 4, 0)
 
 
 def test_shapes_past_the_32_bit_offsets_take_the_plain_kernel(P):
