@@ -210,33 +210,40 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
 
     // ---- across wavefronts through LDS: each partial is relative to its wavefront's maximum.  Accumulator j,
     // element i of lane (q, c) is head 4q + i, column 8c + j.
-    store_acc_tile(red + wave * 16 * AD, AD, q, c, acc);
+    // Rows from G on are padding: the lanes that hold only such rows store nothing, the threads that would
+    // combine them have nothing to do until the end.
+    if (4 * q < G) store_acc_tile(red + wave * 16 * AD, AD, q, c, acc);
     __syncthreads();
     const int m = tid / TPR;           // head
     const int col = (tid % TPR) * CPT; // first of 8 output columns
+    const bool head_ok = m < G;
     float row_max = -__builtin_inff();
-#pragma unroll
-    for (int w = 0; w < ANW; ++w) row_max = fmaxf(row_max, wm[w * 16 + m]);
     float v[CPT], den = 0.f;
 #pragma unroll
     for (int e = 0; e < CPT; ++e) v[e] = 0.f;
+    if (head_ok) {
 #pragma unroll
-    for (int w = 0; w < ANW; ++w) {
-        const float mw = wm[w * 16 + m];
-        const float fw = (mw == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((mw - row_max) * kLog2e);  // a wavefront without keys
-        const float* src = red + (w * 16 + m) * AD + col;
+        for (int w = 0; w < ANW; ++w) row_max = fmaxf(row_max, wm[w * 16 + m]);
 #pragma unroll
-        for (int e = 0; e < CPT; ++e) v[e] = fmaf(fw, src[e], v[e]);
-        den = fmaf(fw, wl[w * 16 + m], den);
+        for (int w = 0; w < ANW; ++w) {
+            const float mw = wm[w * 16 + m];
+            const float fw = (mw == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((mw - row_max) * kLog2e);  // a wavefront without keys
+            const float* src = red + (w * 16 + m) * AD + col;
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) v[e] = fmaf(fw, src[e], v[e]);
+            den = fmaf(fw, wl[w * 16 + m], den);
+        }
     }
 
     // ---- 4. across the slices of this batch entry
     if (S > 1) {
         const __amdgpu_buffer_rsrc_t racc = exchange_rsrc(acc_part, (size_t)gridDim.y * S * 16 * AD);
-        store_partial<CPT>(racc, acc_part, (((size_t)bi * S + s) * 16 + m) * AD + col, v);
-        if (col == 0) {
-            store_coherent(m_part + ((size_t)bi * S + s) * 16 + m, row_max);
-            store_coherent(l_part + ((size_t)bi * S + s) * 16 + m, den);
+        if (head_ok) {
+            store_partial<CPT>(racc, acc_part, (((size_t)bi * S + s) * 16 + m) * AD + col, v);
+            if (col == 0) {
+                store_coherent(m_part + ((size_t)bi * S + s) * 16 + m, row_max);
+                store_coherent(l_part + ((size_t)bi * S + s) * 16 + m, den);
+            }
         }
         wait_stores_acknowledged();
         __syncthreads();
@@ -247,12 +254,14 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
         __syncthreads();
         if (!is_last) return;
         if (tid == 0) tickets[bi] = 0u;  // ready for the next call on this workspace
+        if (!head_ok) return;
         // Global maximum of the row, then the partials rescaled by exp(m_s - max), in slice order.  Eight
         // slices' loads are issued before the first is used (one round trip to memory per batch, not per slice;
-        // sixteen at a time spill registers and double the kernel's time).
+        // sixteen at a time spill registers and double the kernel's time).  With eight slices or fewer the
+        // maximum comes out of the same batch (one round trip in all); with more, the maxima are read first.
         constexpr int BATCH = 8;
         float gmax = -__builtin_inff();
-        for (int t0 = 0; t0 < S; t0 += BATCH) {
+        for (int t0 = 0; S > BATCH && t0 < S; t0 += BATCH) {
             float mm[BATCH];
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) mm[j] = load_coherent(m_part + ((size_t)bi * S + min(t0 + j, S - 1)) * 16 + m);
@@ -271,6 +280,10 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
                 mm[j] = load_coherent(m_part + row);
                 ll[j] = load_coherent(l_part + row);
                 load_partial<CPT>(racc, acc_part, row * AD + col, x[j]);
+            }
+            if (S <= BATCH) {
+#pragma unroll
+                for (int j = 0; j < BATCH; ++j) gmax = fmaxf(gmax, mm[j]);  // slots past the last slice repeat it
             }
 #pragma unroll
             for (int j = 0; j < BATCH; ++j) {

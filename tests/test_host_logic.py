@@ -169,16 +169,18 @@ def test_attention_arguments_and_plan(P):
     assert at(dt=9) == 2 and at(D=2048) == 2 and at(B=0) == 0 and at(G=0) == 0
     f16 = P.PRISM_F16
     p = P.prism_attention_plan(2, 8, 2048, 128, f16)
-    assert p["path"] == P.PRISM_PATH_ATTENTION and p["split_k"] == 8 and p["tile_n"] == 256 and p["grid_y"] == 2
-    assert p["workspace_bytes"] == 262144 + 2 * 8 * 16 * (2 + 128) * 4
+    assert p["path"] == P.PRISM_PATH_ATTENTION and p["split_k"] == 16 and p["tile_n"] == 128 and p["grid_y"] == 2
+    assert p["workspace_bytes"] == 262144 + 2 * 16 * 16 * (2 + 128) * 4
     short = P.prism_attention_plan(2, 8, 1024, 128, f16)
     assert short["split_k"] == 8 and short["tile_n"] == 128
     assert P.prism_attention_plan(2, 8, 100, 128, f16)["split_k"] == 1
     assert P.prism_attention_plan(2, 8, 100, 128, f16)["workspace_bytes"] == 0
     big = P.prism_attention_plan(1, 8, 65536, 128, f16)
-    assert big["split_k"] == 32 and big["tile_n"] == 2048
+    assert big["split_k"] == 64 and big["tile_n"] == 1024
     mid = P.prism_attention_plan(1, 8, 8192, 128, f16)
-    assert mid["split_k"] == 16 and mid["tile_n"] == 512
+    assert mid["split_k"] == 32 and mid["tile_n"] == 256
+    assert P.prism_attention_plan(1, 8, 1536, 128, f16)["split_k"] == 8
+    assert P.prism_attention_plan(1, 8, 4096, 128, f16)["split_k"] == 16
     # what the matrix-core kernel does not cover goes to the plain kernel
     for shape in ((2, 8, 2048, 64), (2, 17, 2048, 128)):
         assert P.prism_attention_plan(*shape, f16)["path"] == P.PRISM_PATH_SIMPLE
