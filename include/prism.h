@@ -190,7 +190,8 @@ prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_
 /*
  * Process-wide override for tests and tuning: force a kernel family and/or a split-K factor and
  * a tile variant (0 = automatic for each).  Variants: PRISM_PATH_DECODE with at most 16 rows: 4, 8 or 16
- * wavefronts per workgroup; with more rows: 32 or 64 rows per workgroup;
+ * wavefronts per workgroup, for gated calls also 104 and 108 (4 or 8 wavefronts, tiles of 64 output columns that
+ * hold the products with W1 and with W2 in one matrix-core tile); with more rows: 32 or 64 rows per workgroup;
  * PRISM_PATH_PREFILL: 1000 * tile_m + tile_n; PRISM_PATH_ROWS: 16 or 32 rows per workgroup (a split applies
  * to 32 only, at most 16 slices).  A forced path that cannot run a shape makes the call
  * return PRISM_ERR_UNSUPPORTED.  The kernels are correct for every admissible value (the paper's
@@ -215,31 +216,39 @@ prism_status_t prism_plan_table_clear(void);
 int32_t prism_plan_table_size(void);
 
 /*
- * Weighted partition of the 16-row decode kernel (the reduction partition of paper Table 1, "parallelized matmul
- * (reduction)", with shares that are equal over the workgroups instead of over the column tiles).  When a grid of
- * column tiles x equal K-slices would need more workgroups than the part has CUs, the library launches 256
- * workgroups instead and gives each the same share of all K-blocks, tile after tile: a share may end one tile
- * and begin the next.  prism_plan then reports a one-dimensional grid and, as split_k, the most workgroups
- * that can share a tile (what the workspace is sized for).
- * slow_slots: bit s set = column tiles whose first byte has s in bits 8-10 of its address weigh 5 : 4 in that
- *   partition, because the 256-byte-wide stripes of W in some slots stream slower than others when the row
- *   pitch of W is a multiple of 2 KiB (on the MI355X measured: slots 1 and 5, 0x22).  Applies when N is a
- *   multiple of 1024, W is on a 256-byte boundary and W2 in step with W1 modulo 2 KiB.  The shares decide the
- *   order of the fp32 sums, so with slots set, results may differ in the last bit between buffers at different
- *   addresses; for given addresses they are reproducible.  Default 0: no slot weighs more.
- * weighted_partition: 1 = use the partition where the rule above asks for it (default), 0 = never.
+ * How the 16-row decode kernel deals K out to its workgroups (the reduction partition of paper Table 1,
+ * "parallelized matmul (reduction)", with shares that are equal in streaming time instead of in K).
+ *
+ * Slow units.  When the row pitch of W is a multiple of 2 KiB, the stripe of W a workgroup streams keeps bits 7-10
+ * of its byte addresses for all rows (which 128 bytes of every 2 KiB: its unit).  On the MI355X measured, the
+ * stripes in units 3 and 11 arrive 40 % later than the others, wherever W starts and whichever CU reads them.
+ * slow_units: bit u set = unit u is slow (default 0x0808; 0: none).  Used for gated calls with at most 16 rows:
+ * they take tiles of 64 output columns (128-byte stripes of W1 and of W2) and cut the tiles in slow units into more
+ * K-slices than the others, provided N is a multiple of 1024 and all workgroups find a CU of their own; the
+ * balanced launch also needs W1 on a 128-byte boundary and W2 in step with W1 modulo 2 KiB (otherwise every tile gets
+ * the same slices).  prism_plan then reports a one-dimensional grid, tile_n = 64 and, as split_k, the slices of a
+ * slow tile (what the workspace is sized for).  The slices decide the order of the fp32 sums, so results may differ
+ * in the last bit between buffers that start in different units; for given addresses they are reproducible.
+ *
+ * mode bit 0 (default on): where a grid of column tiles x equal K-slices would need more workgroups than the part
+ * has CUs, launch 256 workgroups and give each the same share of all K-blocks, tile after tile; a share may end one
+ * tile and begin the next.  prism_plan then reports a one-dimensional grid and, as split_k, the most workgroups
+ * that can share a tile.  mode bit 1 (default off): in that partition, 256-byte-wide tiles that contain a slow
+ * unit weigh 5 : 4 (needs N a multiple of 1024 and W on a 256-byte boundary).
  * Host-side, process-wide.
  */
-prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t weighted_partition);
+prism_status_t prism_set_stream_balance(int32_t slow_units, int32_t mode);
 
 /*
  * Diagnostic, host-side: the K-blocks [*first, *first + *count) of column tile `tile` that workgroup `wg` works on
- * in a weighted partition of n_tiles tiles of kblocks K-blocks over `workgroups` workgroups; slow_tiles: bit j set =
- * tiles j, j + 8, ... weigh 5 : 4.  The same integer functions run in the kernel; this entry point lets a test check
- * that they deal every K-block out exactly once.  PRISM_ERR_UNSUPPORTED if the total weight does not fit 31 bits.
+ * in a weighted partition of n_tiles tiles of kblocks K-blocks over `workgroups` workgroups; a K-block of tile t
+ * weighs w_slow if bit (t mod period) of slow_tiles is set, else w_fast (period 8 or 16).  The same integer
+ * functions run in the kernel; this entry point lets a test check that they deal every K-block out exactly once.
+ * PRISM_ERR_UNSUPPORTED if the total weight does not fit 31 bits.
  */
 prism_status_t prism_stream_partition_blocks(int32_t workgroups, int32_t kblocks, int32_t n_tiles, int32_t slow_tiles,
-                                            int32_t wg, int32_t tile, int32_t* first, int32_t* count);
+                                            int32_t period, int32_t w_fast, int32_t w_slow, int32_t wg, int32_t tile,
+                                            int32_t* first, int32_t* count);
 
 /*
  * Diagnostic, for measurement: streams W[K,N] (16-bit elements, device memory, 16-byte aligned, N a multiple

@@ -89,7 +89,7 @@ def _load():
     L.prism_probe_stream.argtypes = [vp, vp, i64, i64, i32, vp]
     L.prism_probe_stream.restype = i32
     L.prism_set_stream_balance.argtypes = [i32, i32]
-    L.prism_stream_partition_blocks.argtypes = [i32, i32, i32, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.prism_stream_partition_blocks.argtypes = [i32] * 9 + [ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.prism_stream_partition_blocks.restype = i32
     L.prism_set_stream_balance.restype = i32
     L.prism_version.argtypes = []
@@ -165,17 +165,18 @@ def prism_set_override(path=0, split_k=0, variant=0):
         raise PrismError(st, "prism_set_override")
 
 
-def prism_set_stream_balance(slow_slots=0, weighted_partition=1):
-    st = lib.prism_set_stream_balance(int(slow_slots), int(weighted_partition))
+def prism_set_stream_balance(slow_units=0x0808, mode=1):
+    st = lib.prism_set_stream_balance(int(slow_units), int(mode))
     if st != 0:
         raise PrismError(st, "prism_set_stream_balance")
 
 
-def prism_stream_partition_blocks(workgroups, kblocks, n_tiles, slow_tiles, wg, tile):
+def prism_stream_partition_blocks(workgroups, kblocks, n_tiles, slow_tiles, wg, tile, period=8, w_fast=4, w_slow=5):
     """(first, count) of the K-blocks of `tile` that workgroup `wg` of a weighted partition works on."""
     first, count = ctypes.c_int32(0), ctypes.c_int32(0)
-    st = lib.prism_stream_partition_blocks(int(workgroups), int(kblocks), int(n_tiles), int(slow_tiles), int(wg),
-                                           int(tile), ctypes.byref(first), ctypes.byref(count))
+    st = lib.prism_stream_partition_blocks(int(workgroups), int(kblocks), int(n_tiles), int(slow_tiles), int(period),
+                                           int(w_fast), int(w_slow), int(wg), int(tile), ctypes.byref(first),
+                                           ctypes.byref(count))
     if st != 0:
         raise PrismError(st, "prism_stream_partition_blocks")
     return first.value, count.value

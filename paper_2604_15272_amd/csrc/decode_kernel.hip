@@ -16,6 +16,12 @@
 // order (so the result does not depend on arrival order), applies 1/rms (and the SiLU gate) and
 // stores Y.  The normalised X never exists in memory.
 //
+// Gated calls come in two tile forms.  Two tiles: a workgroup owns 128 output columns and keeps one accumulator
+// tile per weight matrix.  Packed: a workgroup owns 64 output columns, and one 16 x 128 MFMA tile holds their
+// products with W1 (lanes c < 8) and with W2 (lanes c >= 8): a row load reads 128 bytes of each matrix, the A
+// operand is the same for both, and the gate pairs column j with column 64 + j of the tile.  Twice the tiles,
+// so half the K-slices for the same number of workgroups (none at 14336 columns), and half the LDS traffic.
+//
 // Two ways to deal K out to workgroups: a plain grid (column tiles x S equal K-slices), or the weighted
 // partition of stream_partition.h, in which every workgroup of a one-dimensional grid gets the same share of
 // streaming time: a run of K-blocks that may end one tile and begin the next (then it makes two passes).
@@ -47,7 +53,7 @@ __device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], u32x4 a, const WRows
 }  // namespace
 
 // LDS: per wavefront a 16 x 128 fp32 tile (two for gated calls with up to eight wavefronts), plus 16 sums of squares.
-template <typename F, int NW, bool GATED>
+template <typename F, int NW, bool GATED, bool PACKED = false>
 __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restrict__ X,
                                                          const uint16_t* __restrict__ g,
                                                          const uint16_t* __restrict__ W1,
@@ -61,6 +67,8 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     constexpr int CPT = 16 * TN / NT;  // columns per thread in the epilogue (4 for 8 wavefronts)
     constexpr int TPR = TN / CPT;      // threads per output row
     static_assert(CPT >= 2 && CPT <= 8 && (CPT & (CPT - 1)) == 0, "epilogue mapping");
+    static_assert(GATED || !PACKED, "the packed tile is a gated tile");
+    constexpr int TNO = PACKED ? TN / 2 : TN;  // output columns of a tile
 
     extern __shared__ float lds[];
     float* red = lds;                    // [NW][16][TN], used once per weight matrix
@@ -76,7 +84,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     // registers across its back edge: 256 instead of 168 registers, with spills).
     auto pass = [&](const int ntile, const int split, const int S, const int b_beg, const int b_cnt)
                     __attribute__((always_inline)) {
-    const int n0 = ntile * TN;
+    const int n0 = ntile * TNO;
 
     // Buffer descriptors.  W starts at this workgroup's first row and first column; its end is the
     // end of the matrix, so rows past K read as zero.
@@ -90,8 +98,12 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     const __amdgpu_buffer_rsrc_t rx = make_rsrc(X, (u32)((size_t)M * K * 2));
     const __amdgpu_buffer_rsrc_t rg = make_rsrc(g, (u32)K * 2u);
 
-    const bool col_ok = (n0 + 8 * c) < N;
-    const u32 w_lane = col_ok ? ((u32)(8 * q) * row_bytes + (u32)(16 * c)) : kOutOfRange;
+    const int cw = PACKED ? (c & 7) : c;  // this lane's 8-column group inside its matrix's share of the tile
+    const bool col_ok = (n0 + 8 * cw) < N;
+    const u32 w_lane = col_ok ? ((u32)(8 * q) * row_bytes + (u32)(16 * cw)) : kOutOfRange;
+    // Packed: lanes c < 8 read W1, lanes c >= 8 read W2, in one instruction, so through per-lane addresses
+    // instead of a descriptor (rows past K and columns past N are predicated off and read as zero).
+    const uint16_t* w_ptr = ((PACKED && c >= 8) ? W2 : W1) + ((size_t)b_beg * KB + 8 * q) * N + n0 + 8 * cw;
     const bool row_ok = c < M;
 
     f32x4 acc1[8], acc2[8];
@@ -103,7 +115,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     float ss = 0.f;
 
     // U K-blocks per trip, so that sixteen 16-byte row loads of W are in flight per lane.
-    constexpr int U = GATED ? 1 : 2;
+    constexpr int U = (GATED && !PACKED) ? 1 : 2;
     for (int i = wave; i < b_cnt; i += U * NW) {
         WRows w1[U], w2[U];
         u32x4 xr[U], gr[U];
@@ -117,14 +129,23 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
             // X and g first: they come from L2 and let the A operand be ready before W lands.
             xr[u] = load16(rx, (row_ok && k_ok) ? (u32)(((size_t)c * K + k) * 2) : kOutOfRange);
             gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
-            load_w_block<true>(w1[u], rw1, woff, row_bytes);
-            if (GATED) load_w_block<true>(w2[u], rw2, woff, row_bytes);
+            if (PACKED) {
+                const uint16_t* pw = w_ptr + (size_t)ib * KB * N;
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    w1[u].r[r] = u32x4{0u, 0u, 0u, 0u};
+                    if (k_ok && col_ok) w1[u].r[r] = __builtin_nontemporal_load((const u32x4*)(pw + (size_t)r * N));
+                }
+            } else {
+                load_w_block<true>(w1[u], rw1, woff, row_bytes);
+                if (GATED) load_w_block<true>(w2[u], rw2, woff, row_bytes);
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const u32x4 a = scaled_a_operand<F>(xr[u], gr[u], ss);
             mfma_block<F>(acc1, a, w1[u]);
-            if (GATED) mfma_block<F>(acc2, a, w2[u]);
+            if (GATED && !PACKED) mfma_block<F>(acc2, a, w2[u]);
         }
     }
 
@@ -136,14 +157,16 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     const int m = tid / TPR;
     const int col = (tid % TPR) * CPT;
     const int n = n0 + col;
-    const bool out_ok = (m < M) && (n < N);  // N % 8 == 0 and CPT | 8: all CPT columns valid together
+    // N % 8 == 0 and CPT | 8: all CPT columns valid together.  Packed: the threads of the tile's first 64 columns
+    // produce the outputs (each pairs its columns with those 64 further on).
+    const bool out_ok = (m < M) && (n < N) && (!PACKED || col < TNO);
 
     // Reduce across wavefronts through LDS.  Accumulator j, element i of lane (q, c) is row 4q + i, column
     // 8c + j of the tile.  A gated call stores both matrices' tiles at once when LDS holds them (up to eight
     // wavefronts): one barrier instead of three (measured: 44.5 -> 43.3 us on X[8,4096], 2 x W[4096,14336]);
     // otherwise the tile of W2 reuses the space of W1's.
-    constexpr bool BOTH_TILES = GATED && NW <= 8;
-    float* red2 = red + NW * 16 * TN + NW * 16;  // behind ss_red
+    constexpr bool BOTH_TILES = GATED && (PACKED || NW <= 8);
+    float* red2 = PACKED ? red + TNO : red + NW * 16 * TN + NW * 16;  // the tile's second half, or behind ss_red
     float v1[CPT], v2[CPT];
     float ssum = 0.f;
 #pragma unroll
@@ -153,14 +176,14 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         // would sum them read nothing (half the LDS traffic with eight rows or fewer).
         if (4 * q < M) {
             store_acc_tile(red + wave * 16 * TN, TN, q, c, gi == 0 ? acc1 : acc2);
-            if (BOTH_TILES) store_acc_tile(red2 + wave * 16 * TN, TN, q, c, acc2);
+            if (BOTH_TILES && !PACKED) store_acc_tile(red2 + wave * 16 * TN, TN, q, c, acc2);
         }
         if (gi == 0 && q == 0) ss_red[wave * 16 + c] = ss;
         __syncthreads();
         float v[CPT], vb[CPT];
 #pragma unroll
         for (int e = 0; e < CPT; ++e) { v[e] = 0.f; vb[e] = 0.f; }
-        if (m < M) {
+        if (m < M && (!PACKED || col < TNO)) {
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 const float* src = red + (w * 16 + m) * TN + col;
@@ -300,17 +323,29 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
 }
 
 template <typename F, int NW>
-static hipError_t launch_decode_nw(const Call& c, int S, const StreamPartition& sp, const DecodeWorkspace& ws) {
-    const int n_tiles = (c.N + TN - 1) / TN;
+static hipError_t launch_decode_nw(const Call& c, int S, const StreamPartition& sp, bool packed,
+                                   const DecodeWorkspace& ws) {
+    const int tile_cols = packed ? TN / 2 : TN;
+    const int n_tiles = (c.N + tile_cols - 1) / tile_cols;
     dim3 grid(n_tiles, S), block(NW * 64);
     if (sp.G != 0) grid = dim3(sp.G);  // S: the most workgroups that share a tile
-    const size_t lds = (size_t)(((c.gated && NW <= 8) ? 2 : 1) * NW * 16 * TN + NW * 16) * sizeof(float);
+    const size_t lds = (size_t)(((c.gated && !packed && NW <= 8) ? 2 : 1) * NW * 16 * TN + NW * 16) * sizeof(float);
     auto* X = (const uint16_t*)c.X;
     auto* g = (const uint16_t*)c.g;
     auto* W1 = (const uint16_t*)c.W1;
     auto* W2 = (const uint16_t*)c.W2;
     auto* Y = (uint16_t*)c.Y;
-    if (c.gated) {
+    if (c.gated && packed) {
+        if constexpr (NW <= 8) {
+            auto kern = decode_kernel<F, NW, true, true>;
+            static std::atomic<uint64_t> opted{0};
+            if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
+            hipLaunchKernelGGL(kern, grid, block, lds, c.stream, X, g, W1, W2, Y, ws.acc_part, ws.ss_part, ws.tickets,
+                               c.M, c.K, c.N, c.eps, S, c.flags, sp);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else if (c.gated) {
         auto kern = decode_kernel<F, NW, true>;
         static std::atomic<uint64_t> opted{0};
         if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
@@ -327,19 +362,20 @@ static hipError_t launch_decode_nw(const Call& c, int S, const StreamPartition& 
 }
 
 template <typename F>
-static hipError_t launch_decode_fmt(const Call& c, int split_k, const StreamPartition& sp, int waves,
+static hipError_t launch_decode_fmt(const Call& c, int split_k, const StreamPartition& sp, int waves, bool packed,
                                     const DecodeWorkspace& ws) {
     switch (waves) {
-        case 4: return launch_decode_nw<F, 4>(c, split_k, sp, ws);
-        case 8: return launch_decode_nw<F, 8>(c, split_k, sp, ws);
-        case 16: return launch_decode_nw<F, 16>(c, split_k, sp, ws);
+        case 4: return launch_decode_nw<F, 4>(c, split_k, sp, packed, ws);
+        case 8: return launch_decode_nw<F, 8>(c, split_k, sp, packed, ws);
+        case 16: return launch_decode_nw<F, 16>(c, split_k, sp, packed, ws);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, const StreamPartition& sp, int waves,
+hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, const StreamPartition& sp, int waves, bool packed,
                                const DecodeWorkspace& ws) {
-    return f16 ? launch_decode_fmt<F16>(c, split_k, sp, waves, ws) : launch_decode_fmt<Bf16>(c, split_k, sp, waves, ws);
+    return f16 ? launch_decode_fmt<F16>(c, split_k, sp, waves, packed, ws)
+               : launch_decode_fmt<Bf16>(c, split_k, sp, waves, packed, ws);
 }
 
 }  // namespace prism

@@ -19,14 +19,20 @@ struct Override {
 };
 Override g_override;
 
-// The weighted partition of stream_partition.h (16-row decode kernel) and the address slots it may weigh.
-// Slots: bits 8-10 of the byte address, i.e. which 256 bytes of every 2 KiB.  Measured on MI355X with per-workgroup
-// time stamps: with a row pitch that is a multiple of 2 KiB a workgroup's 256-byte-wide stripe of W stays in one
-// slot, and the stripes in slots 1 and 5 finish 20 % later than the others (37 us against 30 us on X[8,4096],
-// 2 x W[4096,14336]) whichever XCD reads them; a row pitch of 225 x 256 bytes, which takes every workgroup
-// through all slots, finishes all of them at 32 us.  Weighing those tiles 5 : 4 takes 2 us off partitioned calls
-// with 112 or more tiles and adds 4 us with 32 tiles (more sharers per tile), so no slot is weighed by default.
-std::atomic<int32_t> g_slow_slots{0}, g_stream_partition{1};
+// Address slots that stream slowly, and what the 16-row decode kernel does about them.
+// Measured on MI355X with per-workgroup time stamps: when the row pitch of W is a multiple of 2 KiB, the stripe of
+// W a workgroup streams keeps bits 7-10 of its byte addresses for all rows (which 128 bytes of every 2 KiB: its
+// unit), and the stripes in units 3 and 11 arrive 40 % later than the others (44 us against 32 us for
+// 128-byte-wide stripes of 2 x W[4096,14336]; 256-byte-wide stripes that contain them: 37 us against 30 us),
+// whichever XCD reads them and wherever W starts; a row pitch of 225 x 256 bytes, which takes every workgroup
+// through all units, ends all stripes at 32 us.
+//  - g_slow_units: bit u set = unit u is slow.
+//  - g_stream_mode bit 0: the weighted partition of stream_partition.h where a grid would need more workgroups
+//    than CUs; bit 1: in that partition, 256-byte tiles that contain a slow unit weigh 5 : 4 (off: it takes 2 us
+//    off calls with 112 or more tiles and adds 4 us with 32 tiles, where a tile gets more sharers).
+// Gated calls with at most 16 rows use the packed tile (64 output columns: 128-byte stripes of W1 and of W2) with
+// more K-slices for the tiles in slow units when that fits the CUs: 41.8 -> 35.7 us on X[8,4096], 2 x W[4096,14336].
+std::atomic<int32_t> g_slow_units{0x0808}, g_stream_mode{1};
 
 struct Workspace {
     void* ptr;
@@ -40,8 +46,11 @@ struct Plan {
     prism_plan_t pub;
     int waves;          // decode: wavefronts per workgroup
     int row_groups;     // decode: 16-row groups per workgroup (1: the 16-row kernel)
+    bool packed;        // decode, 16-row kernel, gated: 64 output columns per tile, both matrices in one MFMA tile
     StreamPartition sp; // decode, 16-row kernel: weighted partition (G = 0: plain grid); slow = the slots, not yet
                         // rotated to the address of W
+    int base_split;     // decode, packed and balanced: K-slices of a tile outside the slow units (the grid to fall
+                        // back to when W is not aligned to its units)
     uint64_t ss_bytes;  // decode: bytes of the partial sums of squares (rounded)
 };
 
@@ -258,8 +267,17 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         if ((uint64_t)M * K * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
         // Variant: 4, 8 or 16 wavefronts for at most 16 rows; 32 or 64 rows per workgroup for more.
         int waves = 8, row_groups = 1;
+        bool packed = false;
         if (M <= kDecodeMaxRows) {
-            if (variant > 0) waves = variant;
+            // Variants 4, 8, 16: wavefronts per workgroup; 104, 108 (gated only): the same with the packed tile.
+            int v = variant;
+            if (v >= 100) {
+                if (!gated) return PRISM_ERR_UNSUPPORTED;
+                packed = true;
+                v -= 100;
+                if (v != 4 && v != 8) return PRISM_ERR_UNSUPPORTED;
+            }
+            if (v > 0) waves = v;
             if (waves != 4 && waves != 8 && waves != 16) return PRISM_ERR_UNSUPPORTED;
         } else {
             // Every 16-row group reuses the B operands built from W: 64 rows per workgroup unless the
@@ -269,11 +287,47 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             if (variant == 32 || variant == 64) row_groups = variant / 16;
             else if (variant != 0 && variant != 8) return PRISM_ERR_UNSUPPORTED;
         }
-        const int64_t row_blocks = (M + 16 * row_groups - 1) / (16 * row_groups);
-        const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
         const int64_t kblocks = (K + kDecodeKBlock - 1) / kDecodeKBlock;
+        // Packed tiles with more K-slices for the tiles in slow units (s_slow against s): gated, at most 16 rows,
+        // nothing forced but perhaps the packed variant itself, N a multiple of 1024 (a tile keeps its unit over
+        // all rows, and 16 tiles hold each unit once), every workgroup on a CU of its own.  s as for a plain call
+        // with these tiles; s_slow = s + max(1, (2 s + 2) / 5) (the slow stripes need 1.4 times as long).
+        StreamPartition balanced{};
+        int64_t balanced_slow = 0;
+        if (gated && M <= kDecodeMaxRows && (variant == 0 || packed) && forced_split <= 0 && (N * 2) % 2048 == 0 &&
+            (g_slow_units.load() & 0xFFFF) != 0) {
+            const uint32_t units = (uint32_t)g_slow_units.load() & 0xFFFFu;
+            const int64_t nt = N / (kDecodeTileN / 2), n_slow = nt / 16 * __builtin_popcount(units);
+            int64_t sb = std::min<int64_t>((256 + nt / 2) / nt, std::min<int64_t>(8, kblocks / 4)), ss = 0;
+            for (; sb >= 1; --sb) {
+                ss = sb + std::max<int64_t>(1, (2 * sb + 2) / 5);
+                if (nt * sb + n_slow * (ss - sb) <= 256) break;
+            }
+            const uint64_t G = (uint64_t)(nt * sb + n_slow * (ss - sb)), T = G * (uint64_t)kblocks;
+            const uint64_t run_rows = (uint64_t)((kblocks + std::max<int64_t>(sb, 1) - 1) / std::max<int64_t>(sb, 1)) * kDecodeKBlock + 8;
+            // Against the two-tile form: as many workgroups at work as it would have (its grid of 128-column tiles
+            // x K-slices, at most one per CU; three quarters of that if it would need the two-pass partition).
+            // Measured, packed and balanced against two tiles (us): 8 x 4096 x 14336 40.7 / 42.1, 16 x 1024 x 4096
+            // 11.9 / 13.1, 8 x 4096 x 11264 34.4 / 39.8, 8 x 4096 x 7168 24.7 / 29.5; but 8 x 4096 x 4096 (200
+            // workgroups against 256) 18.9 / 17.1 and 4 x 8192 x 8192 (144 against 256) 73 / 49.
+            const int64_t n128 = (N + kDecodeTileN - 1) / kDecodeTileN;
+            const int64_t s2 = std::max<int64_t>(1, std::min<int64_t>((256 + n128 / 2) / n128, std::min<int64_t>(8, kblocks / 8)));
+            const int64_t two_tile = (n128 * s2 > 256 && n128 < 256) ? 192 : std::min<int64_t>(n128 * s2, 256);
+            const bool worth = packed || (int64_t)G >= two_tile;
+            if (worth && sb >= 1 && nt <= kMaxTickets && ss <= kblocks && ss + 0 <= (int64_t)kStreamMaxSlices && T < (1ull << 31) &&
+                (uint64_t)ss * 2 * M * N * 4 < kTwoGiB && run_rows * (uint64_t)N * 2 < kTwoGiB) {
+                balanced = StreamPartition{(uint32_t)G, (uint32_t)kblocks, (uint32_t)nt, units, 16u, (uint32_t)sb,
+                                           (uint32_t)ss, (uint32_t)kblocks, 0u};
+                balanced_slow = ss;
+                packed = true;
+            }
+        }
+        const int64_t row_blocks = (M + 16 * row_groups - 1) / (16 * row_groups);
+        const int64_t tile_cols = packed ? kDecodeTileN / 2 : kDecodeTileN;
+        const int64_t n_tiles = (N + tile_cols - 1) / tile_cols;
         if (row_blocks > 65535 || n_tiles * row_blocks > kMaxTickets) return PRISM_ERR_UNSUPPORTED;
         int64_t S = forced_split;
+        if (balanced.G != 0) S = balanced.w_fast;
         if (S <= 0) {
             // About one workgroup per CU (measured best on MI355X: more slices only add partial-sum
             // traffic and tickets), each wavefront keeping at least one K-block.
@@ -287,7 +341,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
                 // tuner): never more than eight slices (the last arrival reads eight slices' partials in one
                 // round trip), and a slice keeps at least four K-blocks (eight when gated: two matrices), even
                 // if that leaves wavefronts idle.
-                s_max = std::min<int64_t>(8, std::max<int64_t>(1, kblocks / (gated ? 8 : 4)));
+                s_max = std::min<int64_t>(8, std::max<int64_t>(1, kblocks / ((gated && !packed) ? 8 : 4)));
             }
             if (S > s_max) S = s_max;
             if (S < 1) S = 1;
@@ -317,11 +371,19 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         // 5 : 4 when the row pitch keeps a tile in its slot (whole groups of eight tiles).
         StreamPartition sp{};
         int64_t s_pitch = S;
-        if (row_groups == 1 && forced_split <= 0 && g_stream_partition.load() != 0 && n_tiles * S > 256 &&
-            n_tiles < 256) {
-            const int slow = ((N * 2) % 2048 == 0 && n_tiles % 8 == 0) ? (g_slow_slots.load() & 0xFF) : 0;
-            const uint64_t T = (uint64_t)(4 * n_tiles + n_tiles / 8 * __builtin_popcount((unsigned)slow)) * kblocks;
-            int64_t G = std::min<int64_t>(256, std::min<int64_t>(n_tiles * kblocks / (gated ? 8 : 4), 8 * n_tiles));
+        if (balanced.G != 0) {
+            sp = balanced;
+            s_pitch = balanced_slow;
+        } else if (row_groups == 1 && forced_split <= 0 && (g_stream_mode.load() & 1) != 0 && n_tiles * S > 256 &&
+                   n_tiles < 256) {
+            // slot j (256 bytes) holds units 2j and 2j + 1
+            uint32_t slow = 0;
+            if (!packed && (g_stream_mode.load() & 2) != 0 && (N * 2) % 2048 == 0 && n_tiles % 8 == 0)
+                for (int j = 0; j < 8; ++j)
+                    if ((g_slow_units.load() >> (2 * j)) & 3) slow |= 1u << j;
+            StreamPartition cand{0u, (uint32_t)kblocks, (uint32_t)n_tiles, slow, 8u, 4u, 5u, 0u, 0u};
+            const uint64_t T = sp_total(cand);
+            int64_t G = std::min<int64_t>(256, std::min<int64_t>(n_tiles * kblocks / ((gated && !packed) ? 8 : 4), 8 * n_tiles));
             if (G < 1) G = 1;
             if (T < (1ull << 31) && n_tiles < (1 << 24)) {
                 const uint64_t q = T / G;
@@ -334,18 +396,22 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
                 // q < a tile's weight: a workgroup's range (q or q + 1 units) meets at most two tiles.
                 if (q < 4 * (uint64_t)kblocks && most <= kStreamMaxSlices && partials_fit(most) &&
                     run_rows * (uint64_t)N * 2 < kTwoGiB) {
-                    sp = StreamPartition{(uint32_t)G, (uint32_t)kblocks, (uint32_t)n_tiles, (uint32_t)slow,
-                                         (uint32_t)q, (uint32_t)(T % G)};
+                    sp = cand;
+                    sp.G = (uint32_t)G;
+                    sp.q = (uint32_t)q;
+                    sp.r = (uint32_t)(T % G);
                     s_pitch = most;
                 }
             }
         }
         out->waves = waves;
         out->row_groups = row_groups;
+        out->packed = packed;
         out->sp = sp;
+        out->base_split = (int)S;
         p.split_k = (int32_t)S;
         p.tile_m = 16 * row_groups;
-        p.tile_n = kDecodeTileN;
+        p.tile_n = (int32_t)tile_cols;
         p.grid_x = (int32_t)n_tiles;
         p.grid_y = (int32_t)S;
         if (sp.G != 0) {
@@ -467,24 +533,31 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                 ws.ss_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES);
                 ws.acc_part = (float*)(base + PRISM_WORKSPACE_HEADER_BYTES + plan.ss_bytes);
             }
-            // The slots are read off the address of W: tile j's slot is that of tile 0 plus j.  W off a slot
-            // boundary, or W2 out of step with W1, gets equal weights.
+            // The units are read off the address of W: tile j's unit is that of tile 0 plus j (128-byte tiles) or
+            // its pair of units (256-byte tiles).  W off a tile boundary, or W2 out of step with W1, gets equal
+            // shares: the plain grid for the packed tile, equal weights in the partition.
             StreamPartition sp = plan.sp;
+            int split = plan.pub.split_k;
             if (sp.G != 0 && sp.slow != 0) {
                 const uintptr_t a1 = reinterpret_cast<uintptr_t>(W1), a2 = reinterpret_cast<uintptr_t>(W2);
-                if ((a1 & 255u) != 0 || (gated && ((a1 ^ a2) & 2047u) != 0)) {
-                    const uint64_t T = (uint64_t)4 * sp.n_tiles * sp.kblocks;
+                const uintptr_t tile_bytes = plan.packed ? 128u : 256u;
+                const bool aligned = (a1 & (tile_bytes - 1)) == 0 && (!gated || ((a1 ^ a2) & 2047u) == 0);
+                if (aligned) {
+                    const unsigned first = (unsigned)(a1 / tile_bytes) & (sp.period - 1u), mask = (1u << sp.period) - 1u;
+                    sp.slow = ((sp.slow >> first) | (sp.slow << (sp.period - first))) & mask;
+                } else if (plan.packed) {
+                    sp = StreamPartition{};
+                    split = plan.base_split;
+                } else {
                     sp.slow = 0;
+                    const uint64_t T = sp_total(sp);
                     sp.q = (uint32_t)(T / sp.G);
                     sp.r = (uint32_t)(T % sp.G);
-                } else {
-                    const unsigned slot0 = (unsigned)(a1 >> 8) & 7u;
-                    sp.slow = ((sp.slow >> slot0) | (sp.slow << (8 - slot0))) & 0xFFu;
                 }
             }
             err = plan.row_groups > 1
                       ? launch_decode_rows_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.row_groups, ws)
-                      : launch_decode_16bit(c, dtype == PRISM_F16, plan.pub.split_k, sp, plan.waves, ws);
+                      : launch_decode_16bit(c, dtype == PRISM_F16, split, sp, plan.waves, plan.packed, ws);
             break;
         }
         case PRISM_PATH_PREFILL:
@@ -703,22 +776,23 @@ int32_t prism_plan_table_size(void) {
     return g_table_size;
 }
 
-prism_status_t prism_set_stream_balance(int32_t slow_slots, int32_t weighted_partition) {
-    if (slow_slots < 0 || slow_slots > 0xFF || weighted_partition < 0 || weighted_partition > 1)
-        return PRISM_ERR_INVALID_ARG;
-    g_slow_slots.store(slow_slots);
-    g_stream_partition.store(weighted_partition);
+prism_status_t prism_set_stream_balance(int32_t slow_units, int32_t mode) {
+    if (slow_units < 0 || slow_units > 0xFFFF || mode < 0 || mode > 3) return PRISM_ERR_INVALID_ARG;
+    g_slow_units.store(slow_units);
+    g_stream_mode.store(mode);
     return PRISM_OK;
 }
 
 prism_status_t prism_stream_partition_blocks(int32_t workgroups, int32_t kblocks, int32_t n_tiles, int32_t slow_tiles,
-                                            int32_t wg, int32_t tile, int32_t* first, int32_t* count) {
-    if (!first || !count || workgroups < 1 || workgroups > 65535 || kblocks < 1 || n_tiles < 1 || slow_tiles < 0 ||
-        slow_tiles > 0xFF || wg < 0 || wg >= workgroups || tile < 0 || tile >= n_tiles)
+                                            int32_t period, int32_t w_fast, int32_t w_slow, int32_t wg, int32_t tile,
+                                            int32_t* first, int32_t* count) {
+    if (!first || !count || workgroups < 1 || workgroups > 65535 || kblocks < 1 || n_tiles < 1 ||
+        (period != 8 && period != 16) || slow_tiles < 0 || slow_tiles >= (1 << period) || w_fast < 1 || w_slow < w_fast ||
+        w_slow > 64 || wg < 0 || wg >= workgroups || tile < 0 || tile >= n_tiles)
         return PRISM_ERR_INVALID_ARG;
-    StreamPartition sp{(uint32_t)workgroups, (uint32_t)kblocks, (uint32_t)n_tiles, (uint32_t)slow_tiles, 0, 0};
-    const uint64_t T = (uint64_t)(4 * (uint64_t)n_tiles + (uint64_t)(n_tiles >> 3) * __builtin_popcount((unsigned)slow_tiles) +
-                                  __builtin_popcount((unsigned)slow_tiles & ((1u << (n_tiles & 7)) - 1u))) * (uint64_t)kblocks;
+    StreamPartition sp{(uint32_t)workgroups, (uint32_t)kblocks, (uint32_t)n_tiles, (uint32_t)slow_tiles, (uint32_t)period,
+                       (uint32_t)w_fast, (uint32_t)w_slow, 0u, 0u};
+    const uint64_t T = sp_total(sp);
     if (T >= (1ull << 31)) return PRISM_ERR_UNSUPPORTED;
     sp.q = (uint32_t)(T / sp.G);
     sp.r = (uint32_t)(T % sp.G);

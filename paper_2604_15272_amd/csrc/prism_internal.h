@@ -117,7 +117,7 @@ hipError_t launch_simple_bf16(const Call& c);
 hipError_t launch_simple_f16(const Call& c);
 // The matrix-core kernels, for either 16-bit storage format (f16 = false: bf16).
 struct StreamPartition;
-hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, const StreamPartition& sp, int waves,
+hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, const StreamPartition& sp, int waves, bool packed,
                                const DecodeWorkspace& ws);
 hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, const DecodeWorkspace& ws);
 hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);

@@ -98,32 +98,32 @@ def test_decode_is_bit_reproducible_and_leaves_tickets_clean(P):
 
 # ---- decode path, weighted partition (256 workgroups with equal shares where tiles x slices would be more) -----
 
-@pytest.mark.parametrize("slow", [0, 0x22])
+@pytest.mark.parametrize("mode", [1, 3])
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("M,K,N", [(16, 4096, 11008), (8, 2048, 9216), (16, 1000, 5640), (3, 4096, 18432),
                                    (16, 8192, 7168)])
-def test_decode_weighted_partition(P, M, K, N, gated, slow):
-    """Shares that end one tile and begin the next (two passes), with and without heavier slow-slot tiles."""
-    P.prism_set_stream_balance(slow, 1)
+def test_decode_weighted_partition(P, M, K, N, gated, mode):
+    """Shares that end one tile and begin the next (two passes), with and without heavier tiles around slow units."""
+    P.prism_set_stream_balance(0x0808, mode)
     try:
         plan = P.prism_plan(int(gated), M, K, N, P.PRISM_BF16)
         if not gated:
             assert (plan["path"], plan["grid_x"], plan["grid_y"]) == (P.PRISM_PATH_DECODE, 256, 1), plan
         _case(P, pi.BF16, M, K, N, gated, seed=450 + N % 97, expect_path=P.PRISM_PATH_DECODE)
     finally:
-        P.prism_set_stream_balance(0, 1)
+        P.prism_set_stream_balance(0x0808, 1)
 
 
 def test_decode_weighted_partition_f16_and_grid_agree(P):
     """The partition changes who sums what, not the result beyond rounding: against the oracle, and against the
     plain grid of the same call."""
     e1 = _case(P, pi.F16, 16, 4096, 9216, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
-    P.prism_set_stream_balance(0, 0)
+    P.prism_set_stream_balance(0x0808, 0)
     try:
         assert P.prism_plan(0, 16, 4096, 9216, P.PRISM_F16)["grid_y"] > 1
         e0 = _case(P, pi.F16, 16, 4096, 9216, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
     finally:
-        P.prism_set_stream_balance(0, 1)
+        P.prism_set_stream_balance(0x0808, 1)
     assert abs(e1 - e0) < 2.5e-3
 
 
@@ -140,7 +140,7 @@ def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
     Wb.copy_(Wa)
     assert Wb.data_ptr() % 256 == 16
     yhat = run_oracle(stored, pi.BF16, False, 1e-6)
-    P.prism_set_stream_balance(0x22, 1)
+    P.prism_set_stream_balance(0x0808, 3)
     try:
         assert P.prism_plan(0, M, K, N, P.PRISM_BF16)["grid_x"] == 256
         for W in (Wa, Wb):
@@ -154,7 +154,61 @@ def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
                 assert torch.equal(o.view(torch.uint16), outs[0].view(torch.uint16))
             assert_parity(from_device(outs[0], pi.BF16), yhat, pi.BF16, f"partition, W at {W.data_ptr() % 256} mod 256")
     finally:
-        P.prism_set_stream_balance(0, 1)
+        P.prism_set_stream_balance(0x0808, 1)
+
+
+# ---- gated decode, packed tile (64 output columns: W1 and W2 in one matrix-core tile), balanced over slow units ---
+
+@pytest.mark.parametrize("dtype", [pi.BF16, pi.F16])
+@pytest.mark.parametrize("M,K,N", [(8, 4096, 14336), (16, 1024, 4096), (3, 2048, 7168), (16, 8192, 1024), (1, 512, 2048)])
+def test_decode_packed_and_balanced_as_dispatched(P, M, K, N, dtype):
+    plan = P.prism_plan(1, M, K, N, DTYPE_CODE[dtype])
+    assert (plan["path"], plan["tile_n"], plan["grid_y"]) == (P.PRISM_PATH_DECODE, 64, 1) and plan["grid_x"] > N // 64, plan
+    _case(P, dtype, M, K, N, True, seed=470 + M, expect_path=P.PRISM_PATH_DECODE)
+
+
+@pytest.mark.parametrize("variant", [104, 108])
+@pytest.mark.parametrize("split", [1, 2, 3, 7, 16, 33])
+def test_decode_packed_every_split_and_wave_count(P, split, variant):
+    """The packed tile in a plain grid of K-slices, ragged in K (4104) and in N (520: the ninth tile has 8 columns)."""
+    _case(P, pi.BF16, 16, 4104, 520, True, seed=480 + split, path=P.PRISM_PATH_DECODE, split=split, variant=variant)
+    _case(P, pi.BF16, 5, 1000, 64, True, seed=481 + split, path=P.PRISM_PATH_DECODE, split=split, variant=variant)
+
+
+def test_decode_packed_off_its_units_and_reproducible(P):
+    """W1 off a 128-byte boundary, or W2 out of step with W1, get the same K-slices for every tile; W1 in another
+    unit moves the slow tiles with it.  Every placement matches the oracle and repeats bit for bit."""
+    import torch
+    from gpu_util import to_device, from_device
+    M, K, N = 8, 2048, 7168
+    stored = pi.draw(pi.BF16, M, K, N, True, 490)
+    X, g = (to_device(stored[k], pi.BF16) for k in ("X", "g"))
+    W1a, W2a = to_device(stored["W1"], pi.BF16), to_device(stored["W2"], pi.BF16)
+    yhat = run_oracle(stored, pi.BF16, True, 1e-6)
+    assert P.prism_plan(1, M, K, N, P.PRISM_BF16)["tile_n"] == 64
+
+    def placed(src, offset_elems, anchor):
+        """A copy of src that starts offset_elems elements past a 2 KiB boundary in step with anchor."""
+        flat = torch.empty(K * N + 4096, dtype=torch.bfloat16, device="cuda")
+        skew = (-(flat.data_ptr() - anchor) % 2048) // 2
+        v = flat[skew + offset_elems:skew + offset_elems + K * N].view(K, N)
+        v.copy_(src)
+        return v, flat
+
+    anchor = W1a.data_ptr()
+    for off1, off2 in ((0, 0), (8, 8), (0, 128), (64 * 5, 64 * 5), (64, 64 + 1024)):
+        W1, keep1 = placed(W1a, off1, anchor)
+        W2, keep2 = placed(W2a, off2, anchor)
+        outs = []
+        for _ in range(10):
+            Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+            P.prism_rmsnorm_gated_mlp(X, g, W1, W2, Y)
+            outs.append(Y)
+        torch.cuda.synchronize()
+        for o in outs[1:]:
+            assert torch.equal(o.view(torch.uint16), outs[0].view(torch.uint16))
+        assert_parity(from_device(outs[0], pi.BF16), yhat, pi.BF16,
+                      f"packed, W1 at {W1.data_ptr() % 2048} and W2 at {W2.data_ptr() % 2048} mod 2048")
 
 
 # ---- decode path, more than 16 rows (several 16-row groups per workgroup, row blocks in the grid) --------

@@ -266,16 +266,22 @@ def test_plans_of_random_shapes_are_consistent(P):
         if p["path"] == P.PRISM_PATH_PREFILL:
             assert p["grid_x"] == -(-M // p["tile_m"]) * -(-N // cols), what
         elif p["path"] == P.PRISM_PATH_DECODE or (p["path"] == P.PRISM_PATH_ROWS and p["tile_m"] == 32):
-            if p["path"] == P.PRISM_PATH_DECODE and p["tile_m"] == 16 and p["grid_y"] == 1 and p["grid_x"] != -(-N // 128):
+            tiles = -(-N // p["tile_n"])
+            if p["path"] == P.PRISM_PATH_DECODE and p["tile_n"] == 64:
+                # gated, packed tiles, more K-slices for the tiles in slow units: every workgroup on its own CU
+                assert op == 1 and M <= 16 and N % 1024 == 0 and p["grid_y"] == 1, what
+                assert tiles < p["grid_x"] <= 256 and 2 <= p["split_k"] <= 32, what
+                assert (p["grid_x"] - tiles // 8 * p["split_k"]) % (tiles - tiles // 8) == 0, what
+            elif p["path"] == P.PRISM_PATH_DECODE and p["tile_m"] == 16 and p["grid_y"] == 1 and p["grid_x"] != tiles:
                 # weighted partition: 256 workgroups where tiles x slices would have been more
-                assert p["grid_x"] == 256 and -(-N // 128) < 256 and 2 <= p["split_k"] <= 32, what
+                assert p["grid_x"] == 256 and tiles < 256 and 2 <= p["split_k"] <= 32, what
             else:
-                assert (p["grid_x"], p["grid_y"], max(1, p["grid_z"])) == (-(-N // 128), p["split_k"], -(-M // p["tile_m"])), what
+                assert (p["grid_x"], p["grid_y"], max(1, p["grid_z"])) == (tiles, p["split_k"], -(-M // p["tile_m"])), what
             assert p["tile_m"] in (16, 32, 64) and (p["tile_m"] == 16) == (M <= 16 and op != 2), what
             if p["split_k"] > 1:
                 G = 2 if op == 1 else 1
                 part = (2 * 32 if op == 2 else p["tile_m"]) * 4
-                ss = -(-(-(-N // 128) * -(-M // p["tile_m"]) * p["split_k"] * part) // 256) * 256
+                ss = -(-(tiles * -(-M // p["tile_m"]) * p["split_k"] * part) // 256) * 256
                 assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * G * M * N * 4, what
         else:
             assert (p["grid_x"], p["grid_y"]) == (-(-N // p["tile_n"]), -(-M // p["tile_m"])), what
@@ -325,6 +331,15 @@ def test_weighted_partition_deals_every_k_block_out_once(P):
         assert per_wg.max() - per_wg.min() <= 2 * 5 + 1, (what, per_wg)
         if T // G < 4 * kblocks:
             assert max(len(ts) for ts in tiles_of_wg) <= 2, what
+    # weights (s, s') over G = the sum of s or s' over the tiles: every share is a whole slice of one tile
+    G = 224 * 1 + 28
+    for wg in range(G):
+        runs = [(t,) + P.prism_stream_partition_blocks(G, 128, 224, 0x0808, wg, t, period=16, w_fast=1, w_slow=2)
+                for t in range(224)]
+        runs = [r for r in runs if r[2]]
+        assert len(runs) == 1, (wg, runs)
+        t, first, count = runs[0]
+        assert (count, first % 64) == ((64, 0) if t % 16 in (3, 11) else (128, 0)), (wg, runs)
     # what the dispatcher relies on: a share below one tile's weight meets at most ceil(w * kblocks / q) + 1 workgroups
     owner = _partition(P, 256, 128, 112, 0x22)
     q = (112 * 4 + 28) * 128 // 256
@@ -342,27 +357,67 @@ def test_plan_uses_the_partition_when_the_grid_would_not_fit(P):
     assert p["split_k"] == -(-4 * 128 // q) + 1
     ss = -(-(86 * p["split_k"] * 16 * 4) // 256) * 256
     assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * 16 * 11008 * 4
-    P.prism_set_stream_balance(0, 0)
+    P.prism_set_stream_balance(0x0808, 0)
     try:
         c = P.prism_plan(0, 16, 4096, 11008, bf16)
         assert (c["grid_x"], c["grid_y"], c["split_k"]) == (86, 3, 3)
     finally:
-        P.prism_set_stream_balance(0, 1)
-    # the benchmark configurations fit a grid and keep it
+        P.prism_set_stream_balance(0x0808, 1)
+    # the headline configuration fits a grid and keeps it
     assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 4096, bf16)) == (32, 8)
-    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(1, 8, 4096, 14336, bf16)) == (112, 2)
     # a forced split keeps the grid
     P.prism_set_override(P.PRISM_PATH_DECODE, 3, 0)
     try:
         assert P.prism_plan(0, 16, 4096, 11008, bf16)["grid_y"] == 3
     finally:
         P.prism_set_override(0, 0, 0)
-    with pytest.raises(P.PrismError):
-        P.prism_set_stream_balance(0x100, 1)
-    with pytest.raises(P.PrismError):
-        P.prism_set_stream_balance(0, 2)
+    for bad in ((0x10000, 1), (-1, 1), (0, 4), (0, -1)):
+        with pytest.raises(P.PrismError):
+            P.prism_set_stream_balance(*bad)
     with pytest.raises(P.PrismError):
         P.prism_stream_partition_blocks(4, 8, 8, 0, 4, 0)
+    with pytest.raises(P.PrismError):
+        P.prism_stream_partition_blocks(4, 8, 8, 0, 0, 0, period=12)
+
+
+def test_gated_decode_plan_packs_and_balances(P):
+    """Gated calls with at most 16 rows: tiles of 64 output columns with more K-slices for the tiles in slow units,
+    when that puts at least as many workgroups to work as the two-tile form would."""
+    bf16 = P.PRISM_BF16
+    p = P.prism_plan(1, 8, 4096, 14336, bf16)             # the gated decode configuration: 224 tiles, 28 of them slow
+    assert (p["path"], p["tile_n"], p["grid_x"], p["grid_y"], p["split_k"]) == (P.PRISM_PATH_DECODE, 64, 224 + 28, 1, 2)
+    ss = -(-(224 * 2 * 16 * 4) // 256) * 256
+    assert p["workspace_bytes"] == 262144 + ss + 2 * 2 * 8 * 14336 * 4
+    assert P.prism_plan(1, 8, 4096, 7168, bf16)["grid_x"] == 112 * 2 + 14            # 2 slices, 3 for the slow tiles
+    assert P.prism_plan(1, 8, 4096, 7168, bf16)["split_k"] == 3
+    # fewer workgroups than the two-tile grid would have: two tiles
+    assert (lambda d: (d["tile_n"], d["grid_x"], d["grid_y"]))(P.prism_plan(1, 8, 4096, 4096, bf16)) == (128, 32, 8)
+    assert (lambda d: (d["tile_n"], d["grid_x"], d["grid_y"]))(P.prism_plan(1, 4, 8192, 8192, bf16)) == (128, 64, 4)
+    # no room for more slices (256 tiles of 64 columns), N not a multiple of 1024, more than 16 rows: two tiles
+    assert P.prism_plan(1, 8, 4096, 16384, bf16)["tile_n"] == 128
+    assert P.prism_plan(1, 8, 4096, 14336 + 128, bf16)["tile_n"] == 128
+    assert P.prism_plan(1, 24, 4096, 14336, bf16)["tile_n"] == 128
+    # no slow units named, or a forced split: two tiles; the packed variants by name, with any split
+    P.prism_set_stream_balance(0, 1)
+    try:
+        assert (lambda d: (d["tile_n"], d["grid_x"], d["grid_y"]))(P.prism_plan(1, 8, 4096, 14336, bf16)) == (128, 112, 2)
+    finally:
+        P.prism_set_stream_balance(0x0808, 1)
+    for variant, split, expect in ((0, 2, (128, 112, 2, 512)), (108, 3, (64, 224, 3, 512)), (104, 1, (64, 224, 1, 256)),
+                                   (108, 0, (64, 252, 1, 512))):
+        P.prism_set_override(P.PRISM_PATH_DECODE, split, variant)
+        try:
+            d = P.prism_plan(1, 8, 4096, 14336, bf16)
+            assert (d["tile_n"], d["grid_x"], d["grid_y"], d["block"]) == expect, (variant, split, d)
+        finally:
+            P.prism_set_override(0, 0, 0)
+    for variant in (104, 116, 100):
+        P.prism_set_override(P.PRISM_PATH_DECODE, 0, variant)
+        try:
+            with pytest.raises(P.PrismError):
+                P.prism_plan(0 if variant == 104 else 1, 8, 4096, 14336, bf16)    # not gated; 16 wavefronts; no such count
+        finally:
+            P.prism_set_override(0, 0, 0)
 
 
 def test_shapes_past_the_32_bit_offsets_take_the_plain_kernel(P):
