@@ -17,6 +17,7 @@ import random
 from . import binding as B
 
 _DECODE_VARIANTS = (4, 8, 16, 32, 64)   # wavefronts (at most 16 rows) or rows per workgroup (more)
+_PACKED_VARIANTS = (104, 108)           # gated, at most 16 rows: 4 or 8 wavefronts on tiles of 64 output columns
 _SOFTMAX_MAX_SPLIT = 16
 _DECODE_MAX_ROWS = 512                  # the decode path re-reads W per row block: not worth timing beyond
 _PLAIN_TILES = (256256, 256192, 128128, 64064)
@@ -39,6 +40,9 @@ def candidates(op, M, K, N, dtype, max_split=64):
                 if M > _DECODE_MAX_ROWS:
                     continue
                 grid = [(s, v) for v in _DECODE_VARIANTS for s in range(1, max_split + 1)]
+                if op == B.PRISM_OP_RMSNORM_GATED_MLP:
+                    # split 0: the library's own slices, more of them for the tiles in slow address units
+                    grid += [(s, v) for v in _PACKED_VARIANTS for s in range(0, max_split + 1)]
             else:
                 grid = [(0, t) for t in (_GATED_TILES if op == B.PRISM_OP_RMSNORM_GATED_MLP else _PLAIN_TILES)]
             seen = set()
@@ -49,12 +53,12 @@ def candidates(op, M, K, N, dtype, max_split=64):
                 except B.PrismError:
                     continue
                 # the planner clamps split factors: keep one candidate per distinct plan
-                key = (plan["path"], plan["split_k"], plan["tile_m"], plan["tile_n"], plan["block"])
+                key = (plan["path"], plan["split_k"], plan["tile_m"], plan["tile_n"], plan["block"], plan["grid_x"])
                 if plan["path"] != path or key in seen:
                     continue
                 seen.add(key)
                 out.append({"path": path,
-                            "split_k": plan["split_k"] if path in (B.PRISM_PATH_DECODE, B.PRISM_PATH_ROWS) else 0,
+                            "split_k": plan["split_k"] if (path in (B.PRISM_PATH_DECODE, B.PRISM_PATH_ROWS) and split) else 0,
                             "variant": variant, "plan": plan})
     finally:
         B.prism_set_override(0, 0, 0)

@@ -484,6 +484,11 @@ def test_tuner_enumerates_admissible_assignments(P):
     assert {x["plan"]["tile_m"] for x in mid} == {32, 64} and all(x["plan"]["block"] == 512 for x in mid)
     gmid = [x for x in tune.candidates(1, 100, 2048, 1024, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
     assert {x["plan"]["tile_m"] for x in gmid} == {32, 64}
+    # gated, at most 16 rows: the packed tile too, also with the library's own (balanced) slices
+    gd = [x for x in tune.candidates(1, 8, 4096, 14336, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
+    assert {x["plan"]["tile_n"] for x in gd} == {64, 128}
+    assert any(x["variant"] == 108 and x["split_k"] == 0 and x["plan"]["grid_x"] == 252 for x in gd)
+    assert all(x["plan"]["tile_n"] == 128 for x in dec)
     # the softmax operator: the plain kernel, 16 rows per workgroup, 32 rows with 1..16 K-slices
     sm = tune.candidates(P.PRISM_OP_SOFTMAX_MATMUL, 64, 16384, 128, P.PRISM_F16)
     assert {x["path"] for x in sm} == {P.PRISM_PATH_SIMPLE, P.PRISM_PATH_ROWS}
