@@ -31,7 +31,7 @@ Override g_override;
 //    than CUs; bit 1: in that partition, 256-byte tiles that contain a slow unit weigh 5 : 4 (off: it takes 2 us
 //    off calls with 112 or more tiles and adds 4 us with 32 tiles, where a tile gets more sharers).
 // Gated calls with at most 16 rows use the packed tile (64 output columns: 128-byte stripes of W1 and of W2) with
-// more K-slices for the tiles in slow units when that fits the CUs: 41.8 -> 35.7 us on X[8,4096], 2 x W[4096,14336].
+// more K-slices for the tiles in slow units when that fits the CUs: 42.1 -> 40.7 us on X[8,4096], 2 x W[4096,14336].
 std::atomic<int32_t> g_slow_units{0x0808}, g_stream_mode{1};
 
 struct Workspace {

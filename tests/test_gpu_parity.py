@@ -175,6 +175,17 @@ def test_decode_packed_every_split_and_wave_count(P, split, variant):
     _case(P, pi.BF16, 5, 1000, 64, True, seed=481 + split, path=P.PRISM_PATH_DECODE, split=split, variant=variant)
 
 
+def test_decode_packed_in_the_weighted_partition(P):
+    """The packed tile by name where its grid would not fit (146 tiles x 2 slices): 256 workgroups, two passes."""
+    P.prism_set_override(P.PRISM_PATH_DECODE, 0, 108)
+    try:
+        plan = P.prism_plan(1, 8, 2048, 9344, P.PRISM_BF16)
+        assert (plan["tile_n"], plan["grid_x"], plan["grid_y"]) == (64, 256, 1), plan
+    finally:
+        P.prism_set_override(0, 0, 0)
+    _case(P, pi.BF16, 8, 2048, 9344, True, seed=485, path=P.PRISM_PATH_DECODE, variant=108)
+
+
 def test_decode_packed_off_its_units_and_reproducible(P):
     """W1 off a 128-byte boundary, or W2 out of step with W1, get the same K-slices for every tile; W1 in another
     unit moves the slow tiles with it.  Every placement matches the oracle and repeats bit for bit."""
