@@ -254,20 +254,33 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
         __syncthreads();
         if (!is_last) return;
         if (tid == 0) tickets[bi] = 0u;  // ready for the next call on this workspace
-        if (!head_ok) return;
         // Global maximum of the row, then the partials rescaled by exp(m_s - max), in slice order.  Eight
         // slices' loads are issued before the first is used (one round trip to memory per batch, not per slice;
         // sixteen at a time spill registers and double the kernel's time).  With eight slices or fewer the
-        // maximum comes out of the same batch (one round trip in all); with more, the maxima are read first.
+        // maximum comes out of the same batch (one round trip in all); with more, all slices' maxima are read
+        // first, in one round trip: the workgroup's threads share the (slice, head) pairs and pass them on
+        // through LDS (the partial outputs there have been consumed before the barriers above).
         constexpr int BATCH = 8;
         float gmax = -__builtin_inff();
-        for (int t0 = 0; S > BATCH && t0 < S; t0 += BATCH) {
-            float mm[BATCH];
+        if (S > BATCH) {
+            float* sm = red;  // [S][16]
+            constexpr int PER = kAttnMaxSlices * 16 / NT;
+            float mv[PER];
 #pragma unroll
-            for (int j = 0; j < BATCH; ++j) mm[j] = load_coherent(m_part + ((size_t)bi * S + min(t0 + j, S - 1)) * 16 + m);
+            for (int k = 0; k < PER; ++k) {
+                const int idx = tid + NT * k;
+                mv[k] = idx < S * 16 ? load_coherent(m_part + (size_t)bi * S * 16 + idx) : -__builtin_inff();
+            }
 #pragma unroll
-            for (int j = 0; j < BATCH; ++j) gmax = fmaxf(gmax, mm[j]);
+            for (int k = 0; k < PER; ++k) {
+                const int idx = tid + NT * k;
+                if (idx < S * 16) sm[idx] = mv[k];
+            }
+            __syncthreads();
+            if (head_ok)
+                for (int t = 0; t < S; ++t) gmax = fmaxf(gmax, sm[t * 16 + m]);
         }
+        if (!head_ok) return;
 #pragma unroll
         for (int e = 0; e < CPT; ++e) v[e] = 0.f;
         den = 0.f;

@@ -474,9 +474,9 @@ prism_status_t make_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, p
         // workgroup reads in one round trip; longer contexts get longer slices first and more of them later
         // (measured with two batch entries of eight heads: 1024 keys 8.1 us in 8 slices, 8.7 in 16; 2048 keys
         // 9.3 us in 16, 10.0 in 8; 4096 keys 11.5 us in 16, 12.0 in 32; 8192 keys 14.2 us in 32, 14.9 in 16;
-        // 131072 keys 48 us in 64, 65 in 32).
+        // 32768 keys 22.3 us in 64, 23.7 in 32; 131072 keys 46 us in 64, 65 in 32).
         S = (H + keys - 1) / keys;
-        if (S > 8) S = H <= 1536 ? 8 : (H <= 6144 ? 16 : (H <= 32768 ? 32 : 64));
+        if (S > 8) S = H <= 1536 ? 8 : (H <= 6144 ? 16 : (H <= 16384 ? 32 : 64));
     }
     if (S > kAttnMaxSlices) S = kAttnMaxSlices;
     keys = ((H + S - 1) / S + 31) / 32 * 32;
