@@ -178,6 +178,15 @@ def measure(idx, steps, warmup):
         res["cache_hot_kernel_ms"] = hot_ms
         res["cache_hot_GBps"] = nbytes / (hot_ms * 1e-3) / 1e9
         res["stream_probe_ms"] = r.probe(steps, warmup)
+        if r.plan["tile_n"] == 64:
+            # The dispatcher chose packed tiles with more K-slices for the tiles in slow address units: the same
+            # call with that turned off (two 128-column tiles per workgroup, equal slices), for comparison.
+            r.P.prism_set_stream_balance(0, 1)
+            try:
+                r.P.ensure_workspace(r.P.prism_workspace_bytes(r.op, wl.M, wl.K, wl.N, r.dt))
+                _, res["equal_slices_kernel_ms"] = r.timed(steps, warmup)
+            finally:
+                r.P.prism_set_stream_balance(0x0808, 1)
     else:
         res.update(value=flops / (wall_ms * 1e-3) / 1e12, unit="TFLOP/s", bound="mfma",
                    achieved=flops / (k_mean * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS)
@@ -185,6 +194,8 @@ def measure(idx, steps, warmup):
     if "stream_probe_ms" in res:
         log(f"[bench]   read-only probe (128-column stripes, as many workgroups): {res['stream_probe_ms'] * 1e3:.2f} us per launch "
             f"({nbytes / (res['stream_probe_ms'] * 1e-3) / 1e9:.0f} GB/s)")
+    if "equal_slices_kernel_ms" in res:
+        log(f"[bench]   with equal K-slices for all tiles (two-tile form): {res['equal_slices_kernel_ms'] * 1e3:.2f} us per launch")
     log(f"[bench]   {res['value']:.1f} {res['unit']} back-to-back ({wall_ms * 1e3:.2f} us/step wall, "
         f"{ev_ms * 1e3:.2f} by events); kernel alone {k_mean * 1e3:.2f} us -> {res['achieved']:.1f} {res['unit']} "
         f"= {100 * res['frac']:.1f}% of {res['bound']} peak")
@@ -502,7 +513,7 @@ def main():
             del r
             others.append({k: res[k] for k in ("workload", "plan", "steps", "ms_per_step", "event_ms_per_step",
                                                "kernel_ms", "value", "unit", "bound", "achieved", "peak", "frac",
-                                               "stream_probe_ms") if k in res})
+                                               "stream_probe_ms", "equal_slices_kernel_ms") if k in res})
         out["other_workloads"] = others
         torch.cuda.empty_cache()
         log("[bench] the paper's workloads at its shapes, fp16, no gain (output width assumed: see PAPER_SHAPES)")
