@@ -298,7 +298,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             (g_slow_units.load() & 0xFFFF) != 0) {
             const uint32_t units = (uint32_t)g_slow_units.load() & 0xFFFFu;
             const int64_t nt = N / (kDecodeTileN / 2), n_slow = nt / 16 * __builtin_popcount(units);
-            int64_t sb = std::min<int64_t>((256 + nt / 2) / nt, std::min<int64_t>(8, kblocks / 4)), ss = 0;
+            int64_t sb = std::min<int64_t>((256 + nt / 2) / nt, std::min<int64_t>(8, kblocks / 4)), ss = 0;  // the loop below takes it down to what fits
             for (; sb >= 1; --sb) {
                 ss = sb + std::max<int64_t>(1, (2 * sb + 2) / 5);
                 if (nt * sb + n_slow * (ss - sb) <= 256) break;
@@ -306,13 +306,15 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             const uint64_t G = (uint64_t)(nt * sb + n_slow * (ss - sb)), T = G * (uint64_t)kblocks;
             const uint64_t run_rows = (uint64_t)((kblocks + std::max<int64_t>(sb, 1) - 1) / std::max<int64_t>(sb, 1)) * kDecodeKBlock + 8;
             // Against the two-tile form: as many workgroups at work as it would have (its grid of 128-column tiles
-            // x K-slices, at most one per CU; three quarters of that if it would need the two-pass partition).
+            // x K-slices, at most one per CU).
             // Measured, packed and balanced against two tiles (us): 8 x 4096 x 14336 40.7 / 42.1, 16 x 1024 x 4096
             // 11.9 / 13.1, 8 x 4096 x 11264 34.4 / 39.8, 8 x 4096 x 7168 24.7 / 29.5; but 8 x 4096 x 4096 (200
             // workgroups against 256) 18.9 / 17.1 and 4 x 8192 x 8192 (144 against 256) 73 / 49.
             const int64_t n128 = (N + kDecodeTileN - 1) / kDecodeTileN;
-            const int64_t s2 = std::max<int64_t>(1, std::min<int64_t>((256 + n128 / 2) / n128, std::min<int64_t>(8, kblocks / 8)));
-            const int64_t two_tile = (n128 * s2 > 256 && n128 < 256) ? 192 : std::min<int64_t>(n128 * s2, 256);
+            int64_t s2 = (256 + n128 / 2) / n128;
+            if (n128 * s2 > 256 && n128 <= 256) s2 = 256 / n128;
+            s2 = std::max<int64_t>(1, std::min<int64_t>(s2, std::min<int64_t>(8, kblocks / 8)));
+            const int64_t two_tile = std::min<int64_t>(n128 * s2, 256);
             const bool worth = packed || (int64_t)G >= two_tile;
             if (worth && sb >= 1 && nt <= kMaxTickets && ss <= kblocks && ss + 0 <= (int64_t)kStreamMaxSlices && T < (1ull << 31) &&
                 (uint64_t)ss * 2 * M * N * 4 < kTwoGiB && run_rows * (uint64_t)N * 2 < kTwoGiB) {
@@ -334,7 +336,11 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             const int64_t target = 256;
             const int64_t wgs = n_tiles * row_blocks;
             // The multi-row kernel fits one workgroup per CU: never more workgroups than CUs if that can be helped.
+            // The 16-row kernel: the nearest number of slices, but never a grid that needs a second round for a few
+            // workgroups (X[16,4096] . W[4096,11008], 86 tiles: 20.8 us with 2 slices, 27.7 us with 3; W[4096,7168],
+            // 56 tiles: 14.9 us with 4, 20.3 us with 5).
             S = (row_groups > 1) ? target / wgs : (target + wgs / 2) / wgs;
+            if (row_groups == 1 && wgs * S > target && wgs <= target) S = target / wgs;
             int64_t s_max = kblocks / waves;
             if (row_groups == 1) {
                 // Measured over shapes from 2 to 235 MB of weights streamed from HBM (an exhaustive run of the
@@ -362,20 +368,20 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             while (S > 1 && !partials_fit(S)) --S;
         if (S > 1 && !partials_fit(S)) return PRISM_ERR_UNSUPPORTED;
         if (!slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
-        // The weighted partition instead of a grid of equal K-slices when that grid would have more workgroups
-        // than CUs (a workgroup of this kernel fills a CU, so the surplus would wait for a second round): 256
-        // workgroups with equal shares, a share of at least four K-blocks (eight when gated).  Measured on
-        // X[16,4096] . W[4096,11008] (86 tiles x 3 slices): 27.8 -> 24.4 us.  Where the grid fits, it stays: a
-        // workgroup whose share spans two tiles makes two passes and pays the reduction twice (X[8,4096],
-        // 2 x W[4096,14336]: 42.9 us as 112 x 2, 49.4 us partitioned).  Tiles in the slots of g_slow_slots weigh
-        // 5 : 4 when the row pitch keeps a tile in its slot (whole groups of eight tiles).
+        // The weighted partition instead of a grid of equal K-slices where the grid that fits the CUs leaves more
+        // than a third of them idle and one more slice would not fit (129 to 159 tiles): 256 workgroups with equal
+        // shares, a share of at least four K-blocks (eight when gated).  A workgroup whose share spans two tiles
+        // makes two passes and pays the reduction twice, so a grid that fills at least 160 CUs in one round is
+        // faster (X[16,4096] . W[4096,11008]: 86 x 2 20.8 us, partitioned 24.8 us, 86 x 3 27.7 us; W[4096,18432],
+        // 144 tiles: 144 x 1 34.7 us, partitioned 35.0 us, 144 x 2 40.2 us).  In the partition, 256-byte tiles that
+        // contain a slow unit weigh 5 : 4 if mode bit 1 is set and the row pitch keeps a tile in its units.
         StreamPartition sp{};
         int64_t s_pitch = S;
         if (balanced.G != 0) {
             sp = balanced;
             s_pitch = balanced_slow;
-        } else if (row_groups == 1 && forced_split <= 0 && (g_stream_mode.load() & 1) != 0 && n_tiles * S > 256 &&
-                   n_tiles < 256) {
+        } else if (row_groups == 1 && forced_split <= 0 && (g_stream_mode.load() & 1) != 0 && n_tiles * S < 160 &&
+                   n_tiles * (S + 1) > 256 && n_tiles < 256) {
             // slot j (256 bytes) holds units 2j and 2j + 1
             uint32_t slow = 0;
             if (!packed && (g_stream_mode.load() & 2) != 0 && (N * 2) % 2048 == 0 && n_tiles % 8 == 0)

@@ -100,8 +100,8 @@ def test_decode_is_bit_reproducible_and_leaves_tickets_clean(P):
 
 @pytest.mark.parametrize("mode", [1, 3])
 @pytest.mark.parametrize("gated", [False, True])
-@pytest.mark.parametrize("M,K,N", [(16, 4096, 11008), (8, 2048, 9216), (16, 1000, 5640), (3, 4096, 18432),
-                                   (16, 8192, 7168)])
+@pytest.mark.parametrize("M,K,N", [(16, 4096, 16640), (8, 2048, 18432), (16, 1000, 17032), (3, 4096, 20352),
+                                   (16, 2048, 19456)])
 def test_decode_weighted_partition(P, M, K, N, gated, mode):
     """Shares that end one tile and begin the next (two passes), with and without heavier tiles around slow units."""
     P.prism_set_stream_balance(0x0808, mode)
@@ -117,11 +117,12 @@ def test_decode_weighted_partition(P, M, K, N, gated, mode):
 def test_decode_weighted_partition_f16_and_grid_agree(P):
     """The partition changes who sums what, not the result beyond rounding: against the oracle, and against the
     plain grid of the same call."""
-    e1 = _case(P, pi.F16, 16, 4096, 9216, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
+    assert P.prism_plan(0, 16, 2048, 18432, P.PRISM_F16)["grid_x"] == 256
+    e1 = _case(P, pi.F16, 16, 2048, 18432, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
     P.prism_set_stream_balance(0x0808, 0)
     try:
-        assert P.prism_plan(0, 16, 4096, 9216, P.PRISM_F16)["grid_y"] > 1
-        e0 = _case(P, pi.F16, 16, 4096, 9216, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
+        assert P.prism_plan(0, 16, 2048, 18432, P.PRISM_F16)["grid_x"] == 144
+        e0 = _case(P, pi.F16, 16, 2048, 18432, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
     finally:
         P.prism_set_stream_balance(0x0808, 1)
     assert abs(e1 - e0) < 2.5e-3
@@ -131,7 +132,7 @@ def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
     """W that does not start on a 256-byte boundary gets equal weights; repeated calls agree bit for bit."""
     import torch
     from gpu_util import to_device, from_device
-    M, K, N = 16, 2048, 9216
+    M, K, N = 16, 2048, 18432
     stored = pi.draw(pi.BF16, M, K, N, False, 462)
     X, g = (to_device(stored[k], pi.BF16) for k in ("X", "g"))
     Wa = to_device(stored["W"], pi.BF16)
@@ -158,6 +159,14 @@ def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
 
 
 # ---- gated decode, packed tile (64 output columns: W1 and W2 in one matrix-core tile), balanced over slow units ---
+
+def test_decode_grid_that_fits_in_one_round(P, M=16, K=4096, N=11008):
+    """Tiles x nearest slice count would be 258 workgroups: the dispatcher takes one slice fewer, plain and gated."""
+    for gated in (False, True):
+        plan = P.prism_plan(int(gated), M, K, N, P.PRISM_BF16)
+        assert (plan["grid_x"], plan["grid_y"]) == (86, 2), plan
+        _case(P, pi.BF16, M, K, N, gated, seed=466, expect_path=P.PRISM_PATH_DECODE)
+
 
 @pytest.mark.parametrize("dtype", [pi.BF16, pi.F16])
 @pytest.mark.parametrize("M,K,N", [(8, 4096, 14336), (16, 1024, 4096), (3, 2048, 7168), (16, 8192, 1024), (1, 512, 2048)])

@@ -351,24 +351,27 @@ def test_weighted_partition_deals_every_k_block_out_once(P):
 
 def test_plan_uses_the_partition_when_the_grid_would_not_fit(P):
     bf16 = P.PRISM_BF16
-    p = P.prism_plan(0, 16, 4096, 11008, bf16)            # 86 tiles x 3 slices = 258 workgroups
+    # the nearest slice count would need a second round for two workgroups (86 x 3 = 258): one slice fewer
+    assert (lambda d: (d["grid_x"], d["grid_y"], d["split_k"]))(P.prism_plan(0, 16, 4096, 11008, bf16)) == (86, 2, 2)
+    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 7168, bf16)) == (56, 4)
+    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 4096, bf16)) == (32, 8)
+    # 144 tiles: one slice leaves 112 CUs idle, two do not fit: 256 workgroups with equal shares
+    p = P.prism_plan(0, 16, 4096, 18432, bf16)
     assert (p["path"], p["grid_x"], p["grid_y"], p["block"]) == (P.PRISM_PATH_DECODE, 256, 1, 512)
-    q = 86 * 4 * 128 // 256
+    q = 144 * 4 * 128 // 256
     assert p["split_k"] == -(-4 * 128 // q) + 1
-    ss = -(-(86 * p["split_k"] * 16 * 4) // 256) * 256
-    assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * 16 * 11008 * 4
+    ss = -(-(144 * p["split_k"] * 16 * 4) // 256) * 256
+    assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * 16 * 18432 * 4
     P.prism_set_stream_balance(0x0808, 0)
     try:
-        c = P.prism_plan(0, 16, 4096, 11008, bf16)
-        assert (c["grid_x"], c["grid_y"], c["split_k"]) == (86, 3, 3)
+        c = P.prism_plan(0, 16, 4096, 18432, bf16)
+        assert (c["grid_x"], c["grid_y"], c["split_k"], c["workspace_bytes"]) == (144, 1, 1, 0)
     finally:
         P.prism_set_stream_balance(0x0808, 1)
-    # the headline configuration fits a grid and keeps it
-    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 4096, bf16)) == (32, 8)
     # a forced split keeps the grid
     P.prism_set_override(P.PRISM_PATH_DECODE, 3, 0)
     try:
-        assert P.prism_plan(0, 16, 4096, 11008, bf16)["grid_y"] == 3
+        assert P.prism_plan(0, 16, 4096, 18432, bf16)["grid_y"] == 3
     finally:
         P.prism_set_override(0, 0, 0)
     for bad in ((0x10000, 1), (-1, 1), (0, 4), (0, -1)):
