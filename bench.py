@@ -10,7 +10,8 @@ index 1 (decode RMSNorm -> MatMul, bf16, X[16,4096], W[4096,4096]); the other th
 configurations are timed too and reported under "other_workloads", and the paper's own workloads at its
 shapes and in its precision (fp16, 8 or 16 rows, hidden size 1024 or 4096) under "paper_shapes", its
 running example (softmax, then a matrix product, Figure 1) under "running_example", its two attention
-workloads under "attention", and 32 / 128 / 512 rows against the decode-sized weights under "mid_rows".
+workloads under "attention", 32 / 128 / 512 rows against the decode-sized weights under "mid_rows", and two
+decode calls with about 1 GB of weights under "large_decode".
 
 Decode workloads rotate over enough distinct weight buffers (>= 1 GiB in total) that W is streamed
 from HBM and not from the 256 MB last-level cache; the cache-hot single-buffer time is reported
@@ -406,6 +407,46 @@ def measure_mid_rows(M, K, N, gated, steps=300, warmup=20):
     return res
 
 
+def measure_large_decode(M, K, N, steps=40, warmup=6):
+    """A decode call whose weights are far larger than any cache (an output projection onto a vocabulary, a wide
+    MLP): device-generated bf16 inputs, two weight buffers in turn.  Bound: HBM, algorithmic bytes X + g + W + Y."""
+    import torch
+    import paper_2604_15272_amd as P
+    gen = torch.Generator(device="cuda").manual_seed(0x5EED4000 + N)
+    X = torch.randn((M, K), generator=gen, device="cuda").to(torch.bfloat16)
+    g = (torch.rand((K,), generator=gen, device="cuda") + 0.5).to(torch.bfloat16)
+    Ws = [(torch.randn((K, N), generator=gen, device="cuda") / 64).to(torch.bfloat16) for _ in range(2)]
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    plan = P.prism_plan(P.PRISM_OP_RMSNORM_MATMUL, M, K, N, P.PRISM_BF16)
+    P.ensure_workspace(plan["workspace_bytes"])
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    args = [(vp(X.data_ptr()), vp(g.data_ptr()), vp(W.data_ptr()), vp(Y.data_ptr()), i64(M), i64(K), i64(N),
+             ctypes.c_float(1e-6), ctypes.c_int32(P.PRISM_BF16), stream) for W in Ws]
+    fn = P.lib.prism_rmsnorm_matmul
+    for i in range(warmup):
+        if fn(*args[i % 2]) != 0:
+            raise RuntimeError("large decode call failed")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        fn(*args[(warmup + i) % 2])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    nbytes = 2 * (M * K + K + K * N + M * N)
+    res = {"workload": f"large_decode_M{M}_K{K}_N{N}", "dtype": "bf16", "M": M, "K": K, "N": N, "plan": plan,
+           "steps": steps, "us_per_call": ms * 1e3, "bound": "hbm", "bytes_per_launch": nbytes,
+           "achieved": nbytes / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "data": "synthetic, generated on the device"}
+    log(f"[bench]   large decode X[{M},{K}] W[{K},{N}]: {ms * 1e3:.1f} us/call, {res['achieved']:.0f} GB/s = "
+        f"{100 * res['frac']:.1f}% of hbm peak, grid {plan['grid_x']} x {plan['grid_y']}")
+    del Ws
+    torch.cuda.empty_cache()
+    return res
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the workload's kernel, as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
     and recorded in profiles/hbm_traffic.md (one line per workload: `traffic <workload> fetch_bytes=...
@@ -528,6 +569,8 @@ def main():
                            ((32, 4096, 4096, False), (128, 4096, 4096, False), (512, 4096, 4096, False),
                             (32, 4096, 14336, True))]
         out["attention"] = [measure_attention(h, qk) for h in (1024, 2048) for qk in (False, True)]
+        log("[bench] decode calls with weights of about 1 GB (an output projection onto a vocabulary, a wide layer)")
+        out["large_decode"] = [measure_large_decode(16, 4096, 128256), measure_large_decode(16, 8192, 57344)]
         torch.cuda.empty_cache()
     print(json.dumps(out), flush=True)
 

@@ -334,6 +334,28 @@ def test_prefill_configs_full_size_sampled_rows(P, idx):
         assert abs(y.var() - 13.0 / 12.0) < 0.02
 
 
+@pytest.mark.parametrize("gated", [False, True])
+def test_decode_many_column_tiles_sampled_columns(P, gated):
+    """A weight matrix as wide as a vocabulary slice: 513 column tiles, the last one ragged, several rounds of
+    workgroups.  The oracle recomputes 700 sampled columns (it works on column subsets of W exactly)."""
+    import oracle
+    M, K, N = 16, 2048, 65536 + 72
+    stored = pi.draw(pi.BF16, M, K, N, gated, 495)
+    plan = P.prism_plan(int(gated), M, K, N, P.PRISM_BF16)
+    assert plan["path"] == P.PRISM_PATH_DECODE and plan["split_k"] == 1 and plan["grid_x"] == 513, plan
+    y = run_gpu(stored, pi.BF16, gated, 1e-6)
+    assert np.isfinite(y).all()
+    cols = np.unique(np.concatenate([[0, 127, 128, N - 73, N - 72, N - 1],
+                                     np.random.Generator(np.random.Philox(495)).choice(N, 694, replace=False)]))
+    X, g = pi.to_f64(stored["X"], pi.BF16), pi.to_f64(stored["g"], pi.BF16)
+    if gated:
+        yhat = oracle.rmsnorm_gated_mlp(X, g, pi.to_f64(stored["W1"][:, cols], pi.BF16),
+                                        pi.to_f64(stored["W2"][:, cols], pi.BF16), 1e-6)
+    else:
+        yhat = oracle.rmsnorm_matmul(X, g, pi.to_f64(stored["W"][:, cols], pi.BF16), 1e-6)
+    assert_parity(y[:, cols], yhat, pi.BF16, f"many tiles, gated={gated}")
+
+
 # ---- the paper's own members of the family (Section 7.1), at its shapes (Section 7.1: n in {8, 16}, d in
 # ---- {1024, 4096}) and on every kernel family ----------------------------------------------------------
 
