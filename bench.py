@@ -182,12 +182,12 @@ def measure(idx, steps, warmup):
         if r.plan["tile_n"] == 64:
             # The dispatcher chose packed tiles with more K-slices for the tiles in slow address units: the same
             # call with that turned off (two 128-column tiles per workgroup, equal slices), for comparison.
-            r.P.prism_set_stream_balance(0, 1)
+            r.P.prism_set_stream_balance(0, 0)
             try:
                 r.P.ensure_workspace(r.P.prism_workspace_bytes(r.op, wl.M, wl.K, wl.N, r.dt))
                 _, res["equal_slices_kernel_ms"] = r.timed(steps, warmup)
             finally:
-                r.P.prism_set_stream_balance(0x0808, 1)
+                r.P.prism_set_stream_balance()
     else:
         res.update(value=flops / (wall_ms * 1e-3) / 1e12, unit="TFLOP/s", bound="mfma",
                    achieved=flops / (k_mean * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS)

@@ -230,11 +230,13 @@ int32_t prism_plan_table_size(void);
  * slow tile (what the workspace is sized for).  The slices decide the order of the fp32 sums, so results may differ
  * in the last bit between buffers that start in different units; for given addresses they are reproducible.
  *
- * mode bit 0 (default on): where the grid of column tiles x equal K-slices that fits the CUs would leave more than a
- * third of them idle and one more slice per tile would not fit (129 to 159 column tiles), launch 256 workgroups and
- * give each the same share of all K-blocks, tile after tile; a share may end one tile and begin the next.  prism_plan then reports a one-dimensional grid and, as split_k, the most workgroups
- * that can share a tile.  mode bit 1 (default off): in that partition, 256-byte-wide tiles that contain a slow
- * unit weigh 5 : 4 (needs N a multiple of 1024 and W on a 256-byte boundary).
+ * mode bit 0 (default off): for 129 to 159 column tiles, where one K-slice per tile leaves more than a third of the
+ * CUs idle and two do not fit, launch 256 workgroups and give each the same share of all K-blocks, tile after tile;
+ * a share may end one tile and begin the next (two passes).  prism_plan then reports a one-dimensional grid and,
+ * as split_k, the most workgroups that can share a tile.  Off because three K-slices per tile, which the library
+ * takes by default there, are faster on the MI355X measured.  mode bit 1 (default off): in that partition,
+ * 256-byte-wide tiles that contain a slow unit weigh 5 : 4 (needs N a multiple of 1024 and W on a 256-byte
+ * boundary).
  * Host-side, process-wide.
  */
 prism_status_t prism_set_stream_balance(int32_t slow_units, int32_t mode);

@@ -165,7 +165,8 @@ def prism_set_override(path=0, split_k=0, variant=0):
         raise PrismError(st, "prism_set_override")
 
 
-def prism_set_stream_balance(slow_units=0x0808, mode=1):
+def prism_set_stream_balance(slow_units=0x0808, mode=0):
+    """Without arguments: the library's defaults."""
     st = lib.prism_set_stream_balance(int(slow_units), int(mode))
     if st != 0:
         raise PrismError(st, "prism_set_stream_balance")

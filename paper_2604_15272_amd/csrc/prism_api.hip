@@ -27,12 +27,12 @@ Override g_override;
 // whichever XCD reads them and wherever W starts; a row pitch of 225 x 256 bytes, which takes every workgroup
 // through all units, ends all stripes at 32 us.
 //  - g_slow_units: bit u set = unit u is slow.
-//  - g_stream_mode bit 0: the weighted partition of stream_partition.h where a grid would need more workgroups
-//    than CUs; bit 1: in that partition, 256-byte tiles that contain a slow unit weigh 5 : 4 (off: it takes 2 us
-//    off calls with 112 or more tiles and adds 4 us with 32 tiles, where a tile gets more sharers).
+//  - g_stream_mode bit 0: the two-pass weighted partition of stream_partition.h for 129 to 159 column tiles (off:
+//    a grid of three K-slices per tile is faster there, see make_plan_with); bit 1: in that partition, 256-byte
+//    tiles that contain a slow unit weigh 5 : 4.
 // Gated calls with at most 16 rows use the packed tile (64 output columns: 128-byte stripes of W1 and of W2) with
 // more K-slices for the tiles in slow units when that fits the CUs: 42.1 -> 40.7 us on X[8,4096], 2 x W[4096,14336].
-std::atomic<int32_t> g_slow_units{0x0808}, g_stream_mode{1};
+std::atomic<int32_t> g_slow_units{0x0808}, g_stream_mode{0};
 
 struct Workspace {
     void* ptr;
@@ -341,6 +341,11 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             // 56 tiles: 14.9 us with 4, 20.3 us with 5).
             S = (row_groups > 1) ? target / wgs : (target + wgs / 2) / wgs;
             if (row_groups == 1 && wgs * S > target && wgs <= target) S = target / wgs;
+            // 129 to 159 tiles: one slice per tile leaves more than a third of the CUs idle and two make a second
+            // round of a few workgroups; three (1.5 to 1.9 rounds of shorter workgroups, dealt out as CUs free up)
+            // are faster than both when K is deep enough (W[4096,18432], 144 tiles: 34.9 / 40.2 / 32.0 us with
+            // 1 / 2 / 3 slices; W[2048,20352]: 18.0 / 22.4 / 19.6 us).
+            if (row_groups == 1 && S == 1 && wgs > target / 2 && wgs < 160 && kblocks >= 96) S = 3;
             int64_t s_max = kblocks / waves;
             if (row_groups == 1) {
                 // Measured over shapes from 2 to 235 MB of weights streamed from HBM (an exhaustive run of the
@@ -368,20 +373,19 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             while (S > 1 && !partials_fit(S)) --S;
         if (S > 1 && !partials_fit(S)) return PRISM_ERR_UNSUPPORTED;
         if (!slice_fits(S)) return PRISM_ERR_UNSUPPORTED;
-        // The weighted partition instead of a grid of equal K-slices where the grid that fits the CUs leaves more
-        // than a third of them idle and one more slice would not fit (129 to 159 tiles): 256 workgroups with equal
-        // shares, a share of at least four K-blocks (eight when gated).  A workgroup whose share spans two tiles
-        // makes two passes and pays the reduction twice, so a grid that fills at least 160 CUs in one round is
-        // faster (X[16,4096] . W[4096,11008]: 86 x 2 20.8 us, partitioned 24.8 us, 86 x 3 27.7 us; W[4096,18432],
-        // 144 tiles: 144 x 1 34.7 us, partitioned 35.0 us, 144 x 2 40.2 us).  In the partition, 256-byte tiles that
-        // contain a slow unit weigh 5 : 4 if mode bit 1 is set and the row pitch keeps a tile in its units.
+        // The two-pass weighted partition (an option, mode bit 0): for 129 to 159 column tiles, 256 workgroups with
+        // equal shares of all K-blocks, a share of at least four K-blocks (eight when gated).  A workgroup whose
+        // share spans two tiles makes two passes and pays the reduction twice, which is why it is not the default:
+        // W[4096,18432] 35.2 us against 32.0 us with three slices per tile, X[16,4096] . W[4096,11008] 24.8 us against
+        // 20.8 us as 86 x 2.  In the partition, 256-byte tiles that contain a slow unit weigh 5 : 4 if mode bit 1 is
+        // set and the row pitch keeps a tile in its units.
         StreamPartition sp{};
         int64_t s_pitch = S;
         if (balanced.G != 0) {
             sp = balanced;
             s_pitch = balanced_slow;
-        } else if (row_groups == 1 && forced_split <= 0 && (g_stream_mode.load() & 1) != 0 && n_tiles * S < 160 &&
-                   n_tiles * (S + 1) > 256 && n_tiles < 256) {
+        } else if (row_groups == 1 && forced_split <= 0 && (g_stream_mode.load() & 1) != 0 && n_tiles > 128 &&
+                   n_tiles < 160) {
             // slot j (256 bytes) holds units 2j and 2j + 1
             uint32_t slow = 0;
             if (!packed && (g_stream_mode.load() & 2) != 0 && (N * 2) % 2048 == 0 && n_tiles % 8 == 0)

@@ -111,20 +111,23 @@ def test_decode_weighted_partition(P, M, K, N, gated, mode):
             assert (plan["path"], plan["grid_x"], plan["grid_y"]) == (P.PRISM_PATH_DECODE, 256, 1), plan
         _case(P, pi.BF16, M, K, N, gated, seed=450 + N % 97, expect_path=P.PRISM_PATH_DECODE)
     finally:
-        P.prism_set_stream_balance(0x0808, 1)
+        P.prism_set_stream_balance()
 
 
 def test_decode_weighted_partition_f16_and_grid_agree(P):
     """The partition changes who sums what, not the result beyond rounding: against the oracle, and against the
     plain grid of the same call."""
-    assert P.prism_plan(0, 16, 2048, 18432, P.PRISM_F16)["grid_x"] == 256
-    e1 = _case(P, pi.F16, 16, 2048, 18432, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
-    P.prism_set_stream_balance(0x0808, 0)
+    P.prism_set_stream_balance(0x0808, 1)
+    try:
+        assert P.prism_plan(0, 16, 2048, 18432, P.PRISM_F16)["grid_x"] == 256
+        e1 = _case(P, pi.F16, 16, 2048, 18432, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
+    finally:
+        P.prism_set_stream_balance()
     try:
         assert P.prism_plan(0, 16, 2048, 18432, P.PRISM_F16)["grid_x"] == 144
         e0 = _case(P, pi.F16, 16, 2048, 18432, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
     finally:
-        P.prism_set_stream_balance(0x0808, 1)
+        P.prism_set_stream_balance()
     assert abs(e1 - e0) < 2.5e-3
 
 
@@ -155,17 +158,21 @@ def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
                 assert torch.equal(o.view(torch.uint16), outs[0].view(torch.uint16))
             assert_parity(from_device(outs[0], pi.BF16), yhat, pi.BF16, f"partition, W at {W.data_ptr() % 256} mod 256")
     finally:
-        P.prism_set_stream_balance(0x0808, 1)
+        P.prism_set_stream_balance()
 
 
 # ---- gated decode, packed tile (64 output columns: W1 and W2 in one matrix-core tile), balanced over slow units ---
 
 def test_decode_grid_that_fits_in_one_round(P, M=16, K=4096, N=11008):
-    """Tiles x nearest slice count would be 258 workgroups: the dispatcher takes one slice fewer, plain and gated."""
+    """Tiles x nearest slice count would be 258 workgroups: the dispatcher takes one slice fewer, plain and gated;
+    with 144 tiles it takes three slices (one would leave 112 CUs idle, two would make a second round of 32)."""
     for gated in (False, True):
         plan = P.prism_plan(int(gated), M, K, N, P.PRISM_BF16)
         assert (plan["grid_x"], plan["grid_y"]) == (86, 2), plan
         _case(P, pi.BF16, M, K, N, gated, seed=466, expect_path=P.PRISM_PATH_DECODE)
+    plan = P.prism_plan(0, 16, 3072, 18432, P.PRISM_BF16)
+    assert (plan["grid_x"], plan["grid_y"]) == (144, 3), plan
+    _case(P, pi.BF16, 16, 3072, 18432, False, seed=467, expect_path=P.PRISM_PATH_DECODE)
 
 
 @pytest.mark.parametrize("dtype", [pi.BF16, pi.F16])
@@ -186,13 +193,15 @@ def test_decode_packed_every_split_and_wave_count(P, split, variant):
 
 def test_decode_packed_in_the_weighted_partition(P):
     """The packed tile by name where its grid would not fit (146 tiles x 2 slices): 256 workgroups, two passes."""
+    P.prism_set_stream_balance(0x0808, 1)
     P.prism_set_override(P.PRISM_PATH_DECODE, 0, 108)
     try:
         plan = P.prism_plan(1, 8, 2048, 9344, P.PRISM_BF16)
         assert (plan["tile_n"], plan["grid_x"], plan["grid_y"]) == (64, 256, 1), plan
+        _case(P, pi.BF16, 8, 2048, 9344, True, seed=485, path=P.PRISM_PATH_DECODE, variant=108)
     finally:
         P.prism_set_override(0, 0, 0)
-    _case(P, pi.BF16, 8, 2048, 9344, True, seed=485, path=P.PRISM_PATH_DECODE, variant=108)
+        P.prism_set_stream_balance()
 
 
 def test_decode_packed_off_its_units_and_reproducible(P):

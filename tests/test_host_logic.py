@@ -355,25 +355,27 @@ def test_plan_uses_the_partition_when_the_grid_would_not_fit(P):
     assert (lambda d: (d["grid_x"], d["grid_y"], d["split_k"]))(P.prism_plan(0, 16, 4096, 11008, bf16)) == (86, 2, 2)
     assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 7168, bf16)) == (56, 4)
     assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 4096, bf16)) == (32, 8)
-    # 144 tiles: one slice leaves 112 CUs idle, two do not fit: 256 workgroups with equal shares
-    p = P.prism_plan(0, 16, 4096, 18432, bf16)
-    assert (p["path"], p["grid_x"], p["grid_y"], p["block"]) == (P.PRISM_PATH_DECODE, 256, 1, 512)
-    q = 144 * 4 * 128 // 256
-    assert p["split_k"] == -(-4 * 128 // q) + 1
-    ss = -(-(144 * p["split_k"] * 16 * 4) // 256) * 256
-    assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * 16 * 18432 * 4
-    P.prism_set_stream_balance(0x0808, 0)
+    # 144 tiles: one slice leaves 112 CUs idle, two make a second round of 32 workgroups: three; shallow K: one
+    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 18432, bf16)) == (144, 3)
+    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 2048, 18432, bf16)) == (144, 1)
+    assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 20480, bf16)) == (160, 1)
+    # the two-pass partition is an option: 256 workgroups with equal shares
+    P.prism_set_stream_balance(0x0808, 1)
     try:
-        c = P.prism_plan(0, 16, 4096, 18432, bf16)
-        assert (c["grid_x"], c["grid_y"], c["split_k"], c["workspace_bytes"]) == (144, 1, 1, 0)
+        p = P.prism_plan(0, 16, 4096, 18432, bf16)
+        assert (p["path"], p["grid_x"], p["grid_y"], p["block"]) == (P.PRISM_PATH_DECODE, 256, 1, 512)
+        q = 144 * 4 * 128 // 256
+        assert p["split_k"] == -(-4 * 128 // q) + 1
+        ss = -(-(144 * p["split_k"] * 16 * 4) // 256) * 256
+        assert p["workspace_bytes"] == 262144 + ss + p["split_k"] * 16 * 18432 * 4
+        assert P.prism_plan(0, 16, 4096, 11008, bf16)["grid_y"] == 2          # only for 129 to 159 tiles
+        P.prism_set_override(P.PRISM_PATH_DECODE, 3, 0)                        # a forced split keeps the grid
+        try:
+            assert P.prism_plan(0, 16, 4096, 18432, bf16)["grid_y"] == 3
+        finally:
+            P.prism_set_override(0, 0, 0)
     finally:
-        P.prism_set_stream_balance(0x0808, 1)
-    # a forced split keeps the grid
-    P.prism_set_override(P.PRISM_PATH_DECODE, 3, 0)
-    try:
-        assert P.prism_plan(0, 16, 4096, 18432, bf16)["grid_y"] == 3
-    finally:
-        P.prism_set_override(0, 0, 0)
+        P.prism_set_stream_balance()
     for bad in ((0x10000, 1), (-1, 1), (0, 4), (0, -1)):
         with pytest.raises(P.PrismError):
             P.prism_set_stream_balance(*bad)
@@ -405,7 +407,7 @@ def test_gated_decode_plan_packs_and_balances(P):
     try:
         assert (lambda d: (d["tile_n"], d["grid_x"], d["grid_y"]))(P.prism_plan(1, 8, 4096, 14336, bf16)) == (128, 112, 2)
     finally:
-        P.prism_set_stream_balance(0x0808, 1)
+        P.prism_set_stream_balance()
     for variant, split, expect in ((0, 2, (128, 112, 2, 512)), (108, 3, (64, 224, 3, 512)), (104, 1, (64, 224, 1, 256)),
                                    (108, 0, (64, 252, 1, 512))):
         P.prism_set_override(P.PRISM_PATH_DECODE, split, variant)
