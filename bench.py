@@ -472,6 +472,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", type=int, default=1, help="benchmark configuration index (1..4)")
     ap.add_argument("--no-extra", action="store_true", help="time only the headline workload")
+    ap.add_argument("--only-large-decode", action="store_true",
+                    help="time only the two decode calls with about 1 GB of weights (for profiling)")
     ap.add_argument("--only-attention", action="store_true",
                     help="time only the paper's attention workloads (for profiling that kernel)")
     ap.add_argument("--only-mid-rows", action="store_true",
@@ -509,6 +511,10 @@ def main():
         print(json.dumps({"mid_rows": [measure_mid_rows(M, K, N, g) for M, K, N, g in
                                        ((32, 4096, 4096, False), (128, 4096, 4096, False), (512, 4096, 4096, False),
                                         (32, 4096, 14336, True))]}), flush=True)
+        return
+    if a.only_large_decode:
+        print(json.dumps({"large_decode": [measure_large_decode(16, 4096, 128256), measure_large_decode(16, 8192, 57344)]}),
+              flush=True)
         return
     if a.only_attention:
         print(json.dumps({"attention": [measure_attention(h, qk) for h in (1024, 2048) for qk in (False, True)]}),
