@@ -346,6 +346,21 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             // are faster than both when K is deep enough (W[4096,18432], 144 tiles: 34.9 / 40.2 / 32.0 us with
             // 1 / 2 / 3 slices; W[2048,20352]: 18.0 / 22.4 / 19.6 us).
             if (row_groups == 1 && S == 1 && wgs > target / 2 && wgs < 160 && kblocks >= 96) S = 3;
+            // Between one and two rounds of workgroups, the second round should not be a nearly empty one.  If
+            // one slice per tile fills less than 77 % of the two rounds, take the 2, 3 or 4 slices that fill theirs
+            // best (shorter workgroups, a shorter last round): W[4096,33280], 260 tiles, 68.3 us unsplit, 57.7 us
+            // with 4 slices; W[4096,40960], 320 tiles, 72.2 / 65.1 us; W[4096,49152], 384 tiles, 76.0 us, 73.7 us
+            // with 2 slices; but W[4096,51200], 400 tiles, 76.3 us unsplit against 81.5 us with 3, and from 512
+            // tiles on (520, 640 tiles measured) slices change nothing or cost time.
+            if (row_groups == 1 && S == 1 && wgs > target && wgs < 2 * target) {
+                auto fill = [&](int64_t s) { return (double)(wgs * s) / (double)(target * ((wgs * s + target - 1) / target)); };
+                if (fill(1) < 0.77) {
+                    int64_t best = 1;
+                    for (int64_t s2 = 2; s2 <= 4 && kblocks / s2 >= 16; ++s2)
+                        if (fill(s2) > fill(best) + 1e-9) best = s2;
+                    S = best;
+                }
+            }
             int64_t s_max = kblocks / waves;
             if (row_groups == 1) {
                 // Measured over shapes from 2 to 235 MB of weights streamed from HBM (an exhaustive run of the

@@ -173,6 +173,10 @@ def test_decode_grid_that_fits_in_one_round(P, M=16, K=4096, N=11008):
     plan = P.prism_plan(0, 16, 3072, 18432, P.PRISM_BF16)
     assert (plan["grid_x"], plan["grid_y"]) == (144, 3), plan
     _case(P, pi.BF16, 16, 3072, 18432, False, seed=467, expect_path=P.PRISM_PATH_DECODE)
+    # 260 tiles: four slices fill 4.06 rounds instead of one slice filling half of two
+    plan = P.prism_plan(1, 8, 2048, 33280, P.PRISM_BF16)
+    assert (plan["grid_x"], plan["grid_y"]) == (260, 4), plan
+    _case(P, pi.BF16, 8, 2048, 33280, True, seed=468, expect_path=P.PRISM_PATH_DECODE)
 
 
 @pytest.mark.parametrize("dtype", [pi.BF16, pi.F16])

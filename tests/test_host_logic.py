@@ -359,6 +359,12 @@ def test_plan_uses_the_partition_when_the_grid_would_not_fit(P):
     assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 18432, bf16)) == (144, 3)
     assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 2048, 18432, bf16)) == (144, 1)
     assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 20480, bf16)) == (160, 1)
+    # between one and two rounds of workgroups: slices that fill their rounds (260, 320, 384 tiles), none from 394 on
+    for N, grid in ((33280, (260, 4)), (40960, (320, 4)), (49152, (384, 2)), (51200, (400, 1)), (57344, (448, 1)),
+                    (65664, (513, 1))):
+        assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, N, bf16)) == grid, N
+    assert P.prism_plan(0, 16, 4096, 57344, bf16)["block"] == 256          # unsplit plain calls: four wavefronts
+    assert P.prism_plan(1, 8, 4096, 57344, bf16)["block"] == 512
     # the two-pass partition is an option: 256 workgroups with equal shares
     P.prism_set_stream_balance(0x0808, 1)
     try:
