@@ -93,7 +93,10 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 // rows): the decode path wins while all its workgroups run at once (one per CU) and W is deep enough that
 // the prefill kernel's 64-deep K-steps over few tiles dominate; 32 rows per workgroup win over 64 while the
 // row blocks' re-reads of W stay within the 256 MiB last-level cache (two row blocks that drift apart by more
-// than an L2's worth of W fetch it twice).
+// than an L2's worth of W fetch it twice).  A single row block may have more column tiles than CUs (several
+// rounds of workgroups): X[32,4096] . W[4096,40960] 93.7 us against 111.9 us with the prefill kernel, X[64,4096] .
+// W[4096,33280] 101.1 against 109.0 us, gated X[32,4096], 2 x W[4096,33280] 161.3 (148.3 in two K-slices) against
+// 166.4 us.
 int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
     const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
     const int64_t z32 = (M + 31) / 32, z64 = (M + 63) / 64;
@@ -102,13 +105,13 @@ int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
     if (gated) {
         // Two weight matrices: the accumulators allow 32 rows per wavefront, or 64 with the matrices split
         // across the wavefronts; beyond the last-level cache's worth of re-reads the prefill kernel wins.
-        if (M <= 32) return n_tiles <= 256 ? 2 : 0;
+        if (M <= 32) return 2;
         if (K < 2048) return 0;
         if (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= 256) return 2;
         return (z64 * w_bytes <= (256ull << 20) && n_tiles * z64 <= 256) ? 4 : 0;
     }
-    if ((M <= 32 || z32 * w_bytes <= (256ull << 20)) && n_tiles * z32 <= 256) return 2;
-    return n_tiles * z64 <= 256 ? 4 : 0;
+    if (M <= 32 || (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= 256)) return 2;
+    return (M <= 64 || n_tiles * z64 <= 256) ? 4 : 0;
 }
 
 bool prefill_tile_known(bool gated, int bm, int bn) {
@@ -352,6 +355,9 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             // with 4 slices; W[4096,40960], 320 tiles, 72.2 / 65.1 us; W[4096,49152], 384 tiles, 76.0 us, 73.7 us
             // with 2 slices; but W[4096,51200], 400 tiles, 76.3 us unsplit against 81.5 us with 3, and from 512
             // tiles on (520, 640 tiles measured) slices change nothing or cost time.
+            // The multi-row kernel, a little over one round (260 tiles: 101.1 -> 99.8 us plain with 64 rows, 161.3 ->
+            // 148.3 us gated with 32 rows; 320 tiles are better left unsplit: 93.7 against 95.1 us).
+            if (row_groups > 1 && S <= 1 && wgs > target && wgs * 10 < target * 12 && kblocks >= 32) S = 2;
             if (row_groups == 1 && S == 1 && wgs > target && wgs < 2 * target) {
                 auto fill = [&](int64_t s) { return (double)(wgs * s) / (double)(target * ((wgs * s + target - 1) / target)); };
                 if (fill(1) < 0.77) {

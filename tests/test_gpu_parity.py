@@ -258,6 +258,15 @@ def test_decode_rows_chosen_by_the_dispatcher(P, M, K, N):
     _case(P, pi.BF16, M, K, N, False, seed=460 + M, expect_path=P.PRISM_PATH_DECODE)
 
 
+@pytest.mark.parametrize("M,N,gated,grid", [(32, 33280, False, (260, 2, 1)), (24, 33280, True, (260, 2, 1)),
+                                            (64, 40960, False, (320, 1, 1))])
+def test_decode_rows_with_more_column_tiles_than_cus(P, M, N, gated, grid):
+    """One row block over several rounds of workgroups (a little over one round: two K-slices)."""
+    plan = P.prism_plan(int(gated), M, 2048, N, P.PRISM_BF16)
+    assert (plan["path"], plan["grid_x"], plan["grid_y"], plan["grid_z"]) == (P.PRISM_PATH_DECODE,) + grid, plan
+    _case(P, pi.BF16, M, 2048, N, gated, seed=140 + M, expect_path=P.PRISM_PATH_DECODE)
+
+
 @pytest.mark.parametrize("M", [24, 40, 64])
 def test_decode_rows_gated_chosen_by_the_dispatcher(P, M):
     _case(P, pi.BF16, M, 4096, 14336, True, seed=465 + M, expect_path=P.PRISM_PATH_DECODE)

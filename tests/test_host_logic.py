@@ -243,6 +243,17 @@ def test_decode_plan_for_more_than_sixteen_rows(P):
     assert P.prism_plan(1, 2048, 4096, 14336, bf16)["path"] == P.PRISM_PATH_PREFILL
 
 
+def test_decode_rows_plan_with_more_tiles_than_cus(P):
+    """A single row block of the multi-row kernel may run in several rounds; more row blocks may not."""
+    bf16 = P.PRISM_BF16
+    pl = lambda op, M, K, N: (lambda d: (d["path"], d["tile_m"], d["grid_x"], d["grid_y"], d["grid_z"]))(P.prism_plan(op, M, K, N, bf16))
+    assert pl(0, 32, 4096, 40960) == (P.PRISM_PATH_DECODE, 32, 320, 1, 1)
+    assert pl(0, 64, 4096, 33280) == (P.PRISM_PATH_DECODE, 64, 260, 2, 1)
+    assert pl(1, 32, 4096, 33280) == (P.PRISM_PATH_DECODE, 32, 260, 2, 1)
+    assert pl(0, 128, 4096, 40960)[0] == P.PRISM_PATH_PREFILL
+    assert pl(1, 64, 4096, 33280)[0] == P.PRISM_PATH_PREFILL
+
+
 def test_plans_of_random_shapes_are_consistent(P):
     """Whatever the dispatcher picks: the grid covers the problem, the split leaves no empty slice, the workspace
     is what the kernels index, and the query functions agree with each other."""
