@@ -614,6 +614,14 @@ def test_attention_every_split(P, split):
     _attention_case(P, pi.F16, 2, 8, 2048, 128, seed=1410, qk_norm=True, path=P.PRISM_PATH_ATTENTION, split=split)
 
 
+def test_attention_many_batch_entries(P):
+    """More batch entries: fewer, longer slices (never more workgroups than CUs)."""
+    assert P.prism_attention_plan(40, 8, 2048, 128, P.PRISM_F16)["split_k"] == 6
+    _attention_case(P, pi.F16, 40, 8, 2048, 128, seed=1412, qk_norm=True, expect_path=P.PRISM_PATH_ATTENTION)
+    assert P.prism_attention_plan(300, 4, 600, 128, P.PRISM_BF16)["split_k"] == 1
+    _attention_case(P, pi.BF16, 300, 4, 600, 128, seed=1413, qk_norm=False, expect_path=P.PRISM_PATH_ATTENTION)
+
+
 def test_attention_single_slice(P):
     _attention_case(P, pi.F16, 2, 8, 1000, 128, seed=1411, qk_norm=True, path=P.PRISM_PATH_ATTENTION, split=1)
 

@@ -180,6 +180,12 @@ def test_attention_arguments_and_plan(P):
     mid = P.prism_attention_plan(1, 8, 8192, 128, f16)
     assert mid["split_k"] == 32 and mid["tile_n"] == 256
     assert P.prism_attention_plan(1, 8, 1536, 128, f16)["split_k"] == 8
+    # never more workgroups than CUs over all batch entries, but up to four slices for long contexts
+    assert P.prism_attention_plan(32, 8, 2048, 128, f16)["split_k"] == 8
+    assert P.prism_attention_plan(32, 8, 16384, 128, f16)["split_k"] == 8
+    assert P.prism_attention_plan(64, 16, 4096, 128, f16)["split_k"] == 4
+    assert P.prism_attention_plan(300, 8, 1024, 128, f16)["split_k"] == 1
+    assert P.prism_attention_plan(300, 8, 16384, 128, f16)["split_k"] == 4
     assert P.prism_attention_plan(1, 8, 4096, 128, f16)["split_k"] == 16
     # what the matrix-core kernel does not cover goes to the plain kernel
     for shape in ((2, 8, 2048, 64), (2, 17, 2048, 128)):
