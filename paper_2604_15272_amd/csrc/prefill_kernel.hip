@@ -276,6 +276,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
             if ((i * 3 * MF) / NI != PART * MF + q) continue;
             if (i < XI) request_x(a_x, kt_x, i);
             else load_w(w_ld, kt_x + 1, i - XI);
+            // A small tile puts several of these instructions into one slot; the wait counts below depend on
+            // their order (requests before loads), so nothing may be moved across any of them.
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     constexpr int NI0 = (NI + 2) / 3;  // instructions of part 0: those with i * 3 MF / NI < MF
@@ -380,11 +383,20 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     // counts computed for the loop body hold on entry as well: X 0, W 0, W 1, [stage W 0], part 0 of
     // the refill with X 1 and W 2.
 #pragma unroll
-    for (int i = 0; i < XI; ++i) request_x(As, 0, i);
+    for (int i = 0; i < XI; ++i) {
+        request_x(As, 0, i);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
-    for (int i = 0; i < NWL; ++i) load_w(ws_b, 0, i);
+    for (int i = 0; i < NWL; ++i) {
+        load_w(ws_b, 0, i);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
-    for (int i = 0; i < NWL; ++i) load_w(ws_a, 1, i);
+    for (int i = 0; i < NWL; ++i) {
+        load_w(ws_a, 1, i);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
     for (int p = 0; p < NP; ++p) stage_w_piece(ws_b, Bs, p / 4, p % 4);
     __builtin_amdgcn_sched_barrier(0);
@@ -393,8 +405,9 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int p = 0; p < P3; ++p) stage_w_piece(ws_a, Bs + B_SLOTS, p / 4, p % 4);
-    // X of tile 0 is older than everything but its own requests.
-    stage_barrier(integral_constant<int, 2 * NWL + NI0>{});
+    // X of tile 0 is older than everything but its own requests: 2 NWL + NI0 younger instructions would do; the
+    // prologue runs once, so it simply waits for everything (and does not depend on the order above).
+    stage_barrier(integral_constant<int, 0>{});
     read_frags(As, Bs, 0, xfA, wfA);
 
     for (int kt = 0; kt < KT2; kt += 2) {

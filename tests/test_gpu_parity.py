@@ -324,6 +324,33 @@ def test_prefill_every_tile(P, gated, variant):
     _case(P, pi.BF16, 300, 712, 648, gated, seed=600, path=P.PRISM_PATH_PREFILL, variant=variant)
 
 
+def test_prefill_small_tile_with_fresh_buffers_every_call(P):
+    """The 64 x 64 tile puts several refill instructions into one pipeline slot; X rows that reach LDS late (first
+    touch of freshly allocated pages) must still be waited for.  Every call gets new buffers at other addresses."""
+    import torch
+    from gpu_util import from_device, to_device, worst_error
+    rng = np.random.default_rng(7)
+    cases = []
+    for M, K, N in ((300, 4096, 256), (100, 1024, 520)):
+        stored = pi.draw(pi.BF16, M, K, N, False, 500 + M)
+        cases.append((M, N, stored, run_oracle(stored, pi.BF16, False, 1e-6)))
+    P.prism_set_override(P.PRISM_PATH_PREFILL, 0, 64064)
+    try:
+        junk = []
+        for it in range(200):
+            M, N, stored, yhat = cases[it % 2]
+            junk.append(torch.empty(int(rng.integers(1, 64)) * 4096, dtype=torch.uint8, device="cuda"))
+            junk = junk[-12:]
+            X, g, W = (to_device(stored[n], pi.BF16) for n in ("X", "g", "W"))
+            Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+            P.prism_rmsnorm_matmul(X, g, W, Y)
+            torch.cuda.synchronize()
+            w = worst_error(from_device(Y, pi.BF16), yhat)
+            assert w <= 2e-2, (it, M, N, w)
+    finally:
+        P.prism_set_override(0, 0, 0)
+
+
 def test_prefill_few_rows_forced(P):
     _case(P, pi.BF16, 5, 256, 136, False, seed=601, path=P.PRISM_PATH_PREFILL)
 
