@@ -65,8 +65,11 @@ struct F16 {
     }
     // Largest of the eight elements of four dwords: pairwise in the storage format (packed maximum), widened once.
     static __device__ __forceinline__ float max8(u32x4 x) {
-        f16x2 m = __builtin_elementwise_max(__builtin_bit_cast(f16x2, x[0]), __builtin_bit_cast(f16x2, x[1]));
-        m = __builtin_elementwise_max(m, __builtin_elementwise_max(__builtin_bit_cast(f16x2, x[2]), __builtin_bit_cast(f16x2, x[3])));
+        // The dwords are copied out first: a bit cast applied directly to an element of the vector reads element 0
+        // whichever index is written (seen with this compiler), which made this the maximum of two values only.
+        const u32 d0 = x[0], d1 = x[1], d2 = x[2], d3 = x[3];
+        f16x2 m = __builtin_elementwise_max(__builtin_bit_cast(f16x2, d0), __builtin_bit_cast(f16x2, d1));
+        m = __builtin_elementwise_max(m, __builtin_elementwise_max(__builtin_bit_cast(f16x2, d2), __builtin_bit_cast(f16x2, d3)));
         return fmaxf((float)m[0], (float)m[1]);
     }
     static __device__ __forceinline__ f32x4 mfma_16x16x32(u32x4 a, u32x4 b, f32x4 c) {

@@ -551,6 +551,27 @@ def test_softmax_matmul_split_with_rows_of_very_different_maxima(P):
     assert_parity(y, run_oracle_softmax(st, pi.BF16), pi.BF16, "maxima 300 and 600 apart")
 
 
+@pytest.mark.parametrize("dtype", [pi.F16, pi.BF16])
+@pytest.mark.parametrize("split,rows", [(1, 16), (1, 32), (4, 32)])
+def test_softmax_matmul_maximum_at_every_position_of_a_lanes_eight_values(P, dtype, split, rows):
+    """A row's largest entry, 13 above the rest, at each of the eight positions a lane loads together: if the
+    running maximum missed it, exp(x - max) would leave the range of fp16 (e^13 > 65504)."""
+    M, K, N = 64, 512, 128
+    stored = pi.draw_softmax(pi.F32, M, K, N, 1075, 1.0)
+    x = stored["X"].astype(np.float32)
+    for r in range(M):
+        x[r, 8 * ((5 * r) % (K // 8)) + r % 8] = 14.0
+    w = stored["W"].astype(np.float32)
+    st = {"X": pi._store(x, dtype), "W": pi._store(w, dtype)}
+    P.prism_set_override(P.PRISM_PATH_ROWS, split, rows)
+    try:
+        y = run_gpu_softmax(st, dtype)
+    finally:
+        P.prism_set_override(0, 0, 0)
+    assert np.isfinite(y).all()
+    assert_parity(y, run_oracle_softmax(st, dtype), dtype, f"planted maxima split={split} rows={rows}")
+
+
 def test_softmax_matmul_split_is_bit_reproducible_and_leaves_tickets_clean(P):
     import torch
     from gpu_util import to_device
