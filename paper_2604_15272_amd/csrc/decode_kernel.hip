@@ -31,12 +31,33 @@
 #include "stream_partition.h"
 #include "w_block.h"
 
+#include <type_traits>
+
 namespace prism {
 
 namespace {
 
 constexpr int TN = kDecodeTileN;   // 128
 constexpr int KB = kDecodeKBlock;  // 32
+
+// The same with the A operand in two parts (scaled_a_operand_split): each B operand is built once and used twice.
+template <typename F>
+__device__ __forceinline__ void mfma_block_split(f32x4 (&acc)[8], u32x4 a_hi, u32x4 a_lo, const WRows& w) {
+    auto step = [&](auto jc) __attribute__((always_inline)) {
+        constexpr int J = decltype(jc)::value;
+        const u32x4 b = b_operand<J>(w);
+        acc[J] = F::mfma_16x16x32(a_hi, b, acc[J]);
+        acc[J] = F::mfma_16x16x32(a_lo, b, acc[J]);
+    };
+    step(std::integral_constant<int, 0>{});
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 3>{});
+    step(std::integral_constant<int, 4>{});
+    step(std::integral_constant<int, 5>{});
+    step(std::integral_constant<int, 6>{});
+    step(std::integral_constant<int, 7>{});
+}
 
 template <typename F>
 __device__ __forceinline__ void mfma_block(f32x4 (&acc)[8], u32x4 a, const WRows& w) {
@@ -141,11 +162,21 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
                 if (GATED) load_w_block<true>(w2[u], rw2, woff, row_bytes);
             }
         }
+        // Two-matrix calls carry x * g into the matrix core in two parts: their outputs are products of two sums,
+        // and the rounding of x * g to the storage format on either sum, amplified by the other, is what their far
+        // tail would otherwise consist of.  The matrix pipe has room (the kernel waits for memory); without a gain
+        // the second part is zero.
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const u32x4 a = scaled_a_operand<F>(xr[u], gr[u], ss);
-            mfma_block<F>(acc1, a, w1[u]);
-            if (GATED && !PACKED) mfma_block<F>(acc2, a, w2[u]);
+            if constexpr (GATED) {
+                u32x4 a_hi, a_lo;
+                scaled_a_operand_split<F>(xr[u], gr[u], ss, a_hi, a_lo);
+                mfma_block_split<F>(acc1, a_hi, a_lo, w1[u]);
+                if (!PACKED) mfma_block_split<F>(acc2, a_hi, a_lo, w2[u]);
+            } else {
+                const u32x4 a = scaled_a_operand<F>(xr[u], gr[u], ss);
+                mfma_block<F>(acc1, a, w1[u]);
+            }
         }
     }
 

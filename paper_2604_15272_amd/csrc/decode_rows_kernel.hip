@@ -125,31 +125,45 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
                 if (BOTH) load_w_block<false>(w2[u], rw2, woff, row_bytes);
             }
         }
+        // Two-matrix calls carry x * g in two parts (scaled_a_operand_split), as in the 16-row kernel.
+        auto products = [&](auto split_c) __attribute__((always_inline)) {
+            constexpr bool SPLIT = decltype(split_c)::value;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            u32x4 a[RG];
+            for (int u = 0; u < U; ++u) {
+                u32x4 a[RG], a_lo[SPLIT ? RG : 1];
 #pragma unroll
-            for (int r = 0; r < RG; ++r) a[r] = scaled_a_operand<F>(xr[u][r], gr[u], ss[r]);
-            auto step = [&](auto jc) {
-                constexpr int J = decltype(jc)::value;
-                const u32x4 b1 = b_operand<J>(w1[u]);
-#pragma unroll
-                for (int r = 0; r < RG; ++r) acc1[r][J] = F::mfma_16x16x32(a[r], b1, acc1[r][J]);
-                if (BOTH) {
-                    const u32x4 b2 = b_operand<J>(w2[BOTH ? u : 0]);
-#pragma unroll
-                    for (int r = 0; r < RG; ++r) acc2[r][J] = F::mfma_16x16x32(a[r], b2, acc2[r][J]);
+                for (int r = 0; r < RG; ++r) {
+                    if constexpr (SPLIT) scaled_a_operand_split<F>(xr[u][r], gr[u], ss[r], a[r], a_lo[r]);
+                    else a[r] = scaled_a_operand<F>(xr[u][r], gr[u], ss[r]);
                 }
-            };
-            step(std::integral_constant<int, 0>{});
-            step(std::integral_constant<int, 1>{});
-            step(std::integral_constant<int, 2>{});
-            step(std::integral_constant<int, 3>{});
-            step(std::integral_constant<int, 4>{});
-            step(std::integral_constant<int, 5>{});
-            step(std::integral_constant<int, 6>{});
-            step(std::integral_constant<int, 7>{});
-        }
+                auto step = [&](auto jc) __attribute__((always_inline)) {
+                    constexpr int J = decltype(jc)::value;
+                    const u32x4 b1 = b_operand<J>(w1[u]);
+#pragma unroll
+                    for (int r = 0; r < RG; ++r) {
+                        acc1[r][J] = F::mfma_16x16x32(a[r], b1, acc1[r][J]);
+                        if constexpr (SPLIT) acc1[r][J] = F::mfma_16x16x32(a_lo[r], b1, acc1[r][J]);
+                    }
+                    if (BOTH) {
+                        const u32x4 b2 = b_operand<J>(w2[BOTH ? u : 0]);
+#pragma unroll
+                        for (int r = 0; r < RG; ++r) {
+                            acc2[r][J] = F::mfma_16x16x32(a[r], b2, acc2[r][J]);
+                            if constexpr (SPLIT) acc2[r][J] = F::mfma_16x16x32(a_lo[r], b2, acc2[r][J]);
+                        }
+                    }
+                };
+                step(std::integral_constant<int, 0>{});
+                step(std::integral_constant<int, 1>{});
+                step(std::integral_constant<int, 2>{});
+                step(std::integral_constant<int, 3>{});
+                step(std::integral_constant<int, 4>{});
+                step(std::integral_constant<int, 5>{});
+                step(std::integral_constant<int, 6>{});
+                step(std::integral_constant<int, 7>{});
+            }
+        };
+        products(std::integral_constant<bool, GATED>{});
     }
 
 #pragma unroll

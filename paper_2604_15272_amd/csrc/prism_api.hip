@@ -100,6 +100,10 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
     const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
     const int64_t z32 = (M + 31) / 32, z64 = (M + 63) / 64;
+    // Two weight matrices and at most one K-step of the tiled kernel: nothing to tile, and with so few products
+    // per sum the tiled kernel's single rounding of g * w shows in the far tail of the outputs (2.1e-2 to 2.7e-2
+    // seen in bf16 against a bar of 2e-2); the decode kernels carry x * g in two parts.
+    if (gated && K <= 64 && z32 <= 65535 && n_tiles * z32 <= kMaxTickets) return 2;
     if (M > kDecodeRowsMax || (M > 64 && K < 2048)) return 0;
     const uint64_t w_bytes = (uint64_t)K * N * 2 * (gated ? 2 : 1);
     if (gated) {

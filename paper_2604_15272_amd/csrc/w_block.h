@@ -47,6 +47,27 @@ __device__ __forceinline__ u32x4 scaled_a_operand(u32x4 x, u32x4 gg, float& ss) 
     return a;
 }
 
+// The same operand in two parts, for calls whose error budget does not allow the rounding of x * g: the product of
+// two stored values is exact in fp32 (8 + 8 or 11 + 11 significant bits), `hi` is that product rounded to the storage
+// format and `lo` the rounded remainder, so hi + lo carries the product to 2^-17 (bf16) or 2^-23 (fp16) relative
+// instead of 2^-9 / 2^-12, and (hi + lo) . W costs a second MFMA on the same B operand.  With a gain of exactly 1
+// lo is zero.
+template <typename F>
+__device__ __forceinline__ void scaled_a_operand_split(u32x4 x, u32x4 gg, float& ss, u32x4& hi, u32x4& lo) {
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const float x0 = F::lo(x[d]), x1 = F::hi(x[d]);
+        ss = fmaf(x0, x0, ss);
+        ss = fmaf(x1, x1, ss);
+        const float p0 = x0 * F::lo(gg[d]), p1 = x1 * F::hi(gg[d]);
+        const u32 h = F::pack(p0, p1);
+        hi[d] = h;
+        // (a product beyond the format's range rounds to infinity: no remainder then, the result stays infinite)
+        const float r0 = p0 - F::lo(h), r1 = p1 - F::hi(h);
+        lo[d] = F::pack(__builtin_isfinite(r0) ? r0 : 0.f, __builtin_isfinite(r1) ? r1 : 0.f);
+    }
+}
+
 // A wavefront's 16 x 128 accumulator tile (eight 16x16 MFMA results: accumulator j, element i of lane
 // (q, c) is row 4q + i, column 8c + j) stored as rows of `pitch` floats at `tile`.  A lane owns 32 bytes
 // of a row; lanes c and c + 8 are 256 bytes apart, the same banks: the upper eight write their second
