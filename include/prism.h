@@ -181,6 +181,23 @@ uint64_t prism_workspace_bytes(prism_op_t op, int64_t M, int64_t K, int64_t N, p
 prism_status_t prism_set_workspace(void* dev_ptr, uint64_t bytes);
 
 /*
+ * prism_rmsnorm_matmul for callers that cannot allocate or register device memory: code that is being recorded
+ * into a HIP graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-for-bit the same result as prism_rmsnorm_matmul, but a call whose plan splits K exchanges its partial sums
+ * through an array of PRISM_STATIC_SCRATCH_BYTES that is part of the library's device code (every device the
+ * library runs on holds it until the process ends) instead of the registered workspace.  The call allocates and
+ * frees nothing and ignores prism_set_workspace.  The first call on a device looks the array's address up and
+ * enqueues a small kernel on `stream` that clears its arrival counters; the current device must be the device of
+ * `stream`.  PRISM_ERR_WORKSPACE if the call needs more than PRISM_STATIC_SCRATCH_BYTES
+ * (prism_workspace_bytes tells; at most 16 rows against W[4096,4096] need 2.3 MB).  All calls on a device share the one
+ * array: calls of this entry point that overlap in time on one device race (use one stream, or order the streams).
+ */
+#define PRISM_STATIC_SCRATCH_BYTES 8388608u
+prism_status_t prism_rmsnorm_matmul_static(const void* X, const void* g, const void* W, void* Y,
+                                           int64_t M, int64_t K, int64_t N, float eps,
+                                           prism_dtype_t dtype, hipStream_t stream);
+
+/*
  * Host-side query: fills *plan with the kernel family, split factor, tile and grid the
  * dispatcher would use for this shape under the current override.  Touches no device.
  */

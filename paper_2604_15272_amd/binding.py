@@ -57,6 +57,8 @@ def _load():
         getattr(L, f"prism_rmsnorm_matmul_{sfx}").restype = i32
         getattr(L, f"prism_rmsnorm_gated_mlp_{sfx}").restype = i32
     L.prism_rmsnorm_matmul.restype = i32
+    L.prism_rmsnorm_matmul_static.argtypes = [vp, vp, vp, vp, i64, i64, i64, f32, i32, vp]
+    L.prism_rmsnorm_matmul_static.restype = i32
     L.prism_rmsnorm_gated_mlp.restype = i32
     L.prism_rmsnorm_glu.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, f32, i32, vp]
     L.prism_rmsnorm_glu.restype = i32
@@ -228,6 +230,21 @@ def prism_rmsnorm_matmul(X, g, W, Y, M=None, K=None, N=None, eps=1e-6, dtype=Non
                                   _stream_handle(stream))
     if st != 0:
         raise PrismError(st, "prism_rmsnorm_matmul")
+    return Y
+
+
+STATIC_SCRATCH_BYTES = 8388608
+
+
+def prism_rmsnorm_matmul_static(X, g, W, Y, M=None, K=None, N=None, eps=1e-6, dtype=None, stream=None):
+    """prism_rmsnorm_matmul through the library's own static device scratch: registers and allocates nothing."""
+    if M is None:
+        M, K = X.shape
+        N = W.shape[1]
+    st = lib.prism_rmsnorm_matmul_static(_ptr(X), _ptr(g), _ptr(W), _ptr(Y), int(M), int(K), int(N), float(eps),
+                                         _dtype_of(X, dtype), _stream_handle(stream))
+    if st != 0:
+        raise PrismError(st, "prism_rmsnorm_matmul_static")
     return Y
 
 

@@ -8,8 +8,19 @@
 #include "prism_internal.h"
 #include "stream_partition.h"
 
+// Split-K scratch of prism_rmsnorm_matmul_static: the same layout as a registered workspace (arrival counters,
+// partial sums of squares, partial products), held by every device the library runs on until the process ends.
+// In host code this name is a stand-in, not a device address: the address is asked for once per device
+// (static_scratch below) and only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[PRISM_STATIC_SCRATCH_BYTES];
+
 namespace prism {
 namespace {
+
+__global__ void clear_words_kernel(unsigned* p, unsigned n) {
+    const unsigned i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
 
 constexpr int kMaxDevices = 64;
 constexpr uint64_t kTwoGiB = 0x7FFFFFFFull;
@@ -41,6 +52,29 @@ struct Workspace {
 Workspace g_workspace[kMaxDevices];  // indexed by HIP device ordinal
 
 uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// Address of `scratch` on the current device, looked up on the first call there.  That call also clears the arrival
+// counters with a small kernel on the caller's stream (a kernel, not a memset, so that a caller who is recording a
+// graph records something that replays correctly); afterwards every kernel leaves them at zero.
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+prism_status_t static_scratch(hipStream_t stream, Workspace* out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PRISM_ERR_HIP;
+        constexpr unsigned words = PRISM_WORKSPACE_HEADER_BYTES / 4;
+        hipLaunchKernelGGL(clear_words_kernel, dim3(words / 256), dim3(256), 0, stream, (unsigned*)p, words);
+        if (hipGetLastError() != hipSuccess) return PRISM_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = Workspace{g_scratch_ptr[dev], PRISM_STATIC_SCRATCH_BYTES};
+    return PRISM_OK;
+}
 
 struct Plan {
     prism_plan_t pub;
@@ -546,7 +580,7 @@ bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 // is null).
 prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, const void* W2, void* Y, int64_t M,
                    int64_t K, int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream,
-                   int flags = kFlagGain | kFlagNorm | kFlagSilu) {
+                   int flags = kFlagGain | kFlagNorm | kFlagSilu, bool use_static_scratch = false) {
     const bool gated = op == PRISM_OP_RMSNORM_GATED_MLP;
     if (!g) flags &= ~kFlagGain;
     if (!dtype_known(dtype)) return PRISM_ERR_UNSUPPORTED;
@@ -570,10 +604,16 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
         case PRISM_PATH_DECODE: {
             DecodeWorkspace ws{nullptr, nullptr, nullptr};
             if (plan.pub.split_k > 1) {
-                int dev = 0;
-                if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
-                if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
-                const Workspace w = g_workspace[dev];
+                Workspace w{nullptr, 0};
+                if (use_static_scratch) {
+                    if (plan.pub.workspace_bytes > PRISM_STATIC_SCRATCH_BYTES) return PRISM_ERR_WORKSPACE;
+                    if (const prism_status_t s = static_scratch(stream, &w); s != PRISM_OK) return s;
+                } else {
+                    int dev = 0;
+                    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+                    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
+                    w = g_workspace[dev];
+                }
                 if (!w.ptr || w.bytes < plan.pub.workspace_bytes) return PRISM_ERR_WORKSPACE;
                 char* base = (char*)w.ptr;
                 ws.tickets = (unsigned*)base;
@@ -626,6 +666,12 @@ extern "C" {
 prism_status_t prism_rmsnorm_matmul(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K,
                                     int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream) {
     return run(PRISM_OP_RMSNORM_MATMUL, X, g, W, nullptr, Y, M, K, N, eps, dtype, stream);
+}
+
+prism_status_t prism_rmsnorm_matmul_static(const void* X, const void* g, const void* W, void* Y, int64_t M, int64_t K,
+                                           int64_t N, float eps, prism_dtype_t dtype, hipStream_t stream) {
+    return run(PRISM_OP_RMSNORM_MATMUL, X, g, W, nullptr, Y, M, K, N, eps, dtype, stream,
+               kFlagGain | kFlagNorm | kFlagSilu, /*use_static_scratch=*/true);
 }
 
 prism_status_t prism_rmsnorm_gated_mlp(const void* X, const void* g, const void* W1, const void* W2, void* Y,
