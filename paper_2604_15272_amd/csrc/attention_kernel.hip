@@ -85,7 +85,7 @@ __global__ __launch_bounds__(ANW * 64) void gqa_decode_kernel(const uint16_t* __
     const int KS = slice_keys;         // keys per slice, a multiple of 32
     constexpr int PW = 40;             // row pitch (elements) of a wavefront's 16 x 32 tile of P: rows 80 bytes apart
 
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];  // 16-byte LDS accesses need the alignment said
     float* red = lds;                                   // [ANW][16][AD] partial outputs
     float* wm = red + ANW * 16 * AD;                    // [ANW][16] running maxima of the wavefronts
     float* wl = wm + ANW * 16;                          // [ANW][16] their sums of exponentials

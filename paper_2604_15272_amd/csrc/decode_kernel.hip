@@ -91,7 +91,7 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
     static_assert(GATED || !PACKED, "the packed tile is a gated tile");
     constexpr int TNO = PACKED ? TN / 2 : TN;  // output columns of a tile
 
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];  // 16-byte LDS accesses need the alignment said
     float* red = lds;                    // [NW][16][TN], used once per weight matrix
     float* ss_red = lds + NW * 16 * TN;  // [NW][16]
     __shared__ int is_last;

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
     constexpr bool BOTH = GATED && !HALVES;    // every wavefront takes both matrices
     constexpr int LNW = HALVES ? NW / 2 : NW;  // wavefronts that share one matrix's K-blocks
 
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];  // 16-byte LDS accesses need the alignment said
     float* red = lds;                    // [2][NW][16][TN], reused for every (weight matrix, pair of row groups)
     float* ss_red = lds + 2 * kRedFloats;  // [NW][RB]
     __shared__ int is_last;

@@ -62,7 +62,7 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
     constexpr float kLog2e = 1.4426950408889634f;
     constexpr int CH = 4;  // K-blocks per wavefront and chunk (even: the W register sets alternate per block)
 
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];  // 16-byte LDS accesses need the alignment said
     float* red = lds;                       // [NW][16][TN]
     float* wave_max = lds + NW * 16 * TN;   // [NW][16]
     float* wave_sum = wave_max + NW * 16;   // [NW][16]

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
                                                            uint16_t* __restrict__ Y, float* __restrict__ acc_part,
                                                            float* __restrict__ ml_part, unsigned* __restrict__ tickets,
                                                            int M, int K, int N, int S) {
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];  // 16-byte LDS accesses need the alignment said
     float* red = lds;                       // [RG][NW][16][TN]
     float* wave_max = lds + RG * kRedFloats;  // [NW][RB]
     float* wave_sum = wave_max + NW * RB;     // [NW][RB]
