@@ -98,23 +98,33 @@ class Runner:
             if st != 0:
                 raise RuntimeError(f"library call failed: {self.P.prism_status_string(st)}")
 
-    def timed(self, steps, warmup, sets_used=None):
-        """Returns (wall ms per step, HIP-event ms per step) over exactly `steps` calls."""
+    def timed(self, steps, warmup, sets_used=None, regions=1):
+        """`regions` timed regions of exactly `steps` calls each, after `warmup` untimed calls; every region is
+        bracketed by torch.cuda.synchronize() on both sides.  Returns (wall ms per step, HIP-event ms per step) of
+        the region with the median wall time, or, with regions > 1, the two lists."""
         torch = self.torch
         if sets_used == 1:
             saved, self.args, self.sets = (self.args, self.sets), self.args[:1], 1
         self.run(warmup)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t0 = time.perf_counter()
-        e0.record()
-        self.run(steps, first=warmup)
-        e1.record()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
+        walls, evs = [], []
+        for r in range(regions):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t0 = time.perf_counter()
+            e0.record()
+            self.run(steps, first=warmup + r * steps)
+            e1.record()
+            while not e1.query():   # the clock stops when the last call has finished, not when a sleeping
+                pass                # host thread has been woken up
+            t1 = time.perf_counter()
+            torch.cuda.synchronize()
+            walls.append((t1 - t0) * 1e3 / steps)
+            evs.append(e0.elapsed_time(e1) / steps)
         if sets_used == 1:
             self.args, self.sets = saved
-        return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+        if regions == 1:
+            return walls[0], evs[0]
+        return walls, evs
 
     def probe_split(self):
         """K-slices for the probe's grid of 128-column stripes: about as many workgroups as the kernel launches."""
@@ -154,6 +164,14 @@ class Runner:
         return y.cpu().numpy().astype(np.float64)
 
 
+REGIONS = 5   # timed regions per workload: median and minimum are reported
+
+
+def median(v):
+    v = sorted(v)
+    return v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2])
+
+
 def measure(idx, steps, warmup):
     wl = pi.WORKLOADS[idx]
     nbytes, flops = counted_bytes(wl), counted_flops(wl)
@@ -162,20 +180,24 @@ def measure(idx, steps, warmup):
     sets = max(2, -(-(1 << 30) // wbytes)) if dec else 1
     log(f"[bench] workload {idx} {wl.name}: M={wl.M} K={wl.K} N={wl.N} gated={wl.gated} sets={sets}")
     r = Runner(wl, sets)
-    wall_ms, ev_ms = r.timed(steps, warmup)
-    # Roofline figure: launch duration = HIP-event time of the timed region / launches.  (One event pair
-    # per launch was tried: for a ~13 us kernel the pair reads twice the rocprofv3 duration, the region
-    # average reads 7% above it, the gap between back-to-back launches.)
-    k_mean = k_med = k_min = ev_ms
+    walls, evs = r.timed(steps, warmup, regions=REGIONS)
+    wall_ms, ev_ms = median(walls), median(evs)
+    # Roofline figure: launch duration = HIP-event time of a timed region / its launches, i.e. the average
+    # per launch over the region, gaps between back-to-back launches included (one event pair per launch reads
+    # twice the rocprofv3 duration for a ~10 us kernel; the region average reads a few per cent above it).
+    # Median over the regions; the minimum is reported beside it.
+    k_mean = ev_ms
     res = {
         "workload": wl.name, "config_index": idx, "M": wl.M, "K": wl.K, "N": wl.N, "gated": wl.gated,
-        "plan": r.plan, "steps": steps, "ms_per_step": wall_ms, "event_ms_per_step": ev_ms,
+        "plan": r.plan, "steps": steps, "regions": REGIONS, "ms_per_step": wall_ms, "ms_per_step_min": min(walls),
+        "event_ms_per_step": ev_ms, "event_ms_per_step_min": min(evs), "region_wall_ms_per_step": walls,
+        "region_event_ms_per_step": evs,
         "kernel_ms": k_mean, "buffer_sets": sets, "bytes_per_launch": nbytes, "flops_per_launch": flops,
     }
     if dec:
         res.update(value=nbytes / (wall_ms * 1e-3) / 1e9, unit="GB/s", bound="hbm",
                    achieved=nbytes / (k_mean * 1e-3) / 1e9, peak=HBM_PEAK_GBS)
-        _, hot_ms = r.timed(steps, warmup, sets_used=1)
+        hot_ms = median(r.timed(steps, warmup, sets_used=1, regions=3)[1])
         res["cache_hot_kernel_ms"] = hot_ms
         res["cache_hot_GBps"] = nbytes / (hot_ms * 1e-3) / 1e9
         res["stream_probe_ms"] = r.probe(steps, warmup)
@@ -185,20 +207,23 @@ def measure(idx, steps, warmup):
             r.P.prism_set_stream_balance(0, 0)
             try:
                 r.P.ensure_workspace(r.P.prism_workspace_bytes(r.op, wl.M, wl.K, wl.N, r.dt))
-                _, res["equal_slices_kernel_ms"] = r.timed(steps, warmup)
+                res["equal_slices_kernel_ms"] = median(r.timed(steps, warmup, regions=3)[1])
             finally:
-                r.P.prism_set_stream_balance()
+                r.P.prism_set_stream_balance(SLOW_UNITS["mask"], 0)
     else:
         res.update(value=flops / (wall_ms * 1e-3) / 1e12, unit="TFLOP/s", bound="mfma",
                    achieved=flops / (k_mean * 1e-3) / 1e12, peak=MFMA_BF16_PEAK_TFLOPS)
+        res["vendor_gemm"] = measure_vendor_gemm(wl.M, wl.K, wl.N, wl.gated, max(5, steps // 4), 3)
+        log(f"[bench]   vendor GEMM on the plain product(s): {res['vendor_gemm']['TFLOPs']:.0f} TFLOP/s")
     res["frac"] = res["achieved"] / res["peak"]
     if "stream_probe_ms" in res:
         log(f"[bench]   read-only probe (128-column stripes, as many workgroups): {res['stream_probe_ms'] * 1e3:.2f} us per launch "
             f"({nbytes / (res['stream_probe_ms'] * 1e-3) / 1e9:.0f} GB/s)")
     if "equal_slices_kernel_ms" in res:
         log(f"[bench]   with equal K-slices for all tiles (two-tile form): {res['equal_slices_kernel_ms'] * 1e3:.2f} us per launch")
-    log(f"[bench]   {res['value']:.1f} {res['unit']} back-to-back ({wall_ms * 1e3:.2f} us/step wall, "
-        f"{ev_ms * 1e3:.2f} by events); kernel alone {k_mean * 1e3:.2f} us -> {res['achieved']:.1f} {res['unit']} "
+    log(f"[bench]   {res['value']:.1f} {res['unit']} back-to-back (median of {REGIONS} regions of {steps} calls: "
+        f"{wall_ms * 1e3:.2f} us/step wall, min {min(walls) * 1e3:.2f}; by events {ev_ms * 1e3:.2f}, min "
+        f"{min(evs) * 1e3:.2f}); per launch by events {k_mean * 1e3:.2f} us -> {res['achieved']:.1f} {res['unit']} "
         f"= {100 * res['frac']:.1f}% of {res['bound']} peak")
     return res, r
 
@@ -211,6 +236,10 @@ def cpu_baseline(runner):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
     wl, st = runner.wl, runner.stored
     X, g = pi.to_f64(st["X"], wl.dtype), pi.to_f64(st["g"], wl.dtype)
     Ws = [pi.to_f64(st[n], wl.dtype) for n in (("W1", "W2") if wl.gated else ("W",))]
@@ -228,6 +257,9 @@ def cpu_baseline(runner):
     err = float(np.max(np.abs(y - yhat) / (np.abs(yhat) + 1.0)))
     return {
         "value": counted_bytes(wl) / sec / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+        "nproc": int(os.cpu_count() or 1), "usable_cpus": int(usable),
+        "cores_note": "cores = threads of the BLAS pool that numpy.matmul used; nproc = CPUs the host reports; "
+                      "usable_cpus = CPUs this process may run on",
         "sample": f"whole {wl.name} workload (M={wl.M}), fp64 numpy oracle, mean of {reps} calls, "
                   f"inputs already widened to fp64; {sec * 1e3:.2f} ms per call",
         "gpu_vs_oracle_worst_err": err,
@@ -383,6 +415,91 @@ def measure_attention(h, qk_norm, steps=1000, warmup=50):
 
 
 COPY_CALIBRATION_BYTES = 256 << 20
+SLOW_UNITS = {"mask": 0}   # filled by main() from tune.detect_slow_units()
+
+
+def measure_copy_ceiling(nbytes=256 << 20, buffers=6, steps=30):
+    """Device-to-device copies (torch's copy kernel) over buffers that rotate past the last-level cache: bytes read
+    plus bytes written per second, the measured ceiling of HBM traffic beside the published peak."""
+    import torch
+    srcs = [torch.full((nbytes // 2,), 1.0, dtype=torch.bfloat16, device="cuda") for _ in range(buffers)]
+    dst = torch.empty_like(srcs[0])
+    for i in range(buffers):
+        dst.copy_(srcs[i])
+    res = []
+    for _ in range(REGIONS):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(steps):
+            dst.copy_(srcs[i % buffers])
+        e1.record()
+        torch.cuda.synchronize()
+        res.append(e0.elapsed_time(e1) / steps)
+    ms = median(res)
+    out = {"GBps": 2 * nbytes / (ms * 1e-3) / 1e9, "GBps_best": 2 * nbytes / (min(res) * 1e-3) / 1e9,
+           "bytes_per_copy": nbytes, "ms_per_copy": ms,
+           "note": "torch device-to-device copy of 256 MiB, read + written bytes, sources rotating over 1.5 GiB"}
+    del srcs, dst
+    torch.cuda.empty_cache()
+    return out
+
+
+def measure_mfma_ceiling(iters=4000):
+    """The library's matrix-pipe probe (prism_probe_mfma: 32x32x16 bf16 MFMAs on registers, two workgroups of four
+    wavefronts per compute unit, no memory traffic): what the part sustains under its clock and power limits."""
+    import torch
+    import paper_2604_15272_amd as P
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    vp = ctypes.c_void_p
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    wgs = 2 * P.prism_diag_cu_count()
+    P.lib.prism_probe_mfma(vp(sink.data_ptr()), wgs, 100, stream)
+    res = []
+    for _ in range(REGIONS):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        st = P.lib.prism_probe_mfma(vp(sink.data_ptr()), wgs, iters, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        if st != 0:
+            raise RuntimeError("prism_probe_mfma failed")
+        res.append(e0.elapsed_time(e1))
+    flops = 32768.0 * 16 * iters * 4 * wgs
+    return {"TFLOPs": flops / (median(res) * 1e-3) / 1e12, "TFLOPs_best": flops / (min(res) * 1e-3) / 1e12,
+            "ms": median(res), "workgroups": wgs,
+            "note": "prism_probe_mfma: matrix pipes alone (a launch of about 1 ms; longer runs clock lower)"}
+
+
+def measure_vendor_gemm(M, K, N, two, steps, warmup):
+    """The plain product(s) of a prefill configuration on the vendor GEMM library (torch.matmul, bf16, W stored
+    [K, N] as here), without norm, gain or gate: context for the fused kernel's figure, same flop count."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(0x5EED5000 + N)
+    X = torch.randn((M, K), generator=gen, device="cuda").to(torch.bfloat16)
+    Ws = [(torch.randn((K, N), generator=gen, device="cuda") / 64).to(torch.bfloat16) for _ in range(2 if two else 1)]
+    Ys = [torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in Ws]
+    for _ in range(warmup):
+        for W, Y in zip(Ws, Ys):
+            torch.matmul(X, W, out=Y)
+    res = []
+    for _ in range(3):
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            for W, Y in zip(Ws, Ys):
+                torch.matmul(X, W, out=Y)
+        e1.record()
+        torch.cuda.synchronize()
+        res.append(e0.elapsed_time(e1) / steps)
+    flops = 2.0 * M * K * N * len(Ws)
+    out = {"TFLOPs": flops / (median(res) * 1e-3) / 1e12, "ms": median(res),
+           "note": "torch.matmul (vendor GEMM), plain product(s) only"}
+    del X, Ws, Ys
+    torch.cuda.empty_cache()
+    return out
 
 
 def measure_mid_rows(M, K, N, gated, steps=300, warmup=20):
@@ -520,22 +637,48 @@ def main():
         print(json.dumps({"attention": [measure_attention(h, qk) for h in (1024, 2048) for qk in (False, True)]}),
               flush=True)
         return
+    # Which address units stream slowly is measured on the machine at hand, outside every timed region, and handed
+    # to the library (its own default names none): the dispatcher then balances gated decode calls around them.
+    import paper_2604_15272_amd as P
+    from paper_2604_15272_amd import tune
+    det = tune.detect_slow_units(install=True)
+    SLOW_UNITS["mask"] = det["mask"]
+    log(f"[bench] slow address units on this machine: mask {det['mask']:#06x} (us per unit: "
+        f"{' '.join('%.1f' % t for t in det['us'])})")
     head, runner = measure(a.workload, a.steps, a.warmup)
     traffic = measured_traffic(head["workload"])
+    copy_ceiling, mfma_ceiling = measure_copy_ceiling(), measure_mfma_ceiling()
+    log(f"[bench] measured ceilings: device copy {copy_ceiling['GBps']:.0f} GB/s (read + written), matrix pipes alone "
+        f"{mfma_ceiling['TFLOPs']:.0f} TFLOP/s")
     out = {
         "metric": METRIC, "value": head["value"], "unit": head["unit"], "n_gpus": 1, "steps": a.steps,
         "warmup": a.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "regions": head["regions"], "ms_per_step_min": head["ms_per_step_min"],
+        "region_ms_per_step": head["region_wall_ms_per_step"],
+        "timing_note": f"{head['regions']} timed regions of exactly `steps` calls each, every region bracketed by "
+                       "torch.cuda.synchronize(); ms_per_step and value are the median region's, ms_per_step_min the "
+                       "fastest region's",
         "config": {"workload": head["workload"], "M": head["M"], "K": head["K"], "N": head["N"],
-                   "gated": head["gated"], "plan": head["plan"], "buffer_sets": head["buffer_sets"]},
+                   "gated": head["gated"], "plan": head["plan"], "buffer_sets": head["buffer_sets"],
+                   "slow_units_mask": det["mask"], "compute_units": P.prism_diag_cu_count()},
         "roofline": {"bound": head["bound"], "achieved": head["achieved"], "peak": head["peak"],
                      "unit": head["unit"], "frac": head["frac"],
+                     "achieved_best_region": head["bytes_per_launch"] / (head["event_ms_per_step_min"] * 1e-3) / 1e9
+                     if head["bound"] == "hbm" else head["flops_per_launch"] / (head["event_ms_per_step_min"] * 1e-3) / 1e12,
                      "traffic": None if traffic is None else traffic["fetch_bytes"] + traffic["write_bytes"],
                      "traffic_unit": "bytes per launch", "traffic_detail": traffic,
+                     "traffic_note": "not measured in this run: read from profiles/hbm_traffic.md (rocprofv3 --pmc runs "
+                                     "of this command)",
                      "algorithmic_bytes_per_launch": head.get("bytes_per_launch"),
                      "kernel": "prism::decode_kernel" if head["bound"] == "hbm" else "prism::prefill_kernel",
                      "kernel_ms_per_launch": head["kernel_ms"],
-                     "timing": "HIP events around the timed region on the launch stream, divided by the launches"},
+                     "kernel_ms_per_launch_min": head["event_ms_per_step_min"],
+                     "timing": "HIP events around each timed region on the launch stream, divided by the region's "
+                               "launches (an average per launch, launch gaps included); median of the regions",
+                     "copy_ceiling": copy_ceiling, "mfma_ceiling": mfma_ceiling},
+        "slow_units": {"mask": det["mask"], "us_per_unit": det["us"], "median_us": det["median_us"],
+                       "note": "tune.detect_slow_units: prism_probe_units, all sixteen units read at once, median workgroup time per unit"},
     }
     if "stream_probe_ms" in head:
         out["roofline"]["stream_probe"] = {
@@ -558,9 +701,10 @@ def main():
             torch.cuda.empty_cache()
             res, r = measure(idx, st, wu)
             del r
-            others.append({k: res[k] for k in ("workload", "plan", "steps", "ms_per_step", "event_ms_per_step",
+            others.append({k: res[k] for k in ("workload", "plan", "steps", "regions", "ms_per_step", "ms_per_step_min",
+                                               "event_ms_per_step", "event_ms_per_step_min",
                                                "kernel_ms", "value", "unit", "bound", "achieved", "peak", "frac",
-                                               "stream_probe_ms", "equal_slices_kernel_ms") if k in res})
+                                               "stream_probe_ms", "equal_slices_kernel_ms", "vendor_gemm") if k in res})
         out["other_workloads"] = others
         torch.cuda.empty_cache()
         log("[bench] the paper's workloads at its shapes, fp16, no gain (output width assumed: see PAPER_SHAPES)")

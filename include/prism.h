@@ -171,14 +171,22 @@ prism_status_t prism_rmsnorm_gated_mlp_f32(const void* X, const void* g, const v
  *   HIP device.  The first PRISM_WORKSPACE_HEADER_BYTES hold per-tile arrival counters that
  *   must be zero between calls: this function zeroes them with a blocking hipMemset (the one
  *   place the library waits on the device) and every kernel leaves them zero again.  The
- *   memory must outlive all enqueued work.  Calls that use the workspace must not overlap in
- *   time on one device (use one stream, or order the streams).  Passing NULL/0 unregisters.
+ *   memory must outlive all enqueued work.  Calls that use one workspace must not overlap in
+ *   time (use one stream, or order the streams, or give streams workspaces of their own with
+ *   prism_set_stream_workspace).  Passing NULL/0 unregisters.  The workspace belongs to the current HIP
+ *   device, and a call finds it through the current device: call with the device of `stream` current.
+ *   A kernel that fails after it has taken arrival tickets can leave counters non-zero: register the
+ *   workspace again after any PRISM_ERR_HIP or device error before reusing it.
+ * prism_set_stream_workspace: the same for calls on one stream: a call looks for a workspace registered for
+ *   exactly its stream first and falls back to the device's.  With one workspace per stream, split-K calls on
+ *   different streams may run at the same time.  At most 32 streams; NULL/0 unregisters the stream's.
  *   The calls themselves only enqueue kernels (no memset, no allocation, no synchronisation), so a
  *   sequence of them may be recorded in a HIP graph and replayed (tested).
  */
 #define PRISM_WORKSPACE_HEADER_BYTES 262144u
 uint64_t prism_workspace_bytes(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype);
 prism_status_t prism_set_workspace(void* dev_ptr, uint64_t bytes);
+prism_status_t prism_set_stream_workspace(hipStream_t stream, void* dev_ptr, uint64_t bytes);
 
 /*
  * prism_rmsnorm_matmul for callers that cannot allocate or register device memory: code that is being recorded
@@ -199,7 +207,9 @@ prism_status_t prism_rmsnorm_matmul_static(const void* X, const void* g, const v
 
 /*
  * Host-side query: fills *plan with the kernel family, split factor, tile and grid the
- * dispatcher would use for this shape under the current override.  Touches no device.
+ * dispatcher would use for this shape under the current override.  Launches nothing; the first planning call of
+ * a process asks the current device for its number of compute units (grids are sized by it; 256 is assumed where
+ * there is no device to ask).
  */
 prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_dtype_t dtype,
                           prism_plan_t* plan);
@@ -237,9 +247,12 @@ int32_t prism_plan_table_size(void);
  * "parallelized matmul (reduction)", with shares that are equal in streaming time instead of in K).
  *
  * Slow units.  When the row pitch of W is a multiple of 2 KiB, the stripe of W a workgroup streams keeps bits 7-10
- * of its byte addresses for all rows (which 128 bytes of every 2 KiB: its unit).  On the MI355X measured, the
+ * of its byte addresses for all rows (which 128 bytes of every 2 KiB: its unit).  On the MI355X machines measured, the
  * stripes in units 3 and 11 arrive 40 % later than the others, wherever W starts and whichever CU reads them.
- * slow_units: bit u set = unit u is slow (default 0x0808; 0: none).  Used for gated calls with at most 16 rows:
+ * slow_units: bit u set = unit u is slow.  The default is 0 (none): which units are slow is a property of the
+ * machine, to be measured there (the Python package's tune.detect_slow_units times the sixteen units with
+ * prism_probe_units and returns the mask; 0x0808 on the machines measured, where it takes 3 % off the gated decode
+ * configuration: 42.1 -> 40.7 us).  Used for gated calls with at most 16 rows:
  * they take tiles of 64 output columns (128-byte stripes of W1 and of W2) and cut the tiles in slow units into more
  * K-slices than the others, provided N is a multiple of 1024 and all workgroups find a CU of their own; the
  * balanced launch also needs W1 on a 128-byte boundary and W2 in step with W1 modulo 2 KiB (otherwise every tile gets
@@ -257,28 +270,6 @@ int32_t prism_plan_table_size(void);
  * Host-side, process-wide.
  */
 prism_status_t prism_set_stream_balance(int32_t slow_units, int32_t mode);
-
-/*
- * Diagnostic, host-side: the K-blocks [*first, *first + *count) of column tile `tile` that workgroup `wg` works on
- * in a weighted partition of n_tiles tiles of kblocks K-blocks over `workgroups` workgroups; a K-block of tile t
- * weighs w_slow if bit (t mod period) of slow_tiles is set, else w_fast (period 8 or 16).  The same integer
- * functions run in the kernel; this entry point lets a test check that they deal every K-block out exactly once.
- * PRISM_ERR_UNSUPPORTED if the total weight does not fit 31 bits.
- */
-prism_status_t prism_stream_partition_blocks(int32_t workgroups, int32_t kblocks, int32_t n_tiles, int32_t slow_tiles,
-                                            int32_t period, int32_t w_fast, int32_t w_slow, int32_t wg, int32_t tile,
-                                            int32_t* first, int32_t* count);
-
-/*
- * Diagnostic, for measurement: streams W[K,N] (16-bit elements, device memory, 16-byte aligned, N a multiple
- * of 8; and W2 of the same shape unless NULL) once with the decode kernels' access pattern and split, and
- * computes nothing.  Its duration is the
- * floor that streaming W sets for a decode call on the machine at hand (bench.py reports it beside the
- * kernels).  Needs a registered workspace of at least 2 * PRISM_WORKSPACE_HEADER_BYTES (one word past the
- * counters may be written).
- */
-prism_status_t prism_probe_stream(const void* W, const void* W2, int64_t K, int64_t N, int32_t split_k,
-                                  hipStream_t stream);
 
 const char* prism_status_string(prism_status_t status);
 int32_t prism_version(void);

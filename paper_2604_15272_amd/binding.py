@@ -76,6 +76,16 @@ def _load():
     L.prism_workspace_bytes.restype = u64
     L.prism_set_workspace.argtypes = [vp, u64]
     L.prism_set_workspace.restype = i32
+    L.prism_set_stream_workspace.argtypes = [vp, vp, u64]
+    L.prism_set_stream_workspace.restype = i32
+    L.prism_probe_units.argtypes = [vp, u64, i32, vp, vp]
+    L.prism_probe_units.restype = i32
+    L.prism_probe_mfma.argtypes = [vp, i32, i32, vp]
+    L.prism_probe_mfma.restype = i32
+    L.prism_diag_set_cu_count.argtypes = [i32]
+    L.prism_diag_set_cu_count.restype = i32
+    L.prism_diag_cu_count.argtypes = []
+    L.prism_diag_cu_count.restype = i32
     L.prism_plan.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
     L.prism_plan.restype = i32
     L.prism_plan_table_set.argtypes = [i32, i64, i64, i64, i32, i32, i32, i32]
@@ -153,6 +163,23 @@ def prism_set_workspace(dev_ptr, nbytes):
         raise PrismError(st, "prism_set_workspace")
 
 
+def prism_set_stream_workspace(stream, dev_ptr, nbytes):
+    st = lib.prism_set_stream_workspace(_stream_handle(stream), dev_ptr, int(nbytes))
+    if st != 0:
+        raise PrismError(st, "prism_set_stream_workspace")
+
+
+def prism_diag_set_cu_count(cus=0):
+    """Plan for `cus` compute units (0: the current device's count)."""
+    st = lib.prism_diag_set_cu_count(int(cus))
+    if st != 0:
+        raise PrismError(st, "prism_diag_set_cu_count")
+
+
+def prism_diag_cu_count():
+    return int(lib.prism_diag_cu_count())
+
+
 def prism_plan(op, M, K, N, dtype):
     p = Plan()
     st = lib.prism_plan(int(op), int(M), int(K), int(N), int(dtype), ctypes.byref(p))
@@ -167,8 +194,8 @@ def prism_set_override(path=0, split_k=0, variant=0):
         raise PrismError(st, "prism_set_override")
 
 
-def prism_set_stream_balance(slow_units=0x0808, mode=0):
-    """Without arguments: the library's defaults."""
+def prism_set_stream_balance(slow_units=0, mode=0):
+    """Without arguments: the library's defaults (no unit taken to be slow, no two-pass partition)."""
     st = lib.prism_set_stream_balance(int(slow_units), int(mode))
     if st != 0:
         raise PrismError(st, "prism_set_stream_balance")

@@ -43,15 +43,62 @@ Override g_override;
 //    tiles that contain a slow unit weigh 5 : 4.
 // Gated calls with at most 16 rows use the packed tile (64 output columns: 128-byte stripes of W1 and of W2) with
 // more K-slices for the tiles in slow units when that fits the CUs: 42.1 -> 40.7 us on X[8,4096], 2 x W[4096,14336].
-std::atomic<int32_t> g_slow_units{0x0808}, g_stream_mode{0};
+// No unit is taken to be slow until the caller says so (prism_set_stream_balance; the Python package's tuner
+// measures the sixteen units on the machine at hand): which units are slow is a property of a machine, not of the
+// method.
+std::atomic<int32_t> g_slow_units{0}, g_stream_mode{0};
 
 struct Workspace {
     void* ptr;
     uint64_t bytes;
 };
-Workspace g_workspace[kMaxDevices];  // indexed by HIP device ordinal
+Workspace g_workspace[kMaxDevices];  // indexed by HIP device ordinal: the workspace of calls on any stream
+// Workspaces registered for one stream each (prism_set_stream_workspace): calls on that stream use theirs, so that
+// two streams can run split-K calls at the same time without sharing arrival counters.
+struct StreamWorkspace {
+    int dev;
+    hipStream_t stream;
+    Workspace ws;
+};
+constexpr int kMaxStreamWorkspaces = 32;
+StreamWorkspace g_stream_ws[kMaxStreamWorkspaces];
+int g_stream_ws_count = 0;
+std::mutex g_ws_mutex;
+
+// The workspace a call on `stream` of the current device uses.
+prism_status_t workspace_for(hipStream_t stream, Workspace* out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    for (int i = 0; i < g_stream_ws_count; ++i)
+        if (g_stream_ws[i].dev == dev && g_stream_ws[i].stream == stream) {
+            *out = g_stream_ws[i].ws;
+            return PRISM_OK;
+        }
+    *out = g_workspace[dev];
+    return PRISM_OK;
+}
 
 uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+// Compute units of the device the plans are made for: the current device's count, asked once per process (all
+// devices of a node are alike); 256, an MI355X in its default partition mode, where no device can be asked (the
+// planner also runs on hosts without a GPU).  prism_diag_set_cu_count replaces it for tests.
+constexpr int kDefaultCus = 256;
+std::atomic<int> g_cus{0}, g_cus_forced{0};
+
+int64_t cu_count() {
+    if (const int f = g_cus_forced.load(std::memory_order_relaxed); f > 0) return f;
+    int v = g_cus.load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    int dev = 0, n = 0;
+    v = (hipGetDevice(&dev) == hipSuccess &&
+         hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) ? n : kDefaultCus;
+    (void)hipGetLastError();  // a host without a device: the failed query is not this library's error to report later
+    g_cus.store(v, std::memory_order_relaxed);
+    return v;
+}
 
 // Address of `scratch` on the current device, looked up on the first call there.  That call also clears the arrival
 // counters with a small kernel on the caller's stream (a kernel, not a memset, so that a caller who is recording a
@@ -112,7 +159,7 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
     for (int i = 0; i < nt; ++i) {
         const int cw = gated ? t[i].bn / 2 : t[i].bn;
         const double tiles = (double)((M + t[i].bm - 1) / t[i].bm) * (double)((N + cw - 1) / cw);
-        const double rounds = std::ceil(tiles / 256.0);
+        const double rounds = std::ceil(tiles / (double)cu_count());
         const double cost = rounds * t[i].bm * t[i].bn / t[i].eff;
         if (cost < best) {
             best = cost;
@@ -134,6 +181,7 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
     const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
     const int64_t z32 = (M + 31) / 32, z64 = (M + 63) / 64;
+    const int64_t cus = cu_count();
     // Two weight matrices and at most one K-step of the tiled kernel: nothing to tile, and with so few products
     // per sum the tiled kernel's single rounding of g * w shows in the far tail of the outputs (2.1e-2 to 2.7e-2
     // seen in bf16 against a bar of 2e-2); the decode kernels carry x * g in two parts.
@@ -145,15 +193,15 @@ int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
         // across the wavefronts; beyond the last-level cache's worth of re-reads the prefill kernel wins.
         if (M <= 32) return 2;
         if (K < 2048) return 0;
-        if (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= 256) return 2;
-        return (z64 * w_bytes <= (256ull << 20) && n_tiles * z64 <= 256) ? 4 : 0;
+        if (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= cus) return 2;
+        return (z64 * w_bytes <= (256ull << 20) && n_tiles * z64 <= cus) ? 4 : 0;
     }
     // 33 to 64 rows against a wide, deep W: one 64-row block with more K-slices instead of two 32-row blocks
     // (W[8192,8192] 39.6 -> 37.0 us, W[4096,11008] 36.3 -> 34.2 us; not W[4096,6144], W[2048,8192] or W[4096,8192],
     // where two 32-row blocks take 23.5 us and one 64-row block 25.6 us).
     if (M > 32 && M <= 64 && ((n_tiles >= 80 && K >= 4096) || (n_tiles >= 64 && K >= 8192))) return 4;
-    if (M <= 32 || (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= 256)) return 2;
-    return (M <= 64 || n_tiles * z64 <= 256) ? 4 : 0;
+    if (M <= 32 || (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= cus)) return 2;
+    return (M <= 64 || n_tiles * z64 <= cus) ? 4 : 0;
 }
 
 bool prefill_tile_known(bool gated, int bm, int bn) {
@@ -226,14 +274,14 @@ prism_status_t make_softmax_plan(int64_t M, int64_t K, int64_t N, prism_dtype_t 
     if (S <= 0 && variant == 16) S = 1;
     if (S <= 0) {
         // All workgroups at once (the split kernel fits one per CU) and at least four K-blocks per wavefront.
-        S = std::min<int64_t>(256 / std::max<int64_t>(1, n_tiles * rb32), kblocks / 32);
+        S = std::min<int64_t>(cu_count() / std::max<int64_t>(1, n_tiles * rb32), kblocks / 32);
         S = std::max<int64_t>(1, std::min<int64_t>(S, kSoftmaxMaxSplits));
         if (variant == 0 && rb16 == 1) {
             // At most 16 rows: every workgroup streams its own columns of W, as in the decode kernel, and the
             // same split rule applies (no split for a tile column up to 256 KiB, slices of at least 128 KiB).
             const int64_t column_kib = K * kSoftmaxTileN * 2 / 1024;
             S = column_kib <= 256 ? 1 : std::min<int64_t>(S, std::max<int64_t>(1, column_kib / 128));
-        } else if (variant == 0 && n_tiles * rb16 <= 256) {
+        } else if (variant == 0 && n_tiles * rb16 <= cu_count()) {
             // Both kernels run in one round.  Measured on MI355X: a wavefront's K-block costs about 57 ns of the
             // call with 16 rows per workgroup and 156 ns with 32, and handing partials across slices a few
             // microseconds: the 16-row kernel keeps the call unless the slices shorten the loop by 3 us.
@@ -343,10 +391,11 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             (g_slow_units.load() & 0xFFFF) != 0) {
             const uint32_t units = (uint32_t)g_slow_units.load() & 0xFFFFu;
             const int64_t nt = N / (kDecodeTileN / 2), n_slow = nt / 16 * __builtin_popcount(units);
-            int64_t sb = std::min<int64_t>((256 + nt / 2) / nt, std::min<int64_t>(8, kblocks / 4)), ss = 0;  // the loop below takes it down to what fits
+            const int64_t cus = cu_count();
+            int64_t sb = std::min<int64_t>((cus + nt / 2) / nt, std::min<int64_t>(8, kblocks / 4)), ss = 0;  // the loop below takes it down to what fits
             for (; sb >= 1; --sb) {
                 ss = sb + std::max<int64_t>(1, (2 * sb + 2) / 5);
-                if (nt * sb + n_slow * (ss - sb) <= 256) break;
+                if (nt * sb + n_slow * (ss - sb) <= cus) break;
             }
             const uint64_t G = (uint64_t)(nt * sb + n_slow * (ss - sb)), T = G * (uint64_t)kblocks;
             const uint64_t run_rows = (uint64_t)((kblocks + std::max<int64_t>(sb, 1) - 1) / std::max<int64_t>(sb, 1)) * kDecodeKBlock + 8;
@@ -356,10 +405,10 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             // 11.9 / 13.1, 8 x 4096 x 11264 34.4 / 39.8, 8 x 4096 x 7168 24.7 / 29.5; but 8 x 4096 x 4096 (200
             // workgroups against 256) 18.9 / 17.1 and 4 x 8192 x 8192 (144 against 256) 73 / 49.
             const int64_t n128 = (N + kDecodeTileN - 1) / kDecodeTileN;
-            int64_t s2 = (256 + n128 / 2) / n128;
-            if (n128 * s2 > 256 && n128 <= 256) s2 = 256 / n128;
+            int64_t s2 = (cus + n128 / 2) / n128;
+            if (n128 * s2 > cus && n128 <= cus) s2 = cus / n128;
             s2 = std::max<int64_t>(1, std::min<int64_t>(s2, std::min<int64_t>(8, kblocks / 8)));
-            const int64_t two_tile = std::min<int64_t>(n128 * s2, 256);
+            const int64_t two_tile = std::min<int64_t>(n128 * s2, cus);
             const bool worth = packed || (int64_t)G >= two_tile;
             if (worth && sb >= 1 && nt <= kMaxTickets && ss <= kblocks && ss + 0 <= (int64_t)kStreamMaxSlices && T < (1ull << 31) &&
                 (uint64_t)ss * 2 * M * N * 4 < kTwoGiB && run_rows * (uint64_t)N * 2 < kTwoGiB) {
@@ -378,7 +427,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         if (S <= 0) {
             // About one workgroup per CU (measured best on MI355X: more slices only add partial-sum
             // traffic and tickets), each wavefront keeping at least one K-block.
-            const int64_t target = 256;
+            const int64_t target = cu_count();
             const int64_t wgs = n_tiles * row_blocks;
             // The multi-row kernel fits one workgroup per CU: never more workgroups than CUs if that can be helped.
             // The 16-row kernel: the nearest number of slices, but never a grid that needs a second round for a few
@@ -390,7 +439,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             // round of a few workgroups; three (1.5 to 1.9 rounds of shorter workgroups, dealt out as CUs free up)
             // are faster than both when K is deep enough (W[4096,18432], 144 tiles: 34.9 / 40.2 / 32.0 us with
             // 1 / 2 / 3 slices; W[2048,20352]: 18.0 / 22.4 / 19.6 us).
-            if (row_groups == 1 && S == 1 && wgs > target / 2 && wgs < 160 && kblocks >= 96) S = 3;
+            if (row_groups == 1 && S == 1 && wgs > target / 2 && wgs < target * 5 / 8 && kblocks >= 96) S = 3;
             // Between one and two rounds of workgroups, the second round should not be a nearly empty one.  If
             // one slice per tile fills less than 77 % of the two rounds, take the 2, 3 or 4 slices that fill theirs
             // best (shorter workgroups, a shorter last round): W[4096,33280], 260 tiles, 68.3 us unsplit, 57.7 us
@@ -450,8 +499,8 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         if (balanced.G != 0) {
             sp = balanced;
             s_pitch = balanced_slow;
-        } else if (row_groups == 1 && forced_split <= 0 && (g_stream_mode.load() & 1) != 0 && n_tiles > 128 &&
-                   n_tiles < 160) {
+        } else if (row_groups == 1 && forced_split <= 0 && (g_stream_mode.load() & 1) != 0 && n_tiles > cu_count() / 2 &&
+                   n_tiles < cu_count() * 5 / 8) {
             // slot j (256 bytes) holds units 2j and 2j + 1
             uint32_t slow = 0;
             if (!packed && (g_stream_mode.load() & 2) != 0 && (N * 2) % 2048 == 0 && n_tiles % 8 == 0)
@@ -459,7 +508,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
                     if ((g_slow_units.load() >> (2 * j)) & 3) slow |= 1u << j;
             StreamPartition cand{0u, (uint32_t)kblocks, (uint32_t)n_tiles, slow, 8u, 4u, 5u, 0u, 0u};
             const uint64_t T = sp_total(cand);
-            int64_t G = std::min<int64_t>(256, std::min<int64_t>(n_tiles * kblocks / ((gated && !packed) ? 8 : 4), 8 * n_tiles));
+            int64_t G = std::min<int64_t>(cu_count(), std::min<int64_t>(n_tiles * kblocks / ((gated && !packed) ? 8 : 4), 8 * n_tiles));
             if (G < 1) G = 1;
             if (T < (1ull << 31) && n_tiles < (1 << 24)) {
                 const uint64_t q = T / G;
@@ -557,7 +606,7 @@ prism_status_t make_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, p
         // 13.9 us in 8 slices and 19.4 us in 16; 16384 keys 45.8 us in 8 and 67.7 us in 32.
         // With more batch entries than CUs the workgroups come in rounds anyway, and long contexts still gain from
         // four slices (300 entries, 4096 keys: 137.6 us unsplit, 110.7 us in 4 slices).
-        S = std::min<int64_t>(S, std::max<int64_t>(256 / B, H >= 4096 ? 4 : (H >= 2048 ? 2 : 1)));
+        S = std::min<int64_t>(S, std::max<int64_t>(cu_count() / B, H >= 4096 ? 4 : (H >= 2048 ? 2 : 1)));
     }
     if (S > kAttnMaxSlices) S = kAttnMaxSlices;
     keys = ((H + S - 1) / S + 31) / 32 * 32;
@@ -608,11 +657,8 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                 if (use_static_scratch) {
                     if (plan.pub.workspace_bytes > PRISM_STATIC_SCRATCH_BYTES) return PRISM_ERR_WORKSPACE;
                     if (const prism_status_t s = static_scratch(stream, &w); s != PRISM_OK) return s;
-                } else {
-                    int dev = 0;
-                    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
-                    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
-                    w = g_workspace[dev];
+                } else if (const prism_status_t s = workspace_for(stream, &w); s != PRISM_OK) {
+                    return s;
                 }
                 if (!w.ptr || w.bytes < plan.pub.workspace_bytes) return PRISM_ERR_WORKSPACE;
                 char* base = (char*)w.ptr;
@@ -709,10 +755,8 @@ prism_status_t prism_softmax_matmul(const void* X, const void* W, void* Y, int64
     } else {
         SoftmaxWorkspace ws{nullptr, nullptr, nullptr};
         if (plan.pub.split_k > 1) {
-            int dev = 0;
-            if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
-            if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
-            const Workspace w = g_workspace[dev];
+            Workspace w{nullptr, 0};
+            if (const prism_status_t s = workspace_for(stream, &w); s != PRISM_OK) return s;
             if (!w.ptr || w.bytes < plan.pub.workspace_bytes) return PRISM_ERR_WORKSPACE;
             char* base = (char*)w.ptr;
             ws.tickets = (unsigned*)base;
@@ -739,10 +783,8 @@ prism_status_t prism_gqa_decode_attention(const void* Q, const void* K, const vo
     if (plan.path == PRISM_PATH_ATTENTION) {
         AttentionWorkspace ws{nullptr, nullptr, nullptr, nullptr};
         if (plan.splits > 1) {
-            int dev = 0;
-            if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
-            if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
-            const Workspace w = g_workspace[dev];
+            Workspace w{nullptr, 0};
+            if (const prism_status_t s = workspace_for(stream, &w); s != PRISM_OK) return s;
             if (!w.ptr || w.bytes < plan.workspace_bytes) return PRISM_ERR_WORKSPACE;
             char* base = (char*)w.ptr;
             const uint64_t rows = (uint64_t)B * plan.splits * 16;
@@ -812,13 +854,41 @@ prism_status_t prism_set_workspace(void* dev_ptr, uint64_t bytes) {
     if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
     if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_UNSUPPORTED;
     if (!dev_ptr || bytes == 0) {
+        std::lock_guard<std::mutex> lock(g_ws_mutex);
         g_workspace[dev] = Workspace{nullptr, 0};
         return PRISM_OK;
     }
     if (((uintptr_t)dev_ptr & 255u) != 0 || bytes < PRISM_WORKSPACE_HEADER_BYTES) return PRISM_ERR_INVALID_ARG;
     if (hipMemset(dev_ptr, 0, PRISM_WORKSPACE_HEADER_BYTES) != hipSuccess) return PRISM_ERR_HIP;
     if (hipDeviceSynchronize() != hipSuccess) return PRISM_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
     g_workspace[dev] = Workspace{dev_ptr, bytes};
+    return PRISM_OK;
+}
+
+prism_status_t prism_set_stream_workspace(hipStream_t stream, void* dev_ptr, uint64_t bytes) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_UNSUPPORTED;
+    const bool unregister = !dev_ptr || bytes == 0;
+    if (!unregister) {
+        if (((uintptr_t)dev_ptr & 255u) != 0 || bytes < PRISM_WORKSPACE_HEADER_BYTES) return PRISM_ERR_INVALID_ARG;
+        if (hipMemset(dev_ptr, 0, PRISM_WORKSPACE_HEADER_BYTES) != hipSuccess) return PRISM_ERR_HIP;
+        if (hipDeviceSynchronize() != hipSuccess) return PRISM_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    int slot = -1;
+    for (int i = 0; i < g_stream_ws_count; ++i)
+        if (g_stream_ws[i].dev == dev && g_stream_ws[i].stream == stream) slot = i;
+    if (unregister) {
+        if (slot >= 0) g_stream_ws[slot] = g_stream_ws[--g_stream_ws_count];
+        return PRISM_OK;
+    }
+    if (slot < 0) {
+        if (g_stream_ws_count == kMaxStreamWorkspaces) return PRISM_ERR_UNSUPPORTED;
+        slot = g_stream_ws_count++;
+    }
+    g_stream_ws[slot] = StreamWorkspace{dev, stream, Workspace{dev_ptr, bytes}};
     return PRISM_OK;
 }
 
@@ -905,15 +975,36 @@ prism_status_t prism_probe_stream(const void* W, const void* W2, int64_t K, int6
     if (N % 8 != 0 || split_k > kblocks || split_k > 65535 || n_tiles > 0x7FFFFFFF) return PRISM_ERR_UNSUPPORTED;
     // byte offsets inside a slice fit in 31 bits, as for the decode kernel
     if ((uint64_t)((kblocks + split_k - 1) / split_k * kDecodeKBlock + 8) * (uint64_t)N * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return PRISM_ERR_HIP;
-    if (dev < 0 || dev >= kMaxDevices) return PRISM_ERR_WORKSPACE;
-    const Workspace w = g_workspace[dev];
+    Workspace w{nullptr, 0};
+    if (const prism_status_t s = workspace_for(stream, &w); s != PRISM_OK) return s;
     if (!w.ptr || w.bytes < 2ull * PRISM_WORKSPACE_HEADER_BYTES) return PRISM_ERR_WORKSPACE;
     // the probe's one possible store goes past the arrival counters
     unsigned* sink = (unsigned*)((char*)w.ptr + PRISM_WORKSPACE_HEADER_BYTES);
     return launch_probe_stream(W, W2, sink, (int)K, (int)N, split_k, stream) == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
 }
+
+prism_status_t prism_probe_units(const void* base, uint64_t bytes, int32_t groups, uint64_t* ticks, hipStream_t stream) {
+    if (!base || !ticks || ((uintptr_t)base & 2047u) != 0 || ((uintptr_t)ticks & 7u) != 0 || groups < 1 || groups > 4096)
+        return PRISM_ERR_INVALID_ARG;
+    const uint64_t blocks_per_group = bytes / 2048 / (uint64_t)groups;
+    if (blocks_per_group < 1) return PRISM_ERR_INVALID_ARG;
+    if (blocks_per_group >= (1u << 20)) return PRISM_ERR_UNSUPPORTED;  // 31-bit offsets inside a group
+    return launch_probe_units(base, (unsigned)blocks_per_group, groups, (unsigned long long*)ticks, stream) == hipSuccess
+               ? PRISM_OK : PRISM_ERR_HIP;
+}
+
+prism_status_t prism_probe_mfma(void* sink, int32_t workgroups, int32_t iters, hipStream_t stream) {
+    if (!sink || workgroups < 1 || workgroups > 65535 || iters < 1) return PRISM_ERR_INVALID_ARG;
+    return launch_probe_mfma((float*)sink, workgroups, iters, stream) == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
+}
+
+prism_status_t prism_diag_set_cu_count(int32_t cus) {
+    if (cus < 0 || cus > 65535) return PRISM_ERR_INVALID_ARG;
+    g_cus_forced.store(cus);
+    return PRISM_OK;
+}
+
+int32_t prism_diag_cu_count(void) { return (int32_t)cu_count(); }
 
 const char* prism_status_string(prism_status_t status) {
     switch (status) {
@@ -926,6 +1017,6 @@ const char* prism_status_string(prism_status_t status) {
     }
 }
 
-int32_t prism_version(void) { return 150; }
+int32_t prism_version(void) { return 200; }
 
 }  // extern "C"

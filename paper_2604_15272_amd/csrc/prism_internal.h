@@ -6,6 +6,7 @@
 #include <atomic>
 
 #include "prism.h"
+#include "prism_diag.h"
 
 namespace prism {
 
@@ -124,6 +125,9 @@ hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n)
 hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16);
 hipError_t launch_softmax_split_16bit(const SoftmaxCall& c, bool f16, int split_k, const SoftmaxWorkspace& ws);
 hipError_t launch_probe_stream(const void* W, const void* W2, unsigned* sink, int K, int N, int S, hipStream_t stream);
+hipError_t launch_probe_units(const void* base, unsigned blocks_per_group, int groups, unsigned long long* ticks,
+                              hipStream_t stream);
+hipError_t launch_probe_mfma(float* sink, int workgroups, int iters, hipStream_t stream);
 hipError_t launch_softmax_simple(const SoftmaxCall& c, int dtype);
 hipError_t launch_gqa_16bit(const AttentionCall& c, bool f16, const AttentionPlan& p, const AttentionWorkspace& ws);
 hipError_t launch_gqa_simple(const AttentionCall& c, int dtype);

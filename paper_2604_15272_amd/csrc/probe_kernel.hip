@@ -1,3 +1,4 @@
+// Probes for measurement (declared in prism_diag.h, not part of the operator boundary).
 // Read-only probe: streams one or two [K, N] 16-bit matrices with the decode kernel's access pattern (a workgroup
 // owns 128 columns and one K-slice; a wavefront's load covers 4 rows x 256 contiguous bytes, sixteen
 // 16-byte row loads in flight per lane, non-temporal) and does nothing else.  Its time is what streaming W
@@ -43,6 +44,72 @@ __global__ __launch_bounds__(512) void probe_stream_kernel(const uint16_t* __res
     }
     // Keeps the loads alive; a matrix whose words fold to this value writes one word it may as well write.
     if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u) sink[0] = 1u;
+}
+
+// The sixteen 128-byte address units of every 2 KiB, all read at the same time: workgroup j streams unit j % 16 of
+// the 2 KiB blocks of its group (j / 16) - lanes 8 i .. 8 i + 7 read one 128-byte piece, consecutive pieces are 2 KiB
+// apart, which is what a stripe of a matrix whose row pitch is a multiple of 2 KiB looks like to the memory system -
+// with eight non-temporal 16-byte loads in flight per lane, and reports how long that took on the 100 MHz
+// real-time counter.  Units that stream slowly while the others are busy too show up as longer times.
+__global__ __launch_bounds__(512) void probe_units_kernel(const unsigned char* __restrict__ base, unsigned blocks_per_group,
+                                                          unsigned long long* __restrict__ ticks) {
+    const unsigned j = blockIdx.x, unit = j & 15u, group = j >> 4;
+    const unsigned piece = threadIdx.x >> 3, sub = threadIdx.x & 7u;
+    const __amdgpu_buffer_rsrc_t r =
+        make_rsrc(base + (size_t)group * blocks_per_group * 2048u, blocks_per_group * 2048u);  // below 2 GiB (host)
+    const unsigned long long t0 = wall_clock64();
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (unsigned b = piece; b < blocks_per_group; b += 8u * 64u) {
+        u32x4 v[8];
+#pragma unroll
+        for (unsigned i = 0; i < 8; ++i) {
+            const unsigned bb = b + i * 64u;
+            v[i] = load16_stream(r, bb < blocks_per_group ? bb * 2048u + unit * 128u + sub * 16u : kOutOfRange);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc ^= v[i];
+    }
+    // the value is consumed before the clock is read again: the loads have landed
+    const unsigned fold = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    __syncthreads();
+    if (threadIdx.x == 0) ticks[j] = wall_clock64() - t0 + (fold == 0x9E3779B9u ? 1u : 0u);
+}
+
+hipError_t launch_probe_units(const void* base, unsigned blocks_per_group, int groups, unsigned long long* ticks,
+                              hipStream_t stream) {
+    hipLaunchKernelGGL(probe_units_kernel, dim3(16 * groups), dim3(512), 0, stream, (const unsigned char*)base,
+                       blocks_per_group, ticks);
+    return hipGetLastError();
+}
+
+// Matrix pipes alone: every wavefront (four per workgroup, one per SIMD) issues 16 x iters independent-enough
+// 32x32x16 bf16 MFMAs on registers; no memory, no LDS.  What the part sustains under its power limit.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters) {
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+    const u32 lane = threadIdx.x & 63;
+    const u32x4 a = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+    const u32x4 b = {0x3C003C00u + lane, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = Bf16::mfma_32x32x16(a, b, acc[j]);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t += acc[j][v];
+    if (t == -1.0f) sink[0] = t;  // never true (the sums are positive): keeps the MFMAs alive
+}
+
+hipError_t launch_probe_mfma(float* sink, int workgroups, int iters, hipStream_t stream) {
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(256), 0, stream, sink, iters);
+    return hipGetLastError();
 }
 
 hipError_t launch_probe_stream(const void* W, const void* W2, unsigned* sink, int K, int N, int S, hipStream_t stream) {

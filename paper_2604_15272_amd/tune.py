@@ -25,6 +25,42 @@ _GATED_TILES = (256256, 128256, 128128)
 _TORCH_DTYPE = {B.PRISM_F32: "float32", B.PRISM_BF16: "bfloat16", B.PRISM_F16: "float16"}
 
 
+def detect_slow_units(mbytes=256, repeats=7, threshold=1.18, install=False):
+    """Which of the sixteen 128-byte address units of every 2 KiB stream slowly on this machine.
+
+    ``prism_probe_units`` reads a buffer with one workgroup per (unit, run of 2 KiB blocks), all units at the same
+    time, and reports every workgroup's duration.  Per unit: the median over its workgroups, then the median over
+    ``repeats`` launches (after a warm-up); units that need more than ``threshold`` times the median unit are
+    flagged.  Returns ``{"mask", "us", "median_us"}``; with ``install`` the mask goes to ``prism_set_stream_balance``
+    (the dispatcher then gives the column tiles of gated decode calls that lie in slow units more K-slices)."""
+    import ctypes
+    import statistics
+    import torch
+    nbytes = int(mbytes) << 20
+    groups = max(1, B.prism_diag_cu_count() // 16)
+    buf = torch.empty(nbytes + 2048, dtype=torch.uint8, device="cuda")
+    base = (buf.data_ptr() + 2047) // 2048 * 2048
+    buf.fill_(1)
+    ticks = torch.zeros(16 * groups, dtype=torch.int64, device="cuda")
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    vp = ctypes.c_void_p
+    per_launch = []
+    for it in range(repeats + 1):   # the first launch is a warm-up
+        st = B.lib.prism_probe_units(vp(base), ctypes.c_uint64(nbytes), groups, vp(ticks.data_ptr()), stream)
+        if st != 0:
+            raise B.PrismError(st, "prism_probe_units")
+        torch.cuda.synchronize()
+        t = ticks.cpu().numpy().reshape(groups, 16) * 0.01   # microseconds
+        if it > 0:
+            per_launch.append([statistics.median(t[:, u].tolist()) for u in range(16)])
+    times = [statistics.median([p[u] for p in per_launch]) for u in range(16)]
+    med = statistics.median(times)
+    mask = sum(1 << u for u, t in enumerate(times) if t > threshold * med)
+    if install:
+        B.prism_set_stream_balance(mask, 0)
+    return {"mask": mask, "us": times, "median_us": med}
+
+
 def candidates(op, M, K, N, dtype, max_split=64):
     """Every admissible (path, split_k, variant) for this call, as the library's planner sees it."""
     out = []

@@ -18,8 +18,12 @@ def P():
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     import paper_2604_15272_amd as P
+    # Units 3 and 11 are named slow for this module, as on the machines the kernels were measured on: the packed,
+    # balanced launch of gated decode calls is then what the dispatcher takes (the library's own default names none).
+    P.prism_set_stream_balance(0x0808, 0)
     yield P
     P.prism_set_override(0, 0, 0)
+    P.prism_set_stream_balance(0, 0)
 
 
 def _case(P, dtype, M, K, N, gated, seed, eps=1e-6, path=0, split=0, variant=0, expect_path=None):
@@ -111,7 +115,7 @@ def test_decode_weighted_partition(P, M, K, N, gated, mode):
             assert (plan["path"], plan["grid_x"], plan["grid_y"]) == (P.PRISM_PATH_DECODE, 256, 1), plan
         _case(P, pi.BF16, M, K, N, gated, seed=450 + N % 97, expect_path=P.PRISM_PATH_DECODE)
     finally:
-        P.prism_set_stream_balance()
+        P.prism_set_stream_balance(0x0808, 0)
 
 
 def test_decode_weighted_partition_f16_and_grid_agree(P):
@@ -122,12 +126,12 @@ def test_decode_weighted_partition_f16_and_grid_agree(P):
         assert P.prism_plan(0, 16, 2048, 18432, P.PRISM_F16)["grid_x"] == 256
         e1 = _case(P, pi.F16, 16, 2048, 18432, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
     finally:
-        P.prism_set_stream_balance()
+        P.prism_set_stream_balance(0x0808, 0)
     try:
         assert P.prism_plan(0, 16, 2048, 18432, P.PRISM_F16)["grid_x"] == 144
         e0 = _case(P, pi.F16, 16, 2048, 18432, False, seed=461, expect_path=P.PRISM_PATH_DECODE)
     finally:
-        P.prism_set_stream_balance()
+        P.prism_set_stream_balance(0x0808, 0)
     assert abs(e1 - e0) < 2.5e-3
 
 
@@ -158,7 +162,7 @@ def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
                 assert torch.equal(o.view(torch.uint16), outs[0].view(torch.uint16))
             assert_parity(from_device(outs[0], pi.BF16), yhat, pi.BF16, f"partition, W at {W.data_ptr() % 256} mod 256")
     finally:
-        P.prism_set_stream_balance()
+        P.prism_set_stream_balance(0x0808, 0)
 
 
 # ---- gated decode, packed tile (64 output columns: W1 and W2 in one matrix-core tile), balanced over slow units ---
@@ -205,7 +209,7 @@ def test_decode_packed_in_the_weighted_partition(P):
         _case(P, pi.BF16, 8, 2048, 9344, True, seed=485, path=P.PRISM_PATH_DECODE, variant=108)
     finally:
         P.prism_set_override(0, 0, 0)
-        P.prism_set_stream_balance()
+        P.prism_set_stream_balance(0x0808, 0)
 
 
 def test_decode_packed_off_its_units_and_reproducible(P):
@@ -829,6 +833,78 @@ def test_calls_can_be_captured_in_a_hip_graph_and_replayed(P):
         torch.cuda.synchronize()
         for o, r in zip(outs, ref):
             assert torch.equal(o.view(torch.uint16), r.view(torch.uint16)), f"eager after replay {rep}"
+
+
+# ---- workspaces per stream, machine measurements ---------------------------------------------------------------------
+
+def test_two_streams_with_workspaces_of_their_own_run_split_k_calls_at_the_same_time(P):
+    """Each stream's calls find the workspace registered for that stream (own arrival counters, own partial sums), so
+    the two sequences may overlap in time; every output matches the single-stream result bit for bit."""
+    import torch
+    from gpu_util import to_device
+    M, K, N = 16, 4096, 4096
+    need = P.prism_workspace_bytes(0, M, K, N, P.PRISM_BF16)
+    assert need > 0
+    stored = [pi.draw(pi.BF16, M, K, N, False, 8200 + i) for i in range(2)]
+    dev = [[to_device(st[k], pi.BF16) for k in ("X", "g", "W")] for st in stored]
+    ref = []
+    for X, g, W in dev:
+        Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        P.prism_rmsnorm_matmul(X, g, W, Y)
+        ref.append(Y)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bufs = [torch.empty(need + 4096, dtype=torch.uint8, device="cuda") for _ in streams]
+    for s, b in zip(streams, bufs):
+        P.prism_set_stream_workspace(s, (b.data_ptr() + 255) // 256 * 256, need)
+    try:
+        outs = [[], []]
+        for rep in range(40):
+            for i, s in enumerate(streams):
+                X, g, W = dev[i]
+                Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+                P.prism_rmsnorm_matmul(X, g, W, Y, stream=s)
+                outs[i].append(Y)
+        torch.cuda.synchronize()
+        for i in range(2):
+            for Y in outs[i]:
+                assert torch.equal(Y.view(torch.uint16), ref[i].view(torch.uint16))
+    finally:
+        for s in streams:
+            P.prism_set_stream_workspace(s, None, 0)
+    # unregistered: the streams fall back to the device's workspace
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    P.prism_rmsnorm_matmul(*dev[0], Y, stream=streams[0])
+    torch.cuda.synchronize()
+    assert torch.equal(Y.view(torch.uint16), ref[0].view(torch.uint16))
+
+
+def test_slow_unit_detection_and_probes_run(P):
+    """The tuner's measurement of the sixteen address units and the matrix-pipe probe run and return sane figures
+    (which units are slow differs between machines: the mask is printed, not asserted)."""
+    import ctypes
+    import torch
+    from paper_2604_15272_amd import tune
+    r = tune.detect_slow_units(repeats=3)
+    print("units, us per workgroup:", [round(t, 1) for t in r["us"]], "mask", hex(r["mask"]), flush=True)
+    assert 0 <= r["mask"] <= 0xFFFF and len(r["us"]) == 16 and all(2.0 < t < 2000.0 for t in r["us"])
+    assert bin(r["mask"]).count("1") <= 8
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+    vp = ctypes.c_void_p
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    wgs, iters = 2 * P.prism_diag_cu_count(), 2000
+    assert P.lib.prism_probe_mfma(vp(sink.data_ptr()), wgs, 10, stream) == 0
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    assert P.lib.prism_probe_mfma(vp(sink.data_ptr()), wgs, iters, stream) == 0
+    e1.record()
+    torch.cuda.synchronize()
+    tf = 32768.0 * 16 * iters * 4 * wgs / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    print(f"matrix pipes alone: {tf:.0f} TFLOP/s", flush=True)
+    assert 500.0 < tf < 2600.0 and float(sink[0]) == 0.0
+    assert P.lib.prism_probe_units(None, 1 << 20, 1, vp(sink.data_ptr()), stream) == 1
+    assert P.lib.prism_probe_units(vp(2048), 1 << 20, 0, vp(sink.data_ptr()), stream) == 1
 
 
 # ---- parameter instantiation by sampling and timing (paper Section 5) -------------------------------

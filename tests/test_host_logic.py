@@ -23,14 +23,22 @@ def P(repo_root):
 
 
 def test_every_declared_symbol_is_exported(P, repo_root):
-    text = open(os.path.join(repo_root, "include", "prism.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(prism_[a-z0-9_]+)\s*\(", text))
-    assert {"prism_rmsnorm_matmul", "prism_rmsnorm_gated_mlp", "prism_set_workspace", "prism_plan"} <= names
+    import glob
+    names, per_header = set(), {}
+    for h in sorted(glob.glob(os.path.join(repo_root, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(h).read(), flags=re.S)
+        per_header[os.path.basename(h)] = set(re.findall(r"\b(prism_[a-z0-9_]+)\s*\(", text))
+        names |= per_header[os.path.basename(h)]
+    assert {"prism_rmsnorm_matmul", "prism_rmsnorm_gated_mlp", "prism_set_workspace", "prism_plan",
+            "prism_rmsnorm_matmul_static"} <= per_header["prism.h"]
+    # probes and test hooks live in the diagnostics header, not in the operator boundary
+    assert {"prism_probe_stream", "prism_probe_units", "prism_probe_mfma", "prism_stream_partition_blocks",
+            "prism_diag_set_cu_count"} <= per_header["prism_diag.h"]
+    assert not any(n.startswith(("prism_probe", "prism_diag")) for n in per_header["prism.h"])
     L = ctypes.CDLL(P.library_path())
     for n in sorted(names):
-        assert hasattr(L, n), f"{n} is declared in prism.h but not exported"
-    assert P.prism_version() >= 100
+        assert hasattr(L, n), f"{n} is declared in a header but not exported"
+    assert P.prism_version() >= 200
 
 
 def test_status_strings(P):
@@ -412,6 +420,16 @@ def test_gated_decode_plan_packs_and_balances(P):
     """Gated calls with at most 16 rows: tiles of 64 output columns with more K-slices for the tiles in slow units,
     when that puts at least as many workgroups to work as the two-tile form would."""
     bf16 = P.PRISM_BF16
+    # no unit is slow until the caller says so: two tiles per workgroup, equal slices
+    assert (lambda d: (d["tile_n"], d["grid_x"], d["grid_y"]))(P.prism_plan(1, 8, 4096, 14336, bf16)) == (128, 112, 2)
+    P.prism_set_stream_balance(0x0808, 0)                 # units 3 and 11, as measured on the MI355X at hand
+    try:
+        _gated_decode_plan_with_slow_units(P, bf16)
+    finally:
+        P.prism_set_stream_balance()
+
+
+def _gated_decode_plan_with_slow_units(P, bf16):
     p = P.prism_plan(1, 8, 4096, 14336, bf16)             # the gated decode configuration: 224 tiles, 28 of them slow
     assert (p["path"], p["tile_n"], p["grid_x"], p["grid_y"], p["split_k"]) == (P.PRISM_PATH_DECODE, 64, 224 + 28, 1, 2)
     ss = -(-(224 * 2 * 16 * 4) // 256) * 256
@@ -430,7 +448,7 @@ def test_gated_decode_plan_packs_and_balances(P):
     try:
         assert (lambda d: (d["tile_n"], d["grid_x"], d["grid_y"]))(P.prism_plan(1, 8, 4096, 14336, bf16)) == (128, 112, 2)
     finally:
-        P.prism_set_stream_balance()
+        P.prism_set_stream_balance(0x0808, 0)
     for variant, split, expect in ((0, 2, (128, 112, 2, 512)), (108, 3, (64, 224, 3, 512)), (104, 1, (64, 224, 1, 256)),
                                    (108, 0, (64, 252, 1, 512))):
         P.prism_set_override(P.PRISM_PATH_DECODE, split, variant)
@@ -446,6 +464,32 @@ def test_gated_decode_plan_packs_and_balances(P):
                 P.prism_plan(0 if variant == 104 else 1, 8, 4096, 14336, bf16)    # not gated; 16 wavefronts; no such count
         finally:
             P.prism_set_override(0, 0, 0)
+
+
+def test_plans_follow_the_number_of_compute_units(P):
+    """Grids are sized by the device's compute units (256 where there is no device to ask); the test hook plans for
+    other counts: a part with 128 units gets half the K-slices, one with 304 more."""
+    bf16 = P.PRISM_BF16
+    base = P.prism_diag_cu_count()
+    assert base >= 1
+    try:
+        P.prism_diag_set_cu_count(256)
+        assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 4096, bf16)) == (32, 8)
+        assert P.prism_plan(0, 256, 4096, 4096, bf16)["path"] == P.PRISM_PATH_DECODE      # 32 tiles x 8 row blocks fit
+        P.prism_diag_set_cu_count(128)
+        assert P.prism_diag_cu_count() == 128
+        assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 4096, bf16)) == (32, 4)
+        assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 7168, bf16)) == (56, 2)
+        assert P.prism_plan(0, 512, 4096, 4096, bf16)["path"] == P.PRISM_PATH_PREFILL     # 32 x 8 row blocks do not fit
+        P.prism_diag_set_cu_count(304)
+        assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 8192, 4096, bf16)) == (32, 8)   # never more than 8
+        assert (lambda d: (d["grid_x"], d["grid_y"]))(P.prism_plan(0, 16, 4096, 11008, bf16)) == (86, 3)  # 258 fit 304
+        for bad in (-1, 70000):
+            with pytest.raises(P.PrismError):
+                P.prism_diag_set_cu_count(bad)
+    finally:
+        P.prism_diag_set_cu_count(0)
+    assert P.prism_diag_cu_count() == base
 
 
 def test_shapes_past_the_32_bit_offsets_take_the_plain_kernel(P):
@@ -513,7 +557,11 @@ def test_tuner_enumerates_admissible_assignments(P):
     gmid = [x for x in tune.candidates(1, 100, 2048, 1024, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
     assert {x["plan"]["tile_m"] for x in gmid} == {32, 64}
     # gated, at most 16 rows: the packed tile too, also with the library's own (balanced) slices
-    gd = [x for x in tune.candidates(1, 8, 4096, 14336, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
+    P.prism_set_stream_balance(0x0808, 0)
+    try:
+        gd = [x for x in tune.candidates(1, 8, 4096, 14336, P.PRISM_BF16, max_split=4) if x["path"] == P.PRISM_PATH_DECODE]
+    finally:
+        P.prism_set_stream_balance()
     assert {x["plan"]["tile_n"] for x in gd} == {64, 128}
     assert any(x["variant"] == 108 and x["split_k"] == 0 and x["plan"]["grid_x"] == 252 for x in gd)
     assert all(x["plan"]["tile_n"] == 128 for x in dec)
