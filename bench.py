@@ -472,6 +472,66 @@ def measure_mfma_ceiling(iters=4000):
             "note": "prism_probe_mfma: matrix pipes alone (a launch of about 1 ms; longer runs clock lower)"}
 
 
+def measure_stream_patterns(runner, steps=400, warmup=20):
+    """The headline workload's weight bytes (32 MiB per buffer set, the same rotating sets) read with other access
+    patterns, nothing computed: front to back in 256 contiguous pieces, and as stripes of other shapes (the stream
+    probe on the same bytes viewed as [K', N'] with K' N' = K N).  What a launch of this size can stream at all."""
+    import torch
+    P = runner.P
+    vp, i64 = ctypes.c_void_p, ctypes.c_int64
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    P.ensure_workspace(1 << 20)
+    wl = runner.wl
+    nbytes = 2 * wl.K * wl.N
+    cus = P.prism_diag_cu_count()
+    ptrs = [w[0].data_ptr() for w in runner.W]
+
+    def timed(call):
+        for i in range(warmup):
+            call(ptrs[i % len(ptrs)])
+        res = []
+        for _ in range(REGIONS):
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(steps):
+                call(ptrs[(warmup + i) % len(ptrs)])
+            e1.record()
+            torch.cuda.synchronize()
+            res.append(e0.elapsed_time(e1) / steps * 1e3)
+        return median(res), min(res)
+
+    out = []
+
+    def linear(wgs):
+        def call(p):
+            if P.lib.prism_probe_linear(vp(p), ctypes.c_uint64(nbytes), wgs, vp(sink.data_ptr()), stream) != 0:
+                raise RuntimeError("prism_probe_linear failed")
+        return call
+
+    def stripes(K2, N2, S):
+        def call(p):
+            if P.lib.prism_probe_stream(vp(p), None, i64(K2), i64(N2), ctypes.c_int32(S), stream) != 0:
+                raise RuntimeError("prism_probe_stream failed")
+        return call
+
+    total = wl.K * wl.N
+    patterns = [("front to back, one contiguous piece per compute unit", linear(cus)),
+                ("front to back, two pieces per compute unit", linear(2 * cus)),
+                (f"128-column stripes of [{wl.K},{wl.N}] x {max(1, cus * 128 // wl.N)} K-slices (the kernel's)",
+                 stripes(wl.K, wl.N, max(1, cus * 128 // wl.N)))]
+    for n2 in (wl.N * 2, wl.N // 2, wl.N // 4):
+        k2 = total // n2
+        s2 = max(1, cus * 128 // n2)
+        patterns.append((f"128-column stripes of the same bytes as [{k2},{n2}] x {s2} K-slices", stripes(k2, n2, s2)))
+    for name, call in patterns:
+        med, best = timed(call)
+        out.append({"pattern": name, "us_per_launch": med, "us_per_launch_min": best, "GBps": nbytes / (med * 1e-6) / 1e9})
+        log(f"[bench]   {nbytes >> 20} MiB read, {name}: {med:.2f} us per launch ({nbytes / (med * 1e-6) / 1e9:.0f} GB/s)")
+    return out
+
+
 def measure_vendor_gemm(M, K, N, two, steps, warmup):
     """The plain product(s) of a prefill configuration on the vendor GEMM library (torch.matmul, bf16, W stored
     [K, N] as here), without norm, gain or gate: context for the fused kernel's figure, same flop count."""
@@ -647,6 +707,7 @@ def main():
         f"{' '.join('%.1f' % t for t in det['us'])})")
     head, runner = measure(a.workload, a.steps, a.warmup)
     traffic = measured_traffic(head["workload"])
+    stream_patterns = measure_stream_patterns(runner) if head["bound"] == "hbm" else None
     copy_ceiling, mfma_ceiling = measure_copy_ceiling(), measure_mfma_ceiling()
     log(f"[bench] measured ceilings: device copy {copy_ceiling['GBps']:.0f} GB/s (read + written), matrix pipes alone "
         f"{mfma_ceiling['TFLOPs']:.0f} TFLOP/s")
@@ -676,7 +737,7 @@ def main():
                      "kernel_ms_per_launch_min": head["event_ms_per_step_min"],
                      "timing": "HIP events around each timed region on the launch stream, divided by the region's "
                                "launches (an average per launch, launch gaps included); median of the regions",
-                     "copy_ceiling": copy_ceiling, "mfma_ceiling": mfma_ceiling},
+                     "copy_ceiling": copy_ceiling, "mfma_ceiling": mfma_ceiling, "stream_patterns": stream_patterns},
         "slow_units": {"mask": det["mask"], "us_per_unit": det["us"], "median_us": det["median_us"],
                        "note": "tune.detect_slow_units: prism_probe_units, all sixteen units read at once, median workgroup time per unit"},
     }

@@ -45,6 +45,14 @@ prism_status_t prism_probe_stream(const void* W, const void* W2, int64_t K, int6
 prism_status_t prism_probe_units(const void* base, uint64_t bytes, int32_t groups, uint64_t* ticks, hipStream_t stream);
 
 /*
+ * For measurement: reads [base, base + bytes) (device memory, 16-byte aligned, bytes a multiple of 16) once, front to
+ * back: workgroup j of `workgroups` streams the j-th contiguous piece and computes nothing.  The same bytes as a
+ * weight matrix without any stripe structure: a second opinion on what streaming them costs.  sink: 4 bytes of
+ * device memory (one word may be written).
+ */
+prism_status_t prism_probe_linear(const void* base, uint64_t bytes, int32_t workgroups, void* sink, hipStream_t stream);
+
+/*
  * For measurement: `workgroups` workgroups of four wavefronts issue 16 * iters 32x32x16 bf16 MFMAs each on
  * registers, with no memory or LDS traffic: 32768 * 16 * iters * 4 * workgroups flops.  What the matrix pipes
  * sustain on the machine at hand (clock and power limit included): the measured ceiling beside the published peak.

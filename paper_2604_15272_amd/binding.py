@@ -80,6 +80,8 @@ def _load():
     L.prism_set_stream_workspace.restype = i32
     L.prism_probe_units.argtypes = [vp, u64, i32, vp, vp]
     L.prism_probe_units.restype = i32
+    L.prism_probe_linear.argtypes = [vp, u64, i32, vp, vp]
+    L.prism_probe_linear.restype = i32
     L.prism_probe_mfma.argtypes = [vp, i32, i32, vp]
     L.prism_probe_mfma.restype = i32
     L.prism_diag_set_cu_count.argtypes = [i32]

@@ -993,6 +993,14 @@ prism_status_t prism_probe_units(const void* base, uint64_t bytes, int32_t group
                ? PRISM_OK : PRISM_ERR_HIP;
 }
 
+prism_status_t prism_probe_linear(const void* base, uint64_t bytes, int32_t workgroups, void* sink, hipStream_t stream) {
+    if (!base || !sink || !aligned16(base) || workgroups < 1 || workgroups > 65535 || bytes < 1024ull * (uint64_t)workgroups ||
+        bytes % 16 != 0)
+        return PRISM_ERR_INVALID_ARG;
+    if (bytes / (uint64_t)workgroups + 1024 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;  // 31-bit offsets inside a piece
+    return launch_probe_linear(base, bytes, workgroups, (unsigned*)sink, stream) == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;
+}
+
 prism_status_t prism_probe_mfma(void* sink, int32_t workgroups, int32_t iters, hipStream_t stream) {
     if (!sink || workgroups < 1 || workgroups > 65535 || iters < 1) return PRISM_ERR_INVALID_ARG;
     return launch_probe_mfma((float*)sink, workgroups, iters, stream) == hipSuccess ? PRISM_OK : PRISM_ERR_HIP;

@@ -82,6 +82,35 @@ hipError_t launch_probe_units(const void* base, unsigned blocks_per_group, int g
     return hipGetLastError();
 }
 
+// A buffer read front to back: workgroup j streams the j-th of gridDim.x equal contiguous pieces (every wavefront
+// instruction covers 1 KiB of consecutive bytes, sixteen 16-byte loads in flight per lane, non-temporal).  The
+// simplest access pattern there is: what the same bytes cost when no stripe structure is imposed on them.
+__global__ __launch_bounds__(512) void probe_linear_kernel(const unsigned char* __restrict__ base, unsigned long long bytes,
+                                                           unsigned* __restrict__ sink) {
+    const unsigned long long per = (bytes / gridDim.x) & ~1023ull;
+    const unsigned long long first = per * blockIdx.x;
+    const unsigned long long len = blockIdx.x + 1 == gridDim.x ? bytes - first : per;
+    const __amdgpu_buffer_rsrc_t r = make_rsrc(base + first, (u32)(len < 0x7FFFFFFFull ? len : 0x7FFFFFFFull));
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    constexpr unsigned kStep = 512 * 16;  // bytes the workgroup covers with one load per thread
+    for (unsigned long long off = 0; off < len; off += 16ull * kStep) {
+        u32x4 v[16];
+#pragma unroll
+        for (unsigned i = 0; i < 16; ++i) {
+            const unsigned long long o = off + (unsigned long long)i * kStep + threadIdx.x * 16u;
+            v[i] = load16_stream(r, o < len ? (u32)o : kOutOfRange);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc ^= v[i];
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x9E3779B9u) sink[0] = 1u;
+}
+
+hipError_t launch_probe_linear(const void* base, unsigned long long bytes, int workgroups, unsigned* sink, hipStream_t stream) {
+    hipLaunchKernelGGL(probe_linear_kernel, dim3(workgroups), dim3(512), 0, stream, (const unsigned char*)base, bytes, sink);
+    return hipGetLastError();
+}
+
 // Matrix pipes alone: every wavefront (four per workgroup, one per SIMD) issues 16 x iters independent-enough
 // 32x32x16 bf16 MFMAs on registers; no memory, no LDS.  What the part sustains under its power limit.
 __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ sink, int iters) {

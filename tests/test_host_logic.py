@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(P, repo_root):
     assert {"prism_rmsnorm_matmul", "prism_rmsnorm_gated_mlp", "prism_set_workspace", "prism_plan",
             "prism_rmsnorm_matmul_static"} <= per_header["prism.h"]
     # probes and test hooks live in the diagnostics header, not in the operator boundary
-    assert {"prism_probe_stream", "prism_probe_units", "prism_probe_mfma", "prism_stream_partition_blocks",
+    assert {"prism_probe_stream", "prism_probe_units", "prism_probe_mfma", "prism_probe_linear", "prism_stream_partition_blocks",
             "prism_diag_set_cu_count"} <= per_header["prism_diag.h"]
     assert not any(n.startswith(("prism_probe", "prism_diag")) for n in per_header["prism.h"])
     L = ctypes.CDLL(P.library_path())
