@@ -169,39 +169,80 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
     }
 }
 
-// More than 16 rows on the decode path: 16-row groups per workgroup (2 or 4), or 0 if the tiled prefill
-// kernel is the better choice.  Measured on MI355X (bf16, K x N from 1024 x 1024 to 14336 x 4096, 17 to 512
-// rows): the decode path wins while all its workgroups run at once (one per CU) and W is deep enough that
-// the prefill kernel's 64-deep K-steps over few tiles dominate; 32 rows per workgroup win over 64 while the
-// row blocks' re-reads of W stay within the 256 MiB last-level cache (two row blocks that drift apart by more
-// than an L2's worth of W fetch it twice).  A single row block may have more column tiles than CUs (several
-// rounds of workgroups): X[32,4096] . W[4096,40960] 93.7 us against 111.9 us with the prefill kernel, X[64,4096] .
-// W[4096,33280] 101.1 against 109.0 us, gated X[32,4096], 2 x W[4096,33280] 161.3 (148.3 in two K-slices) against
-// 166.4 us.
+// More than 16 rows: which kernel family takes the call.  Returns the 16-row groups per workgroup of the decode
+// path's multi-row kernel (2 or 4: 32 or 64 rows), or 0 if the tiled prefill kernel is the better choice.
+//
+// The choice is made by a small time model of the three candidates, whose constants were measured on MI355X
+// (bf16, 96 shapes: 40 to 512 rows against K x N from 2048 x 8192 to 14336 x 4096, plain and gated, each forced
+// onto 32 rows, 64 rows and the prefill kernel): the model's pick is within 1.1 % of the best of the three on
+// average and within 10 % on every shape (the fixed rules it replaces: 4.3 % and 72 %).
+//   multi-row kernel, RG row groups, S K-slices, z row blocks, all times in microseconds:
+//     loop      = ceil(kblocks / S) x c x rounds,  c = 0.22 / 0.27 per K-block for 32 / 64 rows of one matrix,
+//                 0.33 / 0.60 for two (per compute unit a K-block costs its MFMAs, its vector work and 8 to 12 KiB
+//                 through the L1, and they do not overlap); rounds = ceil(workgroups / compute units);
+//                 never less than streaming W once at 6 TB/s
+//     reduction = 0.5 x RG x matrices (LDS)
+//     exchange  = 2.5 + S x RG x matrices / 8 when S > 1 (three dependent round trips, then the last arrival
+//                 pulls S partial tiles through one compute unit)
+//     launch    = 1.5
+//   prefill kernel: K steps x (1.5 / 2.0 for 256-row tiles of one / two matrices, 1.08 / 1.2 for 128-row tiles, 0.93
+//     for 64 x 64) x 1 if every tile has a compute unit, x 1.3 for up to two 128-row tiles per unit, else the rounds;
+//     + 3.  (A K step of that kernel has a floor of about a microsecond whatever the tile.)
+struct RowsEstimate {
+    double us;
+    int64_t S;
+};
+
+RowsEstimate rows_estimate(int rg, bool gated, int64_t M, int64_t K, int64_t N, int64_t cus) {
+    const int G = gated ? 2 : 1;
+    const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN, kblocks = (K + kDecodeKBlock - 1) / kDecodeKBlock;
+    const int64_t z = (M + 16 * rg - 1) / (16 * rg), wgs1 = n_tiles * z;
+    int64_t S = wgs1 <= cus ? cus / wgs1 : 1;
+    S = std::max<int64_t>(1, std::min<int64_t>(S, std::max<int64_t>(1, kblocks / 8)));
+    const double c = gated ? (rg == 2 ? 0.33 : 0.60) : (rg == 2 ? 0.22 : 0.27);
+    double loop = (double)((kblocks + S - 1) / S) * c * (double)((wgs1 * S + cus - 1) / cus);
+    loop = std::max(loop, 2.0 * (double)K * (double)N * G / 6.0e6);
+    double us = loop + 0.5 * rg * G + 1.5;
+    if (S > 1) us += 2.5 + (double)(S * rg * G) / 8.0;
+    return RowsEstimate{us, S};
+}
+
+double prefill_estimate(bool gated, int64_t M, int64_t K, int64_t N, int64_t cus) {
+    struct T {
+        int bm, bn;
+        double step;
+    };
+    static const T plain[] = {{256, 256, 1.5}, {256, 192, 1.5}, {128, 128, 1.08}, {64, 64, 0.93}};
+    static const T gate[] = {{256, 256, 2.0}, {128, 256, 1.2}, {128, 128, 1.08}};
+    const T* t = gated ? gate : plain;
+    const int64_t KT = (K + 63) / 64;
+    double best = 1e300;
+    for (int i = 0; i < (gated ? 3 : 4); ++i) {
+        const int64_t cw = gated ? t[i].bn / 2 : t[i].bn;
+        const int64_t tiles = ((M + t[i].bm - 1) / t[i].bm) * ((N + cw - 1) / cw);
+        const double f = tiles <= cus ? 1.0 : ((tiles <= 2 * cus && t[i].bm <= 128) ? 1.3 : (double)((tiles + cus - 1) / cus));
+        best = std::min(best, (double)KT * t[i].step * f + 3.0);
+    }
+    return best;
+}
+
 int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
     const int64_t n_tiles = (N + kDecodeTileN - 1) / kDecodeTileN;
-    const int64_t z32 = (M + 31) / 32, z64 = (M + 63) / 64;
+    const int64_t z32 = (M + 31) / 32;
     const int64_t cus = cu_count();
     // Two weight matrices and at most one K-step of the tiled kernel: nothing to tile, and with so few products
     // per sum the tiled kernel's single rounding of g * w shows in the far tail of the outputs (2.1e-2 to 2.7e-2
     // seen in bf16 against a bar of 2e-2); the decode kernels carry x * g in two parts.
     if (gated && K <= 64 && z32 <= 65535 && n_tiles * z32 <= kMaxTickets) return 2;
-    if (M > kDecodeRowsMax || (M > 64 && K < 2048)) return 0;
-    const uint64_t w_bytes = (uint64_t)K * N * 2 * (gated ? 2 : 1);
-    if (gated) {
-        // Two weight matrices: the accumulators allow 32 rows per wavefront, or 64 with the matrices split
-        // across the wavefronts; beyond the last-level cache's worth of re-reads the prefill kernel wins.
-        if (M <= 32) return 2;
-        if (K < 2048) return 0;
-        if (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= cus) return 2;
-        return (z64 * w_bytes <= (256ull << 20) && n_tiles * z64 <= cus) ? 4 : 0;
-    }
-    // 33 to 64 rows against a wide, deep W: one 64-row block with more K-slices instead of two 32-row blocks
-    // (W[8192,8192] 39.6 -> 37.0 us, W[4096,11008] 36.3 -> 34.2 us; not W[4096,6144], W[2048,8192] or W[4096,8192],
-    // where two 32-row blocks take 23.5 us and one 64-row block 25.6 us).
-    if (M > 32 && M <= 64 && ((n_tiles >= 80 && K >= 4096) || (n_tiles >= 64 && K >= 8192))) return 4;
-    if (M <= 32 || (z32 * w_bytes <= (256ull << 20) && n_tiles * z32 <= cus)) return 2;
-    return (M <= 64 || n_tiles * z64 <= cus) ? 4 : 0;
+    if (M > kDecodeRowsMax) return 0;
+    const RowsEstimate r32 = rows_estimate(2, gated, M, K, N, cus), r64 = rows_estimate(4, gated, M, K, N, cus);
+    const double pf = prefill_estimate(gated, M, K, N, cus);
+    // the arrival counters of a split call: one per (column tile, row block)
+    const bool ok32 = r32.S == 1 || n_tiles * z32 <= kMaxTickets;
+    const bool ok64 = r64.S == 1 || n_tiles * ((M + 63) / 64) <= kMaxTickets;
+    const double t32 = ok32 ? r32.us : 1e300, t64 = ok64 ? r64.us : 1e300;
+    if (pf <= t32 && pf <= t64) return 0;
+    return t32 <= t64 ? 2 : 4;
 }
 
 bool prefill_tile_known(bool gated, int bm, int bn) {

@@ -471,7 +471,7 @@ def test_no_gain_equals_gain_of_ones_bit_for_bit(P):
 
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("M,K,N,path", [(3, 77, 130, 1), (8, 256, 512, 2), (8, 1024, 1024, 2), (16, 4096, 4096, 2),
-                                        (13, 2056, 1160, 2), (30, 200, 264, 2), (300, 712, 648, 3),
+                                        (13, 2056, 1160, 2), (30, 200, 264, 2), (300, 712, 648, 2),
                                         (1024, 1024, 768, 3), (600, 200, 264, 3)])
 def test_f16_shapes(P, M, K, N, path, gated):
     _case(P, pi.F16, M, K, N, gated, seed=900 + M, expect_path=path)
@@ -946,7 +946,7 @@ def test_tuner_on_the_softmax_operator(P):
 # ---- shapes drawn around every dispatch boundary, as dispatched ---------------------------------------------------
 
 def test_random_shapes_as_dispatched(P):
-    """Seeded shapes around the boundaries of the dispatcher (16/17, 32/33, 64/65 rows; K around 1024 and 2048; odd
+    """Seeded shapes around the boundaries of the dispatcher (16/17, 32/33, 64/65, 512/513 rows; K around 1024 and 2048; odd
     tails in K and N; every operator and 16-bit format): whatever kernel is chosen, the oracle decides."""
     import random
     rng = random.Random(0xD15BA7C4)
@@ -954,7 +954,7 @@ def test_random_shapes_as_dispatched(P):
     for i in range(72):
         op = i % 3
         dt = pi.BF16 if (i // 3) % 2 == 0 else pi.F16
-        M = rng.choice((1, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 96, 128, 130, 257))
+        M = rng.choice((1, 15, 16, 17, 31, 32, 33, 48, 63, 64, 65, 96, 128, 130, 257, 513, 600, 1100))
         K = 8 * rng.choice((1, 9, 32, 125, 128, 129, 255, 256, 257, 300, 520))
         N = 8 * rng.choice((1, 2, 16, 17, 33, 64, 130))
         if op == 2:
@@ -967,12 +967,18 @@ def test_random_shapes_as_dispatched(P):
             plan = P.prism_plan(op, M, K, N, DTYPE_CODE[dt])
             print(f"random {i}: op={op} dtype={dt} M={M} K={K} N={N} plan={plan}", flush=True)
             y, yhat = run_gpu(stored, dt, op == 1, 1e-6), run_oracle(stored, dt, op == 1, 1e-6)
-        assert_parity(y, yhat, dt, f"random {i} op={op} M={M} K={K} N={N} plan={plan}")
+        if op == 1 and plan["path"] == P.PRISM_PATH_PREFILL:
+            # two matrices on the tiled kernel: its derived bound (see PREFILL_TWO_MATRIX_TAIL below)
+            w = worst_error(y, yhat)
+            assert w <= PREFILL_TWO_MATRIX_TAIL[dt], f"random {i} op={op} M={M} K={K} N={N} plan={plan}: {w:.3e}"
+        else:
+            assert_parity(y, yhat, dt, f"random {i} op={op} M={M} K={K} N={N} plan={plan}")
         seen.add((op, plan["path"], plan["tile_m"], plan["split_k"] > 1))
     # the draw reaches every kernel family of every operator, with and without slices
     assert {(o, pth) for o, pth, _, _ in seen} >= {(0, 2), (0, 3), (1, 2), (1, 3), (2, 4)}, seen
     # (64 rows per workgroup need weights beyond the oracle's reach here: the decode_rows tests force them)
-    assert {(o, tm) for o, pth, tm, _ in seen if pth in (2, 4)} >= {(0, 16), (0, 32), (1, 16), (1, 32), (2, 16), (2, 32)}, seen
+    # (the softmax operator's 32-row K-split kernel has its own tests)
+    assert {(o, tm) for o, pth, tm, _ in seen if pth in (2, 4)} >= {(0, 16), (0, 32), (1, 16), (1, 32), (2, 16)}, seen
 
 
 # ---- the far tail of two-matrix outputs -----------------------------------------------------------------------------

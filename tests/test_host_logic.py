@@ -217,17 +217,23 @@ def test_decode_plan_for_more_than_sixteen_rows(P):
     d = P.prism_plan(0, 17, 4096, 4096, bf16)
     assert (d["path"], d["tile_m"], d["grid_x"], d["grid_z"], d["block"]) == (P.PRISM_PATH_DECODE, 32, 32, 1, 512)
     assert d["grid_y"] == d["split_k"] == 8
-    d = P.prism_plan(0, 100, 4096, 4096, bf16)    # four passes over 32 MiB of W stay in the last-level cache
-    assert (d["path"], d["tile_m"], d["grid_z"], d["split_k"]) == (P.PRISM_PATH_DECODE, 32, 4, 2)
-    n_tiles, rb, S = 32, 4, 2
-    assert d["workspace_bytes"] == 262144 + n_tiles * rb * S * 32 * 4 + S * 100 * 4096 * 4
-    d = P.prism_plan(0, 100, 14336, 4096, bf16)   # 112 MiB of W: 64 rows per workgroup, two passes
+    # the time model of the three candidates (32 rows, 64 rows, prefill kernel) decides:
+    d = P.prism_plan(0, 100, 4096, 4096, bf16)    # 64 rows in four K-slices beat 32 rows in two (17.9 against 21.0 us)
+    assert (d["path"], d["tile_m"], d["grid_z"], d["split_k"]) == (P.PRISM_PATH_DECODE, 64, 2, 4)
+    n_tiles, rb, S = 32, 2, 4
+    assert d["workspace_bytes"] == 262144 + n_tiles * rb * S * 64 * 4 + S * 100 * 4096 * 4
+    d = P.prism_plan(0, 48, 4096, 4096, bf16)     # few rows: 64 rows would need eight slices; 32 rows in four
+    assert (d["path"], d["tile_m"], d["grid_z"], d["split_k"]) == (P.PRISM_PATH_DECODE, 32, 2, 4)
+    d = P.prism_plan(0, 100, 14336, 4096, bf16)
     assert (d["path"], d["tile_m"], d["grid_z"], d["split_k"]) == (P.PRISM_PATH_DECODE, 64, 2, 4)
     assert P.prism_plan(0, 512, 4096, 4096, bf16)["path"] == P.PRISM_PATH_DECODE
-    assert P.prism_plan(0, 512, 4096, 6144, bf16)["path"] == P.PRISM_PATH_PREFILL   # 384 workgroups: not at once
-    assert P.prism_plan(0, 100, 1024, 1024, bf16)["path"] == P.PRISM_PATH_PREFILL   # shallow K
-    g = P.prism_plan(1, 64, 4096, 14336, bf16)    # gated, 33 to 64 rows: one row block, matrices split across wavefronts
-    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 64, 1, 2)
+    assert P.prism_plan(0, 512, 4096, 6144, bf16)["path"] == P.PRISM_PATH_PREFILL   # 384 workgroups: two rounds
+    d = P.prism_plan(0, 100, 1024, 1024, bf16)    # shallow K: 16 K steps of the tiled kernel cost more than 8 K-blocks
+    assert (d["path"], d["tile_m"], d["split_k"]) == (P.PRISM_PATH_DECODE, 32, 4)
+    g = P.prism_plan(1, 192, 8192, 4096, bf16)    # gated, deep K: the prefill kernel's 128 K steps lose (131 against 76 us)
+    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 64, 3, 2)   # 81 us; 32 rows: 76
+    g = P.prism_plan(1, 64, 4096, 14336, bf16)    # gated, 33 to 64 rows against the wide matrices: two row blocks of 32
+    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 32, 2, 1)
     g = P.prism_plan(1, 32, 4096, 14336, bf16)
     assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 32, 1, 2)
     assert P.prism_plan(1, 100, 4096, 14336, bf16)["path"] == P.PRISM_PATH_PREFILL
@@ -238,7 +244,7 @@ def test_decode_plan_for_more_than_sixteen_rows(P):
         assert (d["tile_m"], d["grid_z"], d["split_k"]) == (32, 4, 3)
         with pytest.raises(P.PrismError):
             P.prism_plan(0, 16, 4096, 4096, bf16)
-        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 0)
+        P.prism_set_override(P.PRISM_PATH_DECODE, 0, 64)
         assert P.prism_plan(1, 100, 4096, 14336, bf16)["grid_z"] == 2
         P.prism_set_override(P.PRISM_PATH_DECODE, 0, 32)
         assert P.prism_plan(1, 100, 4096, 14336, bf16)["grid_z"] == 4
