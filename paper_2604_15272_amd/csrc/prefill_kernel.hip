@@ -145,15 +145,22 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     // step; there a block is 6 columns wide (12-byte loads), so that all 256 threads share the work.
     // Which matrix a wavefront reads is the same for all its lanes (a matrix's threads are a multiple of 64);
     // say so, to keep the descriptor in SGPRs.
+    // A 128-column tile (or 2 x 64 gated) has only 128 such blocks: two of the four wavefronts would carry the
+    // whole transposition (160 vector instructions per K step beside 16 MFMAs) and the step would take as long
+    // as they do.  There a block is 4 (k) x 8 (n): two threads share a column's 16-byte operand, each storing
+    // its 8-byte half.
     constexpr int CB = (BN == 192) ? 6 : 8;
     constexpr int NBG = CW / CB;     // column groups per weight matrix
-    constexpr int TPM = KCH * NBG;   // threads per weight matrix
-    constexpr int NP = 4 * CB;       // staging pieces per thread and tile (4 per column)
+    constexpr int KR = ((GATED ? 2 : 1) * KCH * NBG <= 128) ? 4 : 8;  // k rows of a thread's block
+    constexpr int KQ = BK / KR;      // blocks per column group along k
+    constexpr int TPM = KQ * NBG;    // threads per weight matrix
+    constexpr int NP = (KR / 2) * CB;  // staging pieces per thread and tile (one per pair of k rows and column)
     static_assert(CW % CB == 0 && TPM % 64 == 0 && (GATED ? 2 : 1) * TPM <= 256, "W staging map");
     const int wmat = GATED ? __builtin_amdgcn_readfirstlane((tid / TPM) & 1) : 0;
     const int wt = GATED ? tid % TPM : tid;
     const bool w_active = tid < (GATED ? 2 : 1) * TPM;
-    const int wkb = wt / NBG, wnb = wt % NBG;
+    const int wkq = wt / NBG, wnb = wt % NBG;          // the thread's block: k rows KR wkq .. KR wkq + KR - 1
+    const int wkb = wkq / (8 / KR), whalf = wkq % (8 / KR);  // the 8-deep chunk plane it belongs to, and which half
     // (A 6-column group that straddles N reads columns that belong to the next row of W: they only
     // reach accumulators of columns >= N, which are never stored.)
     const bool w_col_ok = w_active && (n0 + CB * wnb) < N;
@@ -161,7 +168,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     const u32 w_bytes = (u32)(w_left < 0x7FFFFFFFull ? w_left : 0x7FFFFFFFull);
     const __amdgpu_buffer_rsrc_t rw = make_rsrc((wmat ? W2 : W1) + n0, w_bytes);
     const u32 row_bytes = (u32)N * 2u;
-    const u32 w_lane = w_col_ok ? ((u32)(8 * wkb) * row_bytes + (u32)(2 * CB * wnb)) : kOutOfRange;
+    const u32 w_lane = w_col_ok ? ((u32)(KR * wkq) * row_bytes + (u32)(2 * CB * wnb)) : kOutOfRange;
     const int w_lds_col = wmat * (BN / 2) + CB * wnb;  // first LDS column of the block
     // LDS slot of column j of the block, within a stage.  Threads without a block (tiles narrower than
     // 256) store to a padding slot instead of branching, which keeps the K loop one basic block.
@@ -172,8 +179,8 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     // Two register sets for W: while one is being staged into LDS, the other already holds the tile
     // after it, so a tile's loads have more than a whole K step to arrive.
     struct WSet {
-        u32x4 w[8];  // eight rows of the thread's 8 x 8 block of W
-        u32x4 g;     // gain of those eight rows
+        u32x4 w[KR];  // the rows of the thread's block of W
+        u32x4 g;      // gain of those rows (the first KR / 2 dwords)
     };
     WSet ws_a, ws_b;
     const bool has_gain = (flags & kFlagGain) != 0;
@@ -184,14 +191,21 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         if (i == 0) {
             // Without a gain tensor the load is still issued (out of range: it returns zero and touches
             // no memory): the wait counts of the pipeline below count instructions.
-            const u32x4 v = load16(rg, has_gain ? (u32)(kt * BK + 8 * wkb) * 2u : kOutOfRange);
+            const u32 goff = has_gain ? (u32)(kt * BK + KR * wkq) * 2u : kOutOfRange;
+            u32x4 v;
+            if constexpr (KR == 8) {
+                v = load16(rg, goff);
+            } else {
+                const u32x2 h = __builtin_amdgcn_raw_buffer_load_b64(rg, (int)goff, 0, 0);
+                v = u32x4{h[0], h[1], 0u, 0u};
+            }
             const u32x4 one = ones8<F>();
             s.g = u32x4{has_gain ? v[0] : one[0], has_gain ? v[1] : one[1], has_gain ? v[2] : one[2],
                         has_gain ? v[3] : one[3]};
         }
         else s.w[i - 1] = load_cols<CB>(rw, w_lane + (u32)kt * BK * row_bytes + (u32)(i - 1) * row_bytes);
     };
-    constexpr int NWL = 9;  // loads per set
+    constexpr int NWL = KR + 1;  // loads per set
     // X, request i of K step kt: this wavefront moves rows 8 * wave + 32 i .. + 7 (64 K values each)
     // into group wave + 4 i of the stage; lane l = 8 r + p fetches chunk p ^ r of its row.
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -213,7 +227,11 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         const float e0 = (j & 1) ? F::hi(w0) : F::lo(w0);
         const float e1 = (j & 1) ? F::hi(w1) : F::lo(w1);
         wb[t] = F::pack(e0 * F::lo(gg), e1 * F::hi(gg));
-        if (t == 3) b_stage[w_dst[j]] = wb;
+        if constexpr (KR == 8) {
+            if (t == 3) b_stage[w_dst[j]] = wb;
+        } else {
+            if (t == 1) ((u32x2*)(b_stage + w_dst[j]))[whalf] = u32x2{wb[0], wb[1]};
+        }
     };
 
     // ---- LDS -> MFMA operand maps --------------------------------------------------------------
@@ -287,7 +305,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     // reads its share of the next operands (from `a_rd`/`b_rd`, 16-deep phase `kk_rd`), and does its
     // share of this phase's work on the tiles to come: part PART of the refill (none if negative) of
     // X tile `kt_x` into stage `a_x` and of W tile `kt_x` + 1 into the set `w_ld`; W pieces
-    // [WP0, WP0 + NWP) (piece = 4 * column + K pair) of the set `w_st` staged into `b_st`.  A
+    // [WP0, WP0 + NWP) (piece = (KR / 2) * column + K pair) of the set `w_st` staged into `b_st`.  A
     // scheduling barrier closes every slot: the order written here is the order executed.
     auto phase = [&](auto kk_c, auto part_c, auto wp0_c, auto nwp_c, const u32x4* a_rd, const u32x4* b_rd,
                      int kk_rd, const u32x4 (&xf)[TM32], const u32x4 (&wf)[TN32], u32x4 (&xf_n)[TM32],
@@ -329,7 +347,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
             if constexpr (PART >= 0) refill_slot(part_c, q, a_x, kt_x, w_ld);
 #pragma unroll
             for (int it = (q * NWP) / MF; it < ((q + 1) * NWP) / MF; ++it)
-                stage_w_piece(w_st, b_st, (WP0 + it) / 4, (WP0 + it) % 4);
+                stage_w_piece(w_st, b_st, (WP0 + it) / (KR / 2), (WP0 + it) % (KR / 2));
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -345,7 +363,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         asm volatile("" ::: "memory");
     };
 
-    // W pieces (4 per column, NP per tile): the first P3 could be staged a step early, in phase 3 (after
+    // W pieces (KR / 2 per column, NP per tile): the first P3 could be staged a step early, in phase 3 (after
     // the barrier, into the stage just vacated), the rest in phases 0, 1, 2.  Measured best with none
     // in phase 3: the set's last loads are issued only two phases before it.
     constexpr int P3 = 0;
@@ -398,13 +416,13 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
         __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
-    for (int p = 0; p < NP; ++p) stage_w_piece(ws_b, Bs, p / 4, p % 4);
+    for (int p = 0; p < NP; ++p) stage_w_piece(ws_b, Bs, p / (KR / 2), p % (KR / 2));
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int q = 0; q < MF; ++q) refill_slot(integral_constant<int, 0>{}, q, As + A_SLOTS, 1, ws_b);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int p = 0; p < P3; ++p) stage_w_piece(ws_a, Bs + B_SLOTS, p / 4, p % 4);
+    for (int p = 0; p < P3; ++p) stage_w_piece(ws_a, Bs + B_SLOTS, p / (KR / 2), p % (KR / 2));
     // X of tile 0 is older than everything but its own requests: 2 NWL + NI0 younger instructions would do; the
     // prologue runs once, so it simply waits for everything (and does not depend on the order above).
     stage_barrier(integral_constant<int, 0>{});
