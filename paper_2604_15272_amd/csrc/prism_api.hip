@@ -185,7 +185,7 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 //     exchange  = 2.5 + S x RG x matrices / 8 when S > 1 (three dependent round trips, then the last arrival
 //                 pulls S partial tiles through one compute unit)
 //     launch    = 1.5
-//   prefill kernel: K steps x (1.5 / 2.0 for 256-row tiles of one / two matrices, 1.08 / 1.2 for 128-row tiles, 0.93
+//   prefill kernel: K steps x (1.5 / 2.0 for 256-row tiles of one / two matrices, 0.88 to 1.2 for 128-row tiles, 0.93
 //     for 64 x 64) x 1 if every tile has a compute unit, x 1.3 for up to two 128-row tiles per unit, else the rounds;
 //     + 3.  (A K step of that kernel has a floor of about a microsecond whatever the tile.)
 struct RowsEstimate {
@@ -212,8 +212,8 @@ double prefill_estimate(bool gated, int64_t M, int64_t K, int64_t N, int64_t cus
         int bm, bn;
         double step;
     };
-    static const T plain[] = {{256, 256, 1.5}, {256, 192, 1.5}, {128, 128, 1.08}, {64, 64, 0.93}};
-    static const T gate[] = {{256, 256, 2.0}, {128, 256, 1.2}, {128, 128, 1.08}};
+    static const T plain[] = {{256, 256, 1.5}, {256, 192, 1.5}, {128, 128, 0.88}, {64, 64, 0.93}};
+    static const T gate[] = {{256, 256, 2.0}, {128, 256, 1.2}, {128, 128, 0.90}};
     const T* t = gated ? gate : plain;
     const int64_t KT = (K + 63) / 64;
     double best = 1e300;
