@@ -75,7 +75,6 @@ constexpr int kSoftmaxTileN = 128;
 // keeps in registers between its two passes.
 constexpr int kSoftmaxSplitRows = 32;
 constexpr int kSoftmaxMaxSplits = 16;
-constexpr int kSoftmaxKeepBlocks = 8;
 
 struct SoftmaxWorkspace {
     unsigned* tickets;  // [row_blocks][n_tiles], in the workspace header, zero between calls

@@ -83,7 +83,10 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
     const u32 w_lane = col_ok ? ((u32)(8 * q) * row_bytes + (u32)(16 * c)) : kOutOfRange;
     const bool row_ok = (m0 + c) < M;
     const u32 x_row = (u32)c * (u32)K * 2u;
-    auto k_valid = [&](int ib) { return ib < kblocks && ib * KB + 8 * q < K; };
+    // Whether this lane's eight K values of block ib exist (implies ib < kblocks).  Everything in the loop below is
+    // written with selects, not branches: loads whose values are used in a later conditional block get moved
+    // into that block by the compiler, next to their use, and then nothing is in flight ahead of the arithmetic.
+    auto k_valid = [&](int ib) { return ib * KB + 8 * q < K; };
 
     f32x4 acc[8], sum_acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -94,7 +97,7 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
             const int ib = i0 + u * NW;
-            xs[u] = load16(rx, (k_valid(ib) && row_ok) ? x_row + (u32)(ib * KB + 8 * q) * 2u : kOutOfRange);
+            xs[u] = load16(rx, (k_valid(ib) & row_ok) ? x_row + (u32)(ib * KB + 8 * q) * 2u : kOutOfRange);
         }
     };
     auto load_w = [&](WRows& w, int ib) {
@@ -105,7 +108,8 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
         float cm = -__builtin_inff();
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
-            cm = fmaxf(cm, (k_valid(i0 + u * NW) && row_ok) ? F::max8(xs[u]) : -__builtin_inff());
+            const float mx = F::max8(xs[u]);
+            cm = fmaxf(cm, (k_valid(i0 + u * NW) & row_ok) ? mx : -__builtin_inff());
         }
         cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
         cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
@@ -126,10 +130,12 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
         const float shift = row_ok ? -m_run * kLog2e : 0.f;  // a row past M has no maximum: keep the arithmetic finite
 #pragma unroll
         for (int u = 0; u < CH; ++u) {
-            const int ib = i0 + u * NW;
-            if (ib >= kblocks) break;                  // uniform over the wavefront
+            const int ib = i0 + u * NW;                // a block past the end: its loads return zeros, a = 0
             load_w(w[(u + 1) & 1], ib + NW);           // the next block's W, into the other register set
-            const bool v = k_valid(ib) && row_ok;
+            // The loads stay here, a whole block's arithmetic ahead of their use: without the fences the
+            // scheduler pulls the next block's permutes up to just behind them.
+            __builtin_amdgcn_sched_barrier(0);
+            const bool v = k_valid(ib) & row_ok;
             u32x4 a;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
@@ -149,20 +155,21 @@ __global__ __launch_bounds__(NW * 64) void softmax_rows_kernel(const uint16_t* _
             // The row sums ride on the matrix cores too: a ninth product against a block of ones adds up
             // exactly the rounded values the other eight use (every column of the result is the row sum).
             sum_acc = F::mfma_16x16x32(a, ones8<F>(), sum_acc);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     {
         u32x4 xa[CH], xb[CH];
         load_chunk(xa, wave);
         load_w(w[0], wave);
-        for (int i0 = wave; i0 < kblocks;) {
+        // Two chunks per trip of the loop, no exit between them (a chunk past the end adds zeros): see k_valid.
+        for (int i0 = wave; i0 < kblocks; i0 += 2 * CH * NW) {
             load_chunk(xb, i0 + CH * NW);
+            __builtin_amdgcn_sched_barrier(0);
             chunk(xa, i0);
-            i0 += CH * NW;
-            if (i0 >= kblocks) break;
-            load_chunk(xa, i0 + CH * NW);
-            chunk(xb, i0);
-            i0 += CH * NW;
+            load_chunk(xa, i0 + 2 * CH * NW);
+            __builtin_amdgcn_sched_barrier(0);
+            chunk(xb, i0 + CH * NW);
         }
     }
     // Element i of the sum block in lane (q, c) is row 4q + i (any column c: they are all equal).

@@ -2,15 +2,15 @@
 // "parallelized matmul (reduction)" and the compound parallelized sums).
 //
 // The kernel that gives a workgroup 16 rows over the whole of K makes every workgroup read all of its
-// 128 columns of W: at the paper's shape (X[4096,4096], W[4096,128]) that is 1 MiB of W per 128 KiB of X,
-// and the L2 -> CU path, not HBM, sets the time.  Here a workgroup owns 32 rows, 128 columns and one
-// K-slice: half the W per row at once, and a further 1/S of it with S slices, while row blocks x slices
-// still fill the chip.  The softmax of a slice is taken against the slice's own row maximum; what a
-// workgroup hands over is (maximum, sum of exponentials, partial product), and the last arrival of a tile
-// (atomic ticket) rescales every slice to the common maximum, adds them in slice order and divides: the
-// same algebra as the division after the loop in Figure 1(b), applied once more across slices.
-// When a wavefront's share of the slice is at most eight 32-deep K-blocks its part of X stays in
-// registers between the maximum pass and the exponential pass: X is read exactly once.
+// 128 columns of W: at the paper's shape (X[4096,4096], W[4096,128]) that is 1 MiB of W per 128 KiB of X
+// through one compute unit's vector-memory path (64 bytes per clock), which then sets the time, not HBM.
+// Here a workgroup owns 32 rows, 128 columns and one K-slice: every B operand built from W serves two
+// groups of 16 rows, and with S slices a workgroup reads 1/S of W, while row blocks x slices still fill the
+// chip.  A wavefront walks its K-blocks once, with a running row maximum (accumulators rescaled when it
+// moves), as the 16-row kernel does.  What a workgroup hands over is (maximum, sum of exponentials,
+// partial product) relative to the slice's own maximum, and the last arrival of a tile (atomic ticket)
+// rescales every slice to the common maximum, adds them in slice order and divides: the same algebra as the
+// division after the loop in Figure 1(b), applied once more across slices.
 #include <type_traits>
 
 #include "device_utils.h"
@@ -28,7 +28,6 @@ constexpr int NW = 8;
 constexpr int NT = NW * 64;
 constexpr int RG = 2;             // 16-row groups per workgroup
 constexpr int RB = 16 * RG;       // rows per workgroup
-constexpr int KEEP = kSoftmaxKeepBlocks;  // K-blocks of X a wavefront can hold in registers
 constexpr int CPT = 16 * TN / NT;  // 4 columns per thread in the epilogue
 constexpr int TPR = TN / CPT;      // 32 threads per output row
 constexpr int kRedFloats = NW * 16 * TN;
@@ -36,7 +35,7 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 }  // namespace
 
-template <typename F, bool RESIDENT>
+template <typename F>
 __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W,
                                                            uint16_t* __restrict__ Y, float* __restrict__ acc_part,
                                                            float* __restrict__ ml_part, unsigned* __restrict__ tickets,
@@ -75,143 +74,128 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
         row_ok[r] = (m0 + 16 * r + c) < M;
         x_row[r] = (u32)(16 * r + c) * (u32)K * 2u;
     }
-    // Byte offset into X of this lane's 8 values of K-block ib of the slice, or "out of range" (reads as zero).
-    auto x_off = [&](int ib, int r) -> u32 {
-        const int k = (b_beg + ib) * KB + 8 * q;
-        return (ib < b_cnt && k < K && row_ok[r]) ? x_row[r] + (u32)k * 2u : kOutOfRange;
-    };
-    auto k_valid = [&](int ib) { return ib < b_cnt && (b_beg + ib) * KB + 8 * q < K; };
+    // Whether this lane's eight K values of the slice's block ib exist.  The loop below is written with selects and
+    // without exits between its parts: loads whose values are used in a later conditional block get moved
+    // into that block by the compiler, next to their use, and then nothing is in flight ahead of the arithmetic.
+    auto k_valid = [&](int ib) { return (ib < b_cnt) & ((b_beg + ib) * KB + 8 * q < K); };
+    constexpr int CH = 2;  // K-blocks per wavefront and chunk (even: the W register sets alternate per block)
 
-    // ---- pass 1: the slice's row maxima.  All loads of a wavefront's share are issued before the first is
-    // looked at: this pass pulls X from HBM.
-    float mx[RG];
-#pragma unroll
-    for (int r = 0; r < RG; ++r) mx[r] = -__builtin_inff();
-    u32x4 xk[RESIDENT ? KEEP : 1][RG];
-    if (RESIDENT) {
-#pragma unroll
-        for (int u = 0; u < KEEP; ++u)
-#pragma unroll
-            for (int r = 0; r < RG; ++r) xk[u][r] = load16(rx, x_off(wave + u * NW, r));
-#pragma unroll
-        for (int u = 0; u < KEEP; ++u)
-#pragma unroll
-            for (int r = 0; r < RG; ++r) {
-                const bool v = k_valid(wave + u * NW) && row_ok[r];
-                mx[r] = fmaxf(mx[r], v ? F::max8(xk[u][r]) : -__builtin_inff());
-            }
-    } else {
-        constexpr int U = 8;
-        for (int i = wave; i < b_cnt; i += U * NW) {
-            u32x4 xr[U][RG];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int r = 0; r < RG; ++r) xr[u][r] = load16(rx, x_off(i + u * NW, r));
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int r = 0; r < RG; ++r) {
-                    const bool v = k_valid(i + u * NW) && row_ok[r];
-                    mx[r] = fmaxf(mx[r], v ? F::max8(xr[u][r]) : -__builtin_inff());
-                }
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 16, 64));
-        mx[r] = fmaxf(mx[r], __shfl_xor(mx[r], 32, 64));
-        if (q == 0) wave_max[wave * RB + 16 * r + c] = mx[r];
-    }
-    __syncthreads();
-    float shift[RG];  // -max * log2(e): exp(x - max) = exp2(x * log2(e) + shift)
-#pragma unroll
-    for (int r = 0; r < RG; ++r) {
-        float m = -__builtin_inff();
-#pragma unroll
-        for (int w = 0; w < NW; ++w) m = fmaxf(m, wave_max[w * RB + 16 * r + c]);
-        shift[r] = row_ok[r] ? -m * kLog2e : 0.f;  // a row past M has no maximum: keep the arithmetic finite
-    }
-
-    // ---- pass 2: exp, row sums (a ninth MFMA against ones) and the product
     f32x4 acc[RG][8], sum_acc[RG];
+    float m_run[RG];  // running maximum of row c of each group over this wavefront's K-blocks so far
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
         sum_acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run[r] = -__builtin_inff();
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[r][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    auto load_chunk = [&](u32x4 (&xs)[CH][RG], int i0) {
+#pragma unroll
+        for (int u = 0; u < CH; ++u) {
+            const int ib = i0 + u * NW;
+#pragma unroll
+            for (int r = 0; r < RG; ++r)
+                xs[u][r] = load16(rx, (k_valid(ib) & row_ok[r]) ? x_row[r] + (u32)((b_beg + ib) * KB + 8 * q) * 2u : kOutOfRange);
+        }
+    };
     auto load_w = [&](WRows& w, int ib) {
         load_w_block(w, rw, (ib < b_cnt) ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange, row_bytes);
     };
-    auto consume = [&](const u32x4 (&xs)[RG], const WRows& w, int ib) {
-        const bool kv = k_valid(ib);
-        u32x4 a[RG];
+    WRows w[2];
+    auto chunk = [&](const u32x4 (&xs)[CH][RG], int i0) {
+        float m_new[RG];
+        bool moved = false;
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            const bool v = kv && row_ok[r];
+            float cm = -__builtin_inff();
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const float e0 = __builtin_amdgcn_exp2f(fmaf(F::lo(xs[r][d]), kLog2e, shift[r]));
-                const float e1 = __builtin_amdgcn_exp2f(fmaf(F::hi(xs[r][d]), kLog2e, shift[r]));
-                a[r][d] = v ? F::pack(e0, e1) : 0u;
+            for (int u = 0; u < CH; ++u) {
+                const float mx = F::max8(xs[u][r]);
+                cm = fmaxf(cm, (k_valid(i0 + u * NW) & row_ok[r]) ? mx : -__builtin_inff());
+            }
+            cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
+            cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
+            m_new[r] = fmaxf(m_run[r], cm);
+            moved |= (m_new[r] != m_run[r]);
+        }
+        if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+            // Accumulator element i of lane (q, c) belongs to row 4q + i; its factor lives in the lanes of row
+            // 4q + i.  Rows that have seen nothing yet keep the factor 1 (their accumulators are zero).
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                const float f = (m_run[r] == -__builtin_inff()) ? 1.0f
+                                                               : __builtin_amdgcn_exp2f((m_run[r] - m_new[r]) * kLog2e);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float fi = __shfl(f, 4 * q + i, 64);
+                    sum_acc[r][i] *= fi;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[r][j][i] *= fi;
+                }
+                m_run[r] = m_new[r];
             }
         }
-        auto step = [&](auto jc) {
-            constexpr int J = decltype(jc)::value;
-            const u32x4 b = b_operand<J>(w);
+        float shift[RG];  // -max * log2(e): exp(x - max) = exp2(x * log2(e) + shift)
 #pragma unroll
-            for (int r = 0; r < RG; ++r) acc[r][J] = F::mfma_16x16x32(a[r], b, acc[r][J]);
-        };
-        step(std::integral_constant<int, 0>{});
-        step(std::integral_constant<int, 1>{});
-        step(std::integral_constant<int, 2>{});
-        step(std::integral_constant<int, 3>{});
-        step(std::integral_constant<int, 4>{});
-        step(std::integral_constant<int, 5>{});
-        step(std::integral_constant<int, 6>{});
-        step(std::integral_constant<int, 7>{});
+        for (int r = 0; r < RG; ++r) shift[r] = (m_run[r] != -__builtin_inff()) ? -m_run[r] * kLog2e : 0.f;
 #pragma unroll
-        for (int r = 0; r < RG; ++r) sum_acc[r] = F::mfma_16x16x32(a[r], ones8<F>(), sum_acc[r]);
+        for (int u = 0; u < CH; ++u) {
+            const int ib = i0 + u * NW;                // a block past the end: its loads return zeros, a = 0
+            load_w(w[(u + 1) & 1], ib + NW);           // the next block's W, into the other register set
+            // The loads stay here, a whole block's arithmetic ahead of their use: without the fences the
+            // scheduler pulls the next block's permutes up to just behind them.
+            __builtin_amdgcn_sched_barrier(0);
+            const bool kv = k_valid(ib);
+            u32x4 a[RG];
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                const bool v = kv & row_ok[r];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const float e0 = __builtin_amdgcn_exp2f(fmaf(F::lo(xs[u][r][d]), kLog2e, shift[r]));
+                    const float e1 = __builtin_amdgcn_exp2f(fmaf(F::hi(xs[u][r][d]), kLog2e, shift[r]));
+                    a[r][d] = v ? F::pack(e0, e1) : 0u;
+                }
+            }
+            const WRows& wb = w[u & 1];
+            auto step = [&](auto jc) {
+                constexpr int J = decltype(jc)::value;
+                const u32x4 b = b_operand<J>(wb);
+#pragma unroll
+                for (int r = 0; r < RG; ++r) acc[r][J] = F::mfma_16x16x32(a[r], b, acc[r][J]);
+            };
+            step(std::integral_constant<int, 0>{});
+            step(std::integral_constant<int, 1>{});
+            step(std::integral_constant<int, 2>{});
+            step(std::integral_constant<int, 3>{});
+            step(std::integral_constant<int, 4>{});
+            step(std::integral_constant<int, 5>{});
+            step(std::integral_constant<int, 6>{});
+            step(std::integral_constant<int, 7>{});
+            // The row sums ride on the matrix cores too: a ninth product against a block of ones adds up
+            // exactly the rounded values the other eight use (every column of the result is the row sum).
+#pragma unroll
+            for (int r = 0; r < RG; ++r) sum_acc[r] = F::mfma_16x16x32(a[r], ones8<F>(), sum_acc[r]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     };
-    if (RESIDENT) {
-        // X is in registers; W blocks alternate between two register sets, the next one in flight.
-        WRows w[2];
+    {
+        u32x4 xa[CH][RG], xb[CH][RG];
+        load_chunk(xa, wave);
         load_w(w[0], wave);
-#pragma unroll
-        for (int u = 0; u < KEEP; ++u) {
-            const int ib = wave + u * NW;
-            if (ib < b_cnt) {  // uniform over the wavefront
-                if (u + 1 < KEEP) load_w(w[(u + 1) & 1], ib + NW);
-                consume(xk[u], w[u & 1], ib);
-            }
-        }
-    } else {
-        struct Trip {
-            WRows w;
-            u32x4 xr[RG];
-        };
-        auto issue = [&](Trip& t, int ib) {
-#pragma unroll
-            for (int r = 0; r < RG; ++r) t.xr[r] = load16(rx, x_off(ib, r));
-            load_w(t.w, ib);
-        };
-        Trip ta, tb;
-        int i = wave;
-        if (i < b_cnt) {
-            issue(ta, i);
-            for (;;) {
-                issue(tb, i + NW);
-                consume(ta.xr, ta.w, i);
-                i += NW;
-                if (i >= b_cnt) break;
-                issue(ta, i + NW);
-                consume(tb.xr, tb.w, i);
-                i += NW;
-                if (i >= b_cnt) break;
-            }
+        // Two chunks per trip of the loop, no exit between them (a chunk past the end adds zeros).
+        for (int i0 = wave; i0 < b_cnt; i0 += 2 * CH * NW) {
+            load_chunk(xb, i0 + CH * NW);
+            __builtin_amdgcn_sched_barrier(0);
+            chunk(xa, i0);
+            load_chunk(xa, i0 + 2 * CH * NW);
+            __builtin_amdgcn_sched_barrier(0);
+            chunk(xb, i0 + CH * NW);
         }
     }
+#pragma unroll
+    for (int r = 0; r < RG; ++r)
+        if (q == 0) wave_max[wave * RB + 16 * r + c] = m_run[r];
     // Element i of the sum block in lane (q, c) is row 4q + i (any column: they are all equal).
 #pragma unroll
     for (int r = 0; r < RG; ++r) {
@@ -228,6 +212,7 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
 #pragma unroll
     for (int r = 0; r < RG; ++r) store_acc_tile(red + r * kRedFloats + wave * 16 * TN, TN, q, c, acc[r]);
     __syncthreads();
+    // Every wavefront's partials are relative to its own maximum: rescale to the workgroup's.
     float v[RG][CPT], den[RG], rmax[RG];
     bool out_ok[RG];
 #pragma unroll
@@ -236,14 +221,18 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
         den[r] = 0.f;
         rmax[r] = -__builtin_inff();
 #pragma unroll
+        for (int w8 = 0; w8 < NW; ++w8) rmax[r] = fmaxf(rmax[r], wave_max[w8 * RB + 16 * r + m]);
+#pragma unroll
         for (int e = 0; e < CPT; ++e) v[r][e] = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float* src = red + r * kRedFloats + (w * 16 + m) * TN + col;
+        for (int w8 = 0; w8 < NW; ++w8) {
+            const float mw = wave_max[w8 * RB + 16 * r + m];
+            // a wavefront without K-blocks (or a row past M) has maximum -inf and zero partials
+            const float f = (mw == -__builtin_inff()) ? 0.f : __builtin_amdgcn_exp2f((mw - rmax[r]) * kLog2e);
+            const float* src = red + r * kRedFloats + (w8 * 16 + m) * TN + col;
 #pragma unroll
-            for (int e = 0; e < CPT; ++e) v[r][e] += src[e];
-            den[r] += wave_sum[w * RB + 16 * r + m];
-            rmax[r] = fmaxf(rmax[r], wave_max[w * RB + 16 * r + m]);
+            for (int e = 0; e < CPT; ++e) v[r][e] = fmaf(f, src[e], v[r][e]);
+            den[r] = fmaf(f, wave_sum[w8 * RB + 16 * r + m], den[r]);
         }
     }
 
@@ -325,11 +314,11 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
     }
 }
 
-template <typename F, bool RESIDENT>
+template <typename F>
 static hipError_t launch_split(const SoftmaxCall& c, int S, const SoftmaxWorkspace& ws) {
     dim3 grid((c.N + TN - 1) / TN, S, (c.M + RB - 1) / RB), block(NT);
     const size_t lds = (size_t)(RG * kRedFloats + 2 * NW * RB) * sizeof(float);
-    auto kern = softmax_split_kernel<F, RESIDENT>;
+    auto kern = softmax_split_kernel<F>;
     static std::atomic<uint64_t> opted{0};
     if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, block, lds, c.stream, (const uint16_t*)c.X, (const uint16_t*)c.W, (uint16_t*)c.Y,
@@ -339,11 +328,7 @@ static hipError_t launch_split(const SoftmaxCall& c, int S, const SoftmaxWorkspa
 
 hipError_t launch_softmax_split_16bit(const SoftmaxCall& c, bool f16, int split_k, const SoftmaxWorkspace& ws) {
     if (split_k < 1 || split_k > kSoftmaxMaxSplits) return hipErrorInvalidValue;
-    const int kblocks = (c.K + KB - 1) / KB;
-    const int per_wave = ((kblocks + split_k - 1) / split_k + NW - 1) / NW;
-    const bool resident = per_wave <= KEEP;
-    if (f16) return resident ? launch_split<F16, true>(c, split_k, ws) : launch_split<F16, false>(c, split_k, ws);
-    return resident ? launch_split<Bf16, true>(c, split_k, ws) : launch_split<Bf16, false>(c, split_k, ws);
+    return f16 ? launch_split<F16>(c, split_k, ws) : launch_split<Bf16>(c, split_k, ws);
 }
 
 }  // namespace prism
