@@ -314,23 +314,46 @@ prism_status_t make_softmax_plan(int64_t M, int64_t K, int64_t N, prism_dtype_t 
     int variant = choice.variant;
     if (S <= 0 && variant == 16) S = 1;
     if (S <= 0) {
-        // All workgroups at once (the split kernel fits one per CU) and at least four K-blocks per wavefront.
-        S = std::min<int64_t>(cu_count() / std::max<int64_t>(1, n_tiles * rb32), kblocks / 32);
-        S = std::max<int64_t>(1, std::min<int64_t>(S, kSoftmaxMaxSplits));
-        if (variant == 0 && rb16 == 1) {
-            // At most 16 rows: every workgroup streams its own columns of W, as in the decode kernel, and the
-            // same split rule applies (no split for a tile column up to 256 KiB, slices of at least 128 KiB).
-            const int64_t column_kib = K * kSoftmaxTileN * 2 / 1024;
-            S = column_kib <= 256 ? 1 : std::min<int64_t>(S, std::max<int64_t>(1, column_kib / 128));
-        } else if (variant == 0 && n_tiles * rb16 <= cu_count()) {
-            // Both kernels run in one round.  Measured on MI355X: a wavefront's K-block costs about 57 ns of the
-            // call with 16 rows per workgroup and 156 ns with 32, and handing partials across slices a few
-            // microseconds: the 16-row kernel keeps the call unless the slices shorten the loop by 3 us.
-            const double saved_ns = (double)kblocks * (57.0 - 156.0 / (double)S);
-            if (saved_ns < 3000.0) S = 1;
+        // A time model of the candidates, in microseconds, with constants measured on MI355X (K-blocks of 32, eight
+        // wavefronts per workgroup, so a wavefront makes kblocks / 8 trips):
+        //   16 rows, whole K:   5 + rounds x trips x (0.60 + 0.35 fill)
+        //   32 rows, S slices:  7.5 + rounds x trips x (0.80 + 0.60 fill) + [S > 1] (0.5 + 0.9 log2 S (1 + fill))
+        // fill = workgroups / compute units, at most 1; rounds = workgroups over compute units, rounded up.  The
+        // 32-row kernel reads half the W per row (it wins over several rounds) and can cut a deep K into slices
+        // (it wins when there are few workgroups); handing partials across slices costs the last term.
+        const double cus = (double)cu_count();
+        auto rows16 = [&]() {
+            const double w = (double)(n_tiles * rb16), fill = std::min(1.0, w / cus);
+            return 5.0 + std::ceil(w / cus) * std::ceil((double)kblocks / 8.0) * (0.60 + 0.35 * fill);
+        };
+        auto rows32 = [&](int64_t s) {
+            const double w = (double)(n_tiles * rb32 * s), fill = std::min(1.0, w / cus);
+            const double trips = std::ceil(std::ceil((double)kblocks / (double)s) / 8.0);
+            double t = 7.5 + std::ceil(w / cus) * trips * (0.80 + 0.60 * fill);
+            if (s > 1) t += 0.5 + 0.9 * std::log2((double)s) * (1.0 + fill);
+            return t;
+        };
+        auto slices_ok = [&](int64_t s) {
+            if (s == 1) return true;
+            return s <= kblocks && n_tiles * rb32 <= kMaxTickets && (uint64_t)s * M * N * 4 < kTwoGiB;
+        };
+        double best = (variant == 32 || rb32 > 65535) ? 1e300 : rows16();
+        int64_t best_s = 1;
+        int best_v = 16;
+        if (variant != 16 && rb32 <= 65535) {
+            for (int64_t s = 1; s <= kSoftmaxMaxSplits; s *= 2) {
+                if (s > 1 && kblocks / s < 8) break;  // a slice keeps at least one trip of every wavefront
+                if (!slices_ok(s)) continue;
+                const double t = rows32(s);
+                if (t < best) {
+                    best = t;
+                    best_s = s;
+                    best_v = 32;
+                }
+            }
         }
-        // Without slices the 16-row kernel is the faster one (measured, also over several rounds of workgroups).
-        if (variant == 0 && S < 2) variant = 16;
+        S = best_s;
+        if (variant == 0) variant = best_v;
     }
     if (S > kblocks) S = kblocks;
     if (variant == 0) variant = 32;

@@ -125,8 +125,8 @@ def test_softmax_matmul_arguments_and_plan(P):
     op = P.PRISM_OP_SOFTMAX_MATMUL
     p = P.prism_plan(op, 4096, 4096, 128, P.PRISM_F16)   # the paper's shape: 256 workgroups of 16 rows, no slices
     assert (p["path"], p["tile_m"], p["grid_x"], p["grid_y"], p["split_k"], p["workspace_bytes"]) == (P.PRISM_PATH_ROWS, 16, 1, 256, 1, 0)
-    p = P.prism_plan(op, 512, 4096, 128, P.PRISM_F16)    # fewer rows, still no slices (they would save too little)
-    assert (p["tile_m"], p["grid_y"], p["split_k"]) == (16, 32, 1)
+    p = P.prism_plan(op, 512, 4096, 128, P.PRISM_F16)    # fewer rows: 16 row blocks of 32 rows x 4 K-slices
+    assert (p["tile_m"], p["grid_y"], p["grid_z"], p["split_k"]) == (32, 4, 16, 4)
     p = P.prism_plan(op, 512, 16384, 128, P.PRISM_F16)   # deep K: 16 row blocks x 16 K-slices
     assert (p["path"], p["tile_m"], p["grid_x"], p["grid_y"], p["grid_z"], p["split_k"]) == (P.PRISM_PATH_ROWS, 32, 1, 16, 16, 16)
     assert p["workspace_bytes"] == 262144 + 16 * 16 * 32 * 2 * 4 + 16 * 512 * 128 * 4
@@ -135,8 +135,8 @@ def test_softmax_matmul_arguments_and_plan(P):
     assert (p["tile_m"], p["grid_x"], p["grid_y"], p["split_k"], p["workspace_bytes"]) == (16, 32, 1, 1, 0)
     p = P.prism_plan(op, 16, 32768, 128, P.PRISM_BF16)   # 16 rows, deep K: slices
     assert (p["tile_m"], p["split_k"]) == (32, 16)
-    p = P.prism_plan(op, 4096, 4096, 4096, P.PRISM_BF16)
-    assert (p["tile_m"], p["split_k"], p["grid_x"], p["grid_y"], p["workspace_bytes"]) == (16, 1, 32, 256, 0)
+    p = P.prism_plan(op, 4096, 4096, 4096, P.PRISM_BF16)  # many rounds of workgroups: 32 rows (half the W per row), no slices
+    assert (p["tile_m"], p["split_k"], p["grid_x"], p["grid_z"], p["workspace_bytes"]) == (32, 1, 32, 128, 0)
     p = P.prism_plan(op, 16, 4096, 4096, P.PRISM_BF16)   # 16 rows against 32 MB of W: slices, as in the decode kernel
     assert (p["tile_m"], p["split_k"]) == (32, 4)
     try:
