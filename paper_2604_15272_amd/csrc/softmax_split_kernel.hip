@@ -256,51 +256,56 @@ __global__ __launch_bounds__(NT) void softmax_split_kernel(const uint16_t* __res
         if (!is_last) return;
         if (tid == 0) tickets[tile_id] = 0u;
 
-        // Scale factors 2^((m_s - max) log2 e) of every slice first (S is at most kSoftmaxMaxSplits), then the
-        // partial products four slices at a time, added in slice order.
+        // One round trip for up to eight slices: the (maximum, sum) pairs of every slice (S is at most
+        // kSoftmaxMaxSplits) and the partial products of the first eight are requested together; the scale factors
+        // 2^((m_s - max) log2 e) are worked out while the products are on their way.  Added in slice order.
+        constexpr int BATCH = 8;
+        static_assert(kSoftmaxMaxSplits == 2 * BATCH, "two batches of partial products");
         float fac[kSoftmaxMaxSplits][RG], gmax[RG];
-        {
-            f32x2 mls[kSoftmaxMaxSplits][RG];
+        f32x2 mls[kSoftmaxMaxSplits][RG];
 #pragma unroll
-            for (int s = 0; s < kSoftmaxMaxSplits; ++s)
+        for (int s = 0; s < kSoftmaxMaxSplits; ++s)
+#pragma unroll
+            for (int r = 0; r < RG; ++r)
+                mls[s][r] = load_coherent2(ml + (size_t)min(s, S - 1) * (2 * RB) + 2 * (16 * r + m));
+        float pa[BATCH][RG][CPT];
+        auto load_batch = [&](int s0) {
+#pragma unroll
+            for (int j = 0; j < BATCH; ++j)
 #pragma unroll
                 for (int r = 0; r < RG; ++r)
-                    mls[s][r] = load_coherent2(ml + (size_t)min(s, S - 1) * (2 * RB) + 2 * (16 * r + m));
+                    load_partial<CPT>(racc, acc_part,
+                                      out_ok[r] ? ((size_t)min(s0 + j, S - 1) * M + (m0 + 16 * r + m)) * N + n : (size_t)0, pa[j][r]);
+        };
+        auto add_batch = [&](int s0) {
 #pragma unroll
-            for (int r = 0; r < RG; ++r) {
-                gmax[r] = -__builtin_inff();
+            for (int j = 0; j < BATCH; ++j)
 #pragma unroll
-                for (int s = 0; s < kSoftmaxMaxSplits; ++s) gmax[r] = fmaxf(gmax[r], mls[s][r][0]);
-                den[r] = 0.f;
+                for (int r = 0; r < RG; ++r) {
+                    const float f = fac[s0 + j][r];  // zero past the last slice and for a row or column past the end
 #pragma unroll
-                for (int s = 0; s < kSoftmaxMaxSplits; ++s) {
-                    fac[s][r] = (s < S && out_ok[r]) ? __builtin_amdgcn_exp2f((mls[s][r][0] - gmax[r]) * kLog2e) : 0.f;
-                    den[r] = fmaf(fac[s][r], mls[s][r][1], den[r]);
+                    for (int e = 0; e < CPT; ++e) v[r][e] = fmaf(f, pa[j][r][e], v[r][e]);
                 }
+        };
+        load_batch(0);
 #pragma unroll
-                for (int e = 0; e < CPT; ++e) v[r][e] = 0.f;
+        for (int r = 0; r < RG; ++r) {
+            gmax[r] = -__builtin_inff();
+#pragma unroll
+            for (int s = 0; s < kSoftmaxMaxSplits; ++s) gmax[r] = fmaxf(gmax[r], mls[s][r][0]);
+            den[r] = 0.f;
+#pragma unroll
+            for (int s = 0; s < kSoftmaxMaxSplits; ++s) {
+                fac[s][r] = (s < S && out_ok[r]) ? __builtin_amdgcn_exp2f((mls[s][r][0] - gmax[r]) * kLog2e) : 0.f;
+                den[r] = fmaf(fac[s][r], mls[s][r][1], den[r]);
             }
+#pragma unroll
+            for (int e = 0; e < CPT; ++e) v[r][e] = 0.f;
         }
-        constexpr int BATCH = 4;
-#pragma unroll
-        for (int s0 = 0; s0 < kSoftmaxMaxSplits; s0 += BATCH) {
-            if (s0 >= S) break;
-            float pa[BATCH][RG][CPT];
-#pragma unroll
-            for (int j = 0; j < BATCH; ++j)
-#pragma unroll
-                for (int r = 0; r < RG; ++r)
-                    if (out_ok[r])
-                        load_partial<CPT>(racc, acc_part, ((size_t)min(s0 + j, S - 1) * M + (m0 + 16 * r + m)) * N + n, pa[j][r]);
-#pragma unroll
-            for (int j = 0; j < BATCH; ++j)
-#pragma unroll
-                for (int r = 0; r < RG; ++r)
-                    if (out_ok[r]) {
-                        const float f = fac[s0 + j][r];  // zero past the last slice
-#pragma unroll
-                        for (int e = 0; e < CPT; ++e) v[r][e] = fmaf(f, pa[j][r][e], v[r][e]);
-                    }
+        add_batch(0);
+        if (S > BATCH) {
+            load_batch(BATCH);
+            add_batch(BATCH);
         }
     }
 
