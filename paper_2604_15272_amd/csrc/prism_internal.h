@@ -71,8 +71,7 @@ struct AttentionWorkspace {
 // Geometry of the softmax kernel: rows of X and columns of W per workgroup.
 constexpr int kSoftmaxRows = 16;
 constexpr int kSoftmaxTileN = 128;
-// The K-split softmax kernel: rows per workgroup, most K-slices, and the 32-deep K-blocks of X a wavefront
-// keeps in registers between its two passes.
+// The K-split softmax kernel: rows per workgroup and most K-slices.
 constexpr int kSoftmaxSplitRows = 32;
 constexpr int kSoftmaxMaxSplits = 16;
 
