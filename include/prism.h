@@ -218,7 +218,8 @@ prism_status_t prism_plan(prism_op_t op, int64_t M, int64_t K, int64_t N, prism_
  * Process-wide override for tests and tuning: force a kernel family and/or a split-K factor and
  * a tile variant (0 = automatic for each).  Variants: PRISM_PATH_DECODE with at most 16 rows: 4, 8 or 16
  * wavefronts per workgroup, for gated calls also 104 and 108 (4 or 8 wavefronts, tiles of 64 output columns that
- * hold the products with W1 and with W2 in one matrix-core tile); with more rows: 32 or 64 rows per workgroup;
+ * hold the products with W1 and with W2 in one matrix-core tile); with more rows: 32 or 64 rows per workgroup, or 36 / 68 for the same
+ * row counts with X moved through LDS four K-blocks at a time (calls with one weight matrix only);
  * PRISM_PATH_PREFILL: 1000 * tile_m + tile_n; PRISM_PATH_ROWS: 16 or 32 rows per workgroup (a split applies
  * to 32 only, at most 16 slices).  A forced path that cannot run a shape makes the call
  * return PRISM_ERR_UNSUPPORTED.  The kernels are correct for every admissible value (the paper's

@@ -33,7 +33,8 @@ constexpr int kRedFloats = NW * 16 * TN;  // one row group's partial tiles of al
 
 }  // namespace
 
-template <typename F, bool GATED, int RG>
+// XLDS (calls with one weight matrix): X reaches the wavefront through LDS (see the loop).
+template <typename F, bool GATED, int RG, bool XLDS>
 __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ g,
                                                          const uint16_t* __restrict__ W1,
                                                          const uint16_t* __restrict__ W2, uint16_t* __restrict__ Y,
@@ -101,57 +102,63 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
 
     // With one row block W is read once and streamed past the caches; several row blocks share it through the L2.
     const bool stream_w = gridDim.z == 1;
-    // U K-blocks per trip: sixteen 16-byte row loads of W in flight per lane where the registers allow it.
-    constexpr int U = (!GATED && RG <= 2) ? 2 : 1;
-    for (int i = lwave; i < b_cnt; i += U * LNW) {
-        WRows w1[U], w2[BOTH ? U : 1];
-        u32x4 xr[U][RG], gr[U];
+    if constexpr (XLDS) {
+        static_assert(!GATED, "calls with one weight matrix");
+        // A load of X in MFMA operand layout (lane (q, c): row c, eight K values) touches sixteen rows for 64 bytes
+        // each, and the compute unit's memory path moves such loads at a third of the rate of loads that take 256
+        // contiguous bytes from each of four rows (measured: 17 against 57 bytes per clock).  So a wavefront takes
+        // four consecutive K-blocks at a time (128 K values = 256 bytes of a row) and moves their X into an LDS area
+        // of its own with buffer loads that have the LDS flag, four rows x 256 bytes per instruction; the operand
+        // is then read from LDS.  A load puts lane l's 16 bytes at l * 16 of its 1 KB group; lane l = 16 r + s of
+        // group j fetches the eight K values number s ^ (4 j + r) of row 4 j + r, so the sixteen rows of an operand
+        // read sit in sixteen different slots (no bank conflicts) and four consecutive lanes still fetch one aligned
+        // 64-byte piece.
+        typedef __attribute__((address_space(3))) void* lds_ptr;
+        u32x4* xs_lane = (u32x4*)lds + (size_t)wave * (RG * 256);
+        u32x4* xs_uni = (u32x4*)lds + (size_t)__builtin_amdgcn_readfirstlane(wave) * (RG * 256);
+        const int r4 = lane >> 4, slot = lane & 15;
+        const int nsb = (b_cnt + 3) / 4;  // super-blocks of four K-blocks in this slice
+        const bool gain = (flags & kFlagGain) != 0;
+        for (int sb = lwave; sb < nsb; sb += LNW) {
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int ib = i + u * LNW;
-            const bool has = ib < b_cnt;
-            const u32 woff = has ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange;
-            const int k = (b_beg + ib) * KB + 8 * q;
-            const bool k_ok = has && k < K;
+            for (int r = 0; r < RG; ++r) {
 #pragma unroll
-            for (int r = 0; r < RG; ++r)
-                xr[u][r] = load16(rx, (row_ok[r] && k_ok) ? x_row[r] + (u32)k * 2u : kOutOfRange);
-            gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
-            if (stream_w) {
-                load_w_block<true>(w1[u], rw1, woff, row_bytes);
-                if (BOTH) load_w_block<true>(w2[u], rw2, woff, row_bytes);
-            } else {
-                load_w_block<false>(w1[u], rw1, woff, row_bytes);
-                if (BOTH) load_w_block<false>(w2[u], rw2, woff, row_bytes);
-            }
-        }
-        // Two-matrix calls carry x * g in two parts (scaled_a_operand_split), as in the 16-row kernel.
-        auto products = [&](auto split_c) __attribute__((always_inline)) {
-            constexpr bool SPLIT = decltype(split_c)::value;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                u32x4 a[RG], a_lo[SPLIT ? RG : 1];
-#pragma unroll
-                for (int r = 0; r < RG; ++r) {
-                    if constexpr (SPLIT) scaled_a_operand_split<F>(xr[u][r], gr[u], ss[r], a[r], a_lo[r]);
-                    else a[r] = scaled_a_operand<F>(xr[u][r], gr[u], ss[r]);
+                for (int j = 0; j < 4; ++j) {
+                    const int row = 16 * r + 4 * j + r4;          // of this workgroup's rows
+                    const int oct = slot ^ (4 * j + r4);          // eight K values number oct of the super-block
+                    const int ib = 4 * sb + (oct >> 2);
+                    const int k = (b_beg + 4 * sb) * KB + 8 * oct;
+                    const bool ok = (ib < b_cnt) & (k < K) & (m0 + row < M);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (lds_ptr)(xs_uni + (r * 4 + j) * 64), 16,
+                                                             (int)(ok ? (u32)row * (u32)K * 2u + (u32)k * 2u : kOutOfRange), 0, 0, 0);
                 }
+            }
+            // One block at a time (not unrolled: unrolled, the compiler requests all four blocks' W at once and
+            // runs out of registers; a second W set in flight under the products was measured and gains nothing).
+#pragma unroll 1
+            for (int bb = 0; bb < 4; ++bb) {
+                const int ib = 4 * sb + bb;
+                const bool has = ib < b_cnt;
+                const u32 woff = has ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange;
+                const int k = (b_beg + ib) * KB + 8 * q;
+                WRows w1;
+                u32x4 xr[RG];
+                const u32x4 gl = load16(rg, (gain & has & (k < K)) ? (u32)k * 2u : kOutOfRange);
+                if (stream_w) load_w_block<true>(w1, rw1, woff, row_bytes);
+                else load_w_block<false>(w1, rw1, woff, row_bytes);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this super-block's X is in LDS (and W in registers)
+#pragma unroll
+                for (int r = 0; r < RG; ++r)
+                    xr[r] = xs_lane[r * 256 + (c >> 2) * 64 + (c & 3) * 16 + (((4 * bb + q) ^ c) & 15)];
+                const u32x4 gr = gain ? gl : ones8<F>();
+                u32x4 a[RG];
+#pragma unroll
+                for (int r = 0; r < RG; ++r) a[r] = scaled_a_operand<F>(xr[r], gr, ss[r]);
                 auto step = [&](auto jc) __attribute__((always_inline)) {
                     constexpr int J = decltype(jc)::value;
-                    const u32x4 b1 = b_operand<J>(w1[u]);
+                    const u32x4 b1 = b_operand<J>(w1);
 #pragma unroll
-                    for (int r = 0; r < RG; ++r) {
-                        acc1[r][J] = F::mfma_16x16x32(a[r], b1, acc1[r][J]);
-                        if constexpr (SPLIT) acc1[r][J] = F::mfma_16x16x32(a_lo[r], b1, acc1[r][J]);
-                    }
-                    if (BOTH) {
-                        const u32x4 b2 = b_operand<J>(w2[BOTH ? u : 0]);
-#pragma unroll
-                        for (int r = 0; r < RG; ++r) {
-                            acc2[r][J] = F::mfma_16x16x32(a[r], b2, acc2[r][J]);
-                            if constexpr (SPLIT) acc2[r][J] = F::mfma_16x16x32(a_lo[r], b2, acc2[r][J]);
-                        }
-                    }
+                    for (int r = 0; r < RG; ++r) acc1[r][J] = F::mfma_16x16x32(a[r], b1, acc1[r][J]);
                 };
                 step(std::integral_constant<int, 0>{});
                 step(std::integral_constant<int, 1>{});
@@ -162,8 +169,73 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
                 step(std::integral_constant<int, 6>{});
                 step(std::integral_constant<int, 7>{});
             }
-        };
-        products(std::integral_constant<bool, GATED>{});
+        }
+        __syncthreads();  // the areas are reused by the reduction below
+    } else {
+        // U K-blocks per trip: sixteen 16-byte row loads of W in flight per lane where the registers allow it.
+        constexpr int U = (!GATED && RG <= 2) ? 2 : 1;
+        for (int i = lwave; i < b_cnt; i += U * LNW) {
+            WRows w1[U], w2[BOTH ? U : 1];
+            u32x4 xr[U][RG], gr[U];
+    #pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int ib = i + u * LNW;
+                const bool has = ib < b_cnt;
+                const u32 woff = has ? w_lane + (u32)ib * KB * row_bytes : kOutOfRange;
+                const int k = (b_beg + ib) * KB + 8 * q;
+                const bool k_ok = has && k < K;
+    #pragma unroll
+                for (int r = 0; r < RG; ++r)
+                    xr[u][r] = load16(rx, (row_ok[r] && k_ok) ? x_row[r] + (u32)k * 2u : kOutOfRange);
+                gr[u] = (flags & kFlagGain) ? load16(rg, k_ok ? (u32)k * 2u : kOutOfRange) : ones8<F>();
+                if (stream_w) {
+                    load_w_block<true>(w1[u], rw1, woff, row_bytes);
+                    if (BOTH) load_w_block<true>(w2[u], rw2, woff, row_bytes);
+                } else {
+                    load_w_block<false>(w1[u], rw1, woff, row_bytes);
+                    if (BOTH) load_w_block<false>(w2[u], rw2, woff, row_bytes);
+                }
+            }
+            // Two-matrix calls carry x * g in two parts (scaled_a_operand_split), as in the 16-row kernel.
+            auto products = [&](auto split_c) __attribute__((always_inline)) {
+                constexpr bool SPLIT = decltype(split_c)::value;
+    #pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    u32x4 a[RG], a_lo[SPLIT ? RG : 1];
+    #pragma unroll
+                    for (int r = 0; r < RG; ++r) {
+                        if constexpr (SPLIT) scaled_a_operand_split<F>(xr[u][r], gr[u], ss[r], a[r], a_lo[r]);
+                        else a[r] = scaled_a_operand<F>(xr[u][r], gr[u], ss[r]);
+                    }
+                    auto step = [&](auto jc) __attribute__((always_inline)) {
+                        constexpr int J = decltype(jc)::value;
+                        const u32x4 b1 = b_operand<J>(w1[u]);
+    #pragma unroll
+                        for (int r = 0; r < RG; ++r) {
+                            acc1[r][J] = F::mfma_16x16x32(a[r], b1, acc1[r][J]);
+                            if constexpr (SPLIT) acc1[r][J] = F::mfma_16x16x32(a_lo[r], b1, acc1[r][J]);
+                        }
+                        if (BOTH) {
+                            const u32x4 b2 = b_operand<J>(w2[BOTH ? u : 0]);
+    #pragma unroll
+                            for (int r = 0; r < RG; ++r) {
+                                acc2[r][J] = F::mfma_16x16x32(a[r], b2, acc2[r][J]);
+                                if constexpr (SPLIT) acc2[r][J] = F::mfma_16x16x32(a_lo[r], b2, acc2[r][J]);
+                            }
+                        }
+                    };
+                    step(std::integral_constant<int, 0>{});
+                    step(std::integral_constant<int, 1>{});
+                    step(std::integral_constant<int, 2>{});
+                    step(std::integral_constant<int, 3>{});
+                    step(std::integral_constant<int, 4>{});
+                    step(std::integral_constant<int, 5>{});
+                    step(std::integral_constant<int, 6>{});
+                    step(std::integral_constant<int, 7>{});
+                }
+            };
+            products(std::integral_constant<bool, GATED>{});
+        }
     }
 
 #pragma unroll
@@ -308,13 +380,13 @@ __global__ __launch_bounds__(NT) void decode_rows_kernel(const uint16_t* __restr
     }
 }
 
-template <typename F, bool GATED, int RG>
+template <typename F, bool GATED, int RG, bool XLDS>
 static hipError_t launch_rows(const Call& c, int S, const DecodeWorkspace& ws) {
     const int n_tiles = (c.N + TN - 1) / TN;
     const int row_blocks = (c.M + 16 * RG - 1) / (16 * RG);
     dim3 grid(n_tiles, S, row_blocks), block(NT);
     const size_t lds = (size_t)(2 * kRedFloats + NW * 16 * RG) * sizeof(float);
-    auto kern = decode_rows_kernel<F, GATED, RG>;
+    auto kern = decode_rows_kernel<F, GATED, RG, XLDS>;
     static std::atomic<uint64_t> opted{0};
     if (hipError_t e = allow_large_lds((const void*)kern, lds, opted); e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, grid, block, lds, c.stream, (const uint16_t*)c.X, (const uint16_t*)c.g,
@@ -324,19 +396,22 @@ static hipError_t launch_rows(const Call& c, int S, const DecodeWorkspace& ws) {
 }
 
 template <typename F>
-static hipError_t launch_rows_fmt(const Call& c, int split_k, int row_groups, const DecodeWorkspace& ws) {
+static hipError_t launch_rows_fmt(const Call& c, int split_k, int row_groups, bool xlds, const DecodeWorkspace& ws) {
     if (c.gated) {
-        if (row_groups == 2) return launch_rows<F, true, 2>(c, split_k, ws);
-        if (row_groups == 4) return launch_rows<F, true, 4>(c, split_k, ws);
+        if (xlds) return hipErrorInvalidValue;
+        if (row_groups == 2) return launch_rows<F, true, 2, false>(c, split_k, ws);
+        if (row_groups == 4) return launch_rows<F, true, 4, false>(c, split_k, ws);
     } else {
-        if (row_groups == 2) return launch_rows<F, false, 2>(c, split_k, ws);
-        if (row_groups == 4) return launch_rows<F, false, 4>(c, split_k, ws);
+        if (row_groups == 2) return xlds ? launch_rows<F, false, 2, true>(c, split_k, ws) : launch_rows<F, false, 2, false>(c, split_k, ws);
+        if (row_groups == 4) return xlds ? launch_rows<F, false, 4, true>(c, split_k, ws) : launch_rows<F, false, 4, false>(c, split_k, ws);
     }
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, const DecodeWorkspace& ws) {
-    return f16 ? launch_rows_fmt<F16>(c, split_k, row_groups, ws) : launch_rows_fmt<Bf16>(c, split_k, row_groups, ws);
+hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, bool xlds,
+                                    const DecodeWorkspace& ws) {
+    return f16 ? launch_rows_fmt<F16>(c, split_k, row_groups, xlds, ws)
+               : launch_rows_fmt<Bf16>(c, split_k, row_groups, xlds, ws);
 }
 
 }  // namespace prism

@@ -127,6 +127,7 @@ struct Plan {
     prism_plan_t pub;
     int waves;          // decode: wavefronts per workgroup
     int row_groups;     // decode: 16-row groups per workgroup (1: the 16-row kernel)
+    bool xlds;          // decode, several row groups: X through LDS
     bool packed;        // decode, 16-row kernel, gated: 64 output columns per tile, both matrices in one MFMA tile
     StreamPartition sp; // decode, 16-row kernel: weighted partition (G = 0: plain grid); slow = the slots, not yet
                         // rotated to the address of W
@@ -424,7 +425,7 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         if ((uint64_t)M * K * 2 >= kTwoGiB) return PRISM_ERR_UNSUPPORTED;
         // Variant: 4, 8 or 16 wavefronts for at most 16 rows; 32 or 64 rows per workgroup for more.
         int waves = 8, row_groups = 1;
-        bool packed = false;
+        bool packed = false, xlds = false;
         if (M <= kDecodeMaxRows) {
             // Variants 4, 8, 16: wavefronts per workgroup; 104, 108 (gated only): the same with the packed tile.
             int v = variant;
@@ -441,8 +442,15 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
             // registers (gated: two weight matrices) or the row count say 32.
             row_groups = decode_row_groups(gated, M, K, N);
             if (row_groups == 0) row_groups = 4;  // forced onto a shape the heuristic leaves to prefill
+            // Variants 32 / 64: rows per workgroup, X loaded straight into operand registers; 36 / 68 (one weight
+            // matrix only): the same with X through LDS (wide loads of four K-blocks at a time).  Not forced: the
+            // second form where a slice gives every wavefront at least two of those super-blocks.
             if (variant == 32 || variant == 64) row_groups = variant / 16;
-            else if (variant != 0 && variant != 8) return PRISM_ERR_UNSUPPORTED;
+            else if (variant == 36 || variant == 68) {
+                if (gated) return PRISM_ERR_UNSUPPORTED;
+                row_groups = (variant - 4) / 16;
+                xlds = true;
+            } else if (variant != 0 && variant != 8) return PRISM_ERR_UNSUPPORTED;
         }
         const int64_t kblocks = (K + kDecodeKBlock - 1) / kDecodeKBlock;
         // Packed tiles with more K-slices for the tiles in slow units (s_slow against s): gated, at most 16 rows,
@@ -593,8 +601,12 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
                 }
             }
         }
+        // Measured (us, X through LDS against straight loads): 512 x 4096 x 4096 32.1 / 34.1, 256 x 14336 x 4096
+        // 56.6 / 65.5, 1024 x 4096 x 6144 85.4 / 92.7; with slices of 16 K-blocks (64 x 4096 x 4096) 18.3 / 16.7.
+        if (row_groups > 1 && !gated && variant == 0 && kblocks / std::max<int64_t>(1, S) >= 64) xlds = true;
         out->waves = waves;
         out->row_groups = row_groups;
+        out->xlds = xlds;
         out->packed = packed;
         out->sp = sp;
         out->base_split = (int)S;
@@ -753,7 +765,7 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                 }
             }
             err = plan.row_groups > 1
-                      ? launch_decode_rows_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.row_groups, ws)
+                      ? launch_decode_rows_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.row_groups, plan.xlds, ws)
                       : launch_decode_16bit(c, dtype == PRISM_F16, split, sp, plan.waves, plan.packed, ws);
             break;
         }

@@ -118,7 +118,8 @@ hipError_t launch_simple_f16(const Call& c);
 struct StreamPartition;
 hipError_t launch_decode_16bit(const Call& c, bool f16, int split_k, const StreamPartition& sp, int waves, bool packed,
                                const DecodeWorkspace& ws);
-hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, const DecodeWorkspace& ws);
+hipError_t launch_decode_rows_16bit(const Call& c, bool f16, int split_k, int row_groups, bool xlds,
+                                    const DecodeWorkspace& ws);
 hipError_t launch_prefill_16bit(const Call& c, bool f16, int tile_m, int tile_n);
 hipError_t launch_softmax_rows_16bit(const SoftmaxCall& c, bool f16);
 hipError_t launch_softmax_split_16bit(const SoftmaxCall& c, bool f16, int split_k, const SoftmaxWorkspace& ws);

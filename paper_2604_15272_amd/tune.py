@@ -16,7 +16,8 @@ import random
 
 from . import binding as B
 
-_DECODE_VARIANTS = (4, 8, 16, 32, 64)   # wavefronts (at most 16 rows) or rows per workgroup (more)
+_DECODE_VARIANTS = (4, 8, 16, 32, 64, 36, 68)   # wavefronts (at most 16 rows) or rows per workgroup (more; 36, 68:
+                                                # X through LDS, one weight matrix only)
 _PACKED_VARIANTS = (104, 108)           # gated, at most 16 rows: 4 or 8 wavefronts on tiles of 64 output columns
 _SOFTMAX_MAX_SPLIT = 16
 _DECODE_MAX_ROWS = 512                  # the decode path re-reads W per row block: not worth timing beyond

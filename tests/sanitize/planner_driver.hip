@@ -14,7 +14,7 @@ hipError_t launch_simple_f32(const Call&) { return hipSuccess; }
 hipError_t launch_simple_bf16(const Call&) { return hipSuccess; }
 hipError_t launch_simple_f16(const Call&) { return hipSuccess; }
 hipError_t launch_decode_16bit(const Call&, bool, int, const StreamPartition&, int, bool, const DecodeWorkspace&) { return hipSuccess; }
-hipError_t launch_decode_rows_16bit(const Call&, bool, int, int, const DecodeWorkspace&) { return hipSuccess; }
+hipError_t launch_decode_rows_16bit(const Call&, bool, int, int, bool, const DecodeWorkspace&) { return hipSuccess; }
 hipError_t launch_prefill_16bit(const Call&, bool, int, int) { return hipSuccess; }
 hipError_t launch_softmax_rows_16bit(const SoftmaxCall&, bool) { return hipSuccess; }
 hipError_t launch_softmax_split_16bit(const SoftmaxCall&, bool, int, const SoftmaxWorkspace&) { return hipSuccess; }

@@ -289,6 +289,33 @@ def test_decode_rows_every_split_and_row_count(P, split, rows, gated):
     _case(P, pi.BF16, 75, 2056, 1160, gated, seed=470, path=P.PRISM_PATH_DECODE, split=split, variant=rows)
 
 
+@pytest.mark.parametrize("rows", [36, 68])
+@pytest.mark.parametrize("split", [1, 2, 3, 7, 16, 33])
+def test_decode_rows_with_x_through_lds_every_split_and_row_count(P, split, rows):
+    """The same for the loop that moves X through LDS four K-blocks at a time (variants 36 / 68): slices that are
+    no multiple of four K-blocks, slices shorter than a wavefront's share, ragged K, N and M."""
+    _case(P, pi.BF16, 75, 2056, 1160, False, seed=470, path=P.PRISM_PATH_DECODE, split=split, variant=rows)
+
+
+@pytest.mark.parametrize("dtype,M,K,N", [(pi.BF16, 512, 4096, 1024), (pi.F16, 200, 4104, 520), (pi.BF16, 33, 2048, 136),
+                                         (pi.F16, 500, 8192, 256)])
+def test_decode_rows_with_x_through_lds_as_dispatched(P, dtype, M, K, N):
+    """Long slices of one weight matrix: the dispatcher takes that loop by itself; with and without gain."""
+    plan = P.prism_plan(0, M, K, N, DTYPE_CODE[dtype])
+    assert plan["path"] == P.PRISM_PATH_DECODE and plan["tile_m"] in (32, 64), plan
+    _case(P, dtype, M, K, N, False, seed=475)
+    _variant_case(P, dtype, M, K, N, "plain_nogain", seed=476)
+
+
+def test_x_through_lds_is_refused_for_two_weight_matrices(P):
+    P.prism_set_override(P.PRISM_PATH_DECODE, 0, 68)
+    try:
+        with pytest.raises(P.PrismError):
+            P.prism_plan(1, 64, 4096, 4096, P.PRISM_BF16)
+    finally:
+        P.prism_set_override(0, 0, 0)
+
+
 @pytest.mark.parametrize("gated", [False, True])
 def test_decode_rows_f16_and_forced_beyond_the_automatic_range(P, gated):
     _case(P, pi.F16, 300, 1024, 264, gated, seed=480, path=P.PRISM_PATH_DECODE)
