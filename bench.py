@@ -472,6 +472,35 @@ def measure_mfma_ceiling(iters=4000):
             "note": "prism_probe_mfma: matrix pipes alone (a launch of about 1 ms; longer runs clock lower)"}
 
 
+def measure_cu_load_path(reps=8):
+    """The library's load-shape probe (prism_probe_loads): bytes per shader clock that one compute unit's vector-memory
+    path delivers, on L2-resident data, for four shapes of load instruction.  The multi-row decode kernels and the
+    softmax kernels are bound by this path, and the operand-layout shape is the slow one."""
+    import torch
+    import paper_2604_15272_amd as P
+    vp = ctypes.c_void_p
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    wgs = P.prism_diag_cu_count()
+    buf = torch.ones(P.PROBE_LOADS_BYTES, dtype=torch.uint8, device="cuda")
+    ticks = torch.zeros(8 * wgs, dtype=torch.int64, device="cuda")
+    names = ("four rows x 256 B per instruction (W of the decode kernels)", "sixteen rows x 64 B (an operand read in MFMA layout)",
+             "eight rows x 128 B (X requests of the prefill kernel)", "four rows x 128 B with 8-byte loads")
+    out = []
+    for pattern, name in enumerate(names):
+        vals = []
+        for _ in range(3):
+            st = P.lib.prism_probe_loads(vp(buf.data_ptr()), ctypes.c_uint64(buf.numel()), pattern, reps, wgs,
+                                         vp(ticks.data_ptr()), stream)
+            if st != 0:
+                raise RuntimeError("prism_probe_loads failed")
+            torch.cuda.synchronize()
+            per_wg = reps * P.PROBE_LOADS_BYTES * (0.5 if pattern == 3 else 1.0)
+            vals.append(per_wg / float(ticks.double().mean().item()))
+        out.append({"pattern": name, "bytes_per_clock_per_cu": median(vals)})
+        log(f"[bench]   one compute unit's load path, {name}: {median(vals):.1f} B/clk")
+    return out
+
+
 def measure_stream_patterns(runner, steps=400, warmup=20):
     """The headline workload's weight bytes (32 MiB per buffer set, the same rotating sets) read with other access
     patterns, nothing computed: front to back in 256 contiguous pieces, and as stripes of other shapes (the stream
@@ -709,6 +738,7 @@ def main():
     traffic = measured_traffic(head["workload"])
     stream_patterns = measure_stream_patterns(runner) if head["bound"] == "hbm" else None
     copy_ceiling, mfma_ceiling = measure_copy_ceiling(), measure_mfma_ceiling()
+    cu_load_path = measure_cu_load_path()
     log(f"[bench] measured ceilings: device copy {copy_ceiling['GBps']:.0f} GB/s (read + written), matrix pipes alone "
         f"{mfma_ceiling['TFLOPs']:.0f} TFLOP/s")
     out = {
@@ -737,7 +767,8 @@ def main():
                      "kernel_ms_per_launch_min": head["event_ms_per_step_min"],
                      "timing": "HIP events around each timed region on the launch stream, divided by the region's "
                                "launches (an average per launch, launch gaps included); median of the regions",
-                     "copy_ceiling": copy_ceiling, "mfma_ceiling": mfma_ceiling, "stream_patterns": stream_patterns},
+                     "copy_ceiling": copy_ceiling, "mfma_ceiling": mfma_ceiling, "stream_patterns": stream_patterns,
+                     "cu_load_path": cu_load_path},
         "slow_units": {"mask": det["mask"], "us_per_unit": det["us"], "median_us": det["median_us"],
                        "note": "tune.detect_slow_units: prism_probe_units, all sixteen units read at once, median workgroup time per unit"},
     }

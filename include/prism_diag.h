@@ -45,6 +45,19 @@ prism_status_t prism_probe_stream(const void* W, const void* W2, int64_t K, int6
 prism_status_t prism_probe_units(const void* base, uint64_t bytes, int32_t groups, uint64_t* ticks, hipStream_t stream);
 
 /*
+ * For measurement: what one compute unit's vector-memory path delivers for a given shape of load instruction on data
+ * that stays in the L2.  `workgroups` workgroups of eight wavefronts each read the first PRISM_PROBE_LOADS_BYTES of
+ * [base, base + bytes) (device memory, 16-byte aligned; 128 rows of 8 KiB) `reps` times, eight loads in flight per
+ * lane, and compute nothing.  pattern 0: four rows x 256 contiguous bytes per instruction (how the decode kernels
+ * read W); 1: sixteen rows x 64 bytes (an MFMA A operand read straight from a row-major matrix); 2: eight rows x
+ * 128 bytes; 3: four rows x 128 bytes with 8-byte loads.  ticks (device memory, 8 * workgroups words of 8 bytes)
+ * receives the shader-clock cycles of every wavefront; a workgroup moves reps * 1 MiB (pattern 3: half of that).
+ */
+#define PRISM_PROBE_LOADS_BYTES 1048576u
+prism_status_t prism_probe_loads(const void* base, uint64_t bytes, int32_t pattern, int32_t reps, int32_t workgroups,
+                                 uint64_t* ticks, hipStream_t stream);
+
+/*
  * For measurement: reads [base, base + bytes) (device memory, 16-byte aligned, bytes a multiple of 16) once, front to
  * back: workgroup j of `workgroups` streams the j-th contiguous piece and computes nothing.  The same bytes as a
  * weight matrix without any stripe structure: a second opinion on what streaming them costs.  sink: 4 bytes of

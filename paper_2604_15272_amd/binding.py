@@ -80,6 +80,8 @@ def _load():
     L.prism_set_stream_workspace.restype = i32
     L.prism_probe_units.argtypes = [vp, u64, i32, vp, vp]
     L.prism_probe_units.restype = i32
+    L.prism_probe_loads.argtypes = [vp, u64, i32, i32, i32, vp, vp]
+    L.prism_probe_loads.restype = i32
     L.prism_probe_linear.argtypes = [vp, u64, i32, vp, vp]
     L.prism_probe_linear.restype = i32
     L.prism_probe_mfma.argtypes = [vp, i32, i32, vp]
@@ -263,6 +265,7 @@ def prism_rmsnorm_matmul(X, g, W, Y, M=None, K=None, N=None, eps=1e-6, dtype=Non
 
 
 STATIC_SCRATCH_BYTES = 8388608
+PROBE_LOADS_BYTES = 1048576   # PRISM_PROBE_LOADS_BYTES: what prism_probe_loads reads
 
 
 def prism_rmsnorm_matmul_static(X, g, W, Y, M=None, K=None, N=None, eps=1e-6, dtype=None, stream=None):

@@ -1069,6 +1069,15 @@ prism_status_t prism_probe_units(const void* base, uint64_t bytes, int32_t group
                ? PRISM_OK : PRISM_ERR_HIP;
 }
 
+prism_status_t prism_probe_loads(const void* base, uint64_t bytes, int32_t pattern, int32_t reps, int32_t workgroups,
+                                 uint64_t* ticks, hipStream_t stream) {
+    if (!base || !ticks || !aligned16(base) || ((uintptr_t)ticks & 7u) != 0 || pattern < 0 || pattern > 3 || reps < 1 ||
+        reps > 4096 || workgroups < 1 || workgroups > 65535 || bytes < PRISM_PROBE_LOADS_BYTES)
+        return PRISM_ERR_INVALID_ARG;
+    return launch_probe_loads(base, pattern, reps, workgroups, (unsigned long long*)ticks, stream) == hipSuccess
+               ? PRISM_OK : PRISM_ERR_HIP;
+}
+
 prism_status_t prism_probe_linear(const void* base, uint64_t bytes, int32_t workgroups, void* sink, hipStream_t stream) {
     if (!base || !sink || !aligned16(base) || workgroups < 1 || workgroups > 65535 || bytes < 1024ull * (uint64_t)workgroups ||
         bytes % 16 != 0)

@@ -126,6 +126,8 @@ hipError_t launch_softmax_split_16bit(const SoftmaxCall& c, bool f16, int split_
 hipError_t launch_probe_stream(const void* W, const void* W2, unsigned* sink, int K, int N, int S, hipStream_t stream);
 hipError_t launch_probe_units(const void* base, unsigned blocks_per_group, int groups, unsigned long long* ticks,
                               hipStream_t stream);
+hipError_t launch_probe_loads(const void* base, int pattern, int reps, int workgroups, unsigned long long* ticks,
+                              hipStream_t stream);
 hipError_t launch_probe_linear(const void* base, unsigned long long bytes, int workgroups, unsigned* sink, hipStream_t stream);
 hipError_t launch_probe_mfma(float* sink, int workgroups, int iters, hipStream_t stream);
 hipError_t launch_softmax_simple(const SoftmaxCall& c, int dtype);

@@ -82,6 +82,63 @@ hipError_t launch_probe_units(const void* base, unsigned blocks_per_group, int g
     return hipGetLastError();
 }
 
+// What one compute unit's vector-memory path delivers for a given shape of load instruction, on data that stays in
+// the L2: every workgroup (eight wavefronts, eight loads in flight per lane) reads the same 1 MiB region `reps`
+// times and computes nothing; ticks[8 j + w] receives the shader clock cycles wavefront w of workgroup j needed.
+// The region is 128 rows of 8 KiB; a "block" is eight load instructions = 8 KiB (4 KiB for pattern 3), 128 blocks.
+//   0: four rows x 256 contiguous bytes per instruction (how the decode kernels read W)
+//   1: sixteen rows x 64 bytes per instruction (an X operand in MFMA layout: lane (q, c) = row c, eight K values)
+//   2: eight rows x 128 bytes per instruction (how the prefill kernel requests X)
+//   3: four rows x 128 bytes per instruction with 8-byte loads
+template <int PATTERN>
+__global__ __launch_bounds__(512) void probe_loads_kernel(const unsigned char* __restrict__ base, int reps,
+                                                          unsigned long long* __restrict__ ticks) {
+    constexpr u32 kPitch = 8192;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u32 q = lane >> 4, c = lane & 15;
+    const __amdgpu_buffer_rsrc_t r = make_rsrc(base, 128u * kPitch);  // the host checked that the buffer holds it
+    u32 acc = 0;
+    const unsigned long long t0 = __builtin_readcyclecounter();
+    for (int rep = 0; rep < reps; ++rep) {
+        for (u32 ib = wave; ib < 128; ib += 8) {
+            if constexpr (PATTERN == 3) {
+                u32x2 v[8];
+#pragma unroll
+                for (u32 i = 0; i < 8; ++i)
+                    v[i] = __builtin_amdgcn_raw_buffer_load_b64(r, (int)((4 * i + q + 32 * (ib & 3)) * kPitch + (ib >> 2) * 128 + 8 * c), 0, 0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc ^= v[i][0] ^ v[i][1];
+            } else {
+                u32x4 v[8];
+#pragma unroll
+                for (u32 i = 0; i < 8; ++i) {
+                    u32 off;
+                    if (PATTERN == 0) off = (4 * i + q + 32 * (ib & 3)) * kPitch + (ib >> 2) * 256 + 16 * c;
+                    else if (PATTERN == 1) off = (16 * i + c) * kPitch + (ib * 32 + 8 * q) * 2;
+                    else off = (8 * i + (lane >> 3) + 64 * (ib & 1)) * kPitch + (ib >> 1) * 128 + 16 * (lane & 7);
+                    v[i] = load16(r, off);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc ^= v[i][0] ^ v[i][1] ^ v[i][2] ^ v[i][3];
+            }
+        }
+    }
+    // the values are consumed before the clock is read again: the loads have landed
+    const unsigned long long t1 = __builtin_readcyclecounter() + (acc == 0x9E3779B9u ? 1u : 0u);
+    if (lane == 0) ticks[blockIdx.x * 8 + wave] = t1 - t0;
+}
+
+hipError_t launch_probe_loads(const void* base, int pattern, int reps, int workgroups, unsigned long long* ticks,
+                              hipStream_t stream) {
+    const unsigned char* b = (const unsigned char*)base;
+    if (pattern == 0) hipLaunchKernelGGL(probe_loads_kernel<0>, dim3(workgroups), dim3(512), 0, stream, b, reps, ticks);
+    else if (pattern == 1) hipLaunchKernelGGL(probe_loads_kernel<1>, dim3(workgroups), dim3(512), 0, stream, b, reps, ticks);
+    else if (pattern == 2) hipLaunchKernelGGL(probe_loads_kernel<2>, dim3(workgroups), dim3(512), 0, stream, b, reps, ticks);
+    else if (pattern == 3) hipLaunchKernelGGL(probe_loads_kernel<3>, dim3(workgroups), dim3(512), 0, stream, b, reps, ticks);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 // A buffer read front to back: workgroup j streams the j-th of gridDim.x equal contiguous pieces (every wavefront
 // instruction covers 1 KiB of consecutive bytes, sixteen 16-byte loads in flight per lane, non-temporal).  The
 // simplest access pattern there is: what the same bytes cost when no stripe structure is imposed on them.

@@ -21,6 +21,7 @@ hipError_t launch_softmax_split_16bit(const SoftmaxCall&, bool, int, const Softm
 hipError_t launch_probe_stream(const void*, const void*, unsigned*, int, int, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_units(const void*, unsigned, int, unsigned long long*, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_mfma(float*, int, int, hipStream_t) { return hipSuccess; }
+hipError_t launch_probe_loads(const void*, int, int, int, unsigned long long*, hipStream_t) { return hipSuccess; }
 hipError_t launch_probe_linear(const void*, unsigned long long, int, unsigned*, hipStream_t) { return hipSuccess; }
 hipError_t launch_softmax_simple(const SoftmaxCall&, int) { return hipSuccess; }
 hipError_t launch_gqa_16bit(const AttentionCall&, bool, const AttentionPlan&, const AttentionWorkspace&) { return hipSuccess; }

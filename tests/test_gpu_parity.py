@@ -906,6 +906,29 @@ def test_two_streams_with_workspaces_of_their_own_run_split_k_calls_at_the_same_
     assert torch.equal(Y.view(torch.uint16), ref[0].view(torch.uint16))
 
 
+def test_load_shape_probe_finds_the_operand_layout_slow(P):
+    """prism_probe_loads: whole 128-byte lines per row move at several times the rate of the 64-byte pieces of an
+    operand read in MFMA layout (the reason the multi-row kernel takes X through LDS)."""
+    import ctypes
+    import torch
+    vp = ctypes.c_void_p
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    wgs, reps = P.prism_diag_cu_count(), 4
+    buf = torch.ones(P.PROBE_LOADS_BYTES, dtype=torch.uint8, device="cuda")
+    ticks = torch.zeros(8 * wgs, dtype=torch.int64, device="cuda")
+    rate = []
+    for pattern in range(4):
+        for _ in range(2):
+            assert P.lib.prism_probe_loads(vp(buf.data_ptr()), ctypes.c_uint64(buf.numel()), pattern, reps, wgs,
+                                           vp(ticks.data_ptr()), stream) == 0
+            torch.cuda.synchronize()
+        assert int(ticks.min()) > 0
+        rate.append(reps * P.PROBE_LOADS_BYTES * (0.5 if pattern == 3 else 1.0) / float(ticks.double().mean()))
+    print("bytes per clock and compute unit by load shape:", [round(r, 1) for r in rate], flush=True)
+    assert 20.0 < rate[0] < 140.0 and 20.0 < rate[2] < 140.0 and 4.0 < rate[1] < 140.0
+    assert rate[0] > 1.5 * rate[1] and rate[2] > 1.5 * rate[1]
+
+
 def test_slow_unit_detection_and_probes_run(P):
     """The tuner's measurement of the sixteen address units and the matrix-pipe probe run and return sane figures
     (which units are slow differs between machines: the mask is printed, not asserted)."""

@@ -116,6 +116,15 @@ def test_probe_arguments_need_no_device(P):
     assert pr(N=4100) == 2 and pr(S=129) == 2 and pr(K=1 << 20, N=1 << 20, S=1) == 2
 
 
+def test_load_probe_arguments_need_no_device(P):
+    L, a = P.lib, 0x1000
+    pr = lambda base=a, nbytes=P.PROBE_LOADS_BYTES, pattern=0, reps=1, wgs=1, ticks=a: L.prism_probe_loads(
+        base, nbytes, pattern, reps, wgs, ticks, None)
+    assert pr(base=None) == 1 and pr(ticks=None) == 1 and pr(base=a + 4) == 1 and pr(ticks=a + 4) == 1
+    assert pr(nbytes=P.PROBE_LOADS_BYTES - 1) == 1 and pr(pattern=4) == 1 and pr(pattern=-1) == 1
+    assert pr(reps=0) == 1 and pr(wgs=0) == 1 and pr(wgs=70000) == 1
+
+
 def test_softmax_matmul_arguments_and_plan(P):
     L = P.lib
     a = 0x1000
