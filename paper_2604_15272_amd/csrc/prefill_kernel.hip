@@ -299,7 +299,6 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    constexpr int NI0 = (NI + 2) / 3;  // instructions of part 0: those with i * 3 MF / NI < MF
 
     // One phase, as MF slots.  Slot q issues MFMA q on the operands read during the previous phase,
     // reads its share of the next operands (from `a_rd`/`b_rd`, 16-deep phase `kk_rd`), and does its
@@ -423,7 +422,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(const uint16_t* __restrict
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int p = 0; p < P3; ++p) stage_w_piece(ws_a, Bs + B_SLOTS, p / (KR / 2), p % (KR / 2));
-    // X of tile 0 is older than everything but its own requests: 2 NWL + NI0 younger instructions would do; the
+    // X of tile 0 is older than everything but its own requests: 2 NWL + (NI + 2) / 3 younger instructions (part 0 of the refill) would do; the
     // prologue runs once, so it simply waits for everything (and does not depend on the order above).
     stage_barrier(integral_constant<int, 0>{});
     read_frags(As, Bs, 0, xfA, wfA);
