@@ -324,7 +324,27 @@ __global__ __launch_bounds__(NW * 64) void decode_kernel(const uint16_t* __restr
         // Plain grid: column tiles x S_grid equal K-slices.
         const int split = blockIdx.y;
         const int per = kblocks / S_grid, rem = kblocks % S_grid;
-        pass(blockIdx.x, split, S_grid, split * per + min(split, rem), per + (split < rem ? 1 : 0));
+        // Workgroups start in the order of their numbers.  With sp.slow set (bit j: column tiles j, j + 8, ... lie in
+        // address units that stream slowly; the tile count is a multiple of 8) those tiles get the first numbers: in
+        // a launch of several rounds the workgroups that start last then are not the ones that take longest.
+        int tile = blockIdx.x;
+        if (sp.slow != 0) {
+            const uint32_t c_slow = (uint32_t)__builtin_popcount(sp.slow & 0xFFu), n_slow = (gridDim.x >> 3) * c_slow;
+            uint32_t pos = blockIdx.x, mask = sp.slow & 0xFFu, c = c_slow;
+            if (pos >= n_slow) {
+                pos -= n_slow;
+                mask ^= 0xFFu;
+                c = 8u - c_slow;
+            }
+            uint32_t nth = pos % c, bit = 0;  // the nth set bit of mask
+            for (uint32_t j = 0; j < 8; ++j) {
+                const bool set = (mask >> j) & 1u;
+                if (set && nth == 0) bit = j;
+                nth -= set ? 1u : 0u;
+            }
+            tile = (int)(8u * (pos / c) + bit);
+        }
+        pass(tile, split, S_grid, split * per + min(split, rem), per + (split < rem ? 1 : 0));
         return;
     }
     // Weighted partition: this workgroup's range of weight units covers K-blocks of at most two tiles (the host

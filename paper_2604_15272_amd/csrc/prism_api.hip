@@ -701,6 +701,26 @@ prism_status_t make_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, p
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// A plain grid of 128-column tiles over a W whose row pitch is a multiple of 2 KiB: every tile keeps its two 128-byte
+// address units over all rows, and the tiles in slow units (prism_set_stream_balance) take about 1.4 times as long.
+// When the grid needs more than one round of workgroups, those tiles are started first (decode_kernel.hip); which
+// residues of the tile number modulo 8 they are depends on where W starts.
+StreamPartition slow_tiles_first(const void* W, const void* W2, int64_t N, int64_t n_tiles, int64_t split, bool packed) {
+    StreamPartition sp{};
+    const uint32_t units = (uint32_t)g_slow_units.load() & 0xFFFFu;
+    if (units == 0 || packed || (N * 2) % 2048 != 0 || n_tiles % 8 != 0 || ((uintptr_t)W & 255u) != 0 || n_tiles * split <= cu_count() ||
+        (W2 && (((uintptr_t)W ^ (uintptr_t)W2) & 2047u) != 0))
+        return sp;
+    const uint32_t first_pair = (uint32_t)(((uintptr_t)W >> 8) & 7u);  // tile t covers units 2 (first_pair + t) mod 16, + 1
+    uint32_t mask = 0;
+    for (uint32_t r = 0; r < 8; ++r)
+        if ((units >> (2u * ((first_pair + r) & 7u))) & 3u) mask |= 1u << r;
+    if (mask == 0 || mask == 0xFFu) return sp;
+    sp.slow = mask;
+    sp.period = 8;
+    return sp;
+}
+
 // One call of the family: `flags` says which optional steps it takes (gain is dropped here when g
 // is null).
 prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, const void* W2, void* Y, int64_t M,
@@ -764,6 +784,7 @@ prism_status_t run(prism_op_t op, const void* X, const void* g, const void* W1, 
                     sp.r = (uint32_t)(T % sp.G);
                 }
             }
+            if (plan.row_groups == 1 && sp.G == 0) sp = slow_tiles_first(W1, gated ? W2 : nullptr, N, plan.pub.grid_x, split, plan.packed);
             err = plan.row_groups > 1
                       ? launch_decode_rows_16bit(c, dtype == PRISM_F16, plan.pub.split_k, plan.row_groups, plan.xlds, ws)
                       : launch_decode_16bit(c, dtype == PRISM_F16, split, sp, plan.waves, plan.packed, ws);

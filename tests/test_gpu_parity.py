@@ -165,6 +165,45 @@ def test_decode_weighted_partition_off_a_slot_boundary_and_reproducible(P):
         P.prism_set_stream_balance(0x0808, 0)
 
 
+# ---- decode path, plain grid of more than one round: the tiles in slow units start first ----------------------
+
+@pytest.mark.parametrize("units", [0x0808, 0x0003, 0xF0F0, 0x7FFF])
+@pytest.mark.parametrize("M,K,N,gated", [(16, 512, 40960, False), (5, 256, 33792, False), (16, 256, 34816, True)])
+def test_decode_slow_tiles_first_changes_the_order_only(P, M, K, N, gated, units):
+    """A grid of several rounds numbers its column tiles slow units first; every tile is still computed once and by
+    the same arithmetic, so the result equals the plain order's bit for bit, wherever W starts within 2 KiB."""
+    import torch
+    from gpu_util import to_device, from_device
+    stored = pi.draw(pi.BF16, M, K, N, gated, 470 + units % 89)
+    X, g = (to_device(stored[k], pi.BF16) for k in ("X", "g"))
+    names = ("W1", "W2") if gated else ("W",)
+    yhat = run_oracle(stored, pi.BF16, gated, 1e-6)
+    call = P.prism_rmsnorm_gated_mlp if gated else P.prism_rmsnorm_matmul
+    try:
+        for shift in (0, 128, 384):   # elements: W starts 0, 256 and 768 bytes past a 2 KiB boundary
+            Ws = []
+            for nm in names:
+                flat = torch.empty(K * N + 1024, dtype=torch.bfloat16, device="cuda")
+                off = (-(flat.data_ptr() // 2) % 1024 + shift) % 1024
+                W = flat[off:off + K * N].view(K, N)
+                W.copy_(to_device(stored[nm], pi.BF16))
+                assert W.data_ptr() % 2048 == 2 * shift
+                Ws.append(W)
+            outs = []
+            for u in (0, units):
+                P.prism_set_stream_balance(u, 0)
+                plan = P.prism_plan(int(gated), M, K, N, P.PRISM_BF16)
+                assert plan["path"] == P.PRISM_PATH_DECODE and plan["grid_x"] * plan["grid_y"] > P.prism_diag_cu_count(), plan
+                Y = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+                call(X, g, *Ws, Y)
+                torch.cuda.synchronize()
+                outs.append(Y)
+            assert torch.equal(outs[0].view(torch.uint16), outs[1].view(torch.uint16)), (units, shift)
+            assert_parity(from_device(outs[1], pi.BF16), yhat, pi.BF16, f"slow tiles first, units {units:#x}, W at {2 * shift}")
+    finally:
+        P.prism_set_stream_balance(0x0808, 0)
+
+
 # ---- gated decode, packed tile (64 output columns: W1 and W2 in one matrix-core tile), balanced over slow units ---
 
 def test_decode_grid_that_fits_in_one_round(P, M=16, K=4096, N=11008):
