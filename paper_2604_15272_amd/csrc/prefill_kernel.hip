@@ -521,6 +521,7 @@ static hipError_t launch_prefill_fmt(const Call& c, int tile_m, int tile_n) {
     } else {
         if (tile_m == 256 && tile_n == 256) return launch_tile<F, 256, 256, false>(c);
         if (tile_m == 256 && tile_n == 192) return launch_tile<F, 256, 192, false>(c);
+        if (tile_m == 256 && tile_n == 128) return launch_tile<F, 256, 128, false>(c);
         if (tile_m == 128 && tile_n == 128) return launch_tile<F, 128, 128, false>(c);
         if (tile_m == 64 && tile_n == 64) return launch_tile<F, 64, 64, false>(c);
     }

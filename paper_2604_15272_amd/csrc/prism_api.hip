@@ -147,10 +147,10 @@ struct Tile {
 };
 
 void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm, int* bn) {
-    static const Tile plain[] = {{256, 256, 1.0}, {256, 192, 0.95}, {128, 128, 0.75}, {64, 64, 0.35}};
+    static const Tile plain[] = {{256, 256, 1.0}, {256, 192, 0.95}, {256, 128, 0.8}, {128, 128, 0.75}, {64, 64, 0.35}};
     static const Tile gate[] = {{256, 256, 1.0}, {128, 256, 0.85}, {128, 128, 0.6}};
     const Tile* t = gated ? gate : plain;
-    const int nt = gated ? 3 : 4;
+    const int nt = gated ? 3 : 5;
     if (variant > 0) {
         *bm = variant / 1000;
         *bn = variant % 1000;
@@ -186,7 +186,7 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 //     exchange  = 2.5 + S x RG x matrices / 8 when S > 1 (three dependent round trips, then the last arrival
 //                 pulls S partial tiles through one compute unit)
 //     launch    = 1.5
-//   prefill kernel: K steps x (1.5 / 2.0 for 256-row tiles of one / two matrices, 0.88 to 1.2 for 128-row tiles, 0.93
+//   prefill kernel: K steps x (1.5 / 2.0 for 256-row tiles of one / two matrices, 1.25 for 256 x 128, 0.88 to 1.2 for 128-row tiles, 0.93
 //     for 64 x 64) x 1 if every tile has a compute unit, x 1.3 for up to two 128-row tiles per unit, else the rounds;
 //     + 3.  (A K step of that kernel has a floor of about a microsecond whatever the tile.)
 struct RowsEstimate {
@@ -213,12 +213,12 @@ double prefill_estimate(bool gated, int64_t M, int64_t K, int64_t N, int64_t cus
         int bm, bn;
         double step;
     };
-    static const T plain[] = {{256, 256, 1.5}, {256, 192, 1.5}, {128, 128, 0.88}, {64, 64, 0.93}};
+    static const T plain[] = {{256, 256, 1.5}, {256, 192, 1.5}, {256, 128, 1.25}, {128, 128, 0.88}, {64, 64, 0.93}};
     static const T gate[] = {{256, 256, 2.0}, {128, 256, 1.2}, {128, 128, 0.90}};
     const T* t = gated ? gate : plain;
     const int64_t KT = (K + 63) / 64;
     double best = 1e300;
-    for (int i = 0; i < (gated ? 3 : 4); ++i) {
+    for (int i = 0; i < (gated ? 3 : 5); ++i) {
         const int64_t cw = gated ? t[i].bn / 2 : t[i].bn;
         const int64_t tiles = ((M + t[i].bm - 1) / t[i].bm) * ((N + cw - 1) / cw);
         const double f = tiles <= cus ? 1.0 : ((tiles <= 2 * cus && t[i].bm <= 128) ? 1.3 : (double)((tiles + cus - 1) / cus));
@@ -248,7 +248,8 @@ int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {
 
 bool prefill_tile_known(bool gated, int bm, int bn) {
     if (gated) return (bm == 256 && bn == 256) || (bm == 128 && bn == 256) || (bm == 128 && bn == 128);
-    return (bm == 256 && bn == 256) || (bm == 256 && bn == 192) || (bm == 128 && bn == 128) || (bm == 64 && bn == 64);
+    return (bm == 256 && bn == 256) || (bm == 256 && bn == 192) || (bm == 256 && bn == 128) || (bm == 128 && bn == 128) ||
+           (bm == 64 && bn == 64);
 }
 
 // A parameter assignment (paper Section 5, "parameter instantiation"): kernel family, split-K

@@ -21,7 +21,7 @@ _DECODE_VARIANTS = (4, 8, 16, 32, 64, 36, 68)   # wavefronts (at most 16 rows) o
 _PACKED_VARIANTS = (104, 108)           # gated, at most 16 rows: 4 or 8 wavefronts on tiles of 64 output columns
 _SOFTMAX_MAX_SPLIT = 16
 _DECODE_MAX_ROWS = 512                  # the decode path re-reads W per row block: not worth timing beyond
-_PLAIN_TILES = (256256, 256192, 128128, 64064)
+_PLAIN_TILES = (256256, 256192, 256128, 128128, 64064)
 _GATED_TILES = (256256, 128256, 128128)
 _TORCH_DTYPE = {B.PRISM_F32: "float32", B.PRISM_BF16: "bfloat16", B.PRISM_F16: "float16"}
 

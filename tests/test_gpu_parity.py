@@ -387,7 +387,7 @@ def test_prefill_shapes(P, M, K, N, gated):
     _case(P, pi.BF16, M, K, N, gated, seed=500 + M, path=P.PRISM_PATH_PREFILL, expect_path=P.PRISM_PATH_PREFILL)
 
 
-@pytest.mark.parametrize("gated,variant", [(False, 256256), (False, 256192), (False, 128128), (False, 64064),
+@pytest.mark.parametrize("gated,variant", [(False, 256256), (False, 256192), (False, 256128), (False, 128128), (False, 64064),
                                            (True, 256256), (True, 128256), (True, 128128)])
 def test_prefill_every_tile(P, gated, variant):
     """Table 1, parallelized matmul (row / column partition): the result may not depend on the tiling."""
@@ -550,7 +550,7 @@ def test_f16_paper_variants_at_paper_shapes(P, variant, M, K, N):
     _variant_case(P, pi.F16, M, K, N, variant, seed=910 + M + K)
 
 
-@pytest.mark.parametrize("gated,tile", [(False, 256256), (False, 256192), (False, 128128), (False, 64064),
+@pytest.mark.parametrize("gated,tile", [(False, 256256), (False, 256192), (False, 256128), (False, 128128), (False, 64064),
                                         (True, 256256), (True, 128256), (True, 128128)])
 def test_f16_prefill_every_tile(P, gated, tile):
     _case(P, pi.F16, 300, 712, 648, gated, seed=920, path=P.PRISM_PATH_PREFILL, variant=tile)
@@ -1156,6 +1156,21 @@ def test_prefill_long_k_and_many_rows(P):
         rows = np.unique(np.concatenate([[0, M - 1, min(255, M - 1), min(256, M - 1)],
                                          np.random.Generator(np.random.Philox(seed)).choice(M, 60, replace=False)]))
         assert_parity(y[rows], run_oracle(stored, pi.BF16, True, 1e-6, rows=rows), pi.BF16, f"prefill M={M} K={K} N={N}")
+
+
+def test_prefill_256_by_128_tile_as_dispatched(P):
+    """2048 x 4096 x 4096: the 256 x 128 tile gives every compute unit one workgroup (128 x 128 would need two rounds,
+    256 x 256 fill half the chip); 1000 x 2048 x 8192 has a ragged last row tile.  Sampled rows."""
+    for (M, K, N), seed in (((2048, 4096, 4096), 1520), ((1000, 2048, 8192), 1521)):
+        plan = P.prism_plan(0, M, K, N, P.PRISM_BF16)
+        assert (plan["path"], plan["tile_m"], plan["tile_n"]) == (P.PRISM_PATH_PREFILL, 256, 128), plan
+        assert plan["grid_x"] <= P.prism_diag_cu_count()
+        stored = pi.draw(pi.BF16, M, K, N, False, seed)
+        y = run_gpu(stored, pi.BF16, False, 1e-6)
+        assert np.isfinite(y).all()
+        rows = np.unique(np.concatenate([[0, M - 1, 255, 256, M - 233],
+                                         np.random.Generator(np.random.Philox(seed)).choice(M, 60, replace=False)]))
+        assert_parity(y[rows], run_oracle(stored, pi.BF16, False, 1e-6, rows=rows), pi.BF16, f"256x128 M={M} K={K} N={N}")
 
 
 # ---- degenerate inputs -------------------------------------------------------------------------

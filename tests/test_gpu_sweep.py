@@ -46,7 +46,7 @@ def _forced_choices(P, rng, op, M, K, N, dt):
                 cands += [(P.PRISM_PATH_DECODE, split, int(rng.choice((104, 108)))), (P.PRISM_PATH_DECODE, 0, 108)]
         else:
             cands += [(P.PRISM_PATH_DECODE, split, int(rng.choice((32, 64) if gated else (32, 64, 36, 68))))]
-        tiles = (256256, 128256, 128128) if gated else (256256, 256192, 128128, 64064)
+        tiles = (256256, 128256, 128128) if gated else (256256, 256192, 256128, 128128, 64064)
         cands += [(P.PRISM_PATH_PREFILL, 0, int(rng.choice(tiles)))] * 2
     path, split, variant = cands[int(rng.integers(len(cands)))]
     P.prism_set_override(path, split, variant)

@@ -71,7 +71,7 @@ def _check_compiled_kernel(tmp_path):
     res = subprocess.run(cmd, capture_output=True, text=True)
     assert res.returncode == 0, res.stderr[-2000:]
     waits = hand_written_waits(open(out).read())
-    assert len(waits) == 14, sorted(waits)  # 7 tiles x 2 storage formats
+    assert len(waits) == 16, sorted(waits)  # 8 tiles x 2 storage formats
     for name, seq in waits.items():
         in_loop = [(n, since) for n, since in seq if n > 0]
         assert len(in_loop) >= 2, (name, seq)  # the K loop is unrolled twice, one stage barrier per step
