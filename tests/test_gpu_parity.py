@@ -1191,6 +1191,37 @@ def test_zero_rows_and_zero_input(P):
     torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("dtype,M,K,N,path", [(pi.BF16, 16, 512, 384, 2), (pi.BF16, 40, 512, 384, 2), (pi.BF16, 300, 512, 384, 3),
+                                              (pi.F16, 16, 2048, 1024, 2), (pi.F32, 8, 256, 136, 1)])
+def test_non_finite_inputs_stay_in_their_row_or_column(P, dtype, M, K, N, path):
+    """An infinity or a NaN in X makes its own row NaN (x / rms is NaN there) and no other; an infinity in W gives its
+    column the sign of the normalised x it multiplies, whatever kernel, K-split or tile takes the call."""
+    stored = pi.draw(dtype, M, K, N, False, 1600 + M)
+    inf, nan = {pi.BF16: (0x7F80, 0x7FC0), pi.F16: (np.float16(np.inf), np.float16(np.nan)),
+                pi.F32: (np.float32(np.inf), np.float32(np.nan))}[dtype]
+    r_inf, r_nan, k_w, n_w = 1, M - 2, K // 2 + 3, N - 5
+    clean = {k: v.copy() for k, v in stored.items()}
+    stored["X"][r_inf, 7] = inf
+    stored["X"][r_nan, K - 1] = nan
+    stored["W"][k_w, n_w] = inf
+    P.prism_set_override(path, 0, 0)
+    try:
+        plan = P.prism_plan(0, M, K, N, DTYPE_CODE[dtype])
+        assert plan["path"] == path, plan
+        y = run_gpu(stored, dtype, False, 1e-6)
+    finally:
+        P.prism_set_override(0, 0, 0)
+    yhat = run_oracle(clean, dtype, False, 1e-6)
+    xn = pi.to_f64(clean["X"], dtype)[:, k_w]
+    rows_ok = np.ones(M, dtype=bool)
+    rows_ok[[r_inf, r_nan]] = False
+    cols_ok = np.ones(N, dtype=bool)
+    cols_ok[n_w] = False
+    assert np.isnan(y[r_inf]).all() and np.isnan(y[r_nan]).all()
+    assert np.isinf(y[rows_ok, n_w]).all() and (np.sign(y[rows_ok, n_w]) == np.sign(xn[rows_ok])).all()
+    assert_parity(y[np.ix_(rows_ok, cols_ok)], yhat[np.ix_(rows_ok, cols_ok)], dtype, f"beside the non-finite entries, path {path}")
+
+
 def test_large_magnitudes_and_scale_invariance_on_gpu(P):
     """RMSNorm(cX) = RMSNorm(X): c = 2^k scales bf16 inputs exactly, so outputs match bit for bit up to eps."""
     stored = pi.draw(pi.BF16, 16, 1024, 256, False, 700)
