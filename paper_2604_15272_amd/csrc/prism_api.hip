@@ -160,7 +160,11 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
     for (int i = 0; i < nt; ++i) {
         const int cw = gated ? t[i].bn / 2 : t[i].bn;
         const double tiles = (double)((M + t[i].bm - 1) / t[i].bm) * (double)((N + cw - 1) / cw);
-        const double rounds = std::ceil(tiles / (double)cu_count());
+        // Two or more of the small tiles share a compute unit, so a few workgroups beyond a whole number of rounds
+        // ride along (gated 64 x 4096 x 33280 on 128 x 128 tiles, 520 workgroups: 150.7 us; 128 x 256, 260: 176 us);
+        // for the large tiles they are another round.
+        const bool shares_cu = t[i].bm <= 128 && t[i].bn <= 128;
+        const double rounds = std::max(1.0, std::ceil(tiles / (double)cu_count() - (shares_cu ? 0.05 : 0.0)));
         const double cost = rounds * t[i].bm * t[i].bn / t[i].eff;
         if (cost < best) {
             best = cost;
@@ -176,18 +180,21 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 // The choice is made by a small time model of the three candidates, whose constants were measured on MI355X
 // (bf16, 96 shapes: 40 to 512 rows against K x N from 2048 x 8192 to 14336 x 4096, plain and gated, each forced
 // onto 32 rows, 64 rows and the prefill kernel): the model's pick is within 1.1 % of the best of the three on
-// average and within 10 % on every shape (the fixed rules it replaces: 4.3 % and 72 %).
+// average and within 10 % on every shape (the fixed rules it replaces: 4.3 % and 72 %).  Checked again on a second
+// grid (17 to 512 rows against ten K x N from 1024 x 4096 to 8192 x 28672, plain and gated, 300 calls), which the
+// HBM terms and the second-round factor come from: 0.2 % on average, 16 % at worst (2.4 % / 40 % for gated calls
+// before them).
 //   multi-row kernel, RG row groups, S K-slices, z row blocks, all times in microseconds:
-//     loop      = ceil(kblocks / S) x c x rounds,  c = 0.22 / 0.27 per K-block for 32 / 64 rows of one matrix,
+//     loop      = ceil(kblocks / S) x c x rounds (x 1.1 from the second round on),  c = 0.22 / 0.31 per K-block for 32 / 64 rows of one matrix,
 //                 0.33 / 0.60 for two (per compute unit a K-block costs its MFMAs, its vector work and 8 to 12 KiB
 //                 through the L1, and they do not overlap); rounds = ceil(workgroups / compute units);
-//                 never less than streaming W once at 6 TB/s
+//                 never less than streaming W at 6 TB/s: once, or once per row block when W is beyond 128 MB
 //     reduction = 0.5 x RG x matrices (LDS)
 //     exchange  = 2.5 + S x RG x matrices / 8 when S > 1 (three dependent round trips, then the last arrival
 //                 pulls S partial tiles through one compute unit)
 //     launch    = 1.5
 //   prefill kernel: K steps x (1.5 / 2.0 for 256-row tiles of one / two matrices, 1.25 for 256 x 128, 0.88 to 1.2 for 128-row tiles, 0.93
-//     for 64 x 64) x 1 if every tile has a compute unit, x 1.3 for up to two 128-row tiles per unit, else the rounds;
+//     for 64 x 64) x 1 if every tile has a compute unit, x 1.2 for up to two 128-row tiles per unit, else the rounds;
 //     + 3.  (A K step of that kernel has a floor of about a microsecond whatever the tile.)
 struct RowsEstimate {
     double us;
@@ -200,9 +207,14 @@ RowsEstimate rows_estimate(int rg, bool gated, int64_t M, int64_t K, int64_t N, 
     const int64_t z = (M + 16 * rg - 1) / (16 * rg), wgs1 = n_tiles * z;
     int64_t S = wgs1 <= cus ? cus / wgs1 : 1;
     S = std::max<int64_t>(1, std::min<int64_t>(S, std::max<int64_t>(1, kblocks / 8)));
-    const double c = gated ? (rg == 2 ? 0.33 : 0.60) : (rg == 2 ? 0.22 : 0.27);
-    double loop = (double)((kblocks + S - 1) / S) * c * (double)((wgs1 * S + cus - 1) / cus);
-    loop = std::max(loop, 2.0 * (double)K * (double)N * G / 6.0e6);
+    const double c = gated ? (rg == 2 ? 0.33 : 0.60) : (rg == 2 ? 0.22 : 0.31);
+    const int64_t rounds = (wgs1 * S + cus - 1) / cus;
+    double loop = (double)((kblocks + S - 1) / S) * c * (double)rounds * (rounds >= 2 ? 1.1 : 1.0);
+    // Never faster than W streams from HBM; weights too large for the last-level cache to keep between the row
+    // blocks of a tile (256 MB; 128 MB taken) stream once per row block (gated 4096 x 14336, 48 rows as 2 x 32:
+    // 58.7 us against 47.3 us for 32 rows; 8192 x 28672: 321 against 156 us).
+    const double w_bytes = 2.0 * (double)K * (double)N * G;
+    loop = std::max(loop, w_bytes / 6.0e6 * (w_bytes > 128.0e6 ? (double)z : 1.0));
     double us = loop + 0.5 * rg * G + 1.5;
     if (S > 1) us += 2.5 + (double)(S * rg * G) / 8.0;
     return RowsEstimate{us, S};
@@ -215,16 +227,21 @@ double prefill_estimate(bool gated, int64_t M, int64_t K, int64_t N, int64_t cus
     };
     static const T plain[] = {{256, 256, 1.5}, {256, 192, 1.5}, {256, 128, 1.25}, {128, 128, 0.88}, {64, 64, 0.93}};
     static const T gate[] = {{256, 256, 2.0}, {128, 256, 1.2}, {128, 128, 0.90}};
-    const T* t = gated ? gate : plain;
+    // The tile the call would get (choose_prefill_tile), not the best of all: the estimate is of what would run.
+    int bm = 0, bn = 0;
+    choose_prefill_tile(gated, M, N, 0, &bm, &bn);
+    double step = 1.5;
+    for (const T& t : plain)
+        if (!gated && t.bm == bm && t.bn == bn) step = t.step;
+    for (const T& t : gate)
+        if (gated && t.bm == bm && t.bn == bn) step = t.step;
     const int64_t KT = (K + 63) / 64;
-    double best = 1e300;
-    for (int i = 0; i < (gated ? 3 : 5); ++i) {
-        const int64_t cw = gated ? t[i].bn / 2 : t[i].bn;
-        const int64_t tiles = ((M + t[i].bm - 1) / t[i].bm) * ((N + cw - 1) / cw);
-        const double f = tiles <= cus ? 1.0 : ((tiles <= 2 * cus && t[i].bm <= 128) ? 1.3 : (double)((tiles + cus - 1) / cus));
-        best = std::min(best, (double)KT * t[i].step * f + 3.0);
-    }
-    return best;
+    const int64_t cw = gated ? bn / 2 : bn;
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + cw - 1) / cw);
+    const bool shares_cu = bm <= 128 && bn <= 128;
+    const double f = tiles <= cus ? 1.0 : ((shares_cu && tiles <= 2 * cus + cus / 20) ? 1.2 : (double)((tiles + cus - 1) / cus));
+    // (the tiled kernel streams W from HBM at about 5 TB/s at best: gated 17 x 8192 x 28672 193 us)
+    return std::max((double)KT * step * f, 2.0 * (double)K * (double)N * (gated ? 2 : 1) / 5.0e6) + 3.0;
 }
 
 int decode_row_groups(bool gated, int64_t M, int64_t K, int64_t N) {

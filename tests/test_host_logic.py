@@ -241,8 +241,12 @@ def test_decode_plan_for_more_than_sixteen_rows(P):
     assert (d["path"], d["tile_m"], d["split_k"]) == (P.PRISM_PATH_DECODE, 32, 4)
     g = P.prism_plan(1, 192, 8192, 4096, bf16)    # gated, deep K: the prefill kernel's 128 K steps lose (131 against 76 us)
     assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 64, 3, 2)   # 81 us; 32 rows: 76
-    g = P.prism_plan(1, 64, 4096, 14336, bf16)    # gated, 33 to 64 rows against the wide matrices: two row blocks of 32
-    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 32, 2, 1)
+    # gated, 33 to 64 rows against the wide matrices: two row blocks of 32 would each stream the 235 MB of weights
+    # (58 to 60 us); 64 rows in two K-slices read them once (52 to 58 us)
+    g = P.prism_plan(1, 64, 4096, 14336, bf16)
+    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 64, 1, 2)
+    g = P.prism_plan(1, 17, 8192, 28672, bf16)    # 940 MB of weights: the tiled kernel streams them slower (193 against 154 us)
+    assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 32, 1, 1)
     g = P.prism_plan(1, 32, 4096, 14336, bf16)
     assert (g["path"], g["tile_m"], g["grid_z"], g["split_k"]) == (P.PRISM_PATH_DECODE, 32, 1, 2)
     assert P.prism_plan(1, 100, 4096, 14336, bf16)["path"] == P.PRISM_PATH_PREFILL
@@ -277,10 +281,12 @@ def test_decode_rows_plan_with_more_tiles_than_cus(P):
     bf16 = P.PRISM_BF16
     pl = lambda op, M, K, N: (lambda d: (d["path"], d["tile_m"], d["grid_x"], d["grid_y"], d["grid_z"]))(P.prism_plan(op, M, K, N, bf16))
     assert pl(0, 32, 4096, 40960) == (P.PRISM_PATH_DECODE, 32, 320, 1, 1)
-    assert pl(0, 64, 4096, 33280) == (P.PRISM_PATH_DECODE, 64, 260, 2, 1)
+    assert pl(0, 64, 8192, 36864) == (P.PRISM_PATH_DECODE, 64, 288, 2, 1)     # 153 us; the tiled kernel 167 to 178
+    assert pl(0, 64, 4096, 33280)[0] == P.PRISM_PATH_PREFILL                  # 82 us on 128 x 128 tiles; 87 in 260 x 2
     assert pl(1, 32, 4096, 33280) == (P.PRISM_PATH_DECODE, 32, 260, 2, 1)
     assert pl(0, 128, 4096, 40960)[0] == P.PRISM_PATH_PREFILL
-    assert pl(1, 64, 4096, 33280)[0] == P.PRISM_PATH_PREFILL
+    d = P.prism_plan(1, 64, 4096, 33280, bf16)   # 520 small tiles, two to a compute unit: 151 us; 260 of 128 x 256: 176
+    assert (d["path"], d["tile_m"], d["tile_n"], d["grid_x"]) == (P.PRISM_PATH_PREFILL, 128, 128, 520)
 
 
 def test_plans_of_random_shapes_are_consistent(P):
