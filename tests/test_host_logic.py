@@ -282,11 +282,11 @@ def test_decode_rows_plan_with_more_tiles_than_cus(P):
     pl = lambda op, M, K, N: (lambda d: (d["path"], d["tile_m"], d["grid_x"], d["grid_y"], d["grid_z"]))(P.prism_plan(op, M, K, N, bf16))
     assert pl(0, 32, 4096, 40960) == (P.PRISM_PATH_DECODE, 32, 320, 1, 1)
     assert pl(0, 64, 8192, 36864) == (P.PRISM_PATH_DECODE, 64, 288, 2, 1)     # 153 us; the tiled kernel 167 to 178
-    assert pl(0, 64, 4096, 33280)[0] == P.PRISM_PATH_PREFILL                  # 82 us on 128 x 128 tiles; 87 in 260 x 2
+    assert pl(0, 64, 4096, 33280) == (P.PRISM_PATH_DECODE, 64, 260, 2, 1)     # 87 us; the tiled kernel 78 to 95
     assert pl(1, 32, 4096, 33280) == (P.PRISM_PATH_DECODE, 32, 260, 2, 1)
     assert pl(0, 128, 4096, 40960)[0] == P.PRISM_PATH_PREFILL
-    d = P.prism_plan(1, 64, 4096, 33280, bf16)   # 520 small tiles, two to a compute unit: 151 us; 260 of 128 x 256: 176
-    assert (d["path"], d["tile_m"], d["tile_n"], d["grid_x"]) == (P.PRISM_PATH_PREFILL, 128, 128, 520)
+    assert pl(1, 64, 4096, 33280) == (P.PRISM_PATH_DECODE, 64, 260, 2, 1)     # 159 us; the tiled kernel 151 to 176
+    assert pl(1, 128, 4096, 33280)[0] == P.PRISM_PATH_PREFILL
 
 
 def test_plans_of_random_shapes_are_consistent(P):
