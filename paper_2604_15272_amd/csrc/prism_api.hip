@@ -698,7 +698,9 @@ prism_status_t make_attention_plan(int64_t B, int64_t G, int64_t H, int64_t D, p
         // 13.9 us in 8 slices and 19.4 us in 16; 16384 keys 45.8 us in 8 and 67.7 us in 32.
         // With more batch entries than CUs the workgroups come in rounds anyway, and long contexts still gain from
         // four slices (300 entries, 4096 keys: 137.6 us unsplit, 110.7 us in 4 slices).
-        S = std::min<int64_t>(S, std::max<int64_t>(cu_count() / B, H >= 4096 ? 4 : (H >= 2048 ? 2 : 1)));
+        // (128 entries fill the CUs with two slices each: 4096 keys 43.6 us in 2, 46.8 us in 4; 16384 keys 152.6 / 161.1 us)
+        const int64_t per_entry = cu_count() / B;
+        S = std::min<int64_t>(S, per_entry >= 2 ? per_entry : (H >= 4096 ? 4 : (H >= 2048 ? 2 : 1)));
     }
     if (S > kAttnMaxSlices) S = kAttnMaxSlices;
     keys = ((H + S - 1) / S + 31) / 32 * 32;
