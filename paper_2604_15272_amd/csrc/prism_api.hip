@@ -184,16 +184,17 @@ void choose_prefill_tile(bool gated, int64_t M, int64_t N, int variant, int* bm,
 // before them).
 //   multi-row kernel, RG row groups, S K-slices, z row blocks, all times in microseconds:
 //     loop      = ceil(kblocks / S) x c x rounds (x 1.1 from the second round on),  c = 0.22 / 0.31 per K-block for
-//                 32 / 64 rows of one matrix, 0.33 / 0.60 for two (per compute unit a K-block costs its MFMAs, its vector work and 8 to 12 KiB
-//                 through the L1, and they do not overlap); rounds = ceil(workgroups / compute units);
+//                 32 / 64 rows of one matrix, 0.33 / 0.60 for two (per compute unit a K-block costs its MFMAs, its
+//                 vector work and 8 to 12 KiB through the L1, and they do not overlap); rounds = ceil(workgroups /
+//                 compute units);
 //                 never less than streaming W at 6 TB/s: once, or once per row block when W is beyond 128 MB
 //     reduction = 0.5 x RG x matrices (LDS)
 //     exchange  = 2.5 + S x RG x matrices / 8 when S > 1 (three dependent round trips, then the last arrival
 //                 pulls S partial tiles through one compute unit)
 //     launch    = 1.5
 //   prefill kernel: K steps x (1.5 / 2.0 for 256-row tiles of one / two matrices, 1.25 for 256 x 128, 0.88 to 1.2 for
-//     128-row tiles, 0.93 for 64 x 64) x 1 if every tile has a compute unit, x 1.2 for up to two 128-row tiles per unit, else the rounds;
-//     + 3.  (A K step of that kernel has a floor of about a microsecond whatever the tile.)
+//     128-row tiles, 0.93 for 64 x 64) x 1 if every tile has a compute unit, x 1.2 for up to two 128-row tiles per
+//     unit, else the rounds; + 3.  (A K step of that kernel has a floor of about a microsecond whatever the tile.)
 struct RowsEstimate {
     double us;
     int64_t S;
