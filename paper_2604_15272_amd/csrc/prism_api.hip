@@ -620,7 +620,11 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         }
         // Measured (us, X through LDS against straight loads): 512 x 4096 x 4096 32.1 / 34.1, 256 x 14336 x 4096
         // 56.6 / 65.5, 1024 x 4096 x 6144 85.4 / 92.7; with slices of 16 K-blocks (64 x 4096 x 4096) 18.3 / 16.7.
-        if (row_groups > 1 && !gated && variant == 0 && kblocks / std::max<int64_t>(1, S) >= 64) xlds = true;
+        // A single row block whose row groups are less than three quarters full moves padding through LDS for nothing
+        // (17 rows in a 32-row workgroup: 2 to 7 % slower on five shapes; 24 of 32 and 48 of 64: even).
+        if (row_groups > 1 && !gated && variant == 0 && kblocks / std::max<int64_t>(1, S) >= 64 &&
+            (row_blocks > 1 || M * 4 >= 3 * 16 * row_groups))
+            xlds = true;
         out->waves = waves;
         out->row_groups = row_groups;
         out->xlds = xlds;
