@@ -476,7 +476,13 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
         // with these tiles; s_slow = s + max(1, (2 s + 2) / 5) (the slow stripes need 1.4 times as long).
         StreamPartition balanced{};
         int64_t balanced_slow = 0;
-        if (gated && M <= kDecodeMaxRows && (variant == 0 || packed) && forced_split <= 0 && (N * 2) % 2048 == 0 &&
+        // Narrow outputs (at most 32 packed tiles): the packed tile with equal slices.  The two-tile form would put
+        // half as many workgroups to work, and the balanced form below so many slices that the exchange outweighs what
+        // the slow stripes lose (16 x 4096 x 1024: 11.3 us packed in 8 slices, 12.8 us as two tiles, 13.2 us balanced
+        // 8 : 11; 16 x 4096 x 2048: 12.9 / 13.9 / 14.6 us; 16 x 2048 x 2048: 10.6 to 11 / 10.6 / 12.4 us).
+        const bool narrow = gated && M <= kDecodeMaxRows && N <= 32 * (kDecodeTileN / 2);
+        if (narrow && variant == 0 && forced_split <= 0) packed = true;
+        if (!narrow && gated && M <= kDecodeMaxRows && (variant == 0 || packed) && forced_split <= 0 && (N * 2) % 2048 == 0 &&
             (g_slow_units.load() & 0xFFFF) != 0) {
             const uint32_t units = (uint32_t)g_slow_units.load() & 0xFFFFu;
             const int64_t nt = N / (kDecodeTileN / 2), n_slow = nt / 16 * __builtin_popcount(units);

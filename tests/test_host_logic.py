@@ -313,7 +313,11 @@ def test_plans_of_random_shapes_are_consistent(P):
             assert p["grid_x"] == -(-M // p["tile_m"]) * -(-N // cols), what
         elif p["path"] == P.PRISM_PATH_DECODE or (p["path"] == P.PRISM_PATH_ROWS and p["tile_m"] == 32):
             tiles = -(-N // p["tile_n"])
-            if p["path"] == P.PRISM_PATH_DECODE and p["tile_n"] == 64:
+            if p["path"] == P.PRISM_PATH_DECODE and p["tile_n"] == 64 and N <= 2048:
+                # gated, packed tiles, narrow output: equal K-slices
+                assert op == 1 and M <= 16, what
+                assert (p["grid_x"], p["grid_y"], max(1, p["grid_z"])) == (tiles, p["split_k"], 1), what
+            elif p["path"] == P.PRISM_PATH_DECODE and p["tile_n"] == 64:
                 # gated, packed tiles, more K-slices for the tiles in slow units: every workgroup on its own CU
                 assert op == 1 and M <= 16 and N % 1024 == 0 and p["grid_y"] == 1, what
                 assert tiles < p["grid_x"] <= 256 and 2 <= p["split_k"] <= 32, what
