@@ -560,6 +560,12 @@ prism_status_t make_plan_with(prism_op_t op, int64_t M, int64_t K, int64_t N, pr
                 // round trip), and a slice keeps at least four K-blocks (eight when gated: two matrices), even
                 // if that leaves wavefronts idle.
                 s_max = std::min<int64_t>(8, std::max<int64_t>(1, kblocks / ((gated && !packed) ? 8 : 4)));
+                // Few column tiles and a deep K (one weight matrix): eight slices leave at least half the CUs idle and
+                // every workgroup with a long walk; sixteen, read back in two batches, are faster when a slice still
+                // has 16 K-blocks (32 with sixteen tiles): 16 x 8192 x 512 11.3 -> 8.7 us, 16 x 16384 x 1024 18.5 ->
+                // 13.3 us, 16 x 16384 x 2048 20.2 -> 17.8 us; but 16 x 4096 x 1024 8.3 -> 9.0 us, 16 x 8192 x 2048 12.4
+                // -> 12.8 us.
+                if (!gated && n_tiles * 8 <= target / 2 && kblocks >= 16 * (n_tiles <= 8 ? 16 : 32)) s_max = 16;
             }
             if (S > s_max) S = s_max;
             if (S < 1) S = 1;
